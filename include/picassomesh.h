@@ -1,0 +1,144 @@
+/*
+ * picassomesh -- spherical-harmonic continuous-filter mesh convolutions on MI355X (gfx950).
+ *
+ * C ABI of the hot path of "Mesh Convolution with Continuous Filters for 3D Surface Parsing":
+ * facet2vertex (Eq. 5), vertex2facet (Eq. 6), facet2facet (Eq. 7), their backward passes, the
+ * real truncated SH basis (Eq. 3-4) and the vertex->facet adjacency the reductions run over.
+ *
+ * General rules for every entry point
+ *   - Plain C linkage.  Every pointer is a DEVICE pointer unless the comment says HOST; all are
+ *     borrowed (never freed or retained).  `stream` is a hipStream_t passed as void* (NULL = the
+ *     default stream).  All work is enqueued on that stream; no entry point allocates device memory
+ *     and only pm_validate_mesh synchronises with the host.
+ *   - Arrays are row-major and contiguous.  Base pointers of feature, weight, output and workspace
+ *     arrays must be 16-byte aligned (checked -> PM_ERR_INVALID_ARG).
+ *   - Meshes come as one packed heterogeneous batch ("Heterogeneous Batching" subsection): vertex
+ *     arrays of all meshes concatenated, facet index arrays concatenated with the running vertex count
+ *     already added, 0-indexed.  The convolutions themselves never need the per-mesh offsets.
+ *   - n_vert, n_facet, n_tex and 3*n_facet must be < 2^31 (ids are int32); element offsets are
+ *     computed in 64 bits.  Out-of-range ids are undefined behaviour in the convolutions; call
+ *     pm_validate_mesh first when the input is untrusted.
+ *   - Outputs are overwritten, never accumulated (dW included).  Results are bitwise reproducible
+ *     from call to call: no floating-point atomics are used anywhere.
+ *   - Filter coefficients are dense:  W[k][ci][co],  k = l*(l+1)+m,  m in [-l,l];  m > 0 multiplies
+ *     the cos(m phi) function (a_lm of Eq. 4), m < 0 the sin(|m| phi) function (b_l|m|), m = 0 is a_l0.
+ *     K = (L+1)^2 (the paper's kernel size T).  0 <= L <= PM_MAX_L.
+ *   - dtype selects the storage type of features AND coefficients AND feature outputs (PM_F32 or
+ *     PM_BF16).  Geometry, basis values, accumulation and dW are always fp32.
+ *   - Return value: PM_OK or a negative pm_status; pm_last_error() gives a thread-local message.
+ *     Argument errors are detected before anything is enqueued.
+ */
+#ifndef PICASSOMESH_H
+#define PICASSOMESH_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define PM_MAX_L 5
+
+typedef int32_t pm_status;
+enum {
+  PM_OK = 0,
+  PM_ERR_INVALID_ARG = -1, /* NULL / misaligned pointer, negative size, size over the int32 limits   */
+  PM_ERR_UNSUPPORTED = -2, /* L > PM_MAX_L, unknown dtype / norm / op                                */
+  PM_ERR_WORKSPACE = -3,   /* workspace smaller than pm_workspace_bytes reports                      */
+  PM_ERR_HIP = -4,         /* a HIP runtime call or kernel launch failed                             */
+  PM_ERR_BAD_MESH = -5     /* pm_validate_mesh found an out-of-range id or inconsistent offsets      */
+};
+
+typedef enum { PM_F32 = 0, PM_BF16 = 1 } pm_dtype;
+
+/* PM_SH_PAPER: the functions exactly as printed in Eq. 4 (squared L2 norm 1 for m = 0, 1/2 for m != 0).
+ * PM_SH_ORTHONORMAL: m != 0 functions multiplied by sqrt(2), the orthonormal family the abstract names. */
+typedef enum { PM_SH_PAPER = 0, PM_SH_ORTHONORMAL = 1 } pm_sh_norm;
+
+typedef enum {
+  PM_OP_ADJACENCY = 0, PM_OP_F2V = 1, PM_OP_F2V_BWD = 2, PM_OP_V2F = 3, PM_OP_V2F_BWD = 4,
+  PM_OP_F2F = 5, PM_OP_F2F_BWD = 6
+} pm_op;
+
+/* Packed batch of triangle meshes (device arrays). */
+typedef struct pm_mesh {
+  int32_t n_mesh;
+  int64_t n_vert, n_facet;
+  const float* vert;        /* [n_vert,3]   xyz                                                       */
+  const int32_t* facet;     /* [n_facet,3]  global vertex ids; corner order is significant (it fixes
+                               the normal by the right-hand rule and the roles of Eq. 6's three terms) */
+  const int32_t* vert_off;  /* [n_mesh+1]   may be NULL when n_mesh == 1; used by validation only      */
+  const int32_t* facet_off; /* [n_mesh+1]   may be NULL when n_mesh == 1                              */
+} pm_mesh;
+
+/* Vertex -> facet adjacency N(v) of Eq. 5 as CSR over corner slots: entries of vertex v are
+ * col[row_ptr[v] .. row_ptr[v+1]), each equal to 3*f+j (facet f, corner j), ascending. */
+typedef struct pm_vf_adj {
+  const int32_t* row_ptr; /* [n_vert+1] */
+  const int32_t* col;     /* [3*n_facet] */
+} pm_vf_adj;
+
+const char* pm_status_string(pm_status s);
+const char* pm_last_error(void);
+
+/* Bytes of workspace an op needs for these sizes (HOST computation, no GPU call).  n_tex is the number
+ * of texture points (facet2facet only, else 0).  Returns 0 on invalid arguments. */
+size_t pm_workspace_bytes(pm_op op, int64_t n_vert, int64_t n_facet, int64_t n_tex, int L, int cin, int cout,
+                          pm_dtype dtype);
+
+/* Range-checks facet ids against each mesh's vertex range and the offset arrays.  Synchronises.
+ * ws: >= 16 bytes of device memory. */
+pm_status pm_validate_mesh(const pm_mesh* mesh, void* ws, size_t ws_bytes, void* stream);
+
+/* Builds N(v) (the receptive field of Eq. 5) for the whole batch.  row_ptr [n_vert+1] and col [3*n_facet]
+ * are outputs.  Deterministic: col is sorted ascending within each vertex. */
+pm_status pm_build_vf_adjacency(const pm_mesh* mesh, int32_t* row_ptr, int32_t* col, void* ws, size_t ws_bytes,
+                                void* stream);
+
+/* Eq. 3-4 at the facet normals (x2-x1)x(x3-x1) of the mesh (facet2vertex's angular arguments):
+ * basis [n_facet, K] fp32.  A facet whose cross product has squared length < 1e-30 uses (0,0,1). */
+pm_status pm_sh_basis(const pm_mesh* mesh, int L, pm_sh_norm norm, float* basis, void* stream);
+/* Eq. 3-4 at arbitrary directions dirs [n,3] (normalised inside; need not be unit): basis [n,K]. */
+pm_status pm_sh_basis_dirs(int64_t n, const float* dirs, int L, pm_sh_norm norm, float* basis, void* stream);
+/* Gradient of <dbasis, basis(dirs)> with respect to dirs: ddirs [n,3]. */
+pm_status pm_sh_basis_bwd(int64_t n, const float* dirs, int L, pm_sh_norm norm, const float* dbasis, float* ddirs,
+                          void* stream);
+
+/* facet2vertex, Eq. 5:  g_v = 1/|N(v)| sum_{f in N(v)} sum_k sum_ci B_k(n_f) h_f[ci] W[k][ci][co].
+ * h_facet [F,cin], W [K,cin,cout], g_vert [V,cout] (dtype).  Vertices with empty N(v) get zeros. */
+pm_status pm_f2v(const pm_mesh* mesh, const pm_vf_adj* adj, int L, pm_sh_norm norm, int cin, int cout, pm_dtype dtype,
+                 const void* h_facet, const void* W, void* g_vert, void* ws, size_t ws_bytes, void* stream);
+/* Backward of Eq. 5.  dg_vert [V,cout] (dtype) -> dh_facet [F,cin] (dtype, may be NULL),
+ * dW [K,cin,cout] fp32 (may be NULL). */
+pm_status pm_f2v_bwd(const pm_mesh* mesh, const pm_vf_adj* adj, int L, pm_sh_norm norm, int cin, int cout,
+                     pm_dtype dtype, const void* h_facet, const void* W, const void* dg_vert, void* dh_facet,
+                     float* dW, void* ws, size_t ws_bytes, void* stream);
+
+/* vertex2facet, Eq. 6:  g_f = F(pi/2,0) h_{v1} + F(pi/2,pi/2) h_{v2} + F(0,0) h_{v3}  (no 1/3).
+ * h_vert [V,cin], g_facet [F,cout].  Geometry is not read (mesh->vert may be NULL). */
+pm_status pm_v2f(const pm_mesh* mesh, int L, pm_sh_norm norm, int cin, int cout, pm_dtype dtype, const void* h_vert,
+                 const void* W, void* g_facet, void* ws, size_t ws_bytes, void* stream);
+/* Backward of Eq. 6.  dg_facet [F,cout] -> dh_vert [V,cin] (may be NULL; needs adj), dW fp32 (may be NULL). */
+pm_status pm_v2f_bwd(const pm_mesh* mesh, const pm_vf_adj* adj, int L, pm_sh_norm norm, int cin, int cout,
+                     pm_dtype dtype, const void* h_vert, const void* W, const void* dg_facet, void* dh_vert, float* dW,
+                     void* ws, size_t ws_bytes, void* stream);
+
+/* facet2facet, Eq. 7:  g_f = 1/R_f sum_{p in f} sum_k sum_ci B_k(xi_p/|xi_p|) h_p[ci] W[k][ci][co].
+ * tex_off [n_facet+1] is the facet -> texture-point CSR (points of a facet contiguous, R_f may be 0 ->
+ * zero row); bary [n_tex,3] barycentric coordinates; h_tex [n_tex,cin]; g_facet [n_facet,cout]. */
+pm_status pm_f2f(int64_t n_facet, int64_t n_tex, const int32_t* tex_off, const float* bary, int L, pm_sh_norm norm,
+                 int cin, int cout, pm_dtype dtype, const void* h_tex, const void* W, void* g_facet, void* ws,
+                 size_t ws_bytes, void* stream);
+/* Backward of Eq. 7.  dg_facet [n_facet,cout] -> dh_tex [n_tex,cin] (may be NULL), dW fp32 (may be NULL). */
+pm_status pm_f2f_bwd(int64_t n_facet, int64_t n_tex, const int32_t* tex_off, const float* bary, int L,
+                     pm_sh_norm norm, int cin, int cout, pm_dtype dtype, const void* h_tex, const void* W,
+                     const void* dg_facet, void* dh_tex, float* dW, void* ws, size_t ws_bytes, void* stream);
+
+/* Duration in milliseconds of the most recent call's kernels is NOT tracked by the library; time with
+ * HIP events on `stream`. */
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PICASSOMESH_H */

@@ -1,0 +1,295 @@
+"""ctypes binding of libpicassomesh.so: argument marshalling only.
+
+Every function here has the name of the C entry point it calls (include/picassomesh.h).  PyTorch is
+used for device memory and streams; all arithmetic runs in the HIP kernels.  There is no CPU
+fallback: if the library has not been built the import of this module's `lib()` raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+from typing import Optional
+
+import torch
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libpicassomesh.so")
+
+PM_F32, PM_BF16 = 0, 1
+PM_SH_PAPER, PM_SH_ORTHONORMAL = 0, 1
+PM_OP_ADJACENCY, PM_OP_F2V, PM_OP_F2V_BWD, PM_OP_V2F, PM_OP_V2F_BWD, PM_OP_F2F, PM_OP_F2F_BWD = range(7)
+PM_MAX_L = 5
+
+EXPORTS = [
+    "pm_status_string", "pm_last_error", "pm_workspace_bytes", "pm_validate_mesh", "pm_build_vf_adjacency",
+    "pm_sh_basis", "pm_sh_basis_dirs", "pm_sh_basis_bwd", "pm_f2v", "pm_f2v_bwd", "pm_v2f", "pm_v2f_bwd",
+    "pm_f2f", "pm_f2f_bwd",
+]
+
+
+class PmError(RuntimeError):
+    def __init__(self, status: int, msg: str):
+        super().__init__("%s (%d): %s" % (_status_name(status), status, msg))
+        self.status = status
+
+
+class _PmMesh(C.Structure):
+    _fields_ = [("n_mesh", C.c_int32), ("n_vert", C.c_int64), ("n_facet", C.c_int64), ("vert", C.c_void_p),
+                ("facet", C.c_void_p), ("vert_off", C.c_void_p), ("facet_off", C.c_void_p)]
+
+
+class _PmAdj(C.Structure):
+    _fields_ = [("row_ptr", C.c_void_p), ("col", C.c_void_p)]
+
+
+_lib = None
+
+
+def lib():
+    """Load the HIP library; fails loudly when it has not been built (no fallback exists)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError("libpicassomesh.so is missing: run `python -m paper_2112_01801_amd.build` "
+                               "(or __graft_entry__.build()) first; there is no CPU fallback")
+        l = C.CDLL(LIB_PATH)
+        l.pm_status_string.restype = C.c_char_p
+        l.pm_status_string.argtypes = [C.c_int32]
+        l.pm_last_error.restype = C.c_char_p
+        l.pm_workspace_bytes.restype = C.c_size_t
+        l.pm_workspace_bytes.argtypes = [C.c_int, C.c_int64, C.c_int64, C.c_int64, C.c_int, C.c_int, C.c_int, C.c_int]
+        vp, i32, i64, sz = C.c_void_p, C.c_int, C.c_int64, C.c_size_t
+        mp, ap = C.POINTER(_PmMesh), C.POINTER(_PmAdj)
+        sig = {
+            "pm_validate_mesh": [mp, vp, sz, vp],
+            "pm_build_vf_adjacency": [mp, vp, vp, vp, sz, vp],
+            "pm_sh_basis": [mp, i32, i32, vp, vp],
+            "pm_sh_basis_dirs": [i64, vp, i32, i32, vp, vp],
+            "pm_sh_basis_bwd": [i64, vp, i32, i32, vp, vp, vp],
+            "pm_f2v": [mp, ap, i32, i32, i32, i32, i32, vp, vp, vp, vp, sz, vp],
+            "pm_f2v_bwd": [mp, ap, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, sz, vp],
+            "pm_v2f": [mp, i32, i32, i32, i32, i32, vp, vp, vp, vp, sz, vp],
+            "pm_v2f_bwd": [mp, ap, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, sz, vp],
+            "pm_f2f": [i64, i64, vp, vp, i32, i32, i32, i32, i32, vp, vp, vp, vp, sz, vp],
+            "pm_f2f_bwd": [i64, i64, vp, vp, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, sz, vp],
+        }
+        for name, args in sig.items():
+            f = getattr(l, name)
+            f.restype = C.c_int32
+            f.argtypes = args
+        _lib = l
+    return _lib
+
+
+def _status_name(s: int) -> str:
+    return lib().pm_status_string(s).decode()
+
+
+def _check(s: int):
+    if s != 0:
+        raise PmError(s, lib().pm_last_error().decode())
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    if t is None:
+        return None
+    assert t.is_cuda and t.is_contiguous(), "device-resident contiguous tensors only"
+    return C.c_void_p(t.data_ptr())
+
+
+def _stream(stream=None):
+    s = torch.cuda.current_stream() if stream is None else stream
+    return C.c_void_p(s.cuda_stream)
+
+
+def torch_dtype(dtype: int):
+    return torch.bfloat16 if dtype == PM_BF16 else torch.float32
+
+
+@dataclass
+class Mesh:
+    """Device-resident packed mesh batch and the struct the C ABI takes."""
+    vert: Optional[torch.Tensor]      # [V,3] float32
+    facet: torch.Tensor               # [F,3] int32
+    vert_off: Optional[torch.Tensor]  # [n_mesh+1] int32
+    facet_off: Optional[torch.Tensor]
+    n_vert: int
+    n_mesh: int = 1
+
+    @property
+    def n_facet(self) -> int:
+        return int(self.facet.shape[0])
+
+    def c(self) -> _PmMesh:
+        m = _PmMesh()
+        m.n_mesh, m.n_vert, m.n_facet = self.n_mesh, self.n_vert, self.n_facet
+        m.vert = self.vert.data_ptr() if self.vert is not None else None
+        m.facet = self.facet.data_ptr() if self.facet.numel() else None
+        m.vert_off = self.vert_off.data_ptr() if self.vert_off is not None else None
+        m.facet_off = self.facet_off.data_ptr() if self.facet_off is not None else None
+        return m
+
+
+@dataclass
+class Adjacency:
+    row_ptr: torch.Tensor
+    col: torch.Tensor
+
+    def c(self) -> _PmAdj:
+        a = _PmAdj()
+        a.row_ptr = self.row_ptr.data_ptr()
+        a.col = self.col.data_ptr() if self.col.numel() else None
+        return a
+
+
+def mesh_to_device(batch, device="cuda") -> Mesh:
+    """Upload a meshgen.MeshBatch (numpy) to the GPU."""
+    import numpy as np
+    vert = torch.from_numpy(np.ascontiguousarray(batch.vert)).to(device)
+    facet = torch.from_numpy(np.ascontiguousarray(batch.facet)).to(device)
+    vo = torch.from_numpy(np.ascontiguousarray(batch.vert_off)).to(device)
+    fo = torch.from_numpy(np.ascontiguousarray(batch.facet_off)).to(device)
+    return Mesh(vert, facet, vo, fo, int(batch.vert.shape[0]), int(batch.n_mesh))
+
+
+def pm_workspace_bytes(op: int, n_vert: int, n_facet: int, n_tex: int, L: int, cin: int, cout: int, dtype: int) -> int:
+    return int(lib().pm_workspace_bytes(op, n_vert, n_facet, n_tex, L, cin, cout, dtype))
+
+
+def alloc_workspace(nbytes: int, device="cuda") -> torch.Tensor:
+    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
+
+
+def pm_validate_mesh(mesh: Mesh, stream=None) -> None:
+    ws = alloc_workspace(256, mesh.facet.device)
+    m = mesh.c()
+    _check(lib().pm_validate_mesh(C.byref(m), _ptr(ws), ws.numel(), _stream(stream)))
+
+
+def pm_build_vf_adjacency(mesh: Mesh, ws: Optional[torch.Tensor] = None, stream=None) -> Adjacency:
+    dev = mesh.facet.device
+    row_ptr = torch.empty(mesh.n_vert + 1, dtype=torch.int32, device=dev)
+    col = torch.empty(3 * mesh.n_facet, dtype=torch.int32, device=dev)
+    if ws is None:
+        ws = alloc_workspace(pm_workspace_bytes(PM_OP_ADJACENCY, mesh.n_vert, mesh.n_facet, 0, 0, 1, 1, PM_F32), dev)
+    m = mesh.c()
+    _check(lib().pm_build_vf_adjacency(C.byref(m), _ptr(row_ptr), C.c_void_p(col.data_ptr()), _ptr(ws), ws.numel(),
+                                       _stream(stream)))
+    return Adjacency(row_ptr, col)
+
+
+def pm_sh_basis(mesh: Mesh, L: int, norm: int = PM_SH_PAPER, stream=None) -> torch.Tensor:
+    K = (L + 1) ** 2
+    out = torch.empty((mesh.n_facet, K), dtype=torch.float32, device=mesh.facet.device)
+    m = mesh.c()
+    _check(lib().pm_sh_basis(C.byref(m), L, norm, C.c_void_p(out.data_ptr()), _stream(stream)))
+    return out
+
+
+def pm_sh_basis_dirs(dirs: torch.Tensor, L: int, norm: int = PM_SH_PAPER, stream=None) -> torch.Tensor:
+    K = (L + 1) ** 2
+    out = torch.empty((dirs.shape[0], K), dtype=torch.float32, device=dirs.device)
+    _check(lib().pm_sh_basis_dirs(dirs.shape[0], _ptr(dirs), L, norm, C.c_void_p(out.data_ptr()), _stream(stream)))
+    return out
+
+
+def pm_sh_basis_bwd(dirs: torch.Tensor, L: int, dbasis: torch.Tensor, norm: int = PM_SH_PAPER, stream=None):
+    out = torch.empty_like(dirs)
+    _check(lib().pm_sh_basis_bwd(dirs.shape[0], _ptr(dirs), L, norm, _ptr(dbasis), C.c_void_p(out.data_ptr()),
+                                 _stream(stream)))
+    return out
+
+
+def _ws(op, V, F, P, L, cin, cout, dtype, ws, dev):
+    need = pm_workspace_bytes(op, V, F, P, L, cin, cout, dtype)
+    if ws is None:
+        ws = alloc_workspace(need, dev)
+    return ws
+
+
+def pm_f2v(mesh: Mesh, adj: Adjacency, L: int, h_facet: torch.Tensor, W: torch.Tensor, dtype: int,
+           norm: int = PM_SH_PAPER, out: Optional[torch.Tensor] = None, ws: Optional[torch.Tensor] = None, stream=None):
+    K, cin, cout = W.shape
+    dev = h_facet.device
+    if out is None:
+        out = torch.empty((mesh.n_vert, cout), dtype=torch_dtype(dtype), device=dev)
+    ws = _ws(PM_OP_F2V, mesh.n_vert, mesh.n_facet, 0, L, cin, cout, dtype, ws, dev)
+    m, a = mesh.c(), adj.c()
+    _check(lib().pm_f2v(C.byref(m), C.byref(a), L, norm, cin, cout, dtype, _ptr(h_facet), _ptr(W),
+                        C.c_void_p(out.data_ptr()), _ptr(ws), ws.numel(), _stream(stream)))
+    return out
+
+
+def pm_f2v_bwd(mesh: Mesh, adj: Adjacency, L: int, h_facet, W, dg_vert, dtype: int, norm: int = PM_SH_PAPER,
+               want_dh=True, want_dW=True, dh=None, dW=None, ws=None, stream=None):
+    K, cin, cout = W.shape
+    dev = h_facet.device
+    if want_dh and dh is None:
+        dh = torch.empty((mesh.n_facet, cin), dtype=torch_dtype(dtype), device=dev)
+    if want_dW and dW is None:
+        dW = torch.empty((K, cin, cout), dtype=torch.float32, device=dev)
+    ws = _ws(PM_OP_F2V_BWD, mesh.n_vert, mesh.n_facet, 0, L, cin, cout, dtype, ws, dev)
+    m, a = mesh.c(), adj.c()
+    _check(lib().pm_f2v_bwd(C.byref(m), C.byref(a), L, norm, cin, cout, dtype, _ptr(h_facet), _ptr(W), _ptr(dg_vert),
+                            _ptr(dh) if want_dh else None, _ptr(dW) if want_dW else None, _ptr(ws), ws.numel(),
+                            _stream(stream)))
+    return (dh if want_dh else None), (dW if want_dW else None)
+
+
+def pm_v2f(mesh: Mesh, L: int, h_vert, W, dtype: int, norm: int = PM_SH_PAPER, out=None, ws=None, stream=None):
+    K, cin, cout = W.shape
+    dev = h_vert.device
+    if out is None:
+        out = torch.empty((mesh.n_facet, cout), dtype=torch_dtype(dtype), device=dev)
+    ws = _ws(PM_OP_V2F, mesh.n_vert, mesh.n_facet, 0, L, cin, cout, dtype, ws, dev)
+    m = mesh.c()
+    _check(lib().pm_v2f(C.byref(m), L, norm, cin, cout, dtype, _ptr(h_vert), _ptr(W), C.c_void_p(out.data_ptr()),
+                        _ptr(ws), ws.numel(), _stream(stream)))
+    return out
+
+
+def pm_v2f_bwd(mesh: Mesh, adj: Adjacency, L: int, h_vert, W, dg_facet, dtype: int, norm: int = PM_SH_PAPER,
+               want_dh=True, want_dW=True, dh=None, dW=None, ws=None, stream=None):
+    K, cin, cout = W.shape
+    dev = h_vert.device
+    if want_dh and dh is None:
+        dh = torch.empty((mesh.n_vert, cin), dtype=torch_dtype(dtype), device=dev)
+    if want_dW and dW is None:
+        dW = torch.empty((K, cin, cout), dtype=torch.float32, device=dev)
+    ws = _ws(PM_OP_V2F_BWD, mesh.n_vert, mesh.n_facet, 0, L, cin, cout, dtype, ws, dev)
+    m, a = mesh.c(), adj.c()
+    _check(lib().pm_v2f_bwd(C.byref(m), C.byref(a), L, norm, cin, cout, dtype, _ptr(h_vert), _ptr(W), _ptr(dg_facet),
+                            _ptr(dh) if want_dh else None, _ptr(dW) if want_dW else None, _ptr(ws), ws.numel(),
+                            _stream(stream)))
+    return (dh if want_dh else None), (dW if want_dW else None)
+
+
+def pm_f2f(tex_off: torch.Tensor, bary: torch.Tensor, L: int, h_tex, W, dtype: int, norm: int = PM_SH_PAPER, out=None,
+           ws=None, stream=None):
+    K, cin, cout = W.shape
+    F, P = int(tex_off.shape[0]) - 1, int(bary.shape[0])
+    dev = tex_off.device
+    if out is None:
+        out = torch.empty((F, cout), dtype=torch_dtype(dtype), device=dev)
+    ws = _ws(PM_OP_F2F, 0, F, P, L, cin, cout, dtype, ws, dev)
+    _check(lib().pm_f2f(F, P, _ptr(tex_off), _ptr(bary) if P else None, L, norm, cin, cout, dtype,
+                        _ptr(h_tex) if P else None, _ptr(W), C.c_void_p(out.data_ptr()), _ptr(ws), ws.numel(),
+                        _stream(stream)))
+    return out
+
+
+def pm_f2f_bwd(tex_off, bary, L: int, h_tex, W, dg_facet, dtype: int, norm: int = PM_SH_PAPER, want_dh=True,
+               want_dW=True, dh=None, dW=None, ws=None, stream=None):
+    K, cin, cout = W.shape
+    F, P = int(tex_off.shape[0]) - 1, int(bary.shape[0])
+    dev = tex_off.device
+    if want_dh and dh is None:
+        dh = torch.empty((P, cin), dtype=torch_dtype(dtype), device=dev)
+    if want_dW and dW is None:
+        dW = torch.empty((K, cin, cout), dtype=torch.float32, device=dev)
+    ws = _ws(PM_OP_F2F_BWD, 0, F, P, L, cin, cout, dtype, ws, dev)
+    _check(lib().pm_f2f_bwd(F, P, _ptr(tex_off), _ptr(bary) if P else None, L, norm, cin, cout, dtype,
+                            _ptr(h_tex) if P else None, _ptr(W), _ptr(dg_facet), _ptr(dh) if want_dh else None,
+                            _ptr(dW) if want_dW else None, _ptr(ws), ws.numel(), _stream(stream)))
+    return (dh if want_dh else None), (dW if want_dW else None)

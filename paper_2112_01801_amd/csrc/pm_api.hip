@@ -1,0 +1,390 @@
+// C ABI of picassomesh: argument checks, workspace carving, kernel sequencing.  See include/picassomesh.h.
+#include <stdarg.h>
+#include <stdio.h>
+
+#include "pm_host.h"
+
+static thread_local char g_err[512] = "";
+
+pm_status pm_fail(pm_status s, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return s;
+}
+
+extern "C" const char* pm_last_error(void) { return g_err; }
+
+extern "C" const char* pm_status_string(pm_status s) {
+  switch (s) {
+    case PM_OK: return "PM_OK";
+    case PM_ERR_INVALID_ARG: return "PM_ERR_INVALID_ARG";
+    case PM_ERR_UNSUPPORTED: return "PM_ERR_UNSUPPORTED";
+    case PM_ERR_WORKSPACE: return "PM_ERR_WORKSPACE";
+    case PM_ERR_HIP: return "PM_ERR_HIP";
+    case PM_ERR_BAD_MESH: return "PM_ERR_BAD_MESH";
+    default: return "PM_ERR_UNKNOWN";
+  }
+}
+
+#define PM_TRY(expr)                 \
+  do {                               \
+    pm_status s__ = (expr);          \
+    if (s__ != PM_OK) return s__;    \
+  } while (0)
+
+static const int64_t kMaxIds = 2147483647LL;
+
+static pm_status check_conv_common(int L, pm_sh_norm norm, int cin, int cout, pm_dtype dtype) {
+  if (L < 0 || L > PM_MAX_L) return pm_fail(PM_ERR_UNSUPPORTED, "SH degree L=%d outside [0,%d]", L, PM_MAX_L);
+  if (norm != PM_SH_PAPER && norm != PM_SH_ORTHONORMAL) return pm_fail(PM_ERR_UNSUPPORTED, "unknown pm_sh_norm %d", (int)norm);
+  if (dtype != PM_F32 && dtype != PM_BF16) return pm_fail(PM_ERR_UNSUPPORTED, "unknown pm_dtype %d", (int)dtype);
+  if (cin < 1 || cout < 1 || cin > 65536 || cout > 65536) return pm_fail(PM_ERR_INVALID_ARG, "cin=%d cout=%d", cin, cout);
+  return PM_OK;
+}
+
+static pm_status check_mesh(const pm_mesh* m, bool need_vert) {
+  if (!m) return pm_fail(PM_ERR_INVALID_ARG, "mesh is NULL");
+  if (m->n_vert < 0 || m->n_facet < 0 || m->n_mesh < 0) return pm_fail(PM_ERR_INVALID_ARG, "negative mesh size");
+  if (m->n_vert >= kMaxIds || 3 * m->n_facet >= kMaxIds) return pm_fail(PM_ERR_INVALID_ARG, "mesh exceeds int32 ids");
+  if (m->n_facet > 0 && !m->facet) return pm_fail(PM_ERR_INVALID_ARG, "mesh->facet is NULL");
+  if (need_vert && m->n_vert > 0 && !m->vert) return pm_fail(PM_ERR_INVALID_ARG, "mesh->vert is NULL");
+  return PM_OK;
+}
+
+static pm_status check_ptr(const void* p, const char* name, bool required) {
+  if (!p) return required ? pm_fail(PM_ERR_INVALID_ARG, "%s is NULL", name) : (pm_status)PM_OK;
+  if (!pm_aligned16(p)) return pm_fail(PM_ERR_INVALID_ARG, "%s is not 16-byte aligned", name);
+  return PM_OK;
+}
+
+static size_t esize(pm_dtype d) { return d == PM_BF16 ? 2 : 4; }
+
+// workspace layouts ------------------------------------------------------------------------------
+struct WsPlan {
+  size_t apack, inter, owner, small, wgrad, total;
+};
+
+static WsPlan plan_ws(pm_op op, int64_t V, int64_t F, int64_t P, int L, int cin, int cout, pm_dtype dt) {
+  (void)V;
+  const int K = (L + 1) * (L + 1);
+  WsPlan w = {0, 0, 0, 0, 0, 0};
+  switch (op) {
+    case PM_OP_ADJACENCY: w.small = pm_adj_ws_bytes(V, F); break;
+    case PM_OP_F2V:
+      w.apack = pm_pack_bytes(pm_pack_geom(K, cin, cout, dt));
+      w.inter = pm_round_up((size_t)F * cout * 4, 256);
+      break;
+    case PM_OP_F2V_BWD:
+      w.apack = pm_pack_bytes(pm_pack_geom(K, cout, cin, dt));
+      w.wgrad = pm_wgrad_ws_bytes(F, K, cin, cout);
+      break;
+    case PM_OP_V2F:
+      w.apack = pm_pack_bytes(pm_pack_geom(1, 3 * cin, cout, dt));
+      break;
+    case PM_OP_V2F_BWD:
+      w.apack = pm_pack_bytes(pm_pack_geom(1, cout, 3 * cin, dt));
+      w.inter = pm_round_up((size_t)F * 3 * cin * 4, 256);
+      w.small = pm_round_up((size_t)3 * cin * cout * 4, 256);
+      w.wgrad = pm_wgrad_ws_bytes(F, 3, cin, cout);
+      break;
+    case PM_OP_F2F:
+      w.apack = pm_pack_bytes(pm_pack_geom(K, cin, cout, dt));
+      w.inter = pm_round_up((size_t)P * cout * 4, 256);
+      break;
+    case PM_OP_F2F_BWD:
+      w.apack = pm_pack_bytes(pm_pack_geom(K, cout, cin, dt));
+      w.owner = pm_round_up((size_t)(P + 1) * 4, 256);
+      w.wgrad = pm_wgrad_ws_bytes(P, K, cin, cout);
+      break;
+  }
+  w.total = w.apack + w.inter + w.owner + w.small + w.wgrad;
+  if (w.total == 0) w.total = 256;
+  return w;
+}
+
+extern "C" size_t pm_workspace_bytes(pm_op op, int64_t n_vert, int64_t n_facet, int64_t n_tex, int L, int cin, int cout,
+                                     pm_dtype dtype) {
+  if (op < PM_OP_ADJACENCY || op > PM_OP_F2F_BWD) return 0;
+  if (n_vert < 0 || n_facet < 0 || n_tex < 0) return 0;
+  if (op != PM_OP_ADJACENCY && check_conv_common(L, PM_SH_PAPER, cin, cout, dtype) != PM_OK) return 0;
+  if (op == PM_OP_ADJACENCY) { L = 0; cin = cout = 1; dtype = PM_F32; }
+  return plan_ws(op, n_vert, n_facet, n_tex, L, cin, cout, dtype).total;
+}
+
+static pm_status check_ws(const WsPlan& w, void* ws, size_t ws_bytes) {
+  PM_TRY(check_ptr(ws, "ws", true));
+  if (ws_bytes < w.total) return pm_fail(PM_ERR_WORKSPACE, "workspace %zu < required %zu bytes", ws_bytes, w.total);
+  return PM_OK;
+}
+
+// ---- mesh utilities ----------------------------------------------------------------------------
+extern "C" pm_status pm_validate_mesh(const pm_mesh* mesh, void* ws, size_t ws_bytes, void* stream) {
+  PM_TRY(check_mesh(mesh, false));
+  PM_TRY(check_ptr(ws, "ws", true));
+  if (ws_bytes < 16) return pm_fail(PM_ERR_WORKSPACE, "validate needs 16 bytes of workspace");
+  if (mesh->n_mesh > 1 && (!mesh->vert_off || !mesh->facet_off))
+    return pm_fail(PM_ERR_INVALID_ARG, "n_mesh > 1 needs vert_off and facet_off");
+  hipStream_t st = (hipStream_t)stream;
+  PM_TRY(pm_launch_validate(mesh, (int32_t*)ws, st));
+  int32_t flag = 0;
+  PM_CHECK_HIP(hipMemcpyAsync(&flag, ws, sizeof(flag), hipMemcpyDeviceToHost, st));
+  PM_CHECK_HIP(hipStreamSynchronize(st));
+  if (flag & 2) return pm_fail(PM_ERR_BAD_MESH, "offset arrays are not monotone or do not span the batch");
+  if (flag & 1) return pm_fail(PM_ERR_BAD_MESH, "a facet references a vertex outside its mesh");
+  return PM_OK;
+}
+
+extern "C" pm_status pm_build_vf_adjacency(const pm_mesh* mesh, int32_t* row_ptr, int32_t* col, void* ws,
+                                           size_t ws_bytes, void* stream) {
+  PM_TRY(check_mesh(mesh, false));
+  if (!row_ptr || (mesh->n_facet > 0 && !col)) return pm_fail(PM_ERR_INVALID_ARG, "row_ptr / col is NULL");
+  WsPlan w = plan_ws(PM_OP_ADJACENCY, mesh->n_vert, mesh->n_facet, 0, 0, 1, 1, PM_F32);
+  PM_TRY(check_ws(w, ws, ws_bytes));
+  return pm_launch_adjacency(mesh, row_ptr, col, ws, (hipStream_t)stream);
+}
+
+// ---- basis -------------------------------------------------------------------------------------
+extern "C" pm_status pm_sh_basis(const pm_mesh* mesh, int L, pm_sh_norm norm, float* basis, void* stream) {
+  PM_TRY(check_conv_common(L, norm, 1, 1, PM_F32));
+  PM_TRY(check_mesh(mesh, true));
+  if (mesh->n_facet > 0 && !basis) return pm_fail(PM_ERR_INVALID_ARG, "basis is NULL");
+  ShTable T;
+  pm_make_sh_table(L, norm, &T);
+  return pm_launch_basis_mesh(mesh, T, basis, (hipStream_t)stream);
+}
+
+extern "C" pm_status pm_sh_basis_dirs(int64_t n, const float* dirs, int L, pm_sh_norm norm, float* basis, void* stream) {
+  PM_TRY(check_conv_common(L, norm, 1, 1, PM_F32));
+  if (n < 0 || n >= kMaxIds) return pm_fail(PM_ERR_INVALID_ARG, "n=%lld", (long long)n);
+  if (n > 0 && (!dirs || !basis)) return pm_fail(PM_ERR_INVALID_ARG, "dirs / basis is NULL");
+  ShTable T;
+  pm_make_sh_table(L, norm, &T);
+  return pm_launch_basis_dirs(n, dirs, T, basis, (hipStream_t)stream);
+}
+
+extern "C" pm_status pm_sh_basis_bwd(int64_t n, const float* dirs, int L, pm_sh_norm norm, const float* dbasis,
+                                     float* ddirs, void* stream) {
+  PM_TRY(check_conv_common(L, norm, 1, 1, PM_F32));
+  if (n < 0 || n >= kMaxIds) return pm_fail(PM_ERR_INVALID_ARG, "n=%lld", (long long)n);
+  if (n > 0 && (!dirs || !dbasis || !ddirs)) return pm_fail(PM_ERR_INVALID_ARG, "dirs / dbasis / ddirs is NULL");
+  ShTable T;
+  pm_make_sh_table(L, norm, &T);
+  return pm_launch_basis_bwd(n, dirs, T, dbasis, ddirs, (hipStream_t)stream);
+}
+
+// ---- helpers to describe operand rows ------------------------------------------------------------
+static RowSrc row_src(const void* p, pm_dtype dt, int C) {
+  RowSrc s;
+  s.p = p; s.is_bf16 = (dt == PM_BF16); s.C = C;
+  s.facet = nullptr; s.row_ptr = nullptr; s.owner = nullptr; s.seg_off = nullptr;
+  return s;
+}
+static BasisSrc basis_none() {
+  BasisSrc b;
+  b.vert = nullptr; b.facet = nullptr; b.dirs = nullptr; b.owner = nullptr; b.seg_off = nullptr;
+  pm_make_sh_table(0, PM_SH_PAPER, &b.sh);
+  return b;
+}
+static void fold_coef(int L, pm_sh_norm norm, FoldCoef* fc) {
+  double Bc[3][PM_MAX_K];
+  pm_corner_basis(L, norm, Bc);
+  const int K = (L + 1) * (L + 1);
+  for (int j = 0; j < 3; ++j)
+    for (int k = 0; k < PM_MAX_K; ++k) fc->c[j][k] = (k < K) ? (float)Bc[j][k] : 0.f;
+}
+
+// ---- facet2vertex (Eq. 5) ------------------------------------------------------------------------
+extern "C" pm_status pm_f2v(const pm_mesh* mesh, const pm_vf_adj* adj, int L, pm_sh_norm norm, int cin, int cout,
+                            pm_dtype dtype, const void* h_facet, const void* W, void* g_vert, void* ws, size_t ws_bytes,
+                            void* stream) {
+  PM_TRY(check_conv_common(L, norm, cin, cout, dtype));
+  PM_TRY(check_mesh(mesh, true));
+  if (!adj || !adj->row_ptr || (mesh->n_facet > 0 && !adj->col)) return pm_fail(PM_ERR_INVALID_ARG, "adjacency is NULL");
+  PM_TRY(check_ptr(W, "W", true));
+  PM_TRY(check_ptr(h_facet, "h_facet", mesh->n_facet > 0));
+  PM_TRY(check_ptr(g_vert, "g_vert", mesh->n_vert > 0));
+  const int K = (L + 1) * (L + 1);
+  const int64_t V = mesh->n_vert, F = mesh->n_facet;
+  WsPlan w = plan_ws(PM_OP_F2V, V, F, 0, L, cin, cout, dtype);
+  PM_TRY(check_ws(w, ws, ws_bytes));
+  hipStream_t st = (hipStream_t)stream;
+  char* apack = (char*)ws;
+  float* y = (float*)(apack + w.apack);
+
+  PM_TRY(pm_launch_pack(PACK_PLAIN, dtype, K, cin, cout, W, nullptr, apack, st));
+  BasisSrc bs = basis_none();
+  bs.vert = mesh->vert; bs.facet = mesh->facet;
+  pm_make_sh_table(L, norm, &bs.sh);
+  RowSrc xs = row_src(h_facet, dtype, cin);
+  PM_TRY(pm_launch_conv_rows(dtype, B_NORMAL, X_DIRECT, F, K, cin, cout, bs, xs, apack, y, 0, st));
+  return pm_launch_segreduce(V, cout, y, adj->row_ptr, adj->col, 3, 1, g_vert, dtype == PM_BF16, st);
+}
+
+extern "C" pm_status pm_f2v_bwd(const pm_mesh* mesh, const pm_vf_adj* adj, int L, pm_sh_norm norm, int cin, int cout,
+                                pm_dtype dtype, const void* h_facet, const void* W, const void* dg_vert, void* dh_facet,
+                                float* dW, void* ws, size_t ws_bytes, void* stream) {
+  PM_TRY(check_conv_common(L, norm, cin, cout, dtype));
+  PM_TRY(check_mesh(mesh, true));
+  if (!adj || !adj->row_ptr) return pm_fail(PM_ERR_INVALID_ARG, "adjacency is NULL");
+  PM_TRY(check_ptr(W, "W", true));
+  PM_TRY(check_ptr(h_facet, "h_facet", mesh->n_facet > 0));
+  PM_TRY(check_ptr(dg_vert, "dg_vert", mesh->n_vert > 0));
+  PM_TRY(check_ptr(dh_facet, "dh_facet", false));
+  PM_TRY(check_ptr(dW, "dW", false));
+  const int K = (L + 1) * (L + 1);
+  const int64_t V = mesh->n_vert, F = mesh->n_facet;
+  WsPlan w = plan_ws(PM_OP_F2V_BWD, V, F, 0, L, cin, cout, dtype);
+  PM_TRY(check_ws(w, ws, ws_bytes));
+  hipStream_t st = (hipStream_t)stream;
+  char* apack = (char*)ws;
+  void* wg = apack + w.apack;
+
+  BasisSrc bs = basis_none();
+  bs.vert = mesh->vert; bs.facet = mesh->facet;
+  pm_make_sh_table(L, norm, &bs.sh);
+  RowSrc dys = row_src(dg_vert, dtype, cout);   // dy_f = sum_j dg[v_j] / deg(v_j)
+  dys.facet = mesh->facet; dys.row_ptr = adj->row_ptr;
+  if (dh_facet) {
+    PM_TRY(pm_launch_pack(PACK_TRANS, dtype, K, cin, cout, W, nullptr, apack, st));
+    PM_TRY(pm_launch_conv_rows(dtype, B_NORMAL, X_GATHER_SUM, F, K, cout, cin, bs, dys, apack, dh_facet,
+                               dtype == PM_BF16, st));
+  }
+  if (dW) {
+    RowSrc xs = row_src(h_facet, dtype, cin);
+    PM_TRY(pm_launch_wgrad(dtype, B_NORMAL, X_DIRECT, X_GATHER_SUM, F, K, cin, cout, bs, xs, dys, dW, wg, w.wgrad, st));
+  }
+  return PM_OK;
+}
+
+// ---- vertex2facet (Eq. 6) ------------------------------------------------------------------------
+extern "C" pm_status pm_v2f(const pm_mesh* mesh, int L, pm_sh_norm norm, int cin, int cout, pm_dtype dtype,
+                            const void* h_vert, const void* W, void* g_facet, void* ws, size_t ws_bytes, void* stream) {
+  PM_TRY(check_conv_common(L, norm, cin, cout, dtype));
+  PM_TRY(check_mesh(mesh, false));
+  PM_TRY(check_ptr(W, "W", true));
+  PM_TRY(check_ptr(h_vert, "h_vert", mesh->n_vert > 0));
+  PM_TRY(check_ptr(g_facet, "g_facet", mesh->n_facet > 0));
+  const int K = (L + 1) * (L + 1);
+  const int64_t V = mesh->n_vert, F = mesh->n_facet;
+  WsPlan w = plan_ws(PM_OP_V2F, V, F, 0, L, cin, cout, dtype);
+  PM_TRY(check_ws(w, ws, ws_bytes));
+  hipStream_t st = (hipStream_t)stream;
+  FoldCoef fc;
+  fold_coef(L, norm, &fc);
+  // the three corner directions are constants => three folded cin x cout matrices W_j = sum_k B_k(e_j) W[k]
+  PM_TRY(pm_launch_pack(PACK_FOLD, dtype, K, cin, cout, W, &fc, ws, st));
+  RowSrc xs = row_src(h_vert, dtype, cin);
+  xs.facet = mesh->facet;
+  return pm_launch_conv_rows(dtype, B_ONE, X_GATHER_CAT, F, 1, 3 * cin, cout, basis_none(), xs, ws, g_facet,
+                             dtype == PM_BF16, st);
+}
+
+extern "C" pm_status pm_v2f_bwd(const pm_mesh* mesh, const pm_vf_adj* adj, int L, pm_sh_norm norm, int cin, int cout,
+                                pm_dtype dtype, const void* h_vert, const void* W, const void* dg_facet, void* dh_vert,
+                                float* dW, void* ws, size_t ws_bytes, void* stream) {
+  PM_TRY(check_conv_common(L, norm, cin, cout, dtype));
+  PM_TRY(check_mesh(mesh, false));
+  PM_TRY(check_ptr(W, "W", true));
+  PM_TRY(check_ptr(h_vert, "h_vert", mesh->n_vert > 0));
+  PM_TRY(check_ptr(dg_facet, "dg_facet", mesh->n_facet > 0));
+  PM_TRY(check_ptr(dh_vert, "dh_vert", false));
+  PM_TRY(check_ptr(dW, "dW", false));
+  if (dh_vert && (!adj || !adj->row_ptr || (mesh->n_facet > 0 && !adj->col)))
+    return pm_fail(PM_ERR_INVALID_ARG, "dh_vert needs the adjacency");
+  const int K = (L + 1) * (L + 1);
+  const int64_t V = mesh->n_vert, F = mesh->n_facet;
+  WsPlan w = plan_ws(PM_OP_V2F_BWD, V, F, 0, L, cin, cout, dtype);
+  PM_TRY(check_ws(w, ws, ws_bytes));
+  hipStream_t st = (hipStream_t)stream;
+  char* apack = (char*)ws;
+  float* dz = (float*)(apack + w.apack);               // [F][3][cin] per-corner input gradients
+  float* M = (float*)((char*)dz + w.inter);            // [3][cin][cout]
+  void* wg = (char*)M + w.small;
+  FoldCoef fc;
+  fold_coef(L, norm, &fc);
+  if (dh_vert) {
+    PM_TRY(pm_launch_pack(PACK_FOLD_TRANS, dtype, K, cin, cout, W, &fc, apack, st));
+    RowSrc xs = row_src(dg_facet, dtype, cout);
+    PM_TRY(pm_launch_conv_rows(dtype, B_ONE, X_DIRECT, F, 1, cout, 3 * cin, basis_none(), xs, apack, dz, 0, st));
+    // row 3f+j of dz is exactly corner slot 3f+j of the adjacency
+    PM_TRY(pm_launch_segreduce(V, cin, dz, adj->row_ptr, adj->col, 1, 0, dh_vert, dtype == PM_BF16, st));
+  }
+  if (dW) {
+    RowSrc xs = row_src(h_vert, dtype, cin);
+    xs.facet = mesh->facet;
+    RowSrc ys = row_src(dg_facet, dtype, cout);
+    PM_TRY(pm_launch_wgrad(dtype, B_ONE, X_GATHER_CAT, X_DIRECT, F, 3, cin, cout, basis_none(), xs, ys, M, wg, w.wgrad,
+                           st));
+    PM_TRY(pm_launch_unfold(K, cin, cout, M, &fc, dW, st));
+  }
+  return PM_OK;
+}
+
+// ---- facet2facet (Eq. 7) -------------------------------------------------------------------------
+static pm_status check_f2f(int64_t n_facet, int64_t n_tex, const int32_t* tex_off, const float* bary) {
+  if (n_facet < 0 || n_tex < 0 || n_facet >= kMaxIds || n_tex >= kMaxIds)
+    return pm_fail(PM_ERR_INVALID_ARG, "n_facet=%lld n_tex=%lld", (long long)n_facet, (long long)n_tex);
+  if (!tex_off) return pm_fail(PM_ERR_INVALID_ARG, "tex_off is NULL");
+  if (n_tex > 0 && !bary) return pm_fail(PM_ERR_INVALID_ARG, "bary is NULL");
+  return PM_OK;
+}
+
+extern "C" pm_status pm_f2f(int64_t n_facet, int64_t n_tex, const int32_t* tex_off, const float* bary, int L,
+                            pm_sh_norm norm, int cin, int cout, pm_dtype dtype, const void* h_tex, const void* W,
+                            void* g_facet, void* ws, size_t ws_bytes, void* stream) {
+  PM_TRY(check_conv_common(L, norm, cin, cout, dtype));
+  PM_TRY(check_f2f(n_facet, n_tex, tex_off, bary));
+  PM_TRY(check_ptr(W, "W", true));
+  PM_TRY(check_ptr(h_tex, "h_tex", n_tex > 0));
+  PM_TRY(check_ptr(g_facet, "g_facet", n_facet > 0));
+  const int K = (L + 1) * (L + 1);
+  WsPlan w = plan_ws(PM_OP_F2F, 0, n_facet, n_tex, L, cin, cout, dtype);
+  PM_TRY(check_ws(w, ws, ws_bytes));
+  hipStream_t st = (hipStream_t)stream;
+  char* apack = (char*)ws;
+  float* yp = (float*)(apack + w.apack);   // per-point summands of Eq. 7
+  PM_TRY(pm_launch_pack(PACK_PLAIN, dtype, K, cin, cout, W, nullptr, apack, st));
+  BasisSrc bs = basis_none();
+  bs.dirs = bary;
+  pm_make_sh_table(L, norm, &bs.sh);
+  RowSrc xs = row_src(h_tex, dtype, cin);
+  PM_TRY(pm_launch_conv_rows(dtype, B_DIRS, X_DIRECT, n_tex, K, cin, cout, bs, xs, apack, yp, 0, st));
+  return pm_launch_segreduce(n_facet, cout, yp, tex_off, nullptr, 1, 1, g_facet, dtype == PM_BF16, st);
+}
+
+extern "C" pm_status pm_f2f_bwd(int64_t n_facet, int64_t n_tex, const int32_t* tex_off, const float* bary, int L,
+                                pm_sh_norm norm, int cin, int cout, pm_dtype dtype, const void* h_tex, const void* W,
+                                const void* dg_facet, void* dh_tex, float* dW, void* ws, size_t ws_bytes, void* stream) {
+  PM_TRY(check_conv_common(L, norm, cin, cout, dtype));
+  PM_TRY(check_f2f(n_facet, n_tex, tex_off, bary));
+  PM_TRY(check_ptr(W, "W", true));
+  PM_TRY(check_ptr(h_tex, "h_tex", n_tex > 0));
+  PM_TRY(check_ptr(dg_facet, "dg_facet", n_facet > 0));
+  PM_TRY(check_ptr(dh_tex, "dh_tex", false));
+  PM_TRY(check_ptr(dW, "dW", false));
+  const int K = (L + 1) * (L + 1);
+  WsPlan w = plan_ws(PM_OP_F2F_BWD, 0, n_facet, n_tex, L, cin, cout, dtype);
+  PM_TRY(check_ws(w, ws, ws_bytes));
+  hipStream_t st = (hipStream_t)stream;
+  char* apack = (char*)ws;
+  int32_t* owner = (int32_t*)(apack + w.apack);
+  void* wg = (char*)owner + w.owner;
+  PM_TRY(pm_launch_owner(n_facet, tex_off, owner, st));
+  BasisSrc bs = basis_none();
+  bs.dirs = bary;
+  pm_make_sh_table(L, norm, &bs.sh);
+  RowSrc dys = row_src(dg_facet, dtype, cout);   // gradient reaching point p: dg[owner(p)] / R_owner
+  dys.owner = owner; dys.seg_off = tex_off;
+  if (dh_tex) {
+    PM_TRY(pm_launch_pack(PACK_TRANS, dtype, K, cin, cout, W, nullptr, apack, st));
+    PM_TRY(pm_launch_conv_rows(dtype, B_DIRS, X_GATHER1, n_tex, K, cout, cin, bs, dys, apack, dh_tex, dtype == PM_BF16,
+                               st));
+  }
+  if (dW) {
+    RowSrc xs = row_src(h_tex, dtype, cin);
+    PM_TRY(pm_launch_wgrad(dtype, B_DIRS, X_DIRECT, X_GATHER1, n_tex, K, cin, cout, bs, xs, dys, dW, wg, w.wgrad, st));
+  }
+  return PM_OK;
+}

@@ -1,0 +1,254 @@
+// Row-wise SH contraction on the matrix cores, weight packing, and the deterministic segmented reduction.
+//
+// conv_rows computes, for every row r (a facet or a texture point),
+//     out[r][n] = sum_k B_r[k] * ( sum_c X_r[c] * Wp[k][c][n] )
+// i.e. Eq. 5's summand F(theta_r, phi_r) h_r with dense coefficients, re-associated so that the SH
+// weighting happens on the accumulators:  U_k = Wp[k]^T x_r  is a plain GEMM (matrix cores), and
+// out = sum_k B_r[k] U_k is an fp32 FMA epilogue.  The Khatri-Rao operand B_r (x) x_r is never formed.
+//
+// The GEMM is laid out "transposed": MFMA rows = output channels n, MFMA columns = rows r.  Then every
+// lane owns ONE row r (column l%32 of the 32x32 tile) and 16 output channels, so the basis values
+// B_r[k] it multiplies with are the lane's own registers.
+//
+// Weights are pre-packed (pm_launch_pack) into the exact per-lane operand image: a "stage" is the
+// 8 KiB block for one (n-block pair, c-chunk, k); a wave reads its A fragments as 16-byte LDS loads.
+// If all stages fit in LDS they are loaded once per workgroup (which then loops over row tiles);
+// otherwise they stream through a two-slot ring, one barrier per stage.
+#include "pm_conv_kernel.h"
+
+// ------------------------------------------------------------------------------------------------
+// weight packing
+// ------------------------------------------------------------------------------------------------
+struct PackP {
+  int mode, src_bf16, dst_bf16;
+  int K, cin, cout;   // source W[K][cin][cout]
+  int Kp, Cc, Cn;     // packed logical Wp[Kp][Cc][Cn]
+  int NCH, NBG;
+  const void* W;
+  uint4* out;
+  FoldCoef fc;
+};
+
+__device__ __forceinline__ float pack_src(const PackP& p, int k, int ci, int co) {
+  int64_t o = ((int64_t)k * p.cin + ci) * p.cout + co;
+  return p.src_bf16 ? bf16_to_f32(((const uint16_t*)p.W)[o]) : ((const float*)p.W)[o];
+}
+
+// logical Wp[k][c][n]
+__device__ __forceinline__ float pack_value(const PackP& p, int k, int c, int n) {
+  if (c >= p.Cc || n >= p.Cn) return 0.f;
+  switch (p.mode) {
+    case PACK_PLAIN: return pack_src(p, k, c, n);
+    case PACK_TRANS: return pack_src(p, k, n, c);
+    case PACK_FOLD: {
+      int j = c / p.cin, ci = c - j * p.cin;
+      float s = 0.f;
+      for (int kk = 0; kk < p.K; ++kk) s += p.fc.c[j][kk] * pack_src(p, kk, ci, n);
+      return s;
+    }
+    default: {  // PACK_FOLD_TRANS
+      int j = n / p.cin, ci = n - j * p.cin;
+      float s = 0.f;
+      for (int kk = 0; kk < p.K; ++kk) s += p.fc.c[j][kk] * pack_src(p, kk, ci, c);
+      return s;
+    }
+  }
+}
+
+// one thread per (stage, nbi, g, lane) granule
+__global__ void __launch_bounds__(256) k_pack(PackP p, int64_t n_gran) {
+  int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (t >= n_gran) return;
+  const int lane = (int)(t & 63);
+  int64_t q = t >> 6;
+  const int g = (int)(q % PM_GC); q /= PM_GC;
+  const int nbi = (int)(q % PM_NBS); q /= PM_NBS;
+  const int64_t stage = q;
+  const int k = (int)(stage % p.Kp);
+  const int ch = (int)((stage / p.Kp) % p.NCH);
+  const int nbg = (int)(stage / ((int64_t)p.Kp * p.NCH));
+  const int n = (nbg * PM_NBS + nbi) * 32 + (lane & 31);
+  const int hh = lane >> 5;
+  uint4 o;
+  if (p.dst_bf16) {
+    const int c0 = (ch * PM_GC + g) * 16 + hh * 8;
+    float v[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) v[e] = pack_value(p, k, c0 + e, n);
+    o.x = pack_bf16x2(v[0], v[1]); o.y = pack_bf16x2(v[2], v[3]);
+    o.z = pack_bf16x2(v[4], v[5]); o.w = pack_bf16x2(v[6], v[7]);
+  } else {
+    const int c0 = (ch * PM_GC + g) * 8 + hh * 4;
+    o.x = __float_as_uint(pack_value(p, k, c0 + 0, n));
+    o.y = __float_as_uint(pack_value(p, k, c0 + 1, n));
+    o.z = __float_as_uint(pack_value(p, k, c0 + 2, n));
+    o.w = __float_as_uint(pack_value(p, k, c0 + 3, n));
+  }
+  p.out[t] = o;
+}
+
+pm_status pm_launch_pack(PackMode mode, pm_dtype dt, int K, int cin, int cout, const void* W, const FoldCoef* fc,
+                         void* apack, hipStream_t st) {
+  PackP p;
+  p.mode = mode; p.src_bf16 = (dt == PM_BF16); p.dst_bf16 = (dt == PM_BF16);
+  p.K = K; p.cin = cin; p.cout = cout;
+  switch (mode) {
+    case PACK_PLAIN: p.Kp = K; p.Cc = cin; p.Cn = cout; break;
+    case PACK_TRANS: p.Kp = K; p.Cc = cout; p.Cn = cin; break;
+    case PACK_FOLD: p.Kp = 1; p.Cc = 3 * cin; p.Cn = cout; break;
+    default: p.Kp = 1; p.Cc = cout; p.Cn = 3 * cin; break;
+  }
+  PackGeom g = pm_pack_geom(p.Kp, p.Cc, p.Cn, dt);
+  p.NCH = g.NCH; p.NBG = g.NBG;
+  p.W = W; p.out = (uint4*)apack;
+  if (fc) p.fc = *fc; else for (int j = 0; j < 3; ++j) for (int k = 0; k < PM_MAX_K; ++k) p.fc.c[j][k] = 0.f;
+  int64_t n_gran = g.stages * STAGE_U4;
+  hipLaunchKernelGGL(k_pack, dim3((unsigned)((n_gran + 255) / 256)), dim3(256), 0, st, p, n_gran);
+  PM_CHECK_LAUNCH("k_pack");
+  return PM_OK;
+}
+
+// ------------------------------------------------------------------------------------------------
+// conv_rows dispatch (kernels live in pm_conv_kernel.h, instantiated by pm_conv_i*.hip)
+// ------------------------------------------------------------------------------------------------
+PM_CONV_DECLARE(0, B_NORMAL, X_DIRECT)
+PM_CONV_DECLARE(0, B_NORMAL, X_GATHER_SUM)
+PM_CONV_DECLARE(0, B_DIRS, X_DIRECT)
+PM_CONV_DECLARE(0, B_DIRS, X_GATHER1)
+PM_CONV_DECLARE(0, B_ONE, X_DIRECT)
+PM_CONV_DECLARE(0, B_ONE, X_GATHER_CAT)
+PM_CONV_DECLARE(1, B_NORMAL, X_DIRECT)
+PM_CONV_DECLARE(1, B_NORMAL, X_GATHER_SUM)
+PM_CONV_DECLARE(1, B_DIRS, X_DIRECT)
+PM_CONV_DECLARE(1, B_DIRS, X_GATHER1)
+PM_CONV_DECLARE(1, B_ONE, X_DIRECT)
+PM_CONV_DECLARE(1, B_ONE, X_GATHER_CAT)
+
+// Largest weight image kept resident in LDS: 128 KiB, or less when the device offers less per workgroup.
+static size_t lds_resident_max() {
+  static int cached = -1;
+  if (cached < 0) {
+    int dev = 0, v = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&v, hipDeviceAttributeMaxSharedMemoryPerBlock, dev) != hipSuccess)
+      v = 64 * 1024;
+    cached = v;
+  }
+  size_t cap = (size_t)cached;
+  return cap < 128 * 1024 ? cap : 128 * 1024;
+}
+
+#define PM_CONV_CASE(DT, BM, XM) \
+  if (dt == DT && bm == BM && xm == XM) return pm_conv_dispatch_##DT##_##BM##_##XM(p, L, g.stages, st);
+
+pm_status pm_launch_conv_rows(pm_dtype mt, BMode bm, XMode xm, int64_t R, int K, int Cc, int Cn, const BasisSrc& bs,
+                              const RowSrc& xs, const void* apack, void* out, int out_is_bf16, hipStream_t st) {
+  if (R == 0) return PM_OK;
+  PackGeom g = pm_pack_geom(K, Cc, Cn, mt);
+  ConvP p;
+  p.R = R; p.Cc = Cc; p.Cn = Cn; p.NCH = g.NCH; p.NBG = g.NBG;
+  p.resident = pm_pack_bytes(g) <= lds_resident_max();
+  p.bs = bs; p.xs = xs; p.apack = (const uint4*)apack; p.out = out; p.out_bf16 = out_is_bf16;
+  const int L = (bm == B_ONE) ? 0 : bs.sh.L;
+  const int dt = (mt == PM_BF16) ? 1 : 0;
+  PM_CONV_CASE(0, B_NORMAL, X_DIRECT)
+  PM_CONV_CASE(0, B_NORMAL, X_GATHER_SUM)
+  PM_CONV_CASE(0, B_DIRS, X_DIRECT)
+  PM_CONV_CASE(0, B_DIRS, X_GATHER1)
+  PM_CONV_CASE(0, B_ONE, X_DIRECT)
+  PM_CONV_CASE(0, B_ONE, X_GATHER_CAT)
+  PM_CONV_CASE(1, B_NORMAL, X_DIRECT)
+  PM_CONV_CASE(1, B_NORMAL, X_GATHER_SUM)
+  PM_CONV_CASE(1, B_DIRS, X_DIRECT)
+  PM_CONV_CASE(1, B_DIRS, X_GATHER1)
+  PM_CONV_CASE(1, B_ONE, X_DIRECT)
+  PM_CONV_CASE(1, B_ONE, X_GATHER_CAT)
+  return pm_fail(PM_ERR_UNSUPPORTED, "conv_rows mode (%d,%d)", (int)bm, (int)xm);
+}
+
+// ------------------------------------------------------------------------------------------------
+// segmented reduction (facet -> vertex mean of Eq. 5; corner -> vertex sum of Eq. 6's backward;
+// texture point -> facet mean of Eq. 7).  One lane group per segment, lanes span channels, entries
+// are added in ascending order: no atomics, bitwise reproducible.
+// ------------------------------------------------------------------------------------------------
+struct SegP {
+  int64_t n_seg;
+  int C, div, mean, out_bf16, lpg;  // lpg = lanes per segment (power of two, <= 64)
+  const float* src;
+  const int32_t* row_ptr;
+  const int32_t* col;
+  void* out;
+};
+
+__global__ void __launch_bounds__(256) k_segreduce(SegP p) {
+  const int gpb = 256 / p.lpg;  // segments per block
+  const int64_t seg = (int64_t)blockIdx.x * gpb + threadIdx.x / p.lpg;
+  const int sub = threadIdx.x % p.lpg;
+  if (seg >= p.n_seg) return;
+  const int32_t b = p.row_ptr[seg], e = p.row_ptr[seg + 1];
+  const float scale = (p.mean && e > b) ? 1.0f / (float)(e - b) : 1.0f;
+  const bool vec = (p.C & 3) == 0;
+  for (int c0 = sub * 4; c0 < p.C; c0 += p.lpg * 4) {
+    float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
+    for (int32_t i = b; i < e; ++i) {
+      int64_t r = p.col ? (int64_t)(p.col[i] / p.div) : (int64_t)i;
+      const float* s = p.src + r * p.C + c0;
+      if (vec) {
+        float4 f = *(const float4*)s;
+        a0 += f.x; a1 += f.y; a2 += f.z; a3 += f.w;
+      } else {
+        a0 += s[0];
+        if (c0 + 1 < p.C) a1 += s[1];
+        if (c0 + 2 < p.C) a2 += s[2];
+        if (c0 + 3 < p.C) a3 += s[3];
+      }
+    }
+    a0 *= scale; a1 *= scale; a2 *= scale; a3 *= scale;
+    const int64_t o = seg * p.C + c0;
+    if (vec) {
+      if (p.out_bf16) {
+        uint2 w;
+        w.x = pack_bf16x2(a0, a1); w.y = pack_bf16x2(a2, a3);
+        *(uint2*)((uint16_t*)p.out + o) = w;
+      } else {
+        *(float4*)((float*)p.out + o) = make_float4(a0, a1, a2, a3);
+      }
+    } else {
+      const float vv[4] = {a0, a1, a2, a3};
+      for (int i = 0; i < 4; ++i)
+        if (c0 + i < p.C) {
+          if (p.out_bf16) ((uint16_t*)p.out)[o + i] = (uint16_t)f32_to_bf16_bits(vv[i]);
+          else ((float*)p.out)[o + i] = vv[i];
+        }
+    }
+  }
+}
+
+pm_status pm_launch_segreduce(int64_t n_seg, int C, const float* src, const int32_t* row_ptr, const int32_t* col,
+                              int div, int mean, void* out, int out_is_bf16, hipStream_t st) {
+  if (n_seg == 0) return PM_OK;
+  SegP p;
+  p.n_seg = n_seg; p.C = C; p.div = div; p.mean = mean; p.out_bf16 = out_is_bf16;
+  p.src = src; p.row_ptr = row_ptr; p.col = col; p.out = out;
+  int need = (C + 3) / 4, lpg = 1;
+  while (lpg < need && lpg < 64) lpg <<= 1;
+  p.lpg = lpg;
+  int gpb = 256 / lpg;
+  hipLaunchKernelGGL(k_segreduce, dim3((unsigned)((n_seg + gpb - 1) / gpb)), dim3(256), 0, st, p);
+  PM_CHECK_LAUNCH("k_segreduce");
+  return PM_OK;
+}
+
+// owner[p] = f for the points of facet f
+__global__ void k_owner(int64_t F, const int32_t* __restrict__ off, int32_t* __restrict__ owner) {
+  int64_t f = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (f >= F) return;
+  for (int32_t q = off[f]; q < off[f + 1]; ++q) owner[q] = (int32_t)f;
+}
+
+pm_status pm_launch_owner(int64_t n_facet, const int32_t* tex_off, int32_t* owner, hipStream_t st) {
+  if (n_facet == 0) return PM_OK;
+  hipLaunchKernelGGL(k_owner, dim3((unsigned)((n_facet + 255) / 256)), dim3(256), 0, st, n_facet, tex_off, owner);
+  PM_CHECK_LAUNCH("k_owner");
+  return PM_OK;
+}

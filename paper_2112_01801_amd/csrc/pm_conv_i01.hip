@@ -1,0 +1,3 @@
+// conv_rows instances: fp32, B_NORMAL, X_GATHER_SUM
+#include "pm_conv_kernel.h"
+PM_CONV_INSTANCE(0, B_NORMAL, X_GATHER_SUM)

@@ -1,0 +1,3 @@
+// conv_rows instances: fp32, B_DIRS, X_GATHER1
+#include "pm_conv_kernel.h"
+PM_CONV_INSTANCE(0, B_DIRS, X_GATHER1)

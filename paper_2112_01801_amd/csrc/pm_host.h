@@ -1,0 +1,115 @@
+// Host-side declarations shared by the picassomesh translation units.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "pm_device.h"
+
+// ---- error plumbing -------------------------------------------------------------------------
+pm_status pm_fail(pm_status s, const char* fmt, ...);
+#define PM_CHECK_HIP(expr)                                                                        \
+  do {                                                                                            \
+    hipError_t e__ = (expr);                                                                      \
+    if (e__ != hipSuccess) return pm_fail(PM_ERR_HIP, "%s: %s", #expr, hipGetErrorString(e__));   \
+  } while (0)
+#define PM_CHECK_LAUNCH(name)                                                                     \
+  do {                                                                                            \
+    hipError_t e__ = hipGetLastError();                                                           \
+    if (e__ != hipSuccess) return pm_fail(PM_ERR_HIP, "launch %s: %s", name, hipGetErrorString(e__)); \
+  } while (0)
+
+static inline bool pm_aligned16(const void* p) { return (((uintptr_t)p) & 15u) == 0; }
+static inline size_t pm_round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// Eq. 3 normalisation constants in double precision (times sqrt(2) for m > 0 when orthonormal).
+void pm_make_sh_table(int L, pm_sh_norm norm, ShTable* T);
+// Basis values (double) at the three corner directions of Eq. 6: Bc[j][k].
+void pm_corner_basis(int L, pm_sh_norm norm, double Bc[3][PM_MAX_K]);
+
+// ---- tiling constants of the MFMA kernels -----------------------------------------------------
+// A "granule" is the 16 bytes one lane feeds to the matrix core for one c-group:
+//   bf16: 8 contraction channels (one 32x32x16 MFMA covers a group of 16 = 2 half-waves x 8)
+//   fp32: 4 contraction channels (four 32x32x2 MFMAs cover a group of 8 = 2 half-waves x 4)
+#define PM_GC 4   /* c-groups per chunk held in registers            */
+#define PM_NBS 2  /* 32-wide output-channel blocks per weight stage  */
+static inline int pm_group_c(pm_dtype dt) { return dt == PM_BF16 ? 16 : 8; }
+static inline int pm_chunk_c(pm_dtype dt) { return PM_GC * pm_group_c(dt); }
+#define PM_STAGE_BYTES (PM_NBS * PM_GC * 64 * 16)
+
+struct PackGeom {
+  int K, Cc, Cn;   // logical sizes of Wp[k][c][n]
+  int NCH;         // c-chunks
+  int NBG;         // groups of PM_NBS output blocks
+  int64_t stages;  // NBG * NCH * K
+};
+static inline PackGeom pm_pack_geom(int K, int Cc, int Cn, pm_dtype dt) {
+  PackGeom g;
+  g.K = K; g.Cc = Cc; g.Cn = Cn;
+  g.NCH = (Cc + pm_chunk_c(dt) - 1) / pm_chunk_c(dt);
+  g.NBG = (Cn + 32 * PM_NBS - 1) / (32 * PM_NBS);
+  g.stages = (int64_t)g.NBG * g.NCH * K;
+  return g;
+}
+static inline size_t pm_pack_bytes(const PackGeom& g) { return (size_t)g.stages * PM_STAGE_BYTES; }
+
+// ---- kernel launchers (each enqueues on `st`, returns PM_OK or PM_ERR_HIP) ----------------------
+enum PackMode { PACK_PLAIN = 0, PACK_TRANS = 1, PACK_FOLD = 2, PACK_FOLD_TRANS = 3 };
+struct FoldCoef { float c[3][PM_MAX_K]; };
+// Builds the MFMA operand image of Wp[k][c][n] from W[K][cin][cout] (src dtype = dt):
+//   PLAIN: Wp[k][ci][co] = W[k][ci][co]          TRANS: Wp[k][co][ci] = W[k][ci][co]
+//   FOLD:  Wp[0][j*cin+ci][co] = sum_k fc[j][k] W[k][ci][co]    FOLD_TRANS: Wp[0][co][j*cin+ci] = same
+pm_status pm_launch_pack(PackMode mode, pm_dtype dt, int K, int cin, int cout, const void* W, const FoldCoef* fc,
+                         void* apack, hipStream_t st);
+
+enum BMode { B_ONE = 0, B_NORMAL = 1, B_DIRS = 2 };
+enum XMode { X_DIRECT = 0, X_GATHER_SUM = 1, X_GATHER_CAT = 2, X_GATHER1 = 3 };
+
+// Source of one operand row set for the row-wise kernels.
+struct RowSrc {
+  const void* p;            // matrix [*, C] of the source dtype
+  int is_bf16;              // 1: bf16 storage, 0: fp32
+  int C;                    // channels per source row
+  const int32_t* facet;     // [R,3]  X_GATHER_SUM / X_GATHER_CAT: rows gathered through the corner ids
+  const int32_t* row_ptr;   // X_GATHER_SUM: each gathered row is divided by deg(v) = row_ptr[v+1]-row_ptr[v]
+  const int32_t* owner;     // X_GATHER1: source row = owner[r]
+  const int32_t* seg_off;   // X_GATHER1: scale = 1 / (seg_off[o+1] - seg_off[o])
+};
+
+struct BasisSrc {
+  const float* vert;        // B_NORMAL
+  const int32_t* facet;     // B_NORMAL: [R,3]
+  const float* dirs;        // B_DIRS: [R,3]
+  const int32_t* owner;     // optional (B_DIRS): basis scaled by 1/(seg_off[o+1]-seg_off[o]) -- unused when NULL
+  const int32_t* seg_off;
+  ShTable sh;
+};
+
+// out[r][n] = sum_k B_r[k] sum_c X_r[c] Wp[k][c][n]      (B_ONE: K = 1, B = 1)
+pm_status pm_launch_conv_rows(pm_dtype mt, BMode bm, XMode xm, int64_t R, int K, int Cc, int Cn, const BasisSrc& bs,
+                              const RowSrc& xs, const void* apack, void* out, int out_is_bf16, hipStream_t st);
+
+// out[v][c] = scale_v * sum_{e in [row_ptr[v], row_ptr[v+1])} src[(col ? col[e] : e) / div][c]
+// scale_v = 1/deg (mean != 0) or 1.  src is fp32.
+pm_status pm_launch_segreduce(int64_t n_seg, int C, const float* src, const int32_t* row_ptr, const int32_t* col,
+                              int div, int mean, void* out, int out_is_bf16, hipStream_t st);
+
+// dWp[k][c][n] = sum_r B_r[k] X_r[c] Y_r[n], fp32, deterministic (per-workgroup partials + fixed-order sum).
+// X_GATHER_CAT here means: k indexes the corner, X^{(k)}_r = xs.p[facet[r][k]] (K must be 3, B_ONE).
+size_t pm_wgrad_ws_bytes(int64_t R, int K, int Cc, int Cn);
+pm_status pm_launch_wgrad(pm_dtype mt, BMode bm, XMode xm, XMode ym, int64_t R, int K, int Cc, int Cn,
+                          const BasisSrc& bs, const RowSrc& xs, const RowSrc& ys, float* dWp, void* ws, size_t ws_bytes,
+                          hipStream_t st);
+// dW[k][ci][co] = sum_j fc[j][k] M[j][ci][co]
+pm_status pm_launch_unfold(int K, int cin, int cout, const float* M, const FoldCoef* fc, float* dW, hipStream_t st);
+// owner[p] = f for p in [tex_off[f], tex_off[f+1])
+pm_status pm_launch_owner(int64_t n_facet, const int32_t* tex_off, int32_t* owner, hipStream_t st);
+
+pm_status pm_launch_basis_mesh(const pm_mesh* mesh, const ShTable& T, float* basis, hipStream_t st);
+pm_status pm_launch_basis_dirs(int64_t n, const float* dirs, const ShTable& T, float* basis, hipStream_t st);
+pm_status pm_launch_basis_bwd(int64_t n, const float* dirs, const ShTable& T, const float* dbasis, float* ddirs,
+                              hipStream_t st);
+
+size_t pm_adj_ws_bytes(int64_t n_vert, int64_t n_facet);
+pm_status pm_launch_adjacency(const pm_mesh* mesh, int32_t* row_ptr, int32_t* col, void* ws, hipStream_t st);
+pm_status pm_launch_validate(const pm_mesh* mesh, int32_t* flag, hipStream_t st);

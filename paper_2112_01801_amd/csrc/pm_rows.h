@@ -1,0 +1,144 @@
+// Row loaders shared by the row-wise MFMA kernels: how one operand row (a facet, a texture point) gets
+// its channels, its basis vector and its gather metadata.
+#pragma once
+#include "pm_host.h"
+
+// elements [c0, c0+N) of row `row` of a [*, C] matrix (bf16 or fp32 storage) as floats; zero beyond C
+template <int N>
+__device__ __forceinline__ void load_vals(const void* __restrict__ base, int is_bf16, int64_t row, int C, int c0,
+                                          float (&v)[N]) {
+  const int64_t off = row * (int64_t)C + c0;
+  if (c0 + N <= C) {
+    if (is_bf16) {
+      const uint16_t* p = (const uint16_t*)base + off;
+      if ((((uintptr_t)p) & (2 * N - 1)) == 0) {
+        if constexpr (N == 8) {
+          uint4 u = *(const uint4*)p;
+          v[0] = bf16lo_to_f32(u.x); v[1] = bf16hi_to_f32(u.x);
+          v[2] = bf16lo_to_f32(u.y); v[3] = bf16hi_to_f32(u.y);
+          v[4] = bf16lo_to_f32(u.z); v[5] = bf16hi_to_f32(u.z);
+          v[6] = bf16lo_to_f32(u.w); v[7] = bf16hi_to_f32(u.w);
+        } else {
+          uint2 u = *(const uint2*)p;
+          v[0] = bf16lo_to_f32(u.x); v[1] = bf16hi_to_f32(u.x);
+          v[2] = bf16lo_to_f32(u.y); v[3] = bf16hi_to_f32(u.y);
+        }
+      } else {
+#pragma unroll
+        for (int i = 0; i < N; ++i) v[i] = bf16_to_f32(p[i]);
+      }
+    } else {
+      const float* p = (const float*)base + off;
+      if ((((uintptr_t)p) & 15) == 0) {
+#pragma unroll
+        for (int q = 0; q < N / 4; ++q) {
+          float4 f = ((const float4*)p)[q];
+          v[4 * q] = f.x; v[4 * q + 1] = f.y; v[4 * q + 2] = f.z; v[4 * q + 3] = f.w;
+        }
+      } else {
+#pragma unroll
+        for (int i = 0; i < N; ++i) v[i] = p[i];
+      }
+    }
+  } else {
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+      float x = 0.f;
+      if (c0 + i < C) x = is_bf16 ? bf16_to_f32(((const uint16_t*)base)[off + i]) : ((const float*)base)[off + i];
+      v[i] = x;
+    }
+  }
+}
+
+// Gather metadata of one row, loaded once per tile.
+struct RowMeta {
+  int32_t id[3];  // X_GATHER_SUM / X_GATHER_CAT: corner vertex ids;  X_GATHER1: id[0] = owner
+  float w[3];     // X_GATHER_SUM: 1/deg(v_j);  X_GATHER1: w[0] = 1/segment length
+};
+
+template <int XM>
+__device__ __forceinline__ void load_meta(const RowSrc& s, int64_t r, bool valid, RowMeta& m) {
+  m.id[0] = m.id[1] = m.id[2] = 0;
+  m.w[0] = m.w[1] = m.w[2] = 0.f;
+  if (!valid) return;
+  if constexpr (XM == X_GATHER_SUM || XM == X_GATHER_CAT) {
+#pragma unroll
+    for (int j = 0; j < 3; ++j) m.id[j] = s.facet[3 * r + j];
+    if constexpr (XM == X_GATHER_SUM) {
+#pragma unroll
+      for (int j = 0; j < 3; ++j) {
+        int32_t d = s.row_ptr[m.id[j] + 1] - s.row_ptr[m.id[j]];
+        m.w[j] = 1.0f / (float)d;  // d >= 1: the vertex is referenced by this very facet
+      }
+    }
+  } else if constexpr (XM == X_GATHER1) {
+    int32_t o = s.owner[r];
+    m.id[0] = o;
+    m.w[0] = 1.0f / (float)(s.seg_off[o + 1] - s.seg_off[o]);
+  }
+}
+
+// N consecutive channels [c0, c0+N) of the (virtual) operand row r, as floats.
+//   X_DIRECT:      src[r][c]
+//   X_GATHER_SUM:  sum_j src[v_j(r)][c] / deg(v_j(r))            (transposed facet->vertex mean)
+//   X_GATHER_CAT:  concatenation over the three corners, channel c = j*C + cc -> src[v_j(r)][cc]
+//   X_GATHER1:     src[owner(r)][c] / segment length             (transposed segment mean)
+template <int XM, int N>
+__device__ __forceinline__ void fetch_vals(const RowSrc& s, int64_t r, bool valid, const RowMeta& m, int c0,
+                                           float (&v)[N]) {
+  if (!valid) {
+#pragma unroll
+    for (int i = 0; i < N; ++i) v[i] = 0.f;
+    return;
+  }
+  if constexpr (XM == X_DIRECT) {
+    load_vals<N>(s.p, s.is_bf16, r, s.C, c0, v);
+  } else if constexpr (XM == X_GATHER_SUM) {
+    float t[N];
+    load_vals<N>(s.p, s.is_bf16, m.id[0], s.C, c0, t);
+#pragma unroll
+    for (int i = 0; i < N; ++i) v[i] = t[i] * m.w[0];
+    load_vals<N>(s.p, s.is_bf16, m.id[1], s.C, c0, t);
+#pragma unroll
+    for (int i = 0; i < N; ++i) v[i] += t[i] * m.w[1];
+    load_vals<N>(s.p, s.is_bf16, m.id[2], s.C, c0, t);
+#pragma unroll
+    for (int i = 0; i < N; ++i) v[i] += t[i] * m.w[2];
+  } else if constexpr (XM == X_GATHER_CAT) {
+    const int C = s.C;
+    int j = c0 / C, cc = c0 - j * C;
+    if (j < 3 && cc + N <= C) {
+      int32_t id = (j == 0) ? m.id[0] : (j == 1 ? m.id[1] : m.id[2]);
+      load_vals<N>(s.p, s.is_bf16, id, C, cc, v);
+    } else {
+#pragma unroll
+      for (int i = 0; i < N; ++i) {
+        int c = c0 + i;
+        int jj = c / C, ci = c - jj * C;
+        float x = 0.f;
+        if (jj < 3) {
+          int32_t id = (jj == 0) ? m.id[0] : (jj == 1 ? m.id[1] : m.id[2]);
+          int64_t o = (int64_t)id * C + ci;
+          x = s.is_bf16 ? bf16_to_f32(((const uint16_t*)s.p)[o]) : ((const float*)s.p)[o];
+        }
+        v[i] = x;
+      }
+    }
+  } else {  // X_GATHER1
+    load_vals<N>(s.p, s.is_bf16, m.id[0], s.C, c0, v);
+#pragma unroll
+    for (int i = 0; i < N; ++i) v[i] *= m.w[0];
+  }
+}
+
+// Unit direction whose SH basis weights row r: the facet normal (Eq. 5) or a given direction (Eq. 7's
+// barycentric point projected radially onto the sphere).
+template <int BM>
+__device__ __forceinline__ void row_direction(const BasisSrc& b, int64_t r, float& x, float& y, float& z) {
+  if constexpr (BM == B_NORMAL) {
+    facet_normal(b.vert, b.facet[3 * r], b.facet[3 * r + 1], b.facet[3 * r + 2], x, y, z);
+  } else {
+    x = b.dirs[3 * r]; y = b.dirs[3 * r + 1]; z = b.dirs[3 * r + 2];
+    normalize_dir(x, y, z);
+  }
+}

@@ -1,0 +1,338 @@
+// Gradient with respect to the dense filter coefficients:
+//     dWp[k][c][n] = sum_r B_r[k] * X_r[c] * Y_r[n]
+// (F2V: r = facet, X = h_f, Y = dy_f gathered from the vertex gradients; V2F: k = corner, X = h of that
+// corner's vertex, Y = dg_f; F2F: r = texture point, X = h_p, Y = dg of the owning facet / R_f.)
+//
+// This is a GEMM whose contraction runs over rows r.  Row tiles of 64 are staged in LDS TRANSPOSED
+// (channel-major, rows contiguous) so that an MFMA operand fragment -- 8 consecutive rows of one
+// channel -- is a single 16-byte LDS read.  The basis weighting multiplies the Y fragment in fp32
+// before it is packed (the one place where a per-row product has to be formed explicitly).
+//
+// A workgroup (8 waves) owns a 64x64 (c,n) slab for up to 16 values of k: each wave accumulates two k's
+// (8 accumulator blocks of 32x32); when there are fewer than 8 k-pairs the spare waves split the rows
+// of every tile instead.  Each workgroup covers a fixed contiguous range of rows and writes its partial
+// sums to its own slice of a workspace; a second kernel adds the slices in a fixed order, so the result
+// is bitwise reproducible and uses no floating-point atomics.
+#include "pm_rows.h"
+
+#define WG_RT 64          /* rows per staged tile */
+#define WG_KG 16          /* k values per workgroup */
+#define XP_BF16 72        /* LDS pitch of a channel row, bf16 elements (144 B) */
+#define XP_F32 68         /* LDS pitch, fp32 elements (272 B) */
+
+struct WgradP {
+  int64_t R, rows_per_part;
+  int K, Cc, Cn;
+  int KGn, CBP, NBP;   // slab decomposition
+  int NKPW, RS;        // k-pairs per workgroup, row splits
+  BasisSrc bs;
+  RowSrc xs, ys;
+  float* partial;      // [n_part * RS][K][Cc][Cn]
+};
+
+template <int DT, int BM, int XM, int YM>
+__global__ void __launch_bounds__(512) k_wgrad(WgradP p) {
+  extern __shared__ uint4 lds_raw[];
+  constexpr int NSUBX = (XM == X_GATHER_CAT) ? 3 : 1;  // one X tile per corner
+  constexpr int XPB = (DT == 1) ? XP_BF16 * 2 : XP_F32 * 4;  // bytes per channel row of XT
+  char* lds = (char*)lds_raw;
+  char* XT = lds;                                   // [NSUBX][64][XPB]
+  float* YT = (float*)(lds + NSUBX * 64 * XPB);     // [64][XP_F32]
+  float* Bs = YT + 64 * XP_F32;                     // [WG_KG][XP_F32]
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, hh = lane >> 5;
+  const int slab = blockIdx.y;
+  const int kg = slab % p.KGn, cbp = (slab / p.KGn) % p.CBP, nbp = slab / (p.KGn * p.CBP);
+  const int kbase = kg * WG_KG;
+  const int kcount = min(WG_KG, p.K - kbase);
+  const int kp = wave % p.NKPW, rs = wave / p.NKPW;
+  const bool active = (rs < p.RS) && (2 * kp < kcount);
+  const bool kv[2] = {active, active && (2 * kp + 1 < kcount)};
+  const int cbase = cbp * 64, nbase = nbp * 64;
+
+  floatx16 acc[2][2][2];  // [kk][cb][nb]
+#pragma unroll
+  for (int a = 0; a < 2; ++a)
+#pragma unroll
+    for (int b = 0; b < 2; ++b)
+#pragma unroll
+      for (int c = 0; c < 2; ++c)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[a][b][c][i] = 0.f;
+
+  const int64_t rbeg = (int64_t)blockIdx.x * p.rows_per_part;
+  const int64_t rend = min(p.R, rbeg + p.rows_per_part);
+  // staging role of this thread: row tid/8 of the tile, channels 8*(tid%8) .. +7 of the slab
+  const int srow = tid >> 3, soct = tid & 7;
+
+  for (int64_t t0 = rbeg; t0 < rend; t0 += WG_RT) {
+    const int64_t r = t0 + srow;
+    const bool ok = r < rend;
+    // ---- stage X (transposed) ----
+    {
+      RowMeta m;
+      load_meta<XM>(p.xs, r, ok, m);
+#pragma unroll
+      for (int sub = 0; sub < NSUBX; ++sub) {
+        float v[8];
+        if constexpr (XM == X_GATHER_CAT) {
+          if (ok) load_vals<8>(p.xs.p, p.xs.is_bf16, m.id[sub], p.xs.C, cbase + soct * 8, v);
+          else
+#pragma unroll
+            for (int i = 0; i < 8; ++i) v[i] = 0.f;
+        } else {
+          fetch_vals<XM, 8>(p.xs, r, ok, m, cbase + soct * 8, v);
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          char* dst = XT + (sub * 64 + soct * 8 + i) * XPB;
+          if constexpr (DT == 1) ((uint16_t*)dst)[srow] = (uint16_t)f32_to_bf16_bits(v[i]);
+          else ((float*)dst)[srow] = v[i];
+        }
+      }
+    }
+    // ---- stage Y (transposed, fp32) ----
+    {
+      RowMeta m;
+      load_meta<YM>(p.ys, r, ok, m);
+      float v[8];
+      fetch_vals<YM, 8>(p.ys, r, ok, m, nbase + soct * 8, v);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) YT[(soct * 8 + i) * XP_F32 + srow] = v[i];
+    }
+    // ---- stage the basis values of this workgroup's k range ----
+    if constexpr (BM != B_ONE) {
+      if (tid < WG_RT) {
+        const int64_t rr = t0 + tid;
+        if (rr < rend) {
+          float x, y, z;
+          row_direction<BM>(p.bs, rr, x, y, z);
+          sh_eval<-1>(x, y, z, p.bs.sh, [&](int k, float v) {
+            int kl = k - kbase;
+            if (kl >= 0 && kl < WG_KG) Bs[kl * XP_F32 + tid] = v;
+          });
+        } else {
+          for (int kl = 0; kl < kcount; ++kl) Bs[kl * XP_F32 + tid] = 0.f;
+        }
+      }
+    }
+    __syncthreads();
+
+    // ---- accumulate ----
+    if (active) {
+      if constexpr (DT == 1) {
+        for (int ss = rs; ss < WG_RT / 16; ss += p.RS) {
+          const int roff = ss * 16 + hh * 8;
+          float yv[2][8];
+#pragma unroll
+          for (int nb = 0; nb < 2; ++nb) {
+            const float4* s = (const float4*)(YT + (nb * 32 + l32) * XP_F32 + roff);
+            float4 a = s[0], b = s[1];
+            yv[nb][0] = a.x; yv[nb][1] = a.y; yv[nb][2] = a.z; yv[nb][3] = a.w;
+            yv[nb][4] = b.x; yv[nb][5] = b.y; yv[nb][6] = b.z; yv[nb][7] = b.w;
+          }
+          uint4 xf[2][2];  // [kk or 0][cb]
+#pragma unroll
+          for (int kk = 0; kk < 2; ++kk) {
+            const int sub = (XM == X_GATHER_CAT) ? min(kbase + 2 * kp + kk, 2) : 0;
+            if (kk == 0 || XM == X_GATHER_CAT) {
+#pragma unroll
+              for (int cb = 0; cb < 2; ++cb)
+                xf[kk][cb] = *(const uint4*)(XT + (sub * 64 + cb * 32 + l32) * XPB + roff * 2);
+            } else {
+              xf[kk][0] = xf[0][0]; xf[kk][1] = xf[0][1];
+            }
+          }
+#pragma unroll
+          for (int kk = 0; kk < 2; ++kk) {
+            if (!kv[kk]) continue;
+            float bv[8];
+            if constexpr (BM == B_ONE) {
+#pragma unroll
+              for (int i = 0; i < 8; ++i) bv[i] = 1.f;
+            } else {
+              const float4* s = (const float4*)(Bs + (2 * kp + kk) * XP_F32 + roff);
+              float4 a = s[0], b = s[1];
+              bv[0] = a.x; bv[1] = a.y; bv[2] = a.z; bv[3] = a.w;
+              bv[4] = b.x; bv[5] = b.y; bv[6] = b.z; bv[7] = b.w;
+            }
+#pragma unroll
+            for (int nb = 0; nb < 2; ++nb) {
+              uint4 yf;
+              yf.x = pack_bf16x2(bv[0] * yv[nb][0], bv[1] * yv[nb][1]);
+              yf.y = pack_bf16x2(bv[2] * yv[nb][2], bv[3] * yv[nb][3]);
+              yf.z = pack_bf16x2(bv[4] * yv[nb][4], bv[5] * yv[nb][5]);
+              yf.w = pack_bf16x2(bv[6] * yv[nb][6], bv[7] * yv[nb][7]);
+#pragma unroll
+              for (int cb = 0; cb < 2; ++cb)
+                acc[kk][cb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                    __builtin_bit_cast(bf16x8, xf[kk][cb]), __builtin_bit_cast(bf16x8, yf), acc[kk][cb][nb], 0, 0, 0);
+            }
+          }
+        }
+      } else {
+        for (int ss = rs; ss < WG_RT / 8; ss += p.RS) {
+          const int roff = ss * 8 + hh * 4;
+          float4 yv[2];
+#pragma unroll
+          for (int nb = 0; nb < 2; ++nb) yv[nb] = *(const float4*)(YT + (nb * 32 + l32) * XP_F32 + roff);
+          float4 xf[2][2];
+#pragma unroll
+          for (int kk = 0; kk < 2; ++kk) {
+            const int sub = (XM == X_GATHER_CAT) ? min(kbase + 2 * kp + kk, 2) : 0;
+            if (kk == 0 || XM == X_GATHER_CAT) {
+#pragma unroll
+              for (int cb = 0; cb < 2; ++cb)
+                xf[kk][cb] = *(const float4*)(XT + (sub * 64 + cb * 32 + l32) * XPB + roff * 4);
+            } else {
+              xf[kk][0] = xf[0][0]; xf[kk][1] = xf[0][1];
+            }
+          }
+#pragma unroll
+          for (int kk = 0; kk < 2; ++kk) {
+            if (!kv[kk]) continue;
+            float4 bv = make_float4(1.f, 1.f, 1.f, 1.f);
+            if constexpr (BM != B_ONE) bv = *(const float4*)(Bs + (2 * kp + kk) * XP_F32 + roff);
+#pragma unroll
+            for (int nb = 0; nb < 2; ++nb) {
+              const float y0 = bv.x * yv[nb].x, y1 = bv.y * yv[nb].y, y2 = bv.z * yv[nb].z, y3 = bv.w * yv[nb].w;
+#pragma unroll
+              for (int cb = 0; cb < 2; ++cb) {
+                floatx16 a = acc[kk][cb][nb];
+                a = __builtin_amdgcn_mfma_f32_32x32x2f32(xf[kk][cb].x, y0, a, 0, 0, 0);
+                a = __builtin_amdgcn_mfma_f32_32x32x2f32(xf[kk][cb].y, y1, a, 0, 0, 0);
+                a = __builtin_amdgcn_mfma_f32_32x32x2f32(xf[kk][cb].z, y2, a, 0, 0, 0);
+                a = __builtin_amdgcn_mfma_f32_32x32x2f32(xf[kk][cb].w, y3, a, 0, 0, 0);
+                acc[kk][cb][nb] = a;
+              }
+            }
+          }
+        }
+      }
+    }
+    __syncthreads();
+  }
+
+  // ---- write this wave's partial sums ----
+  if (rs < p.RS) {
+    const int64_t slice = (int64_t)blockIdx.x * p.RS + rs;
+#pragma unroll
+    for (int kk = 0; kk < 2; ++kk) {
+      if (!kv[kk]) continue;
+      const int k = kbase + 2 * kp + kk;
+      float* dst = p.partial + (slice * p.K + k) * (int64_t)p.Cc * p.Cn;
+#pragma unroll
+      for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+        for (int nb = 0; nb < 2; ++nb) {
+          const int n = nbase + nb * 32 + l32;
+#pragma unroll
+          for (int i = 0; i < 16; ++i) {
+            const int c = cbase + cb * 32 + 8 * (i >> 2) + 4 * hh + (i & 3);
+            if (c < p.Cc && n < p.Cn) dst[(int64_t)c * p.Cn + n] = acc[kk][cb][nb][i];
+          }
+        }
+    }
+  }
+}
+
+__global__ void __launch_bounds__(256) k_sum_partials(const float* __restrict__ partial, int64_t n, int n_slice,
+                                                      float* __restrict__ out) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n) return;
+  float s = 0.f;
+  for (int q = 0; q < n_slice; ++q) s += partial[(int64_t)q * n + i];
+  out[i] = s;
+}
+
+struct WgradGeom {
+  int KGn, CBP, NBP, slabs, NKPW, RS, n_part;
+  int64_t rows_per_part;
+};
+
+static WgradGeom wgrad_geom(int64_t R, int K, int Cc, int Cn) {
+  WgradGeom g;
+  g.KGn = (K + WG_KG - 1) / WG_KG;
+  g.CBP = (Cc + 63) / 64;
+  g.NBP = (Cn + 63) / 64;
+  g.slabs = g.KGn * g.CBP * g.NBP;
+  int kmax = K < WG_KG ? K : WG_KG;
+  g.NKPW = (kmax + 1) / 2;
+  g.RS = 8 / g.NKPW;
+  if (g.RS > 4) g.RS = 4;  // a 64-row tile has 4 bf16 sub-steps (8 for fp32); 4 serves both
+  int64_t tiles = (R + WG_RT - 1) / WG_RT;
+  int want = 256 / g.slabs;
+  if (want < 16) want = 16;
+  int64_t np = tiles < want ? tiles : want;
+  if (np < 1) np = 1;
+  int64_t tpp = (tiles + np - 1) / np;
+  if (tpp < 1) tpp = 1;
+  g.rows_per_part = tpp * WG_RT;
+  g.n_part = (int)((tiles + tpp - 1) / tpp);
+  if (g.n_part < 1) g.n_part = 1;
+  return g;
+}
+
+size_t pm_wgrad_ws_bytes(int64_t R, int K, int Cc, int Cn) {
+  WgradGeom g = wgrad_geom(R, K, Cc, Cn);
+  return pm_round_up((size_t)g.n_part * g.RS * K * Cc * Cn * sizeof(float), 256);
+}
+
+template <int DT, int BM, int XM, int YM>
+static pm_status launch_wgrad_inst(const WgradP& p, const WgradGeom& g, hipStream_t st) {
+  auto kern = k_wgrad<DT, BM, XM, YM>;
+  const int nsub = (XM == X_GATHER_CAT) ? 3 : 1;
+  const int xpb = (DT == 1) ? XP_BF16 * 2 : XP_F32 * 4;
+  size_t lds = (size_t)nsub * 64 * xpb + (size_t)64 * XP_F32 * 4 + (size_t)WG_KG * XP_F32 * 4;
+  PM_CHECK_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+  hipLaunchKernelGGL(kern, dim3((unsigned)g.n_part, (unsigned)g.slabs), dim3(512), lds, st, p);
+  PM_CHECK_LAUNCH("k_wgrad");
+  return PM_OK;
+}
+
+template <int DT>
+static pm_status launch_wgrad_mode(BMode bm, XMode xm, XMode ym, const WgradP& p, const WgradGeom& g, hipStream_t st) {
+  if (bm == B_NORMAL && xm == X_DIRECT && ym == X_GATHER_SUM)
+    return launch_wgrad_inst<DT, B_NORMAL, X_DIRECT, X_GATHER_SUM>(p, g, st);
+  if (bm == B_ONE && xm == X_GATHER_CAT && ym == X_DIRECT)
+    return launch_wgrad_inst<DT, B_ONE, X_GATHER_CAT, X_DIRECT>(p, g, st);
+  if (bm == B_DIRS && xm == X_DIRECT && ym == X_GATHER1)
+    return launch_wgrad_inst<DT, B_DIRS, X_DIRECT, X_GATHER1>(p, g, st);
+  return pm_fail(PM_ERR_UNSUPPORTED, "wgrad mode (%d,%d,%d)", (int)bm, (int)xm, (int)ym);
+}
+
+pm_status pm_launch_wgrad(pm_dtype mt, BMode bm, XMode xm, XMode ym, int64_t R, int K, int Cc, int Cn,
+                          const BasisSrc& bs, const RowSrc& xs, const RowSrc& ys, float* dWp, void* ws, size_t ws_bytes,
+                          hipStream_t st) {
+  WgradGeom g = wgrad_geom(R, K, Cc, Cn);
+  if (ws_bytes < pm_wgrad_ws_bytes(R, K, Cc, Cn)) return pm_fail(PM_ERR_WORKSPACE, "wgrad workspace too small");
+  WgradP p;
+  p.R = R; p.rows_per_part = g.rows_per_part;
+  p.K = K; p.Cc = Cc; p.Cn = Cn;
+  p.KGn = g.KGn; p.CBP = g.CBP; p.NBP = g.NBP; p.NKPW = g.NKPW; p.RS = g.RS;
+  p.bs = bs; p.xs = xs; p.ys = ys; p.partial = (float*)ws;
+  pm_status s = (mt == PM_BF16) ? launch_wgrad_mode<1>(bm, xm, ym, p, g, st) : launch_wgrad_mode<0>(bm, xm, ym, p, g, st);
+  if (s != PM_OK) return s;
+  int64_t n = (int64_t)K * Cc * Cn;
+  hipLaunchKernelGGL(k_sum_partials, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, (const float*)ws, n,
+                     g.n_part * g.RS, dWp);
+  PM_CHECK_LAUNCH("k_sum_partials");
+  return PM_OK;
+}
+
+// dW[k][ci][co] = sum_j fc[j][k] * M[j][ci][co]   (vertex2facet: the three corner directions are constants)
+__global__ void __launch_bounds__(256) k_unfold(int K, int64_t cc, const float* __restrict__ M, FoldCoef fc,
+                                                float* __restrict__ dW) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= (int64_t)K * cc) return;
+  int k = (int)(i / cc);
+  int64_t e = i - (int64_t)k * cc;
+  dW[i] = fc.c[0][k] * M[e] + fc.c[1][k] * M[cc + e] + fc.c[2][k] * M[2 * cc + e];
+}
+
+pm_status pm_launch_unfold(int K, int cin, int cout, const float* M, const FoldCoef* fc, float* dW, hipStream_t st) {
+  int64_t cc = (int64_t)cin * cout;
+  hipLaunchKernelGGL(k_unfold, dim3((unsigned)((K * cc + 255) / 256)), dim3(256), 0, st, K, cc, M, *fc, dW);
+  PM_CHECK_LAUNCH("k_unfold");
+  return PM_OK;
+}

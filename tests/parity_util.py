@@ -1,0 +1,51 @@
+"""Shared helpers of the GPU parity tests: seeded inputs, the error metric, oracle <-> HIP plumbing."""
+from __future__ import annotations
+
+import numpy as np
+
+from paper_2112_01801_amd import meshgen as mg
+
+TOL = {"f32": 1e-4, "bf16": 2e-2}
+
+
+def rel_err(got: np.ndarray, ref: np.ndarray) -> float:
+    """max_i |got_i - ref_i| / max(|ref_i|, rms(ref))   (the tolerance of 1e-4 / 2e-2 applies to this)."""
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    assert got.shape == ref.shape, (got.shape, ref.shape)
+    if ref.size == 0:
+        return 0.0
+    assert np.all(np.isfinite(got)), "non-finite values in the HIP result"
+    rms = float(np.sqrt(np.mean(ref ** 2)))
+    den = np.maximum(np.abs(ref), rms if rms > 0 else 1.0)
+    return float(np.max(np.abs(got - ref) / den))
+
+
+def make_features(rng, n, c, dtype):
+    x = mg.normal_features(rng, n, c)
+    return mg.round_to_bf16(x) if dtype == "bf16" else x
+
+
+def make_coeffs(rng, K, cin, cout, dtype):
+    w = mg.glorot_coeffs(rng, K, cin, cout)
+    return mg.round_to_bf16(w) if dtype == "bf16" else w
+
+
+def to_dev(x: np.ndarray, dtype: str):
+    import torch
+    t = torch.from_numpy(np.ascontiguousarray(x)).cuda()
+    return t.to(torch.bfloat16) if dtype == "bf16" else t
+
+
+def to_host(t) -> np.ndarray:
+    return t.float().cpu().numpy().astype(np.float64)
+
+
+def pm_dtype(dtype: str) -> int:
+    return 1 if dtype == "bf16" else 0
+
+
+def sample_rows(rng, n, k):
+    if n <= k:
+        return np.arange(n, dtype=np.int64)
+    return np.sort(rng.choice(n, size=k, replace=False)).astype(np.int64)

@@ -1,0 +1,248 @@
+"""HIP path vs the fp64 oracle, element by element, through the C ABI (small and medium sizes).
+
+Index work (adjacency) must be bit-exact; fp32 outputs within 1e-4 and bf16 outputs within 2e-2 of
+the oracle in the metric of parity_util.rel_err.  Sizes span several 512-row tiles plus a ragged tail.
+"""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2112_01801_amd import meshgen as mg
+from parity_util import TOL, make_coeffs, make_features, pm_dtype, rel_err, to_dev, to_host
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def pm():
+    import torch
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    from paper_2112_01801_amd import binding
+    binding.lib()
+    return binding
+
+
+def small_batch(seed=0):
+    """Three meshes, ~2.7k facets: spans 5 full 512-row tiles and a ragged tail; one isolated vertex."""
+    rng = np.random.default_rng(seed)
+    meshes = []
+    for lvl in (3, 2, 3):
+        v, f = mg.icosphere_f64(lvl)
+        v = v * (1 + rng.normal(0, 0.03, (v.shape[0], 1))) * rng.uniform(0.5, 1.5, (1, 3))
+        meshes.append((v.astype(np.float32), f))
+    v, f = meshes[1]
+    meshes[1] = (np.concatenate([v, [[9, 9, 9]]], 0).astype(np.float32), f)
+    return mg.pack_batch(meshes)
+
+
+# ---------------------------------------------------------------------------------- basis
+@pytest.mark.parametrize("L", [0, 1, 2, 3, 4, 5])
+@pytest.mark.parametrize("norm", [0, 1])
+def test_sh_basis_dirs(pm, L, norm):
+    import torch
+    rng = np.random.default_rng(100 + L)
+    d = rng.standard_normal((1000, 3)).astype(np.float32) * rng.uniform(0.1, 10, (1000, 1)).astype(np.float32)
+    d[:6] = [[0, 0, 1], [0, 0, -1], [1, 0, 0], [0, 1, 0], [-1, 0, 0], [0, -2, 0]]
+    got = to_host(pm.pm_sh_basis_dirs(torch.from_numpy(d).cuda(), L, norm))
+    ref = oracle.sh_basis(d, L, norm)
+    assert rel_err(got, ref) < 2e-5
+
+
+def test_sh_basis_mesh_and_degenerate_facet(pm):
+    b = small_batch(1)
+    f = b.facet.copy()
+    f[7] = [f[7, 0], f[7, 0], f[7, 1]]            # zero-area facet -> (0,0,1)
+    b = mg.MeshBatch(b.vert, f, b.vert_off, b.facet_off)
+    mesh = pm.mesh_to_device(b)
+    got = to_host(pm.pm_sh_basis(mesh, 3))
+    ref = oracle.sh_basis(oracle.facet_normals(b.vert, b.facet), 3)
+    assert rel_err(got, ref) < 2e-5
+    np.testing.assert_allclose(got[7], oracle.sh_basis(np.array([[0, 0, 1.0]]), 3)[0], atol=1e-6)
+
+
+@pytest.mark.parametrize("L", [1, 3, 5])
+def test_sh_basis_bwd(pm, L):
+    import torch
+    rng = np.random.default_rng(200 + L)
+    d = rng.standard_normal((300, 3)).astype(np.float32)
+    db = rng.standard_normal((300, (L + 1) ** 2)).astype(np.float32)
+    got = to_host(pm.pm_sh_basis_bwd(torch.from_numpy(d).cuda(), L, torch.from_numpy(db).cuda()))
+    ref = oracle.sh_basis_bwd(d, L, db)
+    assert rel_err(got, ref) < 1e-4
+
+
+# ---------------------------------------------------------------------------------- adjacency
+def fan_mesh(n):
+    """n facets around one hub vertex (valence n >> 64) plus an isolated vertex."""
+    ang = np.linspace(0, 2 * np.pi, n, endpoint=False)
+    v = np.concatenate([[[0, 0, 0.5]], np.stack([np.cos(ang), np.sin(ang), 0 * ang], 1), [[5, 5, 5]]], 0)
+    f = np.stack([np.zeros(n, dtype=np.int64), 1 + np.arange(n), 1 + (np.arange(n) + 1) % n], 1)
+    return v.astype(np.float32), f.astype(np.int32)
+
+
+@pytest.mark.parametrize("case", ["batch", "fan", "deleted", "empty"])
+def test_adjacency_bit_exact(pm, case):
+    if case == "batch":
+        b = small_batch(2)
+    elif case == "fan":
+        b = mg.pack_batch([fan_mesh(5000), mg.icosphere(2)])
+    elif case == "deleted":
+        rng = np.random.default_rng(3)
+        v, f = mg.heightfield(70, 45, rng, random_diag=True)
+        b = mg.pack_batch([(v, mg.delete_facets(f, 0.2, rng))])
+    else:
+        b = mg.pack_batch([(np.zeros((5, 3), np.float32), np.zeros((0, 3), np.int32))])
+    mesh = pm.mesh_to_device(b)
+    pm.pm_validate_mesh(mesh)
+    adj = pm.pm_build_vf_adjacency(mesh)
+    rp, col = oracle.vf_adjacency(b.n_vert, b.facet)
+    assert np.array_equal(adj.row_ptr.cpu().numpy(), rp)
+    assert np.array_equal(adj.col.cpu().numpy(), col)
+
+
+def test_validate_mesh_rejects_bad_ids(pm):
+    b = small_batch(4)
+    f = b.facet.copy()
+    f[100, 1] = b.vert_off[1] + 3          # facet of mesh 0 pointing into mesh 1
+    mesh = pm.mesh_to_device(mg.MeshBatch(b.vert, f, b.vert_off, b.facet_off))
+    with pytest.raises(pm.PmError) as e:
+        pm.pm_validate_mesh(mesh)
+    assert e.value.status == -5
+
+
+# ---------------------------------------------------------------------------------- convolutions
+CASES = [  # (L, cin, cout, dtype)
+    (3, 16, 16, "f32"),
+    (3, 64, 64, "f32"),
+    (3, 64, 64, "bf16"),
+    (2, 3, 5, "f32"),
+    (4, 32, 128, "f32"),
+    (1, 20, 24, "bf16"),
+    (0, 8, 8, "f32"),
+    (5, 8, 40, "bf16"),
+    (3, 128, 96, "bf16"),
+]
+
+
+def _setup(pm, L, cin, cout, dtype, seed):
+    b = small_batch(seed)
+    rng = np.random.default_rng(seed + 1000)
+    K = (L + 1) ** 2
+    W = make_coeffs(rng, K, cin, cout, dtype)
+    mesh = pm.mesh_to_device(b)
+    adj = pm.pm_build_vf_adjacency(mesh)
+    return b, rng, K, W, mesh, adj
+
+
+@pytest.mark.parametrize("L,cin,cout,dtype", CASES)
+def test_f2v_forward_backward(pm, L, cin, cout, dtype):
+    b, rng, K, W, mesh, adj = _setup(pm, L, cin, cout, dtype, 10)
+    h = make_features(rng, b.n_facet, cin, dtype)
+    dg = make_features(rng, b.n_vert, cout, dtype)
+    g = pm.pm_f2v(mesh, adj, L, to_dev(h, dtype), to_dev(W, dtype), pm_dtype(dtype))
+    assert rel_err(to_host(g), oracle.f2v(b.vert, b.facet, L, h, W)) < TOL[dtype]
+    dh, dW = pm.pm_f2v_bwd(mesh, adj, L, to_dev(h, dtype), to_dev(W, dtype), to_dev(dg, dtype), pm_dtype(dtype))
+    rdh, rdW = oracle.f2v_bwd(b.vert, b.facet, L, h, W, dg)
+    assert rel_err(to_host(dh), rdh) < TOL[dtype]
+    assert rel_err(to_host(dW), rdW) < TOL[dtype]
+
+
+@pytest.mark.parametrize("L,cin,cout,dtype", CASES)
+def test_v2f_forward_backward(pm, L, cin, cout, dtype):
+    b, rng, K, W, mesh, adj = _setup(pm, L, cin, cout, dtype, 20)
+    h = make_features(rng, b.n_vert, cin, dtype)
+    dg = make_features(rng, b.n_facet, cout, dtype)
+    g = pm.pm_v2f(mesh, L, to_dev(h, dtype), to_dev(W, dtype), pm_dtype(dtype))
+    assert rel_err(to_host(g), oracle.v2f(b.n_vert, b.facet, L, h, W)) < TOL[dtype]
+    dh, dW = pm.pm_v2f_bwd(mesh, adj, L, to_dev(h, dtype), to_dev(W, dtype), to_dev(dg, dtype), pm_dtype(dtype))
+    rdh, rdW = oracle.v2f_bwd(b.n_vert, b.facet, L, h, W, dg)
+    assert rel_err(to_host(dh), rdh) < TOL[dtype]
+    assert rel_err(to_host(dW), rdW) < TOL[dtype]
+
+
+@pytest.mark.parametrize("L,cin,cout,dtype", CASES)
+def test_f2f_forward_backward(pm, L, cin, cout, dtype):
+    import torch
+    b = small_batch(30)
+    rng = np.random.default_rng(1030)
+    K = (L + 1) ** 2
+    W = make_coeffs(rng, K, cin, cout, dtype)
+    tex_off, bary = mg.texture_layout(b, 3, 1)
+    tex_off = tex_off.copy()
+    P = int(tex_off[-1])
+    h = make_features(rng, P, cin, dtype)
+    dg = make_features(rng, b.n_facet, cout, dtype)
+    t_off, t_bary = torch.from_numpy(tex_off).cuda(), torch.from_numpy(bary).cuda()
+    g = pm.pm_f2f(t_off, t_bary, L, to_dev(h, dtype), to_dev(W, dtype), pm_dtype(dtype))
+    assert rel_err(to_host(g), oracle.f2f(tex_off, bary, L, h, W)) < TOL[dtype]
+    dh, dW = pm.pm_f2f_bwd(t_off, t_bary, L, to_dev(h, dtype), to_dev(W, dtype), to_dev(dg, dtype), pm_dtype(dtype))
+    rdh, rdW = oracle.f2f_bwd(tex_off, bary, L, h, W, dg)
+    assert rel_err(to_host(dh), rdh) < TOL[dtype]
+    assert rel_err(to_host(dW), rdW) < TOL[dtype]
+
+
+def test_f2f_empty_facets_and_paper_shape(pm):
+    """Cin = 3 colour channels (the paper's own shape), some facets without texture points."""
+    import torch
+    rng = np.random.default_rng(40)
+    res = rng.choice([0, 1, 3, 6, 10, 15], size=700)
+    tex_off = np.concatenate([[0], np.cumsum(res)]).astype(np.int32)
+    bary = np.concatenate([mg.bary_lattice({0: 0, 1: 0, 3: 1, 6: 2, 10: 3, 15: 4}[r]) for r in res if r > 0], 0)
+    L, cin, cout = 3, 3, 32
+    W = make_coeffs(rng, 16, cin, cout, "f32")
+    h = make_features(rng, bary.shape[0], cin, "f32")
+    g = pm.pm_f2f(torch.from_numpy(tex_off).cuda(), torch.from_numpy(bary).cuda(), L, to_dev(h, "f32"),
+                  to_dev(W, "f32"), 0)
+    ref = oracle.f2f(tex_off, bary, L, h, W)
+    assert rel_err(to_host(g), ref) < 1e-4
+    assert np.all(to_host(g)[res == 0] == 0)
+
+
+def test_fan_vertex_and_orthonormal_variant(pm):
+    """Valence 5000 at one vertex, an isolated vertex, and the sqrt(2)-scaled basis family."""
+    b = mg.pack_batch([fan_mesh(5000)])
+    rng = np.random.default_rng(50)
+    L, cin, cout = 2, 16, 16
+    W = make_coeffs(rng, 9, cin, cout, "f32")
+    h = make_features(rng, b.n_facet, cin, "f32")
+    mesh = pm.mesh_to_device(b)
+    adj = pm.pm_build_vf_adjacency(mesh)
+    g = to_host(pm.pm_f2v(mesh, adj, L, to_dev(h, "f32"), to_dev(W, "f32"), 0, norm=1))
+    ref = oracle.f2v(b.vert, b.facet, L, h, W, norm=1)
+    assert rel_err(g, ref) < 1e-4
+    assert np.all(g[-1] == 0)
+
+
+def test_results_are_bitwise_reproducible(pm):
+    import torch
+    L, cin, cout, dtype = 3, 64, 64, "bf16"
+    b, rng, K, W, mesh, adj = _setup(pm, L, cin, cout, dtype, 60)
+    h = to_dev(make_features(rng, b.n_facet, cin, dtype), dtype)
+    dg = to_dev(make_features(rng, b.n_vert, cout, dtype), dtype)
+    Wd = to_dev(W, dtype)
+    outs = []
+    for _ in range(2):
+        g = pm.pm_f2v(mesh, adj, L, h, Wd, 1)
+        dh, dW = pm.pm_f2v_bwd(mesh, adj, L, h, Wd, dg, 1)
+        torch.cuda.synchronize()
+        outs.append((g.clone(), dh.clone(), dW.clone()))
+    for a, c in zip(outs[0], outs[1]):
+        assert torch.equal(a, c)
+
+
+def test_argument_errors(pm):
+    import torch
+    b = small_batch(70)
+    mesh = pm.mesh_to_device(b)
+    adj = pm.pm_build_vf_adjacency(mesh)
+    h = torch.zeros((b.n_facet, 8), device="cuda")
+    W = torch.zeros((16, 8, 8), device="cuda")
+    with pytest.raises(pm.PmError) as e:
+        pm.pm_f2v(mesh, adj, 6, h, torch.zeros((49, 8, 8), device="cuda"), 0)
+    assert e.value.status == -2
+    with pytest.raises(pm.PmError) as e:
+        pm.pm_f2v(mesh, adj, 3, h, W, 0, ws=torch.empty(256, dtype=torch.uint8, device="cuda"))
+    assert e.value.status == -3
+    with pytest.raises(pm.PmError) as e:
+        pm.pm_f2v(mesh, adj, 3, h, torch.zeros(16 * 8 * 8 + 1, device="cuda")[1:].view(16, 8, 8), 0)
+    assert e.value.status == -1
