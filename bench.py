@@ -1,0 +1,208 @@
+#!/usr/bin/env python3
+"""Benchmark of the mesh-convolution hot path on one MI355X.
+
+One "step" = facet2vertex forward + backward (dh and dW) over the whole config-3 mesh (1024x1024
+height-field, 2,093,058 facets, L=3, 64->64, bf16 features with fp32 accumulation), everything resident
+in HBM, adjacency and workspaces prepared before the timed region.  Prints ONE JSON line with the
+facets/s figure, the roofline position of the dominant kernel (timed with HIP events inside the library
+on the launch stream) and the fp64 CPU oracle timed on the same box on a bounded sample.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_HBM_GBS = 8000.0
+PEAK_MFMA_TFLOPS = {"bf16": 2500.0, "f32": 157.3}
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--grid", type=int, default=1024, help="height-field side (1024 = the benchmark config)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--oracle-rows", type=int, default=256, help="grid rows of the mesh the oracle is timed on")
+    return ap.parse_args()
+
+
+def kernel_models(F, V, K, cin, cout, e):
+    """Algorithmic work per launch of each kernel of the step ('Kernels')."""
+    flop = 2.0 * K * cin * cout * F
+    w_bytes = K * cin * cout * e
+    geom = F * 12 + V * 12                       # corner ids + vertex positions, each touched once
+    return {
+        # row-wise contraction: read h (and geometry), write the fp32 facet summands
+        "f2v/k_conv_rows": dict(bound="mfma", flop=flop, bytes=F * cin * e + geom + w_bytes + F * cout * 4),
+        # segmented mean: read the summands once + CSR, write g
+        "f2v/k_segreduce": dict(bound="hbm", flop=F * cout * 3.0, bytes=F * cout * 4 + 12 * F + 4 * V + V * cout * e),
+        # dh: gather dg (each vertex row once), geometry, write dh
+        "f2v_bwd/k_conv_rows": dict(bound="mfma", flop=flop,
+                                    bytes=V * cout * e + geom + 4 * V + w_bytes + F * cin * e),
+        # dW: read h, gather dg, geometry; output is tiny
+        "f2v_bwd/k_wgrad": dict(bound="mfma", flop=flop, bytes=F * cin * e + V * cout * e + geom + 4 * V),
+    }
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU only (the hot path is a single-GPU kernel pipeline); "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2112_01801_amd import binding as pm
+    from paper_2112_01801_amd import meshgen as mg
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU (there is no CPU fallback)"
+    torch.cuda.set_device(0)
+    pm.lib()
+
+    cfg = mg.config3(args.grid)
+    b = cfg.batch
+    F, V, K, cin, cout = b.n_facet, b.n_vert, cfg.K, cfg.cin, cfg.cout
+    rng = mg.rng_for(3, 1)
+    h = mg.round_to_bf16(mg.normal_features(rng, F, cin))
+    W = mg.round_to_bf16(mg.glorot_coeffs(rng, K, cin, cout))
+    dg = mg.round_to_bf16(mg.normal_features(rng, V, cout))
+
+    mesh = pm.mesh_to_device(b)
+    bf = lambda x: torch.from_numpy(x).cuda().to(torch.bfloat16)
+    h_d, W_d, dg_d = bf(h), bf(W), bf(dg)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    adj = pm.pm_build_vf_adjacency(mesh)
+    torch.cuda.synchronize()
+    setup_ms = (time.perf_counter() - t0) * 1e3
+
+    DT = pm.PM_BF16
+    ws_f = pm.alloc_workspace(pm.pm_workspace_bytes(pm.PM_OP_F2V, V, F, 0, cfg.L, cin, cout, DT))
+    ws_b = pm.alloc_workspace(pm.pm_workspace_bytes(pm.PM_OP_F2V_BWD, V, F, 0, cfg.L, cin, cout, DT))
+    g = torch.empty((V, cout), dtype=torch.bfloat16, device="cuda")
+    dh = torch.empty((F, cin), dtype=torch.bfloat16, device="cuda")
+    dW = torch.empty((K, cin, cout), dtype=torch.float32, device="cuda")
+
+    def step():
+        pm.pm_f2v(mesh, adj, cfg.L, h_d, W_d, DT, out=g, ws=ws_f)
+        pm.pm_f2v_bwd(mesh, adj, cfg.L, h_d, W_d, dg_d, DT, dh=dh, dW=dW, ws=ws_b)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+
+    pm.pm_profile_reset()
+    pm.pm_profile_enable(True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    pm.pm_profile_enable(False)
+    recs = pm.pm_profile_read()
+    pm.pm_profile_reset()
+    assert torch.isfinite(g.float()).all() and torch.isfinite(dW).all()
+
+    ms_per_step = elapsed * 1e3 / args.steps
+    value = F * args.steps / elapsed
+
+    # per-kernel averages over the timed region
+    agg = {}
+    for name, ms in recs:
+        a = agg.setdefault(name, [0.0, 0])
+        a[0] += ms
+        a[1] += 1
+    models = kernel_models(F, V, K, cin, cout, 2)
+    kernels = []
+    for name, (tot, cnt) in agg.items():
+        per_step = tot / args.steps
+        avg = tot / cnt
+        ent = {"kernel": name, "launches_per_step": cnt / args.steps, "avg_ms": round(avg, 5),
+               "ms_per_step": round(per_step, 5)}
+        m = models.get(name)
+        if m:
+            if m["bound"] == "mfma":
+                ach = m["flop"] / (avg * 1e-3) / 1e12
+                ent.update(bound="mfma", achieved=round(ach, 2), peak=PEAK_MFMA_TFLOPS["bf16"], unit="TFLOP/s",
+                           frac=round(ach / PEAK_MFMA_TFLOPS["bf16"], 4),
+                           hbm_gbs_algorithmic=round(m["bytes"] / (avg * 1e-3) / 1e9, 1))
+            else:
+                ach = m["bytes"] / (avg * 1e-3) / 1e9
+                ent.update(bound="hbm", achieved=round(ach, 1), peak=PEAK_HBM_GBS, unit="GB/s",
+                           frac=round(ach / PEAK_HBM_GBS, 4))
+        kernels.append(ent)
+    kernels.sort(key=lambda k: -k["ms_per_step"])
+    dom = next((k for k in kernels if "bound" in k), None)
+    roofline = None
+    if dom:
+        roofline = {"kernel": dom["kernel"], "bound": dom["bound"], "achieved": dom["achieved"], "peak": dom["peak"],
+                    "unit": dom["unit"], "frac": dom["frac"], "traffic": read_traffic(dom["kernel"], args.grid),
+                    "avg_ms": dom["avg_ms"]}
+
+    cpu_baseline = None
+    if not args.no_cpu_baseline:
+        cpu_baseline = oracle_baseline(cfg, min(args.oracle_rows, args.grid), h, W, dg)
+
+    out = {
+        "metric": "mesh-conv facets/sec (fwd+bwd) at 1 MI355X",
+        "value": value, "unit": "facets/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "config 3: %dx%d height-field, F=%d V=%d, L=3 (K=16), 64->64, bf16 in / fp32 "
+                               "accumulate, facet2vertex forward + backward (dh, dW)" % (args.grid, args.grid, F, V),
+                   "ops": ["pm_f2v", "pm_f2v_bwd"], "adjacency_setup_ms": round(setup_ms, 3)},
+        "roofline": roofline,
+        "cpu_baseline": cpu_baseline,
+        "kernels": kernels,
+    }
+    print(json.dumps(out))
+
+
+def read_traffic(kernel, grid):
+    """HBM bytes per launch from the committed rocprofv3 counter summary, if one covers this kernel."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic_c3.txt")
+    if grid != 1024 or not os.path.exists(path):
+        return None
+    for line in open(path):
+        parts = line.split()
+        if len(parts) >= 2 and parts[0] == kernel:
+            try:
+                return float(parts[1])
+            except ValueError:
+                return None
+    return None
+
+
+def oracle_baseline(cfg, rows, h, W, dg):
+    """The fp64 oracle, as it stands, on the first `rows` grid rows of the same mesh (a bounded sample)."""
+    import numpy as np
+    import oracle
+    from paper_2112_01801_amd import meshgen as mg
+    nx = cfg.info["ny"]
+    b = cfg.batch
+    Vs = rows * nx
+    Fs = 2 * (rows - 1) * (nx - 1)
+    sub = mg.pack_batch([(b.vert[:Vs], b.facet[:Fs])])
+    assert int(sub.facet.max()) < Vs
+    hs, dgs = h[:Fs], dg[:Vs]
+    t0 = time.perf_counter()
+    oracle.f2v(sub.vert, sub.facet, cfg.L, hs, W)
+    oracle.f2v_bwd(sub.vert, sub.facet, cfg.L, hs, W, dgs)
+    dt = time.perf_counter() - t0
+    return {"value": Fs / dt, "unit": "facets/s", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": "facet2vertex forward + backward (dh, dW) in fp64 on the first %d of %d grid rows of the "
+                      "same mesh (%d facets), %.1f s" % (rows, nx, Fs, dt)}
+
+
+if __name__ == "__main__":
+    main()

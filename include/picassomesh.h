@@ -135,8 +135,16 @@ pm_status pm_f2f_bwd(int64_t n_facet, int64_t n_tex, const int32_t* tex_off, con
                      pm_sh_norm norm, int cin, int cout, pm_dtype dtype, const void* h_tex, const void* W,
                      const void* dg_facet, void* dh_tex, float* dW, void* ws, size_t ws_bytes, void* stream);
 
-/* Duration in milliseconds of the most recent call's kernels is NOT tracked by the library; time with
- * HIP events on `stream`. */
+/* Measurement aid (not part of the method): per-kernel timing with HIP events.
+ * After pm_profile_enable(1) every kernel this thread's calls launch is bracketed by a pair of events
+ * recorded on the call's stream (events are created on demand and reused; nothing else changes).
+ * pm_profile_count() is the number of records since the last reset; pm_profile_read(i, ...) waits for
+ * record i's stop event and returns its label ("<entry point>/<kernel>", truncated to name_cap-1
+ * characters) and its duration in milliseconds.  pm_profile_reset() drops the records (keeps the events). */
+pm_status pm_profile_enable(int on);
+int32_t pm_profile_count(void);
+pm_status pm_profile_read(int32_t i, char* name, size_t name_cap, float* ms);
+pm_status pm_profile_reset(void);
 
 #ifdef __cplusplus
 }

@@ -24,7 +24,7 @@ PM_MAX_L = 5
 EXPORTS = [
     "pm_status_string", "pm_last_error", "pm_workspace_bytes", "pm_validate_mesh", "pm_build_vf_adjacency",
     "pm_sh_basis", "pm_sh_basis_dirs", "pm_sh_basis_bwd", "pm_f2v", "pm_f2v_bwd", "pm_v2f", "pm_v2f_bwd",
-    "pm_f2f", "pm_f2f_bwd",
+    "pm_f2f", "pm_f2f_bwd", "pm_profile_enable", "pm_profile_count", "pm_profile_read", "pm_profile_reset",
 ]
 
 
@@ -74,6 +74,8 @@ def lib():
             "pm_f2f": [i64, i64, vp, vp, i32, i32, i32, i32, i32, vp, vp, vp, vp, sz, vp],
             "pm_f2f_bwd": [i64, i64, vp, vp, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, sz, vp],
         }
+        sig.update({"pm_profile_enable": [i32], "pm_profile_count": [], "pm_profile_reset": [],
+                    "pm_profile_read": [i32, C.c_char_p, sz, C.POINTER(C.c_float)]})
         for name, args in sig.items():
             f = getattr(l, name)
             f.restype = C.c_int32
@@ -293,3 +295,22 @@ def pm_f2f_bwd(tex_off, bary, L: int, h_tex, W, dg_facet, dtype: int, norm: int 
                             _ptr(h_tex) if P else None, _ptr(W), _ptr(dg_facet), _ptr(dh) if want_dh else None,
                             _ptr(dW) if want_dW else None, _ptr(ws), ws.numel(), _stream(stream)))
     return (dh if want_dh else None), (dW if want_dW else None)
+
+
+def pm_profile_enable(on: bool) -> None:
+    _check(lib().pm_profile_enable(1 if on else 0))
+
+
+def pm_profile_reset() -> None:
+    _check(lib().pm_profile_reset())
+
+
+def pm_profile_read():
+    """All records since the last reset as a list of (label, milliseconds)."""
+    out = []
+    buf = C.create_string_buffer(64)
+    ms = C.c_float()
+    for i in range(lib().pm_profile_count()):
+        _check(lib().pm_profile_read(i, buf, 64, C.byref(ms)))
+        out.append((buf.value.decode(), float(ms.value)))
+    return out

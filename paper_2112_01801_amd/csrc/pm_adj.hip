@@ -169,21 +169,30 @@ pm_status pm_launch_adjacency(const pm_mesh* mesh, int32_t* row_ptr, int32_t* co
   int32_t* long_rows = (int32_t*)p; p += pm_round_up((size_t)(V + 1) * 4, 256);
   int32_t* n_long = (int32_t*)p;
 
-  hipLaunchKernelGGL(k_fill_i32, dim3(nblk(V + 1, 256)), dim3(256), 0, st, cnt, V + 1, 0);
-  hipLaunchKernelGGL(k_fill_i32, dim3(1), dim3(64), 0, st, n_long, (int64_t)1, 0);
+  { ProfScope ps__(st, "k_fill_i32");
+    hipLaunchKernelGGL(k_fill_i32, dim3(nblk(V + 1, 256)), dim3(256), 0, st, cnt, V + 1, 0); }
+  { ProfScope ps__(st, "k_fill_i32");
+    hipLaunchKernelGGL(k_fill_i32, dim3(1), dim3(64), 0, st, n_long, (int64_t)1, 0); }
   if (V == 0) {
-    hipLaunchKernelGGL(k_fill_i32, dim3(1), dim3(64), 0, st, row_ptr, (int64_t)1, 0);
+    { ProfScope ps__(st, "k_fill_i32");
+      hipLaunchKernelGGL(k_fill_i32, dim3(1), dim3(64), 0, st, row_ptr, (int64_t)1, 0); }
     PM_CHECK_LAUNCH("adjacency(empty)");
     return PM_OK;
   }
   if (n3 > 0) hipLaunchKernelGGL(k_count, dim3(nblk(n3, 256)), dim3(256), 0, st, n3, mesh->facet, cnt);
-  hipLaunchKernelGGL(k_scan_tile_sums, dim3((unsigned)n_tiles), dim3(SCAN_BLOCK), 0, st, cnt, V, tsum);
-  hipLaunchKernelGGL(k_scan_sums, dim3(1), dim3(SCAN_BLOCK), 0, st, tsum, n_tiles);
-  hipLaunchKernelGGL(k_scan_apply, dim3((unsigned)n_tiles), dim3(SCAN_BLOCK), 0, st, cnt, V, tsum, row_ptr, cursor);
+  { ProfScope ps__(st, "k_scan_tile_sums");
+    hipLaunchKernelGGL(k_scan_tile_sums, dim3((unsigned)n_tiles), dim3(SCAN_BLOCK), 0, st, cnt, V, tsum); }
+  { ProfScope ps__(st, "k_scan_sums");
+    hipLaunchKernelGGL(k_scan_sums, dim3(1), dim3(SCAN_BLOCK), 0, st, tsum, n_tiles); }
+  { ProfScope ps__(st, "k_scan_apply");
+    hipLaunchKernelGGL(k_scan_apply, dim3((unsigned)n_tiles), dim3(SCAN_BLOCK), 0, st, cnt, V, tsum, row_ptr, cursor); }
   if (n3 > 0) {
-    hipLaunchKernelGGL(k_scatter, dim3(nblk(n3, 256)), dim3(256), 0, st, n3, mesh->facet, cursor, tmp);
-    hipLaunchKernelGGL(k_sort_short, dim3(nblk(V, 256)), dim3(256), 0, st, V, row_ptr, tmp, col, long_rows, n_long);
-    hipLaunchKernelGGL(k_sort_long, dim3(256), dim3(256), 0, st, row_ptr, tmp, col, long_rows, n_long);
+    { ProfScope ps__(st, "k_scatter");
+      hipLaunchKernelGGL(k_scatter, dim3(nblk(n3, 256)), dim3(256), 0, st, n3, mesh->facet, cursor, tmp); }
+    { ProfScope ps__(st, "k_sort_short");
+      hipLaunchKernelGGL(k_sort_short, dim3(nblk(V, 256)), dim3(256), 0, st, V, row_ptr, tmp, col, long_rows, n_long); }
+    { ProfScope ps__(st, "k_sort_long");
+      hipLaunchKernelGGL(k_sort_long, dim3(256), dim3(256), 0, st, row_ptr, tmp, col, long_rows, n_long); }
   }
   PM_CHECK_LAUNCH("adjacency");
   return PM_OK;
@@ -217,10 +226,12 @@ __global__ void k_validate(int n_mesh, int64_t V, int64_t F, const int32_t* __re
 }
 
 pm_status pm_launch_validate(const pm_mesh* mesh, int32_t* flag, hipStream_t st) {
-  hipLaunchKernelGGL(k_fill_i32, dim3(1), dim3(64), 0, st, flag, (int64_t)1, 0);
+  { ProfScope ps__(st, "k_fill_i32");
+    hipLaunchKernelGGL(k_fill_i32, dim3(1), dim3(64), 0, st, flag, (int64_t)1, 0); }
   int64_t n = mesh->n_facet > 0 ? mesh->n_facet : 1;
-  hipLaunchKernelGGL(k_validate, dim3(nblk(n, 256)), dim3(256), 0, st, mesh->n_mesh, mesh->n_vert, mesh->n_facet,
-                     mesh->facet, mesh->vert_off, mesh->facet_off, flag);
+  { ProfScope ps__(st, "k_validate");
+    hipLaunchKernelGGL(k_validate, dim3(nblk(n, 256)), dim3(256), 0, st, mesh->n_mesh, mesh->n_vert, mesh->n_facet,
+                     mesh->facet, mesh->vert_off, mesh->facet_off, flag); }
   PM_CHECK_LAUNCH("k_validate");
   return PM_OK;
 }

@@ -2,6 +2,10 @@
 #include <stdarg.h>
 #include <stdio.h>
 
+#include <string.h>
+
+#include <vector>
+
 #include "pm_host.h"
 
 static thread_local char g_err[512] = "";
@@ -15,6 +19,74 @@ pm_status pm_fail(pm_status s, const char* fmt, ...) {
 }
 
 extern "C" const char* pm_last_error(void) { return g_err; }
+
+// ---- per-kernel event timing ------------------------------------------------------------------
+struct ProfRec {
+  char name[64];
+  hipEvent_t start, stop;
+};
+static thread_local bool g_prof_on = false;
+static thread_local const char* g_prof_op = "";
+static thread_local std::vector<ProfRec> g_prof_recs;
+static thread_local std::vector<hipEvent_t> g_prof_pool;
+static thread_local bool g_prof_open = false;
+
+static hipEvent_t prof_event() {
+  if (!g_prof_pool.empty()) {
+    hipEvent_t e = g_prof_pool.back();
+    g_prof_pool.pop_back();
+    return e;
+  }
+  hipEvent_t e = nullptr;
+  if (hipEventCreate(&e) != hipSuccess) return nullptr;
+  return e;
+}
+
+void pm_prof_set_op(const char* op) { g_prof_op = op; }
+
+void pm_prof_begin(hipStream_t st, const char* kernel) {
+  g_prof_open = false;
+  if (!g_prof_on) return;
+  ProfRec r;
+  snprintf(r.name, sizeof(r.name), "%s/%s", g_prof_op, kernel);
+  r.start = prof_event();
+  r.stop = prof_event();
+  if (!r.start || !r.stop) return;
+  if (hipEventRecord(r.start, st) != hipSuccess) return;
+  g_prof_recs.push_back(r);
+  g_prof_open = true;
+}
+
+void pm_prof_end(hipStream_t st) {
+  if (!g_prof_open) return;
+  (void)hipEventRecord(g_prof_recs.back().stop, st);
+  g_prof_open = false;
+}
+
+extern "C" pm_status pm_profile_enable(int on) {
+  g_prof_on = on != 0;
+  return PM_OK;
+}
+extern "C" int32_t pm_profile_count(void) { return (int32_t)g_prof_recs.size(); }
+extern "C" pm_status pm_profile_read(int32_t i, char* name, size_t name_cap, float* ms) {
+  if (i < 0 || i >= (int32_t)g_prof_recs.size() || !ms) return pm_fail(PM_ERR_INVALID_ARG, "profile record %d", i);
+  ProfRec& r = g_prof_recs[i];
+  PM_CHECK_HIP(hipEventSynchronize(r.stop));
+  PM_CHECK_HIP(hipEventElapsedTime(ms, r.start, r.stop));
+  if (name && name_cap) {
+    strncpy(name, r.name, name_cap - 1);
+    name[name_cap - 1] = 0;
+  }
+  return PM_OK;
+}
+extern "C" pm_status pm_profile_reset(void) {
+  for (auto& r : g_prof_recs) {
+    g_prof_pool.push_back(r.start);
+    g_prof_pool.push_back(r.stop);
+  }
+  g_prof_recs.clear();
+  return PM_OK;
+}
 
 extern "C" const char* pm_status_string(pm_status s) {
   switch (s) {
@@ -121,6 +193,7 @@ static pm_status check_ws(const WsPlan& w, void* ws, size_t ws_bytes) {
 
 // ---- mesh utilities ----------------------------------------------------------------------------
 extern "C" pm_status pm_validate_mesh(const pm_mesh* mesh, void* ws, size_t ws_bytes, void* stream) {
+  pm_prof_set_op("validate");
   PM_TRY(check_mesh(mesh, false));
   PM_TRY(check_ptr(ws, "ws", true));
   if (ws_bytes < 16) return pm_fail(PM_ERR_WORKSPACE, "validate needs 16 bytes of workspace");
@@ -138,6 +211,7 @@ extern "C" pm_status pm_validate_mesh(const pm_mesh* mesh, void* ws, size_t ws_b
 
 extern "C" pm_status pm_build_vf_adjacency(const pm_mesh* mesh, int32_t* row_ptr, int32_t* col, void* ws,
                                            size_t ws_bytes, void* stream) {
+  pm_prof_set_op("adjacency");
   PM_TRY(check_mesh(mesh, false));
   if (!row_ptr || (mesh->n_facet > 0 && !col)) return pm_fail(PM_ERR_INVALID_ARG, "row_ptr / col is NULL");
   WsPlan w = plan_ws(PM_OP_ADJACENCY, mesh->n_vert, mesh->n_facet, 0, 0, 1, 1, PM_F32);
@@ -147,6 +221,7 @@ extern "C" pm_status pm_build_vf_adjacency(const pm_mesh* mesh, int32_t* row_ptr
 
 // ---- basis -------------------------------------------------------------------------------------
 extern "C" pm_status pm_sh_basis(const pm_mesh* mesh, int L, pm_sh_norm norm, float* basis, void* stream) {
+  pm_prof_set_op("sh_basis");
   PM_TRY(check_conv_common(L, norm, 1, 1, PM_F32));
   PM_TRY(check_mesh(mesh, true));
   if (mesh->n_facet > 0 && !basis) return pm_fail(PM_ERR_INVALID_ARG, "basis is NULL");
@@ -156,6 +231,7 @@ extern "C" pm_status pm_sh_basis(const pm_mesh* mesh, int L, pm_sh_norm norm, fl
 }
 
 extern "C" pm_status pm_sh_basis_dirs(int64_t n, const float* dirs, int L, pm_sh_norm norm, float* basis, void* stream) {
+  pm_prof_set_op("sh_basis_dirs");
   PM_TRY(check_conv_common(L, norm, 1, 1, PM_F32));
   if (n < 0 || n >= kMaxIds) return pm_fail(PM_ERR_INVALID_ARG, "n=%lld", (long long)n);
   if (n > 0 && (!dirs || !basis)) return pm_fail(PM_ERR_INVALID_ARG, "dirs / basis is NULL");
@@ -166,6 +242,7 @@ extern "C" pm_status pm_sh_basis_dirs(int64_t n, const float* dirs, int L, pm_sh
 
 extern "C" pm_status pm_sh_basis_bwd(int64_t n, const float* dirs, int L, pm_sh_norm norm, const float* dbasis,
                                      float* ddirs, void* stream) {
+  pm_prof_set_op("sh_basis_bwd");
   PM_TRY(check_conv_common(L, norm, 1, 1, PM_F32));
   if (n < 0 || n >= kMaxIds) return pm_fail(PM_ERR_INVALID_ARG, "n=%lld", (long long)n);
   if (n > 0 && (!dirs || !dbasis || !ddirs)) return pm_fail(PM_ERR_INVALID_ARG, "dirs / dbasis / ddirs is NULL");
@@ -199,6 +276,7 @@ static void fold_coef(int L, pm_sh_norm norm, FoldCoef* fc) {
 extern "C" pm_status pm_f2v(const pm_mesh* mesh, const pm_vf_adj* adj, int L, pm_sh_norm norm, int cin, int cout,
                             pm_dtype dtype, const void* h_facet, const void* W, void* g_vert, void* ws, size_t ws_bytes,
                             void* stream) {
+  pm_prof_set_op("f2v");
   PM_TRY(check_conv_common(L, norm, cin, cout, dtype));
   PM_TRY(check_mesh(mesh, true));
   if (!adj || !adj->row_ptr || (mesh->n_facet > 0 && !adj->col)) return pm_fail(PM_ERR_INVALID_ARG, "adjacency is NULL");
@@ -225,6 +303,7 @@ extern "C" pm_status pm_f2v(const pm_mesh* mesh, const pm_vf_adj* adj, int L, pm
 extern "C" pm_status pm_f2v_bwd(const pm_mesh* mesh, const pm_vf_adj* adj, int L, pm_sh_norm norm, int cin, int cout,
                                 pm_dtype dtype, const void* h_facet, const void* W, const void* dg_vert, void* dh_facet,
                                 float* dW, void* ws, size_t ws_bytes, void* stream) {
+  pm_prof_set_op("f2v_bwd");
   PM_TRY(check_conv_common(L, norm, cin, cout, dtype));
   PM_TRY(check_mesh(mesh, true));
   if (!adj || !adj->row_ptr) return pm_fail(PM_ERR_INVALID_ARG, "adjacency is NULL");
@@ -261,6 +340,7 @@ extern "C" pm_status pm_f2v_bwd(const pm_mesh* mesh, const pm_vf_adj* adj, int L
 // ---- vertex2facet (Eq. 6) ------------------------------------------------------------------------
 extern "C" pm_status pm_v2f(const pm_mesh* mesh, int L, pm_sh_norm norm, int cin, int cout, pm_dtype dtype,
                             const void* h_vert, const void* W, void* g_facet, void* ws, size_t ws_bytes, void* stream) {
+  pm_prof_set_op("v2f");
   PM_TRY(check_conv_common(L, norm, cin, cout, dtype));
   PM_TRY(check_mesh(mesh, false));
   PM_TRY(check_ptr(W, "W", true));
@@ -284,6 +364,7 @@ extern "C" pm_status pm_v2f(const pm_mesh* mesh, int L, pm_sh_norm norm, int cin
 extern "C" pm_status pm_v2f_bwd(const pm_mesh* mesh, const pm_vf_adj* adj, int L, pm_sh_norm norm, int cin, int cout,
                                 pm_dtype dtype, const void* h_vert, const void* W, const void* dg_facet, void* dh_vert,
                                 float* dW, void* ws, size_t ws_bytes, void* stream) {
+  pm_prof_set_op("v2f_bwd");
   PM_TRY(check_conv_common(L, norm, cin, cout, dtype));
   PM_TRY(check_mesh(mesh, false));
   PM_TRY(check_ptr(W, "W", true));
@@ -334,6 +415,7 @@ static pm_status check_f2f(int64_t n_facet, int64_t n_tex, const int32_t* tex_of
 extern "C" pm_status pm_f2f(int64_t n_facet, int64_t n_tex, const int32_t* tex_off, const float* bary, int L,
                             pm_sh_norm norm, int cin, int cout, pm_dtype dtype, const void* h_tex, const void* W,
                             void* g_facet, void* ws, size_t ws_bytes, void* stream) {
+  pm_prof_set_op("f2f");
   PM_TRY(check_conv_common(L, norm, cin, cout, dtype));
   PM_TRY(check_f2f(n_facet, n_tex, tex_off, bary));
   PM_TRY(check_ptr(W, "W", true));
@@ -357,6 +439,7 @@ extern "C" pm_status pm_f2f(int64_t n_facet, int64_t n_tex, const int32_t* tex_o
 extern "C" pm_status pm_f2f_bwd(int64_t n_facet, int64_t n_tex, const int32_t* tex_off, const float* bary, int L,
                                 pm_sh_norm norm, int cin, int cout, pm_dtype dtype, const void* h_tex, const void* W,
                                 const void* dg_facet, void* dh_tex, float* dW, void* ws, size_t ws_bytes, void* stream) {
+  pm_prof_set_op("f2f_bwd");
   PM_TRY(check_conv_common(L, norm, cin, cout, dtype));
   PM_TRY(check_f2f(n_facet, n_tex, tex_off, bary));
   PM_TRY(check_ptr(W, "W", true));

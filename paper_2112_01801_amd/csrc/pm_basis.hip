@@ -132,21 +132,24 @@ static inline unsigned nblocks(int64_t n, int b) { return (unsigned)((n + b - 1)
 
 pm_status pm_launch_basis_mesh(const pm_mesh* mesh, const ShTable& T, float* basis, hipStream_t st) {
   if (mesh->n_facet == 0) return PM_OK;
-  hipLaunchKernelGGL(k_basis_mesh, dim3(nblocks(mesh->n_facet, 256)), dim3(256), 0, st, mesh->n_facet, mesh->vert,
-                     mesh->facet, T, basis);
+  { ProfScope ps__(st, "k_basis_mesh");
+    hipLaunchKernelGGL(k_basis_mesh, dim3(nblocks(mesh->n_facet, 256)), dim3(256), 0, st, mesh->n_facet, mesh->vert,
+                     mesh->facet, T, basis); }
   PM_CHECK_LAUNCH("k_basis_mesh");
   return PM_OK;
 }
 pm_status pm_launch_basis_dirs(int64_t n, const float* dirs, const ShTable& T, float* basis, hipStream_t st) {
   if (n == 0) return PM_OK;
-  hipLaunchKernelGGL(k_basis_dirs, dim3(nblocks(n, 256)), dim3(256), 0, st, n, dirs, T, basis);
+  { ProfScope ps__(st, "k_basis_dirs");
+    hipLaunchKernelGGL(k_basis_dirs, dim3(nblocks(n, 256)), dim3(256), 0, st, n, dirs, T, basis); }
   PM_CHECK_LAUNCH("k_basis_dirs");
   return PM_OK;
 }
 pm_status pm_launch_basis_bwd(int64_t n, const float* dirs, const ShTable& T, const float* dbasis, float* ddirs,
                               hipStream_t st) {
   if (n == 0) return PM_OK;
-  hipLaunchKernelGGL(k_basis_bwd, dim3(nblocks(n, 256)), dim3(256), 0, st, n, dirs, T, dbasis, ddirs);
+  { ProfScope ps__(st, "k_basis_bwd");
+    hipLaunchKernelGGL(k_basis_bwd, dim3(nblocks(n, 256)), dim3(256), 0, st, n, dirs, T, dbasis, ddirs); }
   PM_CHECK_LAUNCH("k_basis_bwd");
   return PM_OK;
 }

@@ -103,7 +103,8 @@ pm_status pm_launch_pack(PackMode mode, pm_dtype dt, int K, int cin, int cout, c
   p.W = W; p.out = (uint4*)apack;
   if (fc) p.fc = *fc; else for (int j = 0; j < 3; ++j) for (int k = 0; k < PM_MAX_K; ++k) p.fc.c[j][k] = 0.f;
   int64_t n_gran = g.stages * STAGE_U4;
-  hipLaunchKernelGGL(k_pack, dim3((unsigned)((n_gran + 255) / 256)), dim3(256), 0, st, p, n_gran);
+  { ProfScope ps__(st, "k_pack");
+    hipLaunchKernelGGL(k_pack, dim3((unsigned)((n_gran + 255) / 256)), dim3(256), 0, st, p, n_gran); }
   PM_CHECK_LAUNCH("k_pack");
   return PM_OK;
 }
@@ -234,7 +235,8 @@ pm_status pm_launch_segreduce(int64_t n_seg, int C, const float* src, const int3
   while (lpg < need && lpg < 64) lpg <<= 1;
   p.lpg = lpg;
   int gpb = 256 / lpg;
-  hipLaunchKernelGGL(k_segreduce, dim3((unsigned)((n_seg + gpb - 1) / gpb)), dim3(256), 0, st, p);
+  { ProfScope ps__(st, "k_segreduce");
+    hipLaunchKernelGGL(k_segreduce, dim3((unsigned)((n_seg + gpb - 1) / gpb)), dim3(256), 0, st, p); }
   PM_CHECK_LAUNCH("k_segreduce");
   return PM_OK;
 }
@@ -248,7 +250,8 @@ __global__ void k_owner(int64_t F, const int32_t* __restrict__ off, int32_t* __r
 
 pm_status pm_launch_owner(int64_t n_facet, const int32_t* tex_off, int32_t* owner, hipStream_t st) {
   if (n_facet == 0) return PM_OK;
-  hipLaunchKernelGGL(k_owner, dim3((unsigned)((n_facet + 255) / 256)), dim3(256), 0, st, n_facet, tex_off, owner);
+  { ProfScope ps__(st, "k_owner");
+    hipLaunchKernelGGL(k_owner, dim3((unsigned)((n_facet + 255) / 256)), dim3(256), 0, st, n_facet, tex_off, owner); }
   PM_CHECK_LAUNCH("k_owner");
   return PM_OK;
 }

@@ -217,7 +217,8 @@ static pm_status launch_conv_res(const ConvP& p, int64_t S, hipStream_t st) {
   const int NT = NW * 64;
   int64_t n_tiles = (p.R + NT - 1) / NT;
   int64_t grid = n_tiles < 256 ? (n_tiles + 7) / 8 * 8 : 256;
-  hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(NT), lds, st, p);
+  { ProfScope ps__(st, "k_conv_rows");
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(NT), lds, st, p); }
   PM_CHECK_LAUNCH("k_conv_rows");
   return PM_OK;
 }

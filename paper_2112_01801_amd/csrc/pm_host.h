@@ -19,6 +19,16 @@ pm_status pm_fail(pm_status s, const char* fmt, ...);
     if (e__ != hipSuccess) return pm_fail(PM_ERR_HIP, "launch %s: %s", name, hipGetErrorString(e__)); \
   } while (0)
 
+// ---- optional per-kernel event timing (see pm_profile_* in the public header) -----------------
+void pm_prof_begin(hipStream_t st, const char* kernel);
+void pm_prof_end(hipStream_t st);
+void pm_prof_set_op(const char* op);
+struct ProfScope {
+  hipStream_t st;
+  ProfScope(hipStream_t s, const char* kernel) : st(s) { pm_prof_begin(st, kernel); }
+  ~ProfScope() { pm_prof_end(st); }
+};
+
 static inline bool pm_aligned16(const void* p) { return (((uintptr_t)p) & 15u) == 0; }
 static inline size_t pm_round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 

@@ -285,7 +285,8 @@ static pm_status launch_wgrad_inst(const WgradP& p, const WgradGeom& g, hipStrea
   const int xpb = (DT == 1) ? XP_BF16 * 2 : XP_F32 * 4;
   size_t lds = (size_t)nsub * 64 * xpb + (size_t)64 * XP_F32 * 4 + (size_t)WG_KG * XP_F32 * 4;
   PM_CHECK_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-  hipLaunchKernelGGL(kern, dim3((unsigned)g.n_part, (unsigned)g.slabs), dim3(512), lds, st, p);
+  { ProfScope ps__(st, "k_wgrad");
+    hipLaunchKernelGGL(kern, dim3((unsigned)g.n_part, (unsigned)g.slabs), dim3(512), lds, st, p); }
   PM_CHECK_LAUNCH("k_wgrad");
   return PM_OK;
 }
@@ -314,8 +315,9 @@ pm_status pm_launch_wgrad(pm_dtype mt, BMode bm, XMode xm, XMode ym, int64_t R, 
   pm_status s = (mt == PM_BF16) ? launch_wgrad_mode<1>(bm, xm, ym, p, g, st) : launch_wgrad_mode<0>(bm, xm, ym, p, g, st);
   if (s != PM_OK) return s;
   int64_t n = (int64_t)K * Cc * Cn;
-  hipLaunchKernelGGL(k_sum_partials, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, (const float*)ws, n,
-                     g.n_part * g.RS, dWp);
+  { ProfScope ps__(st, "k_sum_partials");
+    hipLaunchKernelGGL(k_sum_partials, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, (const float*)ws, n,
+                     g.n_part * g.RS, dWp); }
   PM_CHECK_LAUNCH("k_sum_partials");
   return PM_OK;
 }
@@ -332,7 +334,8 @@ __global__ void __launch_bounds__(256) k_unfold(int K, int64_t cc, const float* 
 
 pm_status pm_launch_unfold(int K, int cin, int cout, const float* M, const FoldCoef* fc, float* dW, hipStream_t st) {
   int64_t cc = (int64_t)cin * cout;
-  hipLaunchKernelGGL(k_unfold, dim3((unsigned)((K * cc + 255) / 256)), dim3(256), 0, st, K, cc, M, *fc, dW);
+  { ProfScope ps__(st, "k_unfold");
+    hipLaunchKernelGGL(k_unfold, dim3((unsigned)((K * cc + 255) / 256)), dim3(256), 0, st, K, cc, M, *fc, dW); }
   PM_CHECK_LAUNCH("k_unfold");
   return PM_OK;
 }
