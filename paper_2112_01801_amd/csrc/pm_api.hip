@@ -150,6 +150,7 @@ static WsPlan plan_ws(pm_op op, int64_t V, int64_t F, int64_t P, int L, int cin,
       break;
     case PM_OP_F2V_BWD:
       w.apack = pm_pack_bytes(pm_pack_geom(K, cout, cin, dt));
+      w.inter = pm_round_up((size_t)F * K * 4, 256);   // basis rows for the weight gradient
       w.wgrad = pm_wgrad_ws_bytes(F, K, cin, cout);
       break;
     case PM_OP_V2F:
@@ -168,6 +169,7 @@ static WsPlan plan_ws(pm_op op, int64_t V, int64_t F, int64_t P, int L, int cin,
     case PM_OP_F2F_BWD:
       w.apack = pm_pack_bytes(pm_pack_geom(K, cout, cin, dt));
       w.owner = pm_round_up((size_t)(P + 1) * 4, 256);
+      w.inter = pm_round_up((size_t)P * K * 4, 256);   // basis rows for the weight gradient
       w.wgrad = pm_wgrad_ws_bytes(P, K, cin, cout);
       break;
   }
@@ -260,7 +262,7 @@ static RowSrc row_src(const void* p, pm_dtype dt, int C) {
 }
 static BasisSrc basis_none() {
   BasisSrc b;
-  b.vert = nullptr; b.facet = nullptr; b.dirs = nullptr; b.owner = nullptr; b.seg_off = nullptr;
+  b.vert = nullptr; b.facet = nullptr; b.dirs = nullptr; b.bvals = nullptr; b.owner = nullptr; b.seg_off = nullptr;
   pm_make_sh_table(0, PM_SH_PAPER, &b.sh);
   return b;
 }
@@ -318,7 +320,8 @@ extern "C" pm_status pm_f2v_bwd(const pm_mesh* mesh, const pm_vf_adj* adj, int L
   PM_TRY(check_ws(w, ws, ws_bytes));
   hipStream_t st = (hipStream_t)stream;
   char* apack = (char*)ws;
-  void* wg = apack + w.apack;
+  float* bvals = (float*)(apack + w.apack);
+  void* wg = (char*)bvals + w.inter;
 
   BasisSrc bs = basis_none();
   bs.vert = mesh->vert; bs.facet = mesh->facet;
@@ -332,6 +335,8 @@ extern "C" pm_status pm_f2v_bwd(const pm_mesh* mesh, const pm_vf_adj* adj, int L
   }
   if (dW) {
     RowSrc xs = row_src(h_facet, dtype, cin);
+    PM_TRY(pm_launch_basis_mesh(mesh, bs.sh, bvals, st));
+    bs.bvals = bvals;
     PM_TRY(pm_launch_wgrad(dtype, B_NORMAL, X_DIRECT, X_GATHER_SUM, F, K, cin, cout, bs, xs, dys, dW, wg, w.wgrad, st));
   }
   return PM_OK;
@@ -453,7 +458,8 @@ extern "C" pm_status pm_f2f_bwd(int64_t n_facet, int64_t n_tex, const int32_t* t
   hipStream_t st = (hipStream_t)stream;
   char* apack = (char*)ws;
   int32_t* owner = (int32_t*)(apack + w.apack);
-  void* wg = (char*)owner + w.owner;
+  float* bvals = (float*)((char*)owner + w.owner);
+  void* wg = (char*)bvals + w.inter;
   PM_TRY(pm_launch_owner(n_facet, tex_off, owner, st));
   BasisSrc bs = basis_none();
   bs.dirs = bary;
@@ -467,6 +473,8 @@ extern "C" pm_status pm_f2f_bwd(int64_t n_facet, int64_t n_tex, const int32_t* t
   }
   if (dW) {
     RowSrc xs = row_src(h_tex, dtype, cin);
+    PM_TRY(pm_launch_basis_dirs(n_tex, bary, bs.sh, bvals, st));
+    bs.bvals = bvals;
     PM_TRY(pm_launch_wgrad(dtype, B_DIRS, X_DIRECT, X_GATHER1, n_tex, K, cin, cout, bs, xs, dys, dW, wg, w.wgrad, st));
   }
   return PM_OK;

@@ -114,11 +114,21 @@ __global__ void __launch_bounds__(NW * 64) k_conv_rows(ConvP p) {
             fetch_vals<XM, EPG>(p.xs, row[fb], ok[fb], meta[fb], ((ch * PM_GC + g) * 2 + hh) * EPG, v);
             X[fb][g] = pack_granule<DT>(v);
           }
+        // Software pipeline over the chains (k, nbi).  A wave issues in order, so the only way to keep the
+        // matrix pipe busy while the SH weighting runs is to interleave, in program order, the MFMAs of
+        // chain c with the FMA epilogue of chain c-1 (whose U tiles are "pending" in pu0/pu1): every MFMA
+        // is followed by four of the pending FMAs, and sched_barrier keeps that written order.  The A
+        // fragments of chain c+1 are read from LDS while chain c computes.
+        floatx16 pu0, pu1;
+        float pb0 = 0.f, pb1 = 0.f;
+        uint4 afr[PM_GC];  // A fragments of the chain about to run
+        if constexpr (RES) {
+#pragma unroll
+          for (int g = 0; g < PM_GC; ++g) afr[g] = lds[q * STAGE_U4 + g * 64 + lane];
+        }
 #pragma unroll
         for (int k = 0; k < K; ++k, ++q) {
-          // compiler-level fence: the A fragments of this k must be read here, not hoisted to the top
-          // of the unrolled loop (that would keep K x 32 fragment registers live at once)
-          asm volatile("" ::: "memory");
+          asm volatile("" ::: "memory");  // keep LDS reads of later stages from being hoisted up here
           const uint4* stage;
           uint4 pre[PER_T];
           if constexpr (RES) {
@@ -140,24 +150,45 @@ __global__ void __launch_bounds__(NW * 64) k_conv_rows(ConvP p) {
                 y[nbi][1] = mma_group<DT>(a, X[1][g], y[nbi][1]);
               }
             } else {
+              uint4 ac[PM_GC];
+              if constexpr (RES) {
+#pragma unroll
+                for (int g = 0; g < PM_GC; ++g) ac[g] = afr[g];
+                // prefetch the fragments of the next chain (next n-block of this stage, or next stage)
+                const bool last_chain = (k == K - 1) && (nbi == PM_NBS - 1);
+                if (!last_chain) {
+                  const uint4* nxt = (nbi + 1 < PM_NBS) ? stage + (nbi + 1) * PM_GC * 64 : stage + STAGE_U4;
+#pragma unroll
+                  for (int g = 0; g < PM_GC; ++g) afr[g] = nxt[g * 64 + lane];
+                }
+              } else {
+#pragma unroll
+                for (int g = 0; g < PM_GC; ++g) ac[g] = stage[(nbi * PM_GC + g) * 64 + lane];
+              }
+              const bool have_pending = (k > 0 || nbi > 0);
+              const int pn = (nbi == 0) ? PM_NBS - 1 : nbi - 1;
               floatx16 u0, u1;
 #pragma unroll
               for (int i = 0; i < 16; ++i) { u0[i] = 0.f; u1[i] = 0.f; }
+              __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
               for (int g = 0; g < PM_GC; ++g) {
-                uint4 a = stage[(nbi * PM_GC + g) * 64 + lane];
-                u0 = mma_group<DT>(a, X[0][g], u0);
-                u1 = mma_group<DT>(a, X[1][g], u1);
-              }
-              const float b0 = B[0][k], b1 = B[1][k];
+                u0 = mma_group<DT>(ac[g], X[0][g], u0);
+                if (have_pending) {
 #pragma unroll
-              for (int i = 0; i < 16; ++i) {
-                y[nbi][0][i] += b0 * u0[i];
-                y[nbi][1][i] += b1 * u1[i];
+                  for (int i = 4 * g; i < 4 * g + 4; ++i) y[pn][0][i] += pb0 * pu0[i];
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                u1 = mma_group<DT>(ac[g], X[1][g], u1);
+                if (have_pending) {
+#pragma unroll
+                  for (int i = 4 * g; i < 4 * g + 4; ++i) y[pn][1][i] += pb1 * pu1[i];
+                }
+                __builtin_amdgcn_sched_barrier(0);
               }
-              // pin the weighted sum here: without this the optimiser sinks the whole FMA chain below
-              // the unrolled k loop and keeps every U tile alive (spilled) until then
-              asm volatile("" : "+v"(y[nbi][0]), "+v"(y[nbi][1]));
+              if (have_pending) asm volatile("" : "+v"(y[pn][0]), "+v"(y[pn][1]));
+              pu0 = u0; pu1 = u1;
+              pb0 = B[0][k]; pb1 = B[1][k];
             }
           }
           if constexpr (!RES) {
@@ -167,9 +198,14 @@ __global__ void __launch_bounds__(NW * 64) k_conv_rows(ConvP p) {
             }
             __syncthreads();
           }
-          // keep the scheduler from hoisting the LDS reads of later k's over this one: the unrolled
-          // k loop exists only to make B[.][k] a register, not to widen the live range of fragments
-          __builtin_amdgcn_sched_barrier(0);
+        }
+        if constexpr (BM != B_ONE) {  // drain the pipeline
+#pragma unroll
+          for (int i = 0; i < 16; ++i) {
+            y[PM_NBS - 1][0][i] += pb0 * pu0[i];
+            y[PM_NBS - 1][1][i] += pb1 * pu1[i];
+          }
+          asm volatile("" : "+v"(y[PM_NBS - 1][0]), "+v"(y[PM_NBS - 1][1]));
         }
       }
 

@@ -90,6 +90,7 @@ struct BasisSrc {
   const float* vert;        // B_NORMAL
   const int32_t* facet;     // B_NORMAL: [R,3]
   const float* dirs;        // B_DIRS: [R,3]
+  const float* bvals;       // precomputed basis rows [R,K] (weight-gradient kernel)
   const int32_t* owner;     // optional (B_DIRS): basis scaled by 1/(seg_off[o+1]-seg_off[o]) -- unused when NULL
   const int32_t* seg_off;
   ShTable sh;

@@ -25,20 +25,106 @@ struct WgradP {
   int K, Cc, Cn;
   int KGn, CBP, NBP;   // slab decomposition
   int NKPW, RS;        // k-pairs per workgroup, row splits
-  BasisSrc bs;
+  BasisSrc bs;         // bs.bvals: precomputed basis rows [R][K] (unused for B_ONE)
   RowSrc xs, ys;
   float* partial;      // [n_part * RS][K][Cc][Cn]
 };
 
+// Eight consecutive channels of one source row as they sit in memory (no arithmetic yet, so that the
+// loads can stay in flight while the previous tile is being multiplied).
+struct Raw8 {
+  uint4 a, b;   // bf16 source: a holds the 8 values; fp32 source (or the slow path): a, b hold 8 floats
+  int f32;
+};
+
+__device__ __forceinline__ Raw8 raw_load8(const void* __restrict__ base, int is_bf16, int64_t row, int C, int c0,
+                                          bool valid) {
+  Raw8 r;
+  r.a = make_uint4(0, 0, 0, 0);
+  r.b = make_uint4(0, 0, 0, 0);
+  r.f32 = !is_bf16;
+  if (!valid) return r;
+  const int64_t off = row * (int64_t)C + c0;
+  if (c0 + 8 <= C) {
+    if (is_bf16) {
+      const uint16_t* p = (const uint16_t*)base + off;
+      if ((((uintptr_t)p) & 15) == 0) {
+        r.a = *(const uint4*)p;
+        return r;
+      }
+    } else {
+      const float* p = (const float*)base + off;
+      if ((((uintptr_t)p) & 15) == 0) {
+        r.a = ((const uint4*)p)[0];
+        r.b = ((const uint4*)p)[1];
+        return r;
+      }
+    }
+  }
+  float v[8];
+  load_vals<8>(base, is_bf16, row, C, c0, v);   // guarded element path
+  r.a = make_uint4(__float_as_uint(v[0]), __float_as_uint(v[1]), __float_as_uint(v[2]), __float_as_uint(v[3]));
+  r.b = make_uint4(__float_as_uint(v[4]), __float_as_uint(v[5]), __float_as_uint(v[6]), __float_as_uint(v[7]));
+  r.f32 = 1;
+  return r;
+}
+
+__device__ __forceinline__ void raw_to_f32(const Raw8& r, float (&v)[8]) {
+  if (r.f32) {
+    v[0] = __uint_as_float(r.a.x); v[1] = __uint_as_float(r.a.y); v[2] = __uint_as_float(r.a.z); v[3] = __uint_as_float(r.a.w);
+    v[4] = __uint_as_float(r.b.x); v[5] = __uint_as_float(r.b.y); v[6] = __uint_as_float(r.b.z); v[7] = __uint_as_float(r.b.w);
+  } else {
+    v[0] = bf16lo_to_f32(r.a.x); v[1] = bf16hi_to_f32(r.a.x); v[2] = bf16lo_to_f32(r.a.y); v[3] = bf16hi_to_f32(r.a.y);
+    v[4] = bf16lo_to_f32(r.a.z); v[5] = bf16hi_to_f32(r.a.z); v[6] = bf16lo_to_f32(r.a.w); v[7] = bf16hi_to_f32(r.a.w);
+  }
+}
+
+// number of source rows a mode reads per operand row
+template <int M> struct NSrc { static constexpr int n = (M == X_GATHER_SUM || M == X_GATHER_CAT) ? 3 : 1; };
+
+template <int M>
+__device__ __forceinline__ void raw_fetch(const RowSrc& s, int64_t r, bool ok, const RowMeta& m, int c0,
+                                          Raw8 (&raw)[NSrc<M>::n]) {
+  if constexpr (M == X_DIRECT) {
+    raw[0] = raw_load8(s.p, s.is_bf16, r, s.C, c0, ok);
+  } else if constexpr (M == X_GATHER1) {
+    raw[0] = raw_load8(s.p, s.is_bf16, m.id[0], s.C, c0, ok);
+  } else {
+#pragma unroll
+    for (int j = 0; j < 3; ++j) raw[j] = raw_load8(s.p, s.is_bf16, m.id[j], s.C, c0, ok);
+  }
+}
+
+// the operand values of Eq. 5's / Eq. 7's transposed sums from the raw rows
+template <int M>
+__device__ __forceinline__ void raw_combine(const Raw8 (&raw)[NSrc<M>::n], const RowMeta& m, float (&v)[8]) {
+  raw_to_f32(raw[0], v);
+  if constexpr (M == X_GATHER1) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) v[i] *= m.w[0];
+  } else if constexpr (M == X_GATHER_SUM) {
+    float t[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) v[i] *= m.w[0];
+    raw_to_f32(raw[1], t);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) v[i] += t[i] * m.w[1];
+    raw_to_f32(raw[2], t);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) v[i] += t[i] * m.w[2];
+  }
+}
+
 template <int DT, int BM, int XM, int YM>
 __global__ void __launch_bounds__(512) k_wgrad(WgradP p) {
   extern __shared__ uint4 lds_raw[];
-  constexpr int NSUBX = (XM == X_GATHER_CAT) ? 3 : 1;  // one X tile per corner
+  constexpr int NSUBX = (XM == X_GATHER_CAT) ? 3 : 1;        // one X tile per corner
   constexpr int XPB = (DT == 1) ? XP_BF16 * 2 : XP_F32 * 4;  // bytes per channel row of XT
+  constexpr int XT_BYTES = NSUBX * 64 * XPB;
+  constexpr int YT_BYTES = 64 * XP_F32 * 4;
+  constexpr int BS_BYTES = WG_KG * XP_F32 * 4;
+  constexpr int BUF_BYTES = XT_BYTES + YT_BYTES + BS_BYTES;
   char* lds = (char*)lds_raw;
-  char* XT = lds;                                   // [NSUBX][64][XPB]
-  float* YT = (float*)(lds + NSUBX * 64 * XPB);     // [64][XP_F32]
-  float* Bs = YT + 64 * XP_F32;                     // [WG_KG][XP_F32]
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, hh = lane >> 5;
   const int slab = blockIdx.y;
@@ -62,63 +148,105 @@ __global__ void __launch_bounds__(512) k_wgrad(WgradP p) {
 
   const int64_t rbeg = (int64_t)blockIdx.x * p.rows_per_part;
   const int64_t rend = min(p.R, rbeg + p.rows_per_part);
-  // staging role of this thread: row tid/8 of the tile, channels 8*(tid%8) .. +7 of the slab
-  const int srow = tid >> 3, soct = tid & 7;
 
-  for (int64_t t0 = rbeg; t0 < rend; t0 += WG_RT) {
-    const int64_t r = t0 + srow;
-    const bool ok = r < rend;
-    // ---- stage X (transposed) ----
-    {
-      RowMeta m;
-      load_meta<XM>(p.xs, r, ok, m);
+  // Staging role: wave w moves channel octet w (8 channels of X and of Y) of all 64 rows of a tile,
+  // lane = row.  The transposed LDS writes of a wave are then 64 consecutive elements of one channel
+  // row: conflict-free.  Waves 0..3 also move 4 basis values per row.
+  struct Pref {
+    Raw8 x[NSUBX][(XM == X_GATHER_CAT) ? 1 : NSrc<XM>::n];
+    Raw8 y[NSrc<YM>::n];
+    float4 bv;
+  };
+  struct Ids {
+    RowMeta mx, my;
+    bool ok;
+  };
+  auto load_ids = [&](int64_t t0, Ids& d) {
+    const int64_t r = t0 + lane;
+    d.ok = r < rend;
+    load_meta<XM>(p.xs, r, d.ok, d.mx);
+    load_meta<YM>(p.ys, r, d.ok, d.my);
+  };
+  auto load_data = [&](int64_t t0, const Ids& d, Pref& f) {
+    const int64_t r = t0 + lane;
+    if constexpr (XM == X_GATHER_CAT) {
 #pragma unroll
-      for (int sub = 0; sub < NSUBX; ++sub) {
-        float v[8];
-        if constexpr (XM == X_GATHER_CAT) {
-          if (ok) load_vals<8>(p.xs.p, p.xs.is_bf16, m.id[sub], p.xs.C, cbase + soct * 8, v);
-          else
-#pragma unroll
-            for (int i = 0; i < 8; ++i) v[i] = 0.f;
-        } else {
-          fetch_vals<XM, 8>(p.xs, r, ok, m, cbase + soct * 8, v);
-        }
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-          char* dst = XT + (sub * 64 + soct * 8 + i) * XPB;
-          if constexpr (DT == 1) ((uint16_t*)dst)[srow] = (uint16_t)f32_to_bf16_bits(v[i]);
-          else ((float*)dst)[srow] = v[i];
-        }
-      }
+      for (int sub = 0; sub < 3; ++sub)
+        f.x[sub][0] = raw_load8(p.xs.p, p.xs.is_bf16, d.mx.id[sub], p.xs.C, cbase + wave * 8, d.ok);
+    } else {
+      raw_fetch<XM>(p.xs, r, d.ok, d.mx, cbase + wave * 8, f.x[0]);
     }
-    // ---- stage Y (transposed, fp32) ----
-    {
-      RowMeta m;
-      load_meta<YM>(p.ys, r, ok, m);
-      float v[8];
-      fetch_vals<YM, 8>(p.ys, r, ok, m, nbase + soct * 8, v);
-#pragma unroll
-      for (int i = 0; i < 8; ++i) YT[(soct * 8 + i) * XP_F32 + srow] = v[i];
-    }
-    // ---- stage the basis values of this workgroup's k range ----
+    raw_fetch<YM>(p.ys, r, d.ok, d.my, nbase + wave * 8, f.y);
+    f.bv = make_float4(0.f, 0.f, 0.f, 0.f);
     if constexpr (BM != B_ONE) {
-      if (tid < WG_RT) {
-        const int64_t rr = t0 + tid;
-        if (rr < rend) {
-          float x, y, z;
-          row_direction<BM>(p.bs, rr, x, y, z);
-          sh_eval<-1>(x, y, z, p.bs.sh, [&](int k, float v) {
-            int kl = k - kbase;
-            if (kl >= 0 && kl < WG_KG) Bs[kl * XP_F32 + tid] = v;
-          });
+      if (wave < WG_KG / 4 && d.ok) {
+        const int k0 = kbase + wave * 4;
+        const float* src = p.bs.bvals + r * (int64_t)p.K + k0;
+        if (k0 + 4 <= p.K && (((uintptr_t)src) & 15) == 0) {
+          f.bv = *(const float4*)src;
         } else {
-          for (int kl = 0; kl < kcount; ++kl) Bs[kl * XP_F32 + tid] = 0.f;
+          if (k0 + 0 < p.K) f.bv.x = src[0];
+          if (k0 + 1 < p.K) f.bv.y = src[1];
+          if (k0 + 2 < p.K) f.bv.z = src[2];
+          if (k0 + 3 < p.K) f.bv.w = src[3];
         }
       }
     }
-    __syncthreads();
+  };
+  auto store_lds = [&](int buf, const Ids& d, const Pref& f) {
+    char* XT = lds + buf * BUF_BYTES;
+    float* YT = (float*)(XT + XT_BYTES);
+    float* Bs = YT + 64 * XP_F32;
+#pragma unroll
+    for (int sub = 0; sub < NSUBX; ++sub) {
+      float v[8];
+      if constexpr (XM == X_GATHER_CAT) raw_to_f32(f.x[sub][0], v);
+      else raw_combine<XM>(f.x[0], d.mx, v);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        char* dst = XT + (sub * 64 + wave * 8 + i) * XPB;
+        if constexpr (DT == 1) ((uint16_t*)dst)[lane] = (uint16_t)f32_to_bf16_bits(v[i]);
+        else ((float*)dst)[lane] = v[i];
+      }
+    }
+    {
+      float v[8];
+      raw_combine<YM>(f.y, d.my, v);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) YT[(wave * 8 + i) * XP_F32 + lane] = v[i];
+    }
+    if constexpr (BM != B_ONE) {
+      if (wave < WG_KG / 4) {
+        Bs[(wave * 4 + 0) * XP_F32 + lane] = f.bv.x;
+        Bs[(wave * 4 + 1) * XP_F32 + lane] = f.bv.y;
+        Bs[(wave * 4 + 2) * XP_F32 + lane] = f.bv.z;
+        Bs[(wave * 4 + 3) * XP_F32 + lane] = f.bv.w;
+      }
+    }
+  };
 
-    // ---- accumulate ----
+  Ids ids_cur, ids_nxt;
+  Pref pref;
+  if (rbeg < rend) {
+    load_ids(rbeg, ids_cur);
+    load_data(rbeg, ids_cur, pref);
+    load_ids(rbeg + WG_RT, ids_nxt);
+    store_lds(0, ids_cur, pref);
+  }
+  __syncthreads();
+
+  int buf = 0;
+  for (int64_t t0 = rbeg; t0 < rend; t0 += WG_RT, buf ^= 1) {
+    const bool have_next = t0 + WG_RT < rend;
+    // global loads of the next tile go out now and land while this tile is multiplied;
+    // the gather ids of the tile after that are fetched one step earlier still
+    if (have_next) load_data(t0 + WG_RT, ids_nxt, pref);
+    Ids ids_nn;
+    load_ids(t0 + 2 * WG_RT, ids_nn);
+
+    const char* XT = lds + buf * BUF_BYTES;
+    const float* YT = (const float*)(XT + XT_BYTES);
+    const float* Bs = YT + 64 * XP_F32;
     if (active) {
       if constexpr (DT == 1) {
         for (int ss = rs; ss < WG_RT / 16; ss += p.RS) {
@@ -210,7 +338,10 @@ __global__ void __launch_bounds__(512) k_wgrad(WgradP p) {
         }
       }
     }
+    // the other buffer was last read one iteration ago (a barrier has passed since): refill it
+    if (have_next) store_lds(buf ^ 1, ids_nxt, pref);
     __syncthreads();
+    ids_nxt = ids_nn;
   }
 
   // ---- write this wave's partial sums ----
@@ -283,7 +414,7 @@ static pm_status launch_wgrad_inst(const WgradP& p, const WgradGeom& g, hipStrea
   auto kern = k_wgrad<DT, BM, XM, YM>;
   const int nsub = (XM == X_GATHER_CAT) ? 3 : 1;
   const int xpb = (DT == 1) ? XP_BF16 * 2 : XP_F32 * 4;
-  size_t lds = (size_t)nsub * 64 * xpb + (size_t)64 * XP_F32 * 4 + (size_t)WG_KG * XP_F32 * 4;
+  size_t lds = 2 * ((size_t)nsub * 64 * xpb + (size_t)64 * XP_F32 * 4 + (size_t)WG_KG * XP_F32 * 4);
   PM_CHECK_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
   { ProfScope ps__(st, "k_wgrad");
     hipLaunchKernelGGL(kern, dim3((unsigned)g.n_part, (unsigned)g.slabs), dim3(512), lds, st, p); }
