@@ -54,28 +54,58 @@ __device__ __forceinline__ void load_vals(const void* __restrict__ base, int is_
 struct RowMeta {
   int32_t id[3];  // X_GATHER_SUM / X_GATHER_CAT: corner vertex ids;  X_GATHER1: id[0] = owner
   float w[3];     // X_GATHER_SUM: 1/deg(v_j);  X_GATHER1: w[0] = 1/segment length
+  int32_t lo[3], hi[3];  // raw CSR bounds the weights come from (set by load_meta_w, used by meta_finish)
 };
 
+// Two phases, so that a software pipeline can issue them in different iterations: the ids (one load,
+// no dependency) and the weights (loads that depend on the ids).
 template <int XM>
-__device__ __forceinline__ void load_meta(const RowSrc& s, int64_t r, bool valid, RowMeta& m) {
+__device__ __forceinline__ void load_meta_ids(const RowSrc& s, int64_t r, bool valid, RowMeta& m) {
   m.id[0] = m.id[1] = m.id[2] = 0;
   m.w[0] = m.w[1] = m.w[2] = 0.f;
   if (!valid) return;
   if constexpr (XM == X_GATHER_SUM || XM == X_GATHER_CAT) {
 #pragma unroll
     for (int j = 0; j < 3; ++j) m.id[j] = s.facet[3 * r + j];
-    if constexpr (XM == X_GATHER_SUM) {
+  } else if constexpr (XM == X_GATHER1) {
+    m.id[0] = s.owner[r];
+  }
+}
+
+// loads only (no arithmetic on the loaded values, so nothing forces an early wait)
+template <int XM>
+__device__ __forceinline__ void load_meta_w(const RowSrc& s, bool valid, RowMeta& m) {
 #pragma unroll
-      for (int j = 0; j < 3; ++j) {
-        int32_t d = s.row_ptr[m.id[j] + 1] - s.row_ptr[m.id[j]];
-        m.w[j] = 1.0f / (float)d;  // d >= 1: the vertex is referenced by this very facet
-      }
+  for (int j = 0; j < 3; ++j) { m.lo[j] = 0; m.hi[j] = 1; }
+  if (!valid) return;
+  if constexpr (XM == X_GATHER_SUM) {
+#pragma unroll
+    for (int j = 0; j < 3; ++j) {
+      m.lo[j] = s.row_ptr[m.id[j]];
+      m.hi[j] = s.row_ptr[m.id[j] + 1];
     }
   } else if constexpr (XM == X_GATHER1) {
-    int32_t o = s.owner[r];
-    m.id[0] = o;
-    m.w[0] = 1.0f / (float)(s.seg_off[o + 1] - s.seg_off[o]);
+    m.lo[0] = s.seg_off[m.id[0]];
+    m.hi[0] = s.seg_off[m.id[0] + 1];
   }
+}
+
+// weights from the CSR bounds: 1/deg(v_j) (>= 1: the vertex is referenced by this very facet), 1/R_f
+template <int XM>
+__device__ __forceinline__ void meta_finish(RowMeta& m) {
+  if constexpr (XM == X_GATHER_SUM) {
+#pragma unroll
+    for (int j = 0; j < 3; ++j) m.w[j] = 1.0f / (float)(m.hi[j] - m.lo[j]);
+  } else if constexpr (XM == X_GATHER1) {
+    m.w[0] = 1.0f / (float)(m.hi[0] - m.lo[0]);
+  }
+}
+
+template <int XM>
+__device__ __forceinline__ void load_meta(const RowSrc& s, int64_t r, bool valid, RowMeta& m) {
+  load_meta_ids<XM>(s, r, valid, m);
+  load_meta_w<XM>(s, valid, m);
+  meta_finish<XM>(m);
 }
 
 // N consecutive channels [c0, c0+N) of the (virtual) operand row r, as floats.

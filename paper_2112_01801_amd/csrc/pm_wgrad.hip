@@ -69,6 +69,25 @@ __device__ __forceinline__ Raw8 raw_load8(const void* __restrict__ base, int is_
   return r;
 }
 
+// Fast path (host-checked): source dtype == DT, 16-byte aligned rows, octet inside the row.  No branches,
+// so the loads of a whole tile can be in flight together.
+template <int DT>
+__device__ __forceinline__ Raw8 raw_load8_fast(const void* __restrict__ base, int64_t row, int C, int c0) {
+  Raw8 r;
+  const int64_t off = row * (int64_t)C + c0;
+  if constexpr (DT == 1) {
+    r.a = *(const uint4*)((const uint16_t*)base + off);
+    r.b = make_uint4(0, 0, 0, 0);
+    r.f32 = 0;
+  } else {
+    const uint4* p = (const uint4*)((const float*)base + off);
+    r.a = p[0];
+    r.b = p[1];
+    r.f32 = 1;
+  }
+  return r;
+}
+
 __device__ __forceinline__ void raw_to_f32(const Raw8& r, float (&v)[8]) {
   if (r.f32) {
     v[0] = __uint_as_float(r.a.x); v[1] = __uint_as_float(r.a.y); v[2] = __uint_as_float(r.a.z); v[3] = __uint_as_float(r.a.w);
@@ -82,9 +101,20 @@ __device__ __forceinline__ void raw_to_f32(const Raw8& r, float (&v)[8]) {
 // number of source rows a mode reads per operand row
 template <int M> struct NSrc { static constexpr int n = (M == X_GATHER_SUM || M == X_GATHER_CAT) ? 3 : 1; };
 
-template <int M>
+template <int M, int DT, bool FAST>
 __device__ __forceinline__ void raw_fetch(const RowSrc& s, int64_t r, bool ok, const RowMeta& m, int c0,
                                           Raw8 (&raw)[NSrc<M>::n]) {
+  if constexpr (FAST) {
+    if constexpr (M == X_DIRECT) {
+      raw[0] = raw_load8_fast<DT>(s.p, r, s.C, c0);
+    } else if constexpr (M == X_GATHER1) {
+      raw[0] = raw_load8_fast<DT>(s.p, m.id[0], s.C, c0);
+    } else {
+#pragma unroll
+      for (int j = 0; j < 3; ++j) raw[j] = raw_load8_fast<DT>(s.p, m.id[j], s.C, c0);
+    }
+    return;
+  }
   if constexpr (M == X_DIRECT) {
     raw[0] = raw_load8(s.p, s.is_bf16, r, s.C, c0, ok);
   } else if constexpr (M == X_GATHER1) {
@@ -115,7 +145,7 @@ __device__ __forceinline__ void raw_combine(const Raw8 (&raw)[NSrc<M>::n], const
   }
 }
 
-template <int DT, int BM, int XM, int YM>
+template <int DT, int BM, int XM, int YM, bool FAST>
 __global__ void __launch_bounds__(512) k_wgrad(WgradP p) {
   extern __shared__ uint4 lds_raw[];
   constexpr int NSUBX = (XM == X_GATHER_CAT) ? 3 : 1;        // one X tile per corner
@@ -161,25 +191,41 @@ __global__ void __launch_bounds__(512) k_wgrad(WgradP p) {
     RowMeta mx, my;
     bool ok;
   };
+  // On the fast path rows past the end are clamped to the last row (so every load is unconditional and
+  // in bounds) and zeroed when they are written to LDS.
+  auto row_of = [&](int64_t t0) { return FAST ? min(t0 + lane, rend - 1) : t0 + lane; };
   auto load_ids = [&](int64_t t0, Ids& d) {
-    const int64_t r = t0 + lane;
-    d.ok = r < rend;
-    load_meta<XM>(p.xs, r, d.ok, d.mx);
-    load_meta<YM>(p.ys, r, d.ok, d.my);
+    const int64_t r = row_of(t0);
+    d.ok = t0 + lane < rend;
+    const bool go = FAST ? true : d.ok;
+    load_meta_ids<XM>(p.xs, r, go, d.mx);
+    load_meta_ids<YM>(p.ys, r, go, d.my);
+  };
+  auto load_w = [&](Ids& d) {   // loads that depend on the ids: issued one pipeline step after them
+    const bool go = FAST ? true : d.ok;
+    load_meta_w<XM>(p.xs, go, d.mx);
+    load_meta_w<YM>(p.ys, go, d.my);
   };
   auto load_data = [&](int64_t t0, const Ids& d, Pref& f) {
-    const int64_t r = t0 + lane;
+    const int64_t r = row_of(t0);
     if constexpr (XM == X_GATHER_CAT) {
 #pragma unroll
-      for (int sub = 0; sub < 3; ++sub)
-        f.x[sub][0] = raw_load8(p.xs.p, p.xs.is_bf16, d.mx.id[sub], p.xs.C, cbase + wave * 8, d.ok);
+      for (int sub = 0; sub < 3; ++sub) {
+        if constexpr (FAST) f.x[sub][0] = raw_load8_fast<DT>(p.xs.p, d.mx.id[sub], p.xs.C, cbase + wave * 8);
+        else f.x[sub][0] = raw_load8(p.xs.p, p.xs.is_bf16, d.mx.id[sub], p.xs.C, cbase + wave * 8, d.ok);
+      }
     } else {
-      raw_fetch<XM>(p.xs, r, d.ok, d.mx, cbase + wave * 8, f.x[0]);
+      raw_fetch<XM, DT, FAST>(p.xs, r, d.ok, d.mx, cbase + wave * 8, f.x[0]);
     }
-    raw_fetch<YM>(p.ys, r, d.ok, d.my, nbase + wave * 8, f.y);
+    raw_fetch<YM, DT, FAST>(p.ys, r, d.ok, d.my, nbase + wave * 8, f.y);
     f.bv = make_float4(0.f, 0.f, 0.f, 0.f);
     if constexpr (BM != B_ONE) {
-      if (wave < WG_KG / 4 && d.ok) {
+      if constexpr (FAST) {
+        // host guarantees K % 4 == 0: one aligned 16-byte load, unconditional (waves without a k range
+        // read a clamped address and drop the value when the tile is written to LDS)
+        const int k0 = min(kbase + (wave & 3) * 4, p.K - 4);
+        f.bv = *(const float4*)(p.bs.bvals + r * (int64_t)p.K + k0);
+      } else if (wave < WG_KG / 4 && d.ok) {
         const int k0 = kbase + wave * 4;
         const float* src = p.bs.bvals + r * (int64_t)p.K + k0;
         if (k0 + 4 <= p.K && (((uintptr_t)src) & 15) == 0) {
@@ -193,7 +239,9 @@ __global__ void __launch_bounds__(512) k_wgrad(WgradP p) {
       }
     }
   };
-  auto store_lds = [&](int buf, const Ids& d, const Pref& f) {
+  auto store_lds = [&](int buf, Ids& d, const Pref& f) {
+    meta_finish<XM>(d.mx);
+    meta_finish<YM>(d.my);
     char* XT = lds + buf * BUF_BYTES;
     float* YT = (float*)(XT + XT_BYTES);
     float* Bs = YT + 64 * XP_F32;
@@ -202,6 +250,10 @@ __global__ void __launch_bounds__(512) k_wgrad(WgradP p) {
       float v[8];
       if constexpr (XM == X_GATHER_CAT) raw_to_f32(f.x[sub][0], v);
       else raw_combine<XM>(f.x[0], d.mx, v);
+      if constexpr (FAST) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) v[i] = d.ok ? v[i] : 0.f;
+      }
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
         char* dst = XT + (sub * 64 + wave * 8 + i) * XPB;
@@ -212,15 +264,23 @@ __global__ void __launch_bounds__(512) k_wgrad(WgradP p) {
     {
       float v[8];
       raw_combine<YM>(f.y, d.my, v);
+      if constexpr (FAST) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) v[i] = d.ok ? v[i] : 0.f;
+      }
 #pragma unroll
       for (int i = 0; i < 8; ++i) YT[(wave * 8 + i) * XP_F32 + lane] = v[i];
     }
     if constexpr (BM != B_ONE) {
       if (wave < WG_KG / 4) {
-        Bs[(wave * 4 + 0) * XP_F32 + lane] = f.bv.x;
-        Bs[(wave * 4 + 1) * XP_F32 + lane] = f.bv.y;
-        Bs[(wave * 4 + 2) * XP_F32 + lane] = f.bv.z;
-        Bs[(wave * 4 + 3) * XP_F32 + lane] = f.bv.w;
+        float4 bv = f.bv;
+        if constexpr (FAST) {
+          if (!d.ok || kbase + wave * 4 >= p.K) bv = make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+        Bs[(wave * 4 + 0) * XP_F32 + lane] = bv.x;
+        Bs[(wave * 4 + 1) * XP_F32 + lane] = bv.y;
+        Bs[(wave * 4 + 2) * XP_F32 + lane] = bv.z;
+        Bs[(wave * 4 + 3) * XP_F32 + lane] = bv.w;
       }
     }
   };
@@ -229,6 +289,7 @@ __global__ void __launch_bounds__(512) k_wgrad(WgradP p) {
   Pref pref;
   if (rbeg < rend) {
     load_ids(rbeg, ids_cur);
+    load_w(ids_cur);
     load_data(rbeg, ids_cur, pref);
     load_ids(rbeg + WG_RT, ids_nxt);
     store_lds(0, ids_cur, pref);
@@ -240,9 +301,13 @@ __global__ void __launch_bounds__(512) k_wgrad(WgradP p) {
     const bool have_next = t0 + WG_RT < rend;
     // global loads of the next tile go out now and land while this tile is multiplied;
     // the gather ids of the tile after that are fetched one step earlier still
-    if (have_next) load_data(t0 + WG_RT, ids_nxt, pref);
+    if (have_next) {
+      load_w(ids_nxt);
+      load_data(t0 + WG_RT, ids_nxt, pref);
+    }
     Ids ids_nn;
     load_ids(t0 + 2 * WG_RT, ids_nn);
+    __builtin_amdgcn_sched_barrier(0);  // everything above is loads only: nothing may wait on them yet
 
     const char* XT = lds + buf * BUF_BYTES;
     const float* YT = (const float*)(XT + XT_BYTES);
@@ -338,6 +403,7 @@ __global__ void __launch_bounds__(512) k_wgrad(WgradP p) {
         }
       }
     }
+    __builtin_amdgcn_sched_barrier(0);
     // the other buffer was last read one iteration ago (a barrier has passed since): refill it
     if (have_next) store_lds(buf ^ 1, ids_nxt, pref);
     __syncthreads();
@@ -409,9 +475,9 @@ size_t pm_wgrad_ws_bytes(int64_t R, int K, int Cc, int Cn) {
   return pm_round_up((size_t)g.n_part * g.RS * K * Cc * Cn * sizeof(float), 256);
 }
 
-template <int DT, int BM, int XM, int YM>
-static pm_status launch_wgrad_inst(const WgradP& p, const WgradGeom& g, hipStream_t st) {
-  auto kern = k_wgrad<DT, BM, XM, YM>;
+template <int DT, int BM, int XM, int YM, bool FAST>
+static pm_status launch_wgrad_fast(const WgradP& p, const WgradGeom& g, hipStream_t st) {
+  auto kern = k_wgrad<DT, BM, XM, YM, FAST>;
   const int nsub = (XM == X_GATHER_CAT) ? 3 : 1;
   const int xpb = (DT == 1) ? XP_BF16 * 2 : XP_F32 * 4;
   size_t lds = 2 * ((size_t)nsub * 64 * xpb + (size_t)64 * XP_F32 * 4 + (size_t)WG_KG * XP_F32 * 4);
@@ -420,6 +486,20 @@ static pm_status launch_wgrad_inst(const WgradP& p, const WgradGeom& g, hipStrea
     hipLaunchKernelGGL(kern, dim3((unsigned)g.n_part, (unsigned)g.slabs), dim3(512), lds, st, p); }
   PM_CHECK_LAUNCH("k_wgrad");
   return PM_OK;
+}
+
+// The branch-free loaders need: storage dtype == MFMA dtype, 16-byte aligned rows, every 64-channel slab
+// inside the row, and (with a basis) K a multiple of 4.
+template <int DT, int BM, int XM, int YM>
+static pm_status launch_wgrad_inst(const WgradP& p, const WgradGeom& g, hipStream_t st) {
+  const int esz = (DT == 1) ? 2 : 4;
+  bool fast = (p.xs.is_bf16 == (DT == 1)) && (p.ys.is_bf16 == (DT == 1));
+  fast = fast && (p.Cc % 64 == 0) && (p.Cn % 64 == 0) && (p.xs.C % 8 == 0) && (p.ys.C % 8 == 0);
+  fast = fast && ((p.xs.C * esz) % 16 == 0) && ((p.ys.C * esz) % 16 == 0);
+  fast = fast && pm_aligned16(p.xs.p) && pm_aligned16(p.ys.p);
+  if (BM != B_ONE) fast = fast && (p.K % 4 == 0) && pm_aligned16(p.bs.bvals);
+  if (fast) return launch_wgrad_fast<DT, BM, XM, YM, true>(p, g, st);
+  return launch_wgrad_fast<DT, BM, XM, YM, false>(p, g, st);
 }
 
 template <int DT>
