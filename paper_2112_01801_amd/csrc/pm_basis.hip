@@ -50,16 +50,25 @@ void pm_corner_basis(int L, pm_sh_norm norm, double Bc[3][PM_MAX_K]) {
   }
 }
 
+template <int LT>
 __global__ void __launch_bounds__(256) k_basis_mesh(int64_t F, const float* __restrict__ vert,
                                                     const int32_t* __restrict__ facet, ShTable T,
                                                     float* __restrict__ basis) {
   int64_t f = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (f >= F) return;
-  const int K = (T.L + 1) * (T.L + 1);
+  constexpr int K = (LT + 1) * (LT + 1);
   float nx, ny, nz;
   facet_normal(vert, facet[3 * f], facet[3 * f + 1], facet[3 * f + 2], nx, ny, nz);
+  float B[K];
+  sh_eval<LT>(nx, ny, nz, T, [&](int k, float v) { B[k] = v; });
   float* out = basis + f * K;
-  sh_eval<-1>(nx, ny, nz, T, [&](int k, float v) { out[k] = v; });
+  if constexpr (K % 4 == 0) {   // a row is a whole number of 16-byte pieces: vector stores
+#pragma unroll
+    for (int q = 0; q < K / 4; ++q) ((float4*)out)[q] = make_float4(B[4 * q], B[4 * q + 1], B[4 * q + 2], B[4 * q + 3]);
+  } else {
+#pragma unroll
+    for (int k = 0; k < K; ++k) out[k] = B[k];
+  }
 }
 
 __global__ void __launch_bounds__(256) k_basis_dirs(int64_t n, const float* __restrict__ dirs, ShTable T,
@@ -133,8 +142,15 @@ static inline unsigned nblocks(int64_t n, int b) { return (unsigned)((n + b - 1)
 pm_status pm_launch_basis_mesh(const pm_mesh* mesh, const ShTable& T, float* basis, hipStream_t st) {
   if (mesh->n_facet == 0) return PM_OK;
   { ProfScope ps__(st, "k_basis_mesh");
-    hipLaunchKernelGGL(k_basis_mesh, dim3(nblocks(mesh->n_facet, 256)), dim3(256), 0, st, mesh->n_facet, mesh->vert,
-                     mesh->facet, T, basis); }
+    const dim3 grid(nblocks(mesh->n_facet, 256)), block(256);
+    switch (T.L) {
+      case 0: hipLaunchKernelGGL(k_basis_mesh<0>, grid, block, 0, st, mesh->n_facet, mesh->vert, mesh->facet, T, basis); break;
+      case 1: hipLaunchKernelGGL(k_basis_mesh<1>, grid, block, 0, st, mesh->n_facet, mesh->vert, mesh->facet, T, basis); break;
+      case 2: hipLaunchKernelGGL(k_basis_mesh<2>, grid, block, 0, st, mesh->n_facet, mesh->vert, mesh->facet, T, basis); break;
+      case 3: hipLaunchKernelGGL(k_basis_mesh<3>, grid, block, 0, st, mesh->n_facet, mesh->vert, mesh->facet, T, basis); break;
+      case 4: hipLaunchKernelGGL(k_basis_mesh<4>, grid, block, 0, st, mesh->n_facet, mesh->vert, mesh->facet, T, basis); break;
+      default: hipLaunchKernelGGL(k_basis_mesh<5>, grid, block, 0, st, mesh->n_facet, mesh->vert, mesh->facet, T, basis); break;
+    } }
   PM_CHECK_LAUNCH("k_basis_mesh");
   return PM_OK;
 }

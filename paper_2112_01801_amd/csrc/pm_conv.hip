@@ -150,6 +150,7 @@ pm_status pm_launch_conv_rows(pm_dtype mt, BMode bm, XMode xm, int64_t R, int K,
   p.R = R; p.Cc = Cc; p.Cn = Cn; p.NCH = g.NCH; p.NBG = g.NBG;
   p.resident = pm_pack_bytes(g) <= lds_resident_max();
   p.bs = bs; p.xs = xs; p.apack = (const uint4*)apack; p.out = out; p.out_bf16 = out_is_bf16;
+  p.store_fast = (Cn % (PM_NBS * 32) == 0) && pm_aligned16(out);
   const int L = (bm == B_ONE) ? 0 : bs.sh.L;
   const int dt = (mt == PM_BF16) ? 1 : 0;
   PM_CONV_CASE(0, B_NORMAL, X_DIRECT)

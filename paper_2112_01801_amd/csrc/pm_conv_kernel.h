@@ -16,6 +16,7 @@ struct ConvP {
   const uint4* apack;
   void* out;
   int out_bf16;
+  int store_fast;        // Cn % 64 == 0 and the output rows are 16-byte aligned: unguarded vector stores
 };
 
 template <int DT>
@@ -46,7 +47,62 @@ __device__ __forceinline__ floatx16 mma_group(uint4 a, uint4 x, floatx16 c) {
   }
 }
 
-template <int DT, int BM, int XM, int LT, int NW, bool RES>
+// Fast path of the operand fetch (conditions checked on the host: storage dtype == MFMA dtype, rows
+// 16-byte aligned, every granule inside its row).  Straight-line code in two halves -- loads only, then
+// arithmetic -- so that the loads of a whole tile can be in flight while the previous tile is multiplied.
+// `rowc` is a row index clamped into range; rows past the end are masked at the store.
+template <int XM> struct NRaw { static constexpr int n = (XM == X_GATHER_SUM) ? 3 : 1; };
+
+template <int XM, int DT>
+__device__ __forceinline__ void granule_load(const RowSrc& s, int64_t rowc, const RowMeta& m, int c0,
+                                             uint4 (&raw)[NRaw<XM>::n]) {
+  constexpr int ESZ = (DT == 1) ? 2 : 4;
+  const char* base = (const char*)s.p;
+  if constexpr (XM == X_DIRECT) {
+    raw[0] = *(const uint4*)(base + (rowc * (int64_t)s.C + c0) * ESZ);
+  } else if constexpr (XM == X_GATHER_CAT) {
+    const int j = c0 / s.C, cc = c0 - j * s.C;
+    const int32_t id = (j == 0) ? m.id[0] : (j == 1 ? m.id[1] : m.id[2]);
+    raw[0] = *(const uint4*)(base + ((int64_t)id * s.C + cc) * ESZ);
+  } else {
+#pragma unroll
+    for (int j = 0; j < NRaw<XM>::n; ++j) raw[j] = *(const uint4*)(base + ((int64_t)m.id[j] * s.C + c0) * ESZ);
+  }
+}
+
+template <int XM, int DT>
+__device__ __forceinline__ uint4 granule_finish(const uint4 (&raw)[NRaw<XM>::n], const RowMeta& m) {
+  if constexpr (XM == X_DIRECT || XM == X_GATHER_CAT) {
+    return raw[0];   // storage format == operand format
+  } else {
+    constexpr int EPG = (DT == 1) ? 8 : 4;
+    float acc[EPG];
+#pragma unroll
+    for (int j = 0; j < NRaw<XM>::n; ++j) {
+      float t[EPG];
+      if constexpr (DT == 1) {
+        t[0] = bf16lo_to_f32(raw[j].x); t[1] = bf16hi_to_f32(raw[j].x); t[2] = bf16lo_to_f32(raw[j].y);
+        t[3] = bf16hi_to_f32(raw[j].y); t[4] = bf16lo_to_f32(raw[j].z); t[5] = bf16hi_to_f32(raw[j].z);
+        t[6] = bf16lo_to_f32(raw[j].w); t[7] = bf16hi_to_f32(raw[j].w);
+      } else {
+        t[0] = __uint_as_float(raw[j].x); t[1] = __uint_as_float(raw[j].y);
+        t[2] = __uint_as_float(raw[j].z); t[3] = __uint_as_float(raw[j].w);
+      }
+#pragma unroll
+      for (int i = 0; i < EPG; ++i) acc[i] = (j == 0) ? t[i] * m.w[0] : acc[i] + t[i] * m.w[j];
+    }
+    return pack_granule<DT>(acc);
+  }
+}
+
+template <int XM, int DT>
+__device__ __forceinline__ uint4 fetch_granule_fast(const RowSrc& s, int64_t rowc, const RowMeta& m, int c0) {
+  uint4 raw[NRaw<XM>::n];
+  granule_load<XM, DT>(s, rowc, m, c0, raw);
+  return granule_finish<XM, DT>(raw, m);
+}
+
+template <int DT, int BM, int XM, int LT, int NW, bool RES, bool FAST>
 __global__ void __launch_bounds__(NW * 64) k_conv_rows(ConvP p) {
   extern __shared__ uint4 lds[];
   constexpr int K = (BM == B_ONE) ? 1 : (LT + 1) * (LT + 1);
@@ -67,187 +123,315 @@ __global__ void __launch_bounds__(NW * 64) k_conv_rows(ConvP p) {
     __syncthreads();
   }
 
+  // Fast path: a two-deep software pipeline over the tiles of this workgroup.  While tile t is multiplied,
+  // the row data of tile t+1 (operand rows, corner positions, CSR bounds) is already in flight, and the
+  // ids those loads needed were fetched one tile earlier still.  Arithmetic on the loaded values is
+  // deferred to the top of the tile that uses them, so nothing waits on memory inside the MFMA loop.
+  struct TileRaw {
+    int32_t gid[2][3];
+    RowMeta meta[2];
+    DirRaw dr[2];
+    uint4 xr[2][PM_GC][NRaw<XM>::n];
+  };
+  auto rows_of = [&](int64_t ti_, int fb) {
+    const int64_t t_ = (int64_t)xcd * tpx + ti_;
+    return min(t_ * NT + wave * 64 + fb * 32 + l32, p.R - 1);   // clamped: loads are unconditional
+  };
+  auto issue_ids = [&](int64_t ti_, TileRaw& t) {
+#pragma unroll
+    for (int fb = 0; fb < 2; ++fb) {
+      const int64_t rc = rows_of(ti_, fb);
+      dir_ids<BM>(p.bs, rc, t.gid[fb]);
+      load_meta_ids<XM>(p.xs, rc, true, t.meta[fb]);
+    }
+  };
+  auto issue_loads = [&](int64_t ti_, TileRaw& t) {
+#pragma unroll
+    for (int fb = 0; fb < 2; ++fb) {
+      const int64_t rc = rows_of(ti_, fb);
+      if constexpr (BM != B_ONE) dir_load<BM>(p.bs, rc, t.gid[fb], t.dr[fb]);
+      load_meta_w<XM>(p.xs, true, t.meta[fb]);
+#pragma unroll
+      for (int g = 0; g < PM_GC; ++g) granule_load<XM, DT>(p.xs, rc, t.meta[fb], (g * 2 + hh) * EPG, t.xr[fb][g]);
+    }
+  };
+  TileRaw cur, nxt;
+  if constexpr (FAST) {
+    issue_ids(slot, cur);
+    issue_loads(slot, cur);
+    issue_ids(slot + wg_per_xcd, nxt);
+  }
+
   for (int64_t ti = slot; ti < tpx; ti += wg_per_xcd) {
     const int64_t tile = (int64_t)xcd * tpx + ti;
     const bool tile_ok = tile < n_tiles;
     const int64_t r0 = tile * NT + wave * 64;
-    int64_t row[2];
+    int64_t row[2], rowc[2];
     bool ok[2];
     RowMeta meta[2];
     float B[2][K];
+    uint4 X0[2][PM_GC];  // fast path: first chunk of the operand rows
 #pragma unroll
     for (int fb = 0; fb < 2; ++fb) {
       row[fb] = r0 + fb * 32 + l32;
       ok[fb] = tile_ok && row[fb] < p.R;
-      load_meta<XM>(p.xs, row[fb], ok[fb], meta[fb]);
-      if constexpr (BM != B_ONE) {
-        float x = 0.f, y = 0.f, z = 1.f;
-        if (ok[fb]) row_direction<BM>(p.bs, row[fb], x, y, z);
-        sh_eval<LT>(x, y, z, p.bs.sh, [&](int k, float v) { B[fb][k] = v; });
-      } else {
-        B[fb][0] = 1.f;
+      rowc[fb] = FAST ? min(row[fb], p.R - 1) : row[fb];
+    }
+    if constexpr (FAST) {
+      // arithmetic on this tile's data (loaded during the previous tile)
+#pragma unroll
+      for (int fb = 0; fb < 2; ++fb) {
+        meta[fb] = cur.meta[fb];
+        meta_finish<XM>(meta[fb]);
+        if constexpr (BM != B_ONE) {
+          float x, y, z;
+          dir_finish<BM>(cur.dr[fb], x, y, z);
+          sh_eval<LT>(x, y, z, p.bs.sh, [&](int k, float v) { B[fb][k] = v; });
+        } else {
+          B[fb][0] = 1.f;
+        }
+#pragma unroll
+        for (int g = 0; g < PM_GC; ++g) X0[fb][g] = granule_finish<XM, DT>(cur.xr[fb][g], meta[fb]);
+      }
+      // next tile: its ids are here, send out everything that depends on them; then the ids after that
+      __builtin_amdgcn_sched_barrier(0);
+      issue_loads(ti + wg_per_xcd, nxt);
+      cur = nxt;
+      issue_ids(ti + 2 * wg_per_xcd, nxt);
+      __builtin_amdgcn_sched_barrier(0);
+    } else {
+#pragma unroll
+      for (int fb = 0; fb < 2; ++fb) {
+        load_meta<XM>(p.xs, rowc[fb], ok[fb], meta[fb]);
+        if constexpr (BM != B_ONE) {
+          float x = 0.f, y = 0.f, z = 1.f;
+          if (ok[fb]) row_direction<BM>(p.bs, rowc[fb], x, y, z);
+          sh_eval<LT>(x, y, z, p.bs.sh, [&](int k, float v) { B[fb][k] = v; });
+        } else {
+          B[fb][0] = 1.f;
+        }
       }
     }
 
-    if constexpr (!RES) {  // prologue of the weight stream for this tile
+    // ---- helpers shared by the two loop orders -----------------------------------------------------
+    auto fetch_chunk = [&](int ch, uint4 (&X)[2][PM_GC]) {
+#pragma unroll
+      for (int fb = 0; fb < 2; ++fb)
+#pragma unroll
+        for (int g = 0; g < PM_GC; ++g) {
+          const int c0 = ((ch * PM_GC + g) * 2 + hh) * EPG;
+          if constexpr (FAST) {
+            if (ch == 0) X[fb][g] = X0[fb][g];
+            else X[fb][g] = fetch_granule_fast<XM, DT>(p.xs, rowc[fb], meta[fb], c0);
+          } else {
+            float v[EPG];
+            fetch_vals<XM, EPG>(p.xs, row[fb], ok[fb], meta[fb], c0, v);
+            X[fb][g] = pack_granule<DT>(v);
+          }
+        }
+    };
+    // one 32-wide block nb of output channels of row block fb
+    auto store_block = [&](int nb, int fb, const floatx16& yv) {
+      if (!ok[fb]) return;
+      if (p.store_fast) {   // Cn % 64 == 0, aligned rows: unguarded 16-byte (fp32) / 8-byte (bf16) pieces
+        const int64_t o = row[fb] * (int64_t)p.Cn + nb * 32 + hh * 4;
+        if (p.out_bf16) {
+          uint16_t* dst = (uint16_t*)p.out + o;
+#pragma unroll
+          for (int q4 = 0; q4 < 4; ++q4) {
+            uint2 w;
+            w.x = pack_bf16x2(yv[q4 * 4], yv[q4 * 4 + 1]);
+            w.y = pack_bf16x2(yv[q4 * 4 + 2], yv[q4 * 4 + 3]);
+            *(uint2*)(dst + q4 * 8) = w;
+          }
+        } else {
+          float* dst = (float*)p.out + o;
+#pragma unroll
+          for (int q4 = 0; q4 < 4; ++q4)
+            *(float4*)(dst + q4 * 8) = make_float4(yv[q4 * 4], yv[q4 * 4 + 1], yv[q4 * 4 + 2], yv[q4 * 4 + 3]);
+        }
+        return;
+      }
+#pragma unroll
+      for (int q4 = 0; q4 < 4; ++q4) {
+        const int n0 = nb * 32 + q4 * 8 + hh * 4;
+        if (n0 >= p.Cn) continue;
+        const float vv[4] = {yv[q4 * 4], yv[q4 * 4 + 1], yv[q4 * 4 + 2], yv[q4 * 4 + 3]};
+        const int64_t o = row[fb] * (int64_t)p.Cn + n0;
+        if (n0 + 4 <= p.Cn && (p.Cn & 3) == 0) {
+          if (p.out_bf16) {
+            uint2 w;
+            w.x = pack_bf16x2(vv[0], vv[1]); w.y = pack_bf16x2(vv[2], vv[3]);
+            *(uint2*)((uint16_t*)p.out + o) = w;
+          } else {
+            *(float4*)((float*)p.out + o) = make_float4(vv[0], vv[1], vv[2], vv[3]);
+          }
+        } else {
+#pragma unroll
+          for (int i = 0; i < 4; ++i)
+            if (n0 + i < p.Cn) {
+              if (p.out_bf16) ((uint16_t*)p.out)[o + i] = (uint16_t)f32_to_bf16_bits(vv[i]);
+              else ((float*)p.out)[o + i] = vv[i];
+            }
+        }
+      }
+    };
+    // One chain = the 2*GC MFMA groups of one (k, n-block) for both row blocks, software-pipelined with
+    // the FMA epilogue of the previous chain: a wave issues in order, so the matrix pipe only stays busy
+    // during the SH weighting if every MFMA is followed, in program order, by a few of the pending FMAs
+    // (sched_barrier pins that order).
+    auto chain = [&](const uint4 (&ac)[PM_GC], const uint4 (&X)[2][PM_GC], bool have_pending, floatx16& y0,
+                     floatx16& y1, floatx16& pu0, floatx16& pu1, float pb0, float pb1) {
+      floatx16 u0, u1;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) { u0[i] = 0.f; u1[i] = 0.f; }
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int g = 0; g < PM_GC; ++g) {
+        u0 = mma_group<DT>(ac[g], X[0][g], u0);
+        if (have_pending) {
+#pragma unroll
+          for (int i = 4 * g; i < 4 * g + 4; ++i) y0[i] += pb0 * pu0[i];
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        u1 = mma_group<DT>(ac[g], X[1][g], u1);
+        if (have_pending) {
+#pragma unroll
+          for (int i = 4 * g; i < 4 * g + 4; ++i) y1[i] += pb1 * pu1[i];
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      // pin the sums here: otherwise the optimiser sinks the FMA chains below the unrolled loop and
+      // keeps every U tile alive (spilled) until then
+      if (have_pending) asm volatile("" : "+v"(y0), "+v"(y1));
+      pu0 = u0; pu1 = u1;
+    };
+
+    if constexpr (RES) {
+      // Weights resident in LDS: one 32-wide block of output channels at a time (32 accumulator
+      // registers), loop order  n-block -> c-chunk -> k.
+      for (int nb = 0; nb < NBG * PM_NBS; ++nb) {
+        if (nb * 32 >= p.Cn) break;
+        const int nbg = nb / PM_NBS, nbi = nb % PM_NBS;
+        floatx16 y0, y1;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) { y0[i] = 0.f; y1[i] = 0.f; }
+        for (int ch = 0; ch < NCH; ++ch) {
+          uint4 X[2][PM_GC];
+          fetch_chunk(ch, X);
+          const uint4* base = lds + ((int64_t)(nbg * NCH + ch) * K) * STAGE_U4 + nbi * PM_GC * 64 + lane;
+          if constexpr (BM == B_ONE) {
+#pragma unroll
+            for (int g = 0; g < PM_GC; ++g) {
+              const uint4 a = base[g * 64];
+              y0 = mma_group<DT>(a, X[0][g], y0);
+              y1 = mma_group<DT>(a, X[1][g], y1);
+            }
+          } else {
+            floatx16 pu0, pu1;
+            float pb0 = 0.f, pb1 = 0.f;
+            uint4 afr[PM_GC];
+#pragma unroll
+            for (int g = 0; g < PM_GC; ++g) afr[g] = base[g * 64];
+#pragma unroll
+            for (int k = 0; k < K; ++k) {
+              asm volatile("" ::: "memory");  // keep LDS reads of later k from being hoisted up here
+              uint4 ac[PM_GC];
+#pragma unroll
+              for (int g = 0; g < PM_GC; ++g) ac[g] = afr[g];
+              if (k + 1 < K) {   // fragments of the next chain, read while this one computes
+#pragma unroll
+                for (int g = 0; g < PM_GC; ++g) afr[g] = base[(k + 1) * STAGE_U4 + g * 64];
+              }
+              chain(ac, X, k > 0, y0, y1, pu0, pu1, pb0, pb1);
+              pb0 = B[0][k]; pb1 = B[1][k];
+            }
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {   // drain the pipeline
+              y0[i] += pb0 * pu0[i];
+              y1[i] += pb1 * pu1[i];
+            }
+            asm volatile("" : "+v"(y0), "+v"(y1));
+          }
+        }
+        store_block(nb, 0, y0);
+        store_block(nb, 1, y1);
+      }
+    } else {
+      // Weights streamed through a two-slot LDS ring, one barrier per stage: loop order
+      // n-block pair -> c-chunk -> k -> n-block, so that every stage is fetched once per tile.
 #pragma unroll
       for (int i = 0; i < PER_T; ++i) lds[i * NT + tid] = p.apack[i * NT + tid];
       __syncthreads();
-    }
-    int64_t q = 0;  // stage sequence number inside this tile
-    for (int nbg = 0; nbg < NBG; ++nbg) {
-      floatx16 y[PM_NBS][2];
+      int64_t q = 0;  // stage sequence number inside this tile
+      for (int nbg = 0; nbg < NBG; ++nbg) {
+        floatx16 y[PM_NBS][2];
 #pragma unroll
-      for (int a = 0; a < PM_NBS; ++a)
+        for (int a = 0; a < PM_NBS; ++a)
 #pragma unroll
-        for (int fb = 0; fb < 2; ++fb)
+          for (int fb = 0; fb < 2; ++fb)
 #pragma unroll
-          for (int i = 0; i < 16; ++i) y[a][fb][i] = 0.f;
-
-      for (int ch = 0; ch < NCH; ++ch) {
-        uint4 X[2][PM_GC];
+            for (int i = 0; i < 16; ++i) y[a][fb][i] = 0.f;
+        for (int ch = 0; ch < NCH; ++ch) {
+          uint4 X[2][PM_GC];
+          fetch_chunk(ch, X);
+          floatx16 pu0, pu1;
+          float pb0 = 0.f, pb1 = 0.f;
 #pragma unroll
-        for (int fb = 0; fb < 2; ++fb)
-#pragma unroll
-          for (int g = 0; g < PM_GC; ++g) {
-            float v[EPG];
-            fetch_vals<XM, EPG>(p.xs, row[fb], ok[fb], meta[fb], ((ch * PM_GC + g) * 2 + hh) * EPG, v);
-            X[fb][g] = pack_granule<DT>(v);
-          }
-        // Software pipeline over the chains (k, nbi).  A wave issues in order, so the only way to keep the
-        // matrix pipe busy while the SH weighting runs is to interleave, in program order, the MFMAs of
-        // chain c with the FMA epilogue of chain c-1 (whose U tiles are "pending" in pu0/pu1): every MFMA
-        // is followed by four of the pending FMAs, and sched_barrier keeps that written order.  The A
-        // fragments of chain c+1 are read from LDS while chain c computes.
-        floatx16 pu0, pu1;
-        float pb0 = 0.f, pb1 = 0.f;
-        uint4 afr[PM_GC];  // A fragments of the chain about to run
-        if constexpr (RES) {
-#pragma unroll
-          for (int g = 0; g < PM_GC; ++g) afr[g] = lds[q * STAGE_U4 + g * 64 + lane];
-        }
-#pragma unroll
-        for (int k = 0; k < K; ++k, ++q) {
-          asm volatile("" ::: "memory");  // keep LDS reads of later stages from being hoisted up here
-          const uint4* stage;
-          uint4 pre[PER_T];
-          if constexpr (RES) {
-            stage = lds + q * STAGE_U4;
-          } else {
-            stage = lds + (q & 1) * STAGE_U4;
+          for (int k = 0; k < K; ++k, ++q) {
+            asm volatile("" ::: "memory");
+            const uint4* stage = lds + (q & 1) * STAGE_U4;
+            uint4 pre[PER_T];
             if (q + 1 < S) {
 #pragma unroll
               for (int i = 0; i < PER_T; ++i) pre[i] = p.apack[(q + 1) * STAGE_U4 + i * NT + tid];
             }
-          }
 #pragma unroll
-          for (int nbi = 0; nbi < PM_NBS; ++nbi) {
-            if constexpr (BM == B_ONE) {
-#pragma unroll
-              for (int g = 0; g < PM_GC; ++g) {
-                uint4 a = stage[(nbi * PM_GC + g) * 64 + lane];
-                y[nbi][0] = mma_group<DT>(a, X[0][g], y[nbi][0]);
-                y[nbi][1] = mma_group<DT>(a, X[1][g], y[nbi][1]);
-              }
-            } else {
+            for (int nbi = 0; nbi < PM_NBS; ++nbi) {
               uint4 ac[PM_GC];
-              if constexpr (RES) {
 #pragma unroll
-                for (int g = 0; g < PM_GC; ++g) ac[g] = afr[g];
-                // prefetch the fragments of the next chain (next n-block of this stage, or next stage)
-                const bool last_chain = (k == K - 1) && (nbi == PM_NBS - 1);
-                if (!last_chain) {
-                  const uint4* nxt = (nbi + 1 < PM_NBS) ? stage + (nbi + 1) * PM_GC * 64 : stage + STAGE_U4;
+              for (int g = 0; g < PM_GC; ++g) ac[g] = stage[(nbi * PM_GC + g) * 64 + lane];
+              if constexpr (BM == B_ONE) {
 #pragma unroll
-                  for (int g = 0; g < PM_GC; ++g) afr[g] = nxt[g * 64 + lane];
+                for (int g = 0; g < PM_GC; ++g) {
+                  y[nbi][0] = mma_group<DT>(ac[g], X[0][g], y[nbi][0]);
+                  y[nbi][1] = mma_group<DT>(ac[g], X[1][g], y[nbi][1]);
                 }
               } else {
-#pragma unroll
-                for (int g = 0; g < PM_GC; ++g) ac[g] = stage[(nbi * PM_GC + g) * 64 + lane];
+                constexpr int LASTB = PM_NBS - 1;
+                const int pn = (nbi == 0) ? LASTB : nbi - 1;
+                chain(ac, X, (k > 0 || nbi > 0), y[pn][0], y[pn][1], pu0, pu1, pb0, pb1);
+                pb0 = B[0][k]; pb1 = B[1][k];
               }
-              const bool have_pending = (k > 0 || nbi > 0);
-              const int pn = (nbi == 0) ? PM_NBS - 1 : nbi - 1;
-              floatx16 u0, u1;
-#pragma unroll
-              for (int i = 0; i < 16; ++i) { u0[i] = 0.f; u1[i] = 0.f; }
-              __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-              for (int g = 0; g < PM_GC; ++g) {
-                u0 = mma_group<DT>(ac[g], X[0][g], u0);
-                if (have_pending) {
-#pragma unroll
-                  for (int i = 4 * g; i < 4 * g + 4; ++i) y[pn][0][i] += pb0 * pu0[i];
-                }
-                __builtin_amdgcn_sched_barrier(0);
-                u1 = mma_group<DT>(ac[g], X[1][g], u1);
-                if (have_pending) {
-#pragma unroll
-                  for (int i = 4 * g; i < 4 * g + 4; ++i) y[pn][1][i] += pb1 * pu1[i];
-                }
-                __builtin_amdgcn_sched_barrier(0);
-              }
-              if (have_pending) asm volatile("" : "+v"(y[pn][0]), "+v"(y[pn][1]));
-              pu0 = u0; pu1 = u1;
-              pb0 = B[0][k]; pb1 = B[1][k];
             }
-          }
-          if constexpr (!RES) {
             if (q + 1 < S) {
 #pragma unroll
               for (int i = 0; i < PER_T; ++i) lds[((q + 1) & 1) * STAGE_U4 + i * NT + tid] = pre[i];
             }
             __syncthreads();
           }
-        }
-        if constexpr (BM != B_ONE) {  // drain the pipeline
+          if constexpr (BM != B_ONE) {  // drain the pipeline
 #pragma unroll
-          for (int i = 0; i < 16; ++i) {
-            y[PM_NBS - 1][0][i] += pb0 * pu0[i];
-            y[PM_NBS - 1][1][i] += pb1 * pu1[i];
+            for (int i = 0; i < 16; ++i) {
+              y[PM_NBS - 1][0][i] += pb0 * pu0[i];
+              y[PM_NBS - 1][1][i] += pb1 * pu1[i];
+            }
+            asm volatile("" : "+v"(y[PM_NBS - 1][0]), "+v"(y[PM_NBS - 1][1]));
           }
-          asm volatile("" : "+v"(y[PM_NBS - 1][0]), "+v"(y[PM_NBS - 1][1]));
+        }
+#pragma unroll
+        for (int nbi = 0; nbi < PM_NBS; ++nbi) {
+          store_block(nbg * PM_NBS + nbi, 0, y[nbi][0]);
+          store_block(nbg * PM_NBS + nbi, 1, y[nbi][1]);
         }
       }
-
-      // store the NBS x 32 output channels of this pass
-#pragma unroll
-      for (int nbi = 0; nbi < PM_NBS; ++nbi)
-#pragma unroll
-        for (int fb = 0; fb < 2; ++fb) {
-          if (!ok[fb]) continue;
-#pragma unroll
-          for (int q4 = 0; q4 < 4; ++q4) {
-            const int n0 = (nbg * PM_NBS + nbi) * 32 + q4 * 8 + hh * 4;
-            if (n0 >= p.Cn) continue;
-            const float v0 = y[nbi][fb][q4 * 4], v1 = y[nbi][fb][q4 * 4 + 1], v2 = y[nbi][fb][q4 * 4 + 2],
-                        v3 = y[nbi][fb][q4 * 4 + 3];
-            const int64_t o = row[fb] * (int64_t)p.Cn + n0;
-            if (n0 + 4 <= p.Cn && (p.Cn & 3) == 0) {
-              if (p.out_bf16) {
-                uint2 w;
-                w.x = pack_bf16x2(v0, v1); w.y = pack_bf16x2(v2, v3);
-                *(uint2*)((uint16_t*)p.out + o) = w;
-              } else {
-                *(float4*)((float*)p.out + o) = make_float4(v0, v1, v2, v3);
-              }
-            } else {
-              const float vv[4] = {v0, v1, v2, v3};
-#pragma unroll
-              for (int i = 0; i < 4; ++i)
-                if (n0 + i < p.Cn) {
-                  if (p.out_bf16) ((uint16_t*)p.out)[o + i] = (uint16_t)f32_to_bf16_bits(vv[i]);
-                  else ((float*)p.out)[o + i] = vv[i];
-                }
-            }
-          }
-        }
     }
   }
 }
 
-template <int DT, int BM, int XM, int LT, int NW, bool RES>
-static pm_status launch_conv_res(const ConvP& p, int64_t S, hipStream_t st) {
-  auto kern = k_conv_rows<DT, BM, XM, LT, NW, RES>;
+template <int DT, int BM, int XM, int LT, int NW, bool RES, bool FAST>
+static pm_status launch_conv_fast(const ConvP& p, int64_t S, hipStream_t st) {
+  auto kern = k_conv_rows<DT, BM, XM, LT, NW, RES, FAST>;
   size_t lds = RES ? (size_t)S * PM_STAGE_BYTES : 2 * (size_t)PM_STAGE_BYTES;
   PM_CHECK_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
   const int NT = NW * 64;
@@ -259,6 +443,17 @@ static pm_status launch_conv_res(const ConvP& p, int64_t S, hipStream_t st) {
   return PM_OK;
 }
 
+// The branch-free fetch needs: storage dtype == MFMA dtype, 16-byte aligned rows, whole chunks of channels.
+template <int DT, int BM, int XM, int LT, int NW, bool RES>
+static pm_status launch_conv_res(const ConvP& p, int64_t S, hipStream_t st) {
+  const int esz = (DT == 1) ? 2 : 4;
+  const int chunk = PM_GC * ((DT == 1) ? 16 : 8);
+  bool fast = (p.xs.is_bf16 == (DT == 1)) && pm_aligned16(p.xs.p) && ((p.xs.C * esz) % 16 == 0) &&
+              (p.Cc % chunk == 0);
+  if (fast) return launch_conv_fast<DT, BM, XM, LT, NW, RES, true>(p, S, st);
+  return launch_conv_fast<DT, BM, XM, LT, NW, RES, false>(p, S, st);
+}
+
 template <int DT, int BM, int XM, int LT, int NW>
 static pm_status launch_conv_inst(const ConvP& p, int64_t S, hipStream_t st) {
   if (p.resident) return launch_conv_res<DT, BM, XM, LT, NW, true>(p, S, st);
@@ -268,13 +463,13 @@ static pm_status launch_conv_inst(const ConvP& p, int64_t S, hipStream_t st) {
 template <int DT, int BM, int XM>
 static pm_status launch_conv_L(const ConvP& p, int L, int64_t S, hipStream_t st) {
   if constexpr (BM == B_ONE) {
-    return launch_conv_inst<DT, BM, XM, 0, 8>(p, S, st);
+    return launch_conv_inst<DT, BM, XM, 0, 4>(p, S, st);
   } else {
     switch (L) {
-      case 0: return launch_conv_inst<DT, BM, XM, 0, 8>(p, S, st);
-      case 1: return launch_conv_inst<DT, BM, XM, 1, 8>(p, S, st);
-      case 2: return launch_conv_inst<DT, BM, XM, 2, 8>(p, S, st);
-      case 3: return launch_conv_inst<DT, BM, XM, 3, 8>(p, S, st);
+      case 0: return launch_conv_inst<DT, BM, XM, 0, 4>(p, S, st);
+      case 1: return launch_conv_inst<DT, BM, XM, 1, 4>(p, S, st);
+      case 2: return launch_conv_inst<DT, BM, XM, 2, 4>(p, S, st);
+      case 3: return launch_conv_inst<DT, BM, XM, 3, 4>(p, S, st);
       case 4: return launch_conv_inst<DT, BM, XM, 4, 4>(p, S, st);
       case 5: return launch_conv_inst<DT, BM, XM, 5, 4>(p, S, st);
       default: return pm_fail(PM_ERR_UNSUPPORTED, "SH degree %d", L);

@@ -172,3 +172,50 @@ __device__ __forceinline__ void row_direction(const BasisSrc& b, int64_t r, floa
     normalize_dir(x, y, z);
   }
 }
+
+// ---- the same, split into pipeline phases for the branch-free fast path ----------------------------
+// phase 0: ids (no dependency)   phase 1: loads that need the ids   phase 2: arithmetic
+struct DirRaw {
+  float v[9];  // B_NORMAL: the three corner positions; B_DIRS: v[0..2] = the direction
+};
+
+template <int BM>
+__device__ __forceinline__ void dir_ids(const BasisSrc& b, int64_t rowc, int32_t (&gid)[3]) {
+  gid[0] = gid[1] = gid[2] = 0;
+  if constexpr (BM == B_NORMAL) {
+#pragma unroll
+    for (int j = 0; j < 3; ++j) gid[j] = b.facet[3 * rowc + j];
+  }
+}
+
+template <int BM>
+__device__ __forceinline__ void dir_load(const BasisSrc& b, int64_t rowc, const int32_t (&gid)[3], DirRaw& d) {
+  if constexpr (BM == B_NORMAL) {
+#pragma unroll
+    for (int j = 0; j < 3; ++j) {
+      const float* q = b.vert + 3 * (int64_t)gid[j];
+      d.v[3 * j] = q[0]; d.v[3 * j + 1] = q[1]; d.v[3 * j + 2] = q[2];
+    }
+  } else if constexpr (BM == B_DIRS) {
+    d.v[0] = b.dirs[3 * rowc]; d.v[1] = b.dirs[3 * rowc + 1]; d.v[2] = b.dirs[3 * rowc + 2];
+  }
+}
+
+// unit direction: facet normal by the right-hand rule ((0,0,1) when degenerate), or the normalised direction
+template <int BM>
+__device__ __forceinline__ void dir_finish(const DirRaw& d, float& x, float& y, float& z) {
+  if constexpr (BM == B_NORMAL) {
+    const float ux = d.v[3] - d.v[0], uy = d.v[4] - d.v[1], uz = d.v[5] - d.v[2];
+    const float wx = d.v[6] - d.v[0], wy = d.v[7] - d.v[1], wz = d.v[8] - d.v[2];
+    const float cx = uy * wz - uz * wy, cy = uz * wx - ux * wz, cz = ux * wy - uy * wx;
+    const float l2 = cx * cx + cy * cy + cz * cz;
+    const bool deg = l2 < 1e-30f;
+    const float r = 1.0f / sqrtf(deg ? 1.0f : l2);
+    x = deg ? 0.f : cx * r;
+    y = deg ? 0.f : cy * r;
+    z = deg ? 1.f : cz * r;
+  } else {
+    x = d.v[0]; y = d.v[1]; z = d.v[2];
+    normalize_dir(x, y, z);
+  }
+}
