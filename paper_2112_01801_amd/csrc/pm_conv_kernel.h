@@ -290,20 +290,23 @@ __global__ void __launch_bounds__(NW * 64) k_conv_rows(ConvP p) {
       for (int g = 0; g < PM_GC; ++g) {
         u0 = mma_group<DT>(ac[g], X[0][g], u0);
         if (have_pending) {
-#pragma unroll
-          for (int i = 4 * g; i < 4 * g + 4; ++i) y0[i] += pb0 * pu0[i];
+          // four pending FMAs, pinned right here (an empty asm that "modifies" them): without the pin
+          // the optimiser gathers all FMAs of a chain at its end and the MFMAs run back to back alone
+          float t0 = y0[4 * g] + pb0 * pu0[4 * g], t1 = y0[4 * g + 1] + pb0 * pu0[4 * g + 1];
+          float t2 = y0[4 * g + 2] + pb0 * pu0[4 * g + 2], t3 = y0[4 * g + 3] + pb0 * pu0[4 * g + 3];
+          asm volatile("" : "+v"(t0), "+v"(t1), "+v"(t2), "+v"(t3));
+          y0[4 * g] = t0; y0[4 * g + 1] = t1; y0[4 * g + 2] = t2; y0[4 * g + 3] = t3;
         }
         __builtin_amdgcn_sched_barrier(0);
         u1 = mma_group<DT>(ac[g], X[1][g], u1);
         if (have_pending) {
-#pragma unroll
-          for (int i = 4 * g; i < 4 * g + 4; ++i) y1[i] += pb1 * pu1[i];
+          float t0 = y1[4 * g] + pb1 * pu1[4 * g], t1 = y1[4 * g + 1] + pb1 * pu1[4 * g + 1];
+          float t2 = y1[4 * g + 2] + pb1 * pu1[4 * g + 2], t3 = y1[4 * g + 3] + pb1 * pu1[4 * g + 3];
+          asm volatile("" : "+v"(t0), "+v"(t1), "+v"(t2), "+v"(t3));
+          y1[4 * g] = t0; y1[4 * g + 1] = t1; y1[4 * g + 2] = t2; y1[4 * g + 3] = t3;
         }
         __builtin_amdgcn_sched_barrier(0);
       }
-      // pin the sums here: otherwise the optimiser sinks the FMA chains below the unrolled loop and
-      // keeps every U tile alive (spilled) until then
-      if (have_pending) asm volatile("" : "+v"(y0), "+v"(y1));
       pu0 = u0; pu1 = u1;
     };
 
