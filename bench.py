@@ -40,10 +40,10 @@ def kernel_models(F, V, K, cin, cout, e):
     w_bytes = K * cin * cout * e
     geom = F * 12 + V * 12                       # corner ids + vertex positions, each touched once
     return {
-        # row-wise contraction: read h (and geometry), write the fp32 facet summands
-        "f2v/k_conv_rows": dict(bound="mfma", flop=flop, bytes=F * cin * e + geom + w_bytes + F * cout * 4),
+        # row-wise contraction: read h (and geometry), write the facet summands (feature dtype)
+        "f2v/k_conv_rows": dict(bound="mfma", flop=flop, bytes=F * cin * e + geom + w_bytes + F * cout * e),
         # segmented mean: read the summands once + CSR, write g
-        "f2v/k_segreduce": dict(bound="hbm", flop=F * cout * 3.0, bytes=F * cout * 4 + 12 * F + 4 * V + V * cout * e),
+        "f2v/k_segreduce": dict(bound="hbm", flop=F * cout * 3.0, bytes=F * cout * e + 12 * F + 4 * V + V * cout * e),
         # dh: gather dg (each vertex row once), geometry, write dh
         "f2v_bwd/k_conv_rows": dict(bound="mfma", flop=flop,
                                     bytes=V * cout * e + geom + 4 * V + w_bytes + F * cin * e),

@@ -146,7 +146,7 @@ static WsPlan plan_ws(pm_op op, int64_t V, int64_t F, int64_t P, int L, int cin,
     case PM_OP_ADJACENCY: w.small = pm_adj_ws_bytes(V, F); break;
     case PM_OP_F2V:
       w.apack = pm_pack_bytes(pm_pack_geom(K, cin, cout, dt));
-      w.inter = pm_round_up((size_t)F * cout * 4, 256);
+      w.inter = pm_round_up((size_t)F * cout * esize(dt), 256);   // per-facet summands, feature dtype
       break;
     case PM_OP_F2V_BWD:
       w.apack = pm_pack_bytes(pm_pack_geom(K, cout, cin, dt));
@@ -291,15 +291,16 @@ extern "C" pm_status pm_f2v(const pm_mesh* mesh, const pm_vf_adj* adj, int L, pm
   PM_TRY(check_ws(w, ws, ws_bytes));
   hipStream_t st = (hipStream_t)stream;
   char* apack = (char*)ws;
-  float* y = (float*)(apack + w.apack);
+  void* y = apack + w.apack;   // per-facet summands of Eq. 5 in the feature dtype (summed in fp32 below)
 
   PM_TRY(pm_launch_pack(PACK_PLAIN, dtype, K, cin, cout, W, nullptr, apack, st));
   BasisSrc bs = basis_none();
   bs.vert = mesh->vert; bs.facet = mesh->facet;
   pm_make_sh_table(L, norm, &bs.sh);
   RowSrc xs = row_src(h_facet, dtype, cin);
-  PM_TRY(pm_launch_conv_rows(dtype, B_NORMAL, X_DIRECT, F, K, cin, cout, bs, xs, apack, y, 0, st));
-  return pm_launch_segreduce(V, cout, y, adj->row_ptr, adj->col, 3, 1, g_vert, dtype == PM_BF16, st);
+  const int yb = dtype == PM_BF16;
+  PM_TRY(pm_launch_conv_rows(dtype, B_NORMAL, X_DIRECT, F, K, cin, cout, bs, xs, apack, y, yb, st));
+  return pm_launch_segreduce(V, cout, y, yb, adj->row_ptr, adj->col, 3, 1, g_vert, dtype == PM_BF16, st);
 }
 
 extern "C" pm_status pm_f2v_bwd(const pm_mesh* mesh, const pm_vf_adj* adj, int L, pm_sh_norm norm, int cin, int cout,
@@ -395,7 +396,7 @@ extern "C" pm_status pm_v2f_bwd(const pm_mesh* mesh, const pm_vf_adj* adj, int L
     RowSrc xs = row_src(dg_facet, dtype, cout);
     PM_TRY(pm_launch_conv_rows(dtype, B_ONE, X_DIRECT, F, 1, cout, 3 * cin, basis_none(), xs, apack, dz, 0, st));
     // row 3f+j of dz is exactly corner slot 3f+j of the adjacency
-    PM_TRY(pm_launch_segreduce(V, cin, dz, adj->row_ptr, adj->col, 1, 0, dh_vert, dtype == PM_BF16, st));
+    PM_TRY(pm_launch_segreduce(V, cin, dz, 0, adj->row_ptr, adj->col, 1, 0, dh_vert, dtype == PM_BF16, st));
   }
   if (dW) {
     RowSrc xs = row_src(h_vert, dtype, cin);
@@ -438,7 +439,7 @@ extern "C" pm_status pm_f2f(int64_t n_facet, int64_t n_tex, const int32_t* tex_o
   pm_make_sh_table(L, norm, &bs.sh);
   RowSrc xs = row_src(h_tex, dtype, cin);
   PM_TRY(pm_launch_conv_rows(dtype, B_DIRS, X_DIRECT, n_tex, K, cin, cout, bs, xs, apack, yp, 0, st));
-  return pm_launch_segreduce(n_facet, cout, yp, tex_off, nullptr, 1, 1, g_facet, dtype == PM_BF16, st);
+  return pm_launch_segreduce(n_facet, cout, yp, 0, tex_off, nullptr, 1, 1, g_facet, dtype == PM_BF16, st);
 }
 
 extern "C" pm_status pm_f2f_bwd(int64_t n_facet, int64_t n_tex, const int32_t* tex_off, const float* bary, int L,

@@ -176,68 +176,88 @@ pm_status pm_launch_conv_rows(pm_dtype mt, BMode bm, XMode xm, int64_t R, int K,
 struct SegP {
   int64_t n_seg;
   int C, div, mean, out_bf16, lpg;  // lpg = lanes per segment (power of two, <= 64)
-  const float* src;
+  const void* src;                  // fp32 or bf16 rows
   const int32_t* row_ptr;
   const int32_t* col;
   void* out;
 };
 
+// SRC_BF16: the rows being reduced are bf16 (8 channels = 16 bytes per lane) instead of fp32 (4 channels)
+template <bool SRC_BF16>
 __global__ void __launch_bounds__(256) k_segreduce(SegP p) {
+  constexpr int CPL = SRC_BF16 ? 8 : 4;
   const int gpb = 256 / p.lpg;  // segments per block
   const int64_t seg = (int64_t)blockIdx.x * gpb + threadIdx.x / p.lpg;
   const int sub = threadIdx.x % p.lpg;
   if (seg >= p.n_seg) return;
   const int32_t b = p.row_ptr[seg], e = p.row_ptr[seg + 1];
   const float scale = (p.mean && e > b) ? 1.0f / (float)(e - b) : 1.0f;
-  const bool vec = (p.C & 3) == 0;
-  for (int c0 = sub * 4; c0 < p.C; c0 += p.lpg * 4) {
-    float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
+  const bool vec = (p.C % CPL) == 0;
+  for (int c0 = sub * CPL; c0 < p.C; c0 += p.lpg * CPL) {
+    float a[CPL];
+#pragma unroll
+    for (int i = 0; i < CPL; ++i) a[i] = 0.f;
     for (int32_t i = b; i < e; ++i) {
-      int64_t r = p.col ? (int64_t)(p.col[i] / p.div) : (int64_t)i;
-      const float* s = p.src + r * p.C + c0;
+      const int64_t r = p.col ? (int64_t)(p.col[i] / p.div) : (int64_t)i;
+      const int64_t o = r * p.C + c0;
       if (vec) {
-        float4 f = *(const float4*)s;
-        a0 += f.x; a1 += f.y; a2 += f.z; a3 += f.w;
+        if constexpr (SRC_BF16) {
+          const uint4 u = *(const uint4*)((const uint16_t*)p.src + o);
+          a[0] += bf16lo_to_f32(u.x); a[1] += bf16hi_to_f32(u.x); a[2] += bf16lo_to_f32(u.y); a[3] += bf16hi_to_f32(u.y);
+          a[4] += bf16lo_to_f32(u.z); a[5] += bf16hi_to_f32(u.z); a[6] += bf16lo_to_f32(u.w); a[7] += bf16hi_to_f32(u.w);
+        } else {
+          const float4 f = *(const float4*)((const float*)p.src + o);
+          a[0] += f.x; a[1] += f.y; a[2] += f.z; a[3] += f.w;
+        }
       } else {
-        a0 += s[0];
-        if (c0 + 1 < p.C) a1 += s[1];
-        if (c0 + 2 < p.C) a2 += s[2];
-        if (c0 + 3 < p.C) a3 += s[3];
+#pragma unroll
+        for (int q = 0; q < CPL; ++q)
+          if (c0 + q < p.C)
+            a[q] += SRC_BF16 ? bf16_to_f32(((const uint16_t*)p.src)[o + q]) : ((const float*)p.src)[o + q];
       }
     }
-    a0 *= scale; a1 *= scale; a2 *= scale; a3 *= scale;
+#pragma unroll
+    for (int i = 0; i < CPL; ++i) a[i] *= scale;
     const int64_t o = seg * p.C + c0;
     if (vec) {
       if (p.out_bf16) {
-        uint2 w;
-        w.x = pack_bf16x2(a0, a1); w.y = pack_bf16x2(a2, a3);
-        *(uint2*)((uint16_t*)p.out + o) = w;
+#pragma unroll
+        for (int q = 0; q < CPL / 4; ++q) {
+          uint2 w;
+          w.x = pack_bf16x2(a[4 * q], a[4 * q + 1]); w.y = pack_bf16x2(a[4 * q + 2], a[4 * q + 3]);
+          *(uint2*)((uint16_t*)p.out + o + 4 * q) = w;
+        }
       } else {
-        *(float4*)((float*)p.out + o) = make_float4(a0, a1, a2, a3);
+#pragma unroll
+        for (int q = 0; q < CPL / 4; ++q)
+          *(float4*)((float*)p.out + o + 4 * q) = make_float4(a[4 * q], a[4 * q + 1], a[4 * q + 2], a[4 * q + 3]);
       }
     } else {
-      const float vv[4] = {a0, a1, a2, a3};
-      for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int i = 0; i < CPL; ++i)
         if (c0 + i < p.C) {
-          if (p.out_bf16) ((uint16_t*)p.out)[o + i] = (uint16_t)f32_to_bf16_bits(vv[i]);
-          else ((float*)p.out)[o + i] = vv[i];
+          if (p.out_bf16) ((uint16_t*)p.out)[o + i] = (uint16_t)f32_to_bf16_bits(a[i]);
+          else ((float*)p.out)[o + i] = a[i];
         }
     }
   }
 }
 
-pm_status pm_launch_segreduce(int64_t n_seg, int C, const float* src, const int32_t* row_ptr, const int32_t* col,
-                              int div, int mean, void* out, int out_is_bf16, hipStream_t st) {
+pm_status pm_launch_segreduce(int64_t n_seg, int C, const void* src, int src_is_bf16, const int32_t* row_ptr,
+                              const int32_t* col, int div, int mean, void* out, int out_is_bf16, hipStream_t st) {
   if (n_seg == 0) return PM_OK;
   SegP p;
   p.n_seg = n_seg; p.C = C; p.div = div; p.mean = mean; p.out_bf16 = out_is_bf16;
   p.src = src; p.row_ptr = row_ptr; p.col = col; p.out = out;
-  int need = (C + 3) / 4, lpg = 1;
+  const int cpl = src_is_bf16 ? 8 : 4;
+  int need = (C + cpl - 1) / cpl, lpg = 1;
   while (lpg < need && lpg < 64) lpg <<= 1;
   p.lpg = lpg;
   int gpb = 256 / lpg;
+  const dim3 grid((unsigned)((n_seg + gpb - 1) / gpb));
   { ProfScope ps__(st, "k_segreduce");
-    hipLaunchKernelGGL(k_segreduce, dim3((unsigned)((n_seg + gpb - 1) / gpb)), dim3(256), 0, st, p); }
+    if (src_is_bf16) hipLaunchKernelGGL(k_segreduce<true>, grid, dim3(256), 0, st, p);
+    else hipLaunchKernelGGL(k_segreduce<false>, grid, dim3(256), 0, st, p); }
   PM_CHECK_LAUNCH("k_segreduce");
   return PM_OK;
 }

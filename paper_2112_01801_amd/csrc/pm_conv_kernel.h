@@ -127,11 +127,16 @@ __global__ void __launch_bounds__(NW * 64) k_conv_rows(ConvP p) {
   // the row data of tile t+1 (operand rows, corner positions, CSR bounds) is already in flight, and the
   // ids those loads needed were fetched one tile earlier still.  Arithmetic on the loaded values is
   // deferred to the top of the tile that uses them, so nothing waits on memory inside the MFMA loop.
+  // With 4 waves (512 registers each) the operand rows are prefetched a tile ahead as well and the A
+  // fragments a chain ahead; with 8 waves (256 registers, two waves per SIMD that cover for each other)
+  // only the geometry is, and the operand rows are fetched at the top of their tile, ahead of the SH
+  // arithmetic that hides most of their latency.
+  constexpr bool XPRE = (NW <= 4);
   struct TileRaw {
     int32_t gid[2][3];
     RowMeta meta[2];
     DirRaw dr[2];
-    uint4 xr[2][PM_GC][NRaw<XM>::n];
+    uint4 xr[XPRE ? 2 : 1][PM_GC][NRaw<XM>::n];
   };
   auto rows_of = [&](int64_t ti_, int fb) {
     const int64_t t_ = (int64_t)xcd * tpx + ti_;
@@ -151,8 +156,10 @@ __global__ void __launch_bounds__(NW * 64) k_conv_rows(ConvP p) {
       const int64_t rc = rows_of(ti_, fb);
       if constexpr (BM != B_ONE) dir_load<BM>(p.bs, rc, t.gid[fb], t.dr[fb]);
       load_meta_w<XM>(p.xs, true, t.meta[fb]);
+      if constexpr (XPRE) {
 #pragma unroll
-      for (int g = 0; g < PM_GC; ++g) granule_load<XM, DT>(p.xs, rc, t.meta[fb], (g * 2 + hh) * EPG, t.xr[fb][g]);
+        for (int g = 0; g < PM_GC; ++g) granule_load<XM, DT>(p.xs, rc, t.meta[fb], (g * 2 + hh) * EPG, t.xr[fb][g]);
+      }
     }
   };
   TileRaw cur, nxt;
@@ -178,6 +185,14 @@ __global__ void __launch_bounds__(NW * 64) k_conv_rows(ConvP p) {
       rowc[fb] = FAST ? min(row[fb], p.R - 1) : row[fb];
     }
     if constexpr (FAST) {
+      uint4 xnow[2][PM_GC][NRaw<XM>::n];
+      if constexpr (!XPRE) {   // operand rows of this tile: out first, used after the SH arithmetic
+#pragma unroll
+        for (int fb = 0; fb < 2; ++fb)
+#pragma unroll
+          for (int g = 0; g < PM_GC; ++g)
+            granule_load<XM, DT>(p.xs, rowc[fb], cur.meta[fb], (g * 2 + hh) * EPG, xnow[fb][g]);
+      }
       // arithmetic on this tile's data (loaded during the previous tile)
 #pragma unroll
       for (int fb = 0; fb < 2; ++fb) {
@@ -191,7 +206,10 @@ __global__ void __launch_bounds__(NW * 64) k_conv_rows(ConvP p) {
           B[fb][0] = 1.f;
         }
 #pragma unroll
-        for (int g = 0; g < PM_GC; ++g) X0[fb][g] = granule_finish<XM, DT>(cur.xr[fb][g], meta[fb]);
+        for (int g = 0; g < PM_GC; ++g) {
+          if constexpr (XPRE) X0[fb][g] = granule_finish<XM, DT>(cur.xr[fb][g], meta[fb]);
+          else X0[fb][g] = granule_finish<XM, DT>(xnow[fb][g], meta[fb]);
+        }
       }
       // next tile: its ids are here, send out everything that depends on them; then the ids after that
       __builtin_amdgcn_sched_barrier(0);
@@ -334,17 +352,24 @@ __global__ void __launch_bounds__(NW * 64) k_conv_rows(ConvP p) {
             floatx16 pu0, pu1;
             float pb0 = 0.f, pb1 = 0.f;
             uint4 afr[PM_GC];
+            if constexpr (XPRE) {
 #pragma unroll
-            for (int g = 0; g < PM_GC; ++g) afr[g] = base[g * 64];
+              for (int g = 0; g < PM_GC; ++g) afr[g] = base[g * 64];
+            }
 #pragma unroll
             for (int k = 0; k < K; ++k) {
               asm volatile("" ::: "memory");  // keep LDS reads of later k from being hoisted up here
               uint4 ac[PM_GC];
+              if constexpr (XPRE) {
 #pragma unroll
-              for (int g = 0; g < PM_GC; ++g) ac[g] = afr[g];
-              if (k + 1 < K) {   // fragments of the next chain, read while this one computes
+                for (int g = 0; g < PM_GC; ++g) ac[g] = afr[g];
+                if (k + 1 < K) {   // fragments of the next chain, read while this one computes
 #pragma unroll
-                for (int g = 0; g < PM_GC; ++g) afr[g] = base[(k + 1) * STAGE_U4 + g * 64];
+                  for (int g = 0; g < PM_GC; ++g) afr[g] = base[(k + 1) * STAGE_U4 + g * 64];
+                }
+              } else {
+#pragma unroll
+                for (int g = 0; g < PM_GC; ++g) ac[g] = base[k * STAGE_U4 + g * 64];
               }
               chain(ac, X, k > 0, y0, y1, pu0, pu1, pb0, pb1);
               pb0 = B[0][k]; pb1 = B[1][k];
@@ -472,7 +497,8 @@ static pm_status launch_conv_L(const ConvP& p, int L, int64_t S, hipStream_t st)
       case 0: return launch_conv_inst<DT, BM, XM, 0, 4>(p, S, st);
       case 1: return launch_conv_inst<DT, BM, XM, 1, 4>(p, S, st);
       case 2: return launch_conv_inst<DT, BM, XM, 2, 4>(p, S, st);
-      case 3: return launch_conv_inst<DT, BM, XM, 3, 4>(p, S, st);
+      // two waves per SIMD when the row loader is light enough to fit 256 registers
+      case 3: return launch_conv_inst<DT, BM, XM, 3, (XM == X_GATHER_SUM || XM == X_GATHER1) ? 4 : 8>(p, S, st);
       case 4: return launch_conv_inst<DT, BM, XM, 4, 4>(p, S, st);
       case 5: return launch_conv_inst<DT, BM, XM, 5, 4>(p, S, st);
       default: return pm_fail(PM_ERR_UNSUPPORTED, "SH degree %d", L);

@@ -101,9 +101,9 @@ pm_status pm_launch_conv_rows(pm_dtype mt, BMode bm, XMode xm, int64_t R, int K,
                               const RowSrc& xs, const void* apack, void* out, int out_is_bf16, hipStream_t st);
 
 // out[v][c] = scale_v * sum_{e in [row_ptr[v], row_ptr[v+1])} src[(col ? col[e] : e) / div][c]
-// scale_v = 1/deg (mean != 0) or 1.  src is fp32.
-pm_status pm_launch_segreduce(int64_t n_seg, int C, const float* src, const int32_t* row_ptr, const int32_t* col,
-                              int div, int mean, void* out, int out_is_bf16, hipStream_t st);
+// scale_v = 1/deg (mean != 0) or 1.  src is fp32 or bf16; the sum is always accumulated in fp32.
+pm_status pm_launch_segreduce(int64_t n_seg, int C, const void* src, int src_is_bf16, const int32_t* row_ptr,
+                              const int32_t* col, int div, int mean, void* out, int out_is_bf16, hipStream_t st);
 
 // dWp[k][c][n] = sum_r B_r[k] X_r[c] Y_r[n], fp32, deterministic (per-workgroup partials + fixed-order sum).
 // X_GATHER_CAT here means: k indexes the corner, X^{(k)}_r = xs.p[facet[r][k]] (K must be 3, B_ONE).
