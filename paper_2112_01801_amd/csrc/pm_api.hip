@@ -336,8 +336,10 @@ extern "C" pm_status pm_f2v_bwd(const pm_mesh* mesh, const pm_vf_adj* adj, int L
   }
   if (dW) {
     RowSrc xs = row_src(h_facet, dtype, cin);
-    PM_TRY(pm_launch_basis_mesh(mesh, bs.sh, bvals, st));
-    bs.bvals = bvals;
+    if (!pm_wgrad_fuses_basis(dtype, B_NORMAL, X_DIRECT, X_GATHER_SUM, K, cin, cout, xs, dys)) {
+      PM_TRY(pm_launch_basis_mesh(mesh, bs.sh, bvals, st));
+      bs.bvals = bvals;
+    }
     PM_TRY(pm_launch_wgrad(dtype, B_NORMAL, X_DIRECT, X_GATHER_SUM, F, K, cin, cout, bs, xs, dys, dW, wg, w.wgrad, st));
   }
   return PM_OK;
@@ -474,8 +476,10 @@ extern "C" pm_status pm_f2f_bwd(int64_t n_facet, int64_t n_tex, const int32_t* t
   }
   if (dW) {
     RowSrc xs = row_src(h_tex, dtype, cin);
-    PM_TRY(pm_launch_basis_dirs(n_tex, bary, bs.sh, bvals, st));
-    bs.bvals = bvals;
+    if (!pm_wgrad_fuses_basis(dtype, B_DIRS, X_DIRECT, X_GATHER1, K, cin, cout, xs, dys)) {
+      PM_TRY(pm_launch_basis_dirs(n_tex, bary, bs.sh, bvals, st));
+      bs.bvals = bvals;
+    }
     PM_TRY(pm_launch_wgrad(dtype, B_DIRS, X_DIRECT, X_GATHER1, n_tex, K, cin, cout, bs, xs, dys, dW, wg, w.wgrad, st));
   }
   return PM_OK;

@@ -13,22 +13,7 @@
 // of every tile instead.  Each workgroup covers a fixed contiguous range of rows and writes its partial
 // sums to its own slice of a workspace; a second kernel adds the slices in a fixed order, so the result
 // is bitwise reproducible and uses no floating-point atomics.
-#include "pm_rows.h"
-
-#define WG_RT 64          /* rows per staged tile */
-#define WG_KG 16          /* k values per workgroup */
-#define XP_BF16 72        /* LDS pitch of a channel row, bf16 elements (144 B) */
-#define XP_F32 68         /* LDS pitch, fp32 elements (272 B) */
-
-struct WgradP {
-  int64_t R, rows_per_part;
-  int K, Cc, Cn;
-  int KGn, CBP, NBP;   // slab decomposition
-  int NKPW, RS;        // k-pairs per workgroup, row splits
-  BasisSrc bs;         // bs.bvals: precomputed basis rows [R][K] (unused for B_ONE)
-  RowSrc xs, ys;
-  float* partial;      // [n_part * RS][K][Cc][Cn]
-};
+#include "pm_wgrad.h"
 
 // Eight consecutive channels of one source row as they sit in memory (no arithmetic yet, so that the
 // loads can stay in flight while the previous tile is being multiplied).
@@ -433,13 +418,36 @@ __global__ void __launch_bounds__(512) k_wgrad(WgradP p) {
   }
 }
 
+// out[i] = sum over the slices in a fixed order (bitwise reproducible): the slices are cut into eight
+// consecutive groups, each group is added sequentially by one thread (eight loads in flight), and the
+// eight group sums are then added in group order.
 __global__ void __launch_bounds__(256) k_sum_partials(const float* __restrict__ partial, int64_t n, int n_slice,
                                                       float* __restrict__ out) {
-  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i >= n) return;
+  __shared__ float part[8][32];
+  const int il = threadIdx.x & 31, g = threadIdx.x >> 5;
+  const int64_t i = (int64_t)blockIdx.x * 32 + il;
+  const int per = (n_slice + 7) / 8;
+  const int q0 = g * per, q1 = min(n_slice, q0 + per);
   float s = 0.f;
-  for (int q = 0; q < n_slice; ++q) s += partial[(int64_t)q * n + i];
-  out[i] = s;
+  if (i < n) {
+    int q = q0;
+    for (; q + 8 <= q1; q += 8) {
+      float v[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) v[j] = partial[(int64_t)(q + j) * n + i];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) s += v[j];
+    }
+    for (; q < q1; ++q) s += partial[(int64_t)q * n + i];
+  }
+  part[g][il] = s;
+  __syncthreads();
+  if (g == 0 && i < n) {
+    float t = part[0][il];
+#pragma unroll
+    for (int j = 1; j < 8; ++j) t += part[j][il];
+    out[i] = t;
+  }
 }
 
 struct WgradGeom {
@@ -523,11 +531,15 @@ pm_status pm_launch_wgrad(pm_dtype mt, BMode bm, XMode xm, XMode ym, int64_t R, 
   p.K = K; p.Cc = Cc; p.Cn = Cn;
   p.KGn = g.KGn; p.CBP = g.CBP; p.NBP = g.NBP; p.NKPW = g.NKPW; p.RS = g.RS;
   p.bs = bs; p.xs = xs; p.ys = ys; p.partial = (float*)ws;
-  pm_status s = (mt == PM_BF16) ? launch_wgrad_mode<1>(bm, xm, ym, p, g, st) : launch_wgrad_mode<0>(bm, xm, ym, p, g, st);
+  pm_status s;
+  if (pm_wgrad_fuses_basis(mt, bm, xm, ym, K, Cc, Cn, xs, ys))
+    s = pm_launch_wgrad_pc(bm, ym, p, g.n_part, g.slabs, st);
+  else
+    s = (mt == PM_BF16) ? launch_wgrad_mode<1>(bm, xm, ym, p, g, st) : launch_wgrad_mode<0>(bm, xm, ym, p, g, st);
   if (s != PM_OK) return s;
   int64_t n = (int64_t)K * Cc * Cn;
   { ProfScope ps__(st, "k_sum_partials");
-    hipLaunchKernelGGL(k_sum_partials, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, (const float*)ws, n,
+    hipLaunchKernelGGL(k_sum_partials, dim3((unsigned)((n + 31) / 32)), dim3(256), 0, st, (const float*)ws, n,
                      g.n_part * g.RS, dWp); }
   PM_CHECK_LAUNCH("k_sum_partials");
   return PM_OK;

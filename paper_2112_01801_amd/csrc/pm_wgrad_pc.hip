@@ -1,0 +1,310 @@
+// Gradient with respect to the dense filter coefficients, producer/consumer form:
+//     dWp[k][c][n] = sum_r B_r[k] * X_r[c] * Y_r[n]
+// for bf16 rows X read directly and Y gathered (transposed sums of Eq. 5 and Eq. 7), with the basis B
+// evaluated inside the kernel from the row's direction (Eq. 3-4).
+//
+// A workgroup has 12 waves.  Waves 8..11 are producers: lane = row of a 64-row tile; they fetch the
+// row's channels, its gathered gradient rows and its corner positions two tiles ahead, combine them
+// and write the tile TRANSPOSED into LDS (channel-major, so an MFMA operand fragment -- 8 consecutive
+// rows of one channel -- is one 16-byte read).  Waves 0..7 are consumers: each owns two k's of a
+// 64x64 (c,n) slab (8 accumulator blocks of 32x32); per 16 rows it scales the Y fragment by the basis
+// values (kept compactly, two registers per k, and broadcast inside lane quads by the multiply's own
+// lane-select modifier) and issues the matrix instructions.  One barrier per tile separates the two
+// LDS buffers; producers and consumers work on different tiles at the same time, so global-memory
+// latency, the gather arithmetic and the matrix pipe overlap across waves of a SIMD.
+//
+// Each workgroup covers a fixed contiguous range of rows and writes its partial sums to its own
+// slice; the slices are added in a fixed order afterwards (bitwise reproducible, no float atomics).
+#include "pm_wgrad.h"
+
+#define PC_CONS 8
+#define PC_PROD 4
+#define PC_THREADS ((PC_CONS + PC_PROD) * 64)
+#define PC_XPB (XP_BF16 * 2)                          /* bytes per channel row of the X tile */
+#define PC_XT_BYTES (64 * PC_XPB)
+#define PC_YT_BYTES (64 * XP_F32 * 4)
+#define PC_BS_BYTES (WG_KG * 64 * 4)
+#define PC_BUF_BYTES (PC_XT_BYTES + PC_YT_BYTES + PC_BS_BYTES)
+
+// value of lane (4*(lane/4) + J) of the same quad
+template <int J>
+__device__ __forceinline__ float quad_bcast(float v) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, v), J * 0x55, 0xf, 0xf, true));
+}
+
+// position of a tile row inside its group of 8 in the basis tile: (r0,r4,r1,r5,r2,r6,r3,r7), so that
+// quad lane q reads (B[q], B[4+q]) of a group with one 8-byte access
+__device__ __forceinline__ int basis_pos(int row) { return (row & ~7) + 2 * (row & 3) + ((row >> 2) & 1); }
+
+struct PcIds {
+  int32_t y[3];  // gather ids of the Y rows
+  int32_t g[3];  // corner ids for the facet normal
+};
+
+template <int NYS, int NY, int NX>
+struct PcSet {
+  uint4 x[NX > 0 ? NX : 1];
+  uint4 y[NY > 0 ? NY : 1][NYS];
+  int32_t lo[3], hi[3];
+  DirRaw d;
+};
+
+// One producer wave.  It moves NX channel octets of X starting at octet X0, NY octets of Y starting at
+// Y0 and (HASB) the basis values of the tile's 64 rows.  Tile i lives in register set i&1; its loads
+// are issued three barriers before it is consumed.
+template <int BM, int YM, int LT, bool HASB, int NY, int Y0, int NX, int X0>
+__device__ __forceinline__ void pc_producer(const WgradP& p, char* lds, const int lane, const int64_t rbeg,
+                                            const int64_t rend, const int n_tiles, const int cbase, const int nbase,
+                                            const int kbase) {
+  constexpr int NYS = (YM == X_GATHER_SUM) ? 3 : 1;
+  using Set = PcSet<NYS, NY, NX>;
+  // rows past the end are clamped to the last row (every load unconditional and in bounds); their basis
+  // values are written as zero, which removes them from every sum
+  auto rowc = [&](int t) { return min(rbeg + (int64_t)t * WG_RT + lane, rend - 1); };
+
+  auto load_ids = [&](int t, PcIds& d) {
+    const int64_t r = rowc(t);
+    d.y[0] = d.y[1] = d.y[2] = 0;
+    if constexpr (NY > 0) {
+      if constexpr (YM == X_GATHER_SUM) {
+#pragma unroll
+        for (int j = 0; j < 3; ++j) d.y[j] = p.ys.facet[3 * r + j];
+      } else if constexpr (YM == X_GATHER1) {
+        d.y[0] = p.ys.owner[r];
+      }
+    }
+    if constexpr (HASB) dir_ids<BM>(p.bs, r, d.g);
+  };
+
+  auto issue = [&](int t, const PcIds& d, Set& s) {
+    const int64_t r = rowc(t);
+#pragma unroll
+    for (int i = 0; i < NX; ++i)
+      s.x[i] = *(const uint4*)((const uint16_t*)p.xs.p + r * (int64_t)p.xs.C + cbase + (X0 + i) * 8);
+    if constexpr (NY > 0) {
+#pragma unroll
+      for (int j = 0; j < NYS; ++j) {
+        const int64_t src = (YM == X_DIRECT) ? r : (int64_t)d.y[j];
+#pragma unroll
+        for (int i = 0; i < NY; ++i)
+          s.y[i][j] = *(const uint4*)((const uint16_t*)p.ys.p + src * (int64_t)p.ys.C + nbase + (Y0 + i) * 8);
+      }
+      if constexpr (YM == X_GATHER_SUM) {
+#pragma unroll
+        for (int j = 0; j < 3; ++j) {
+          s.lo[j] = p.ys.row_ptr[d.y[j]];
+          s.hi[j] = p.ys.row_ptr[d.y[j] + 1];
+        }
+      } else if constexpr (YM == X_GATHER1) {
+        s.lo[0] = p.ys.seg_off[d.y[0]];
+        s.hi[0] = p.ys.seg_off[d.y[0] + 1];
+      }
+    }
+    if constexpr (HASB) dir_load<BM>(p.bs, r, d.g, s.d);
+  };
+
+  auto store = [&](int t, Set& s) {
+    const bool ok = rbeg + (int64_t)t * WG_RT + lane < rend;
+    char* XT = lds + (t & 1) * PC_BUF_BYTES;
+    float* YT = (float*)(XT + PC_XT_BYTES);
+    float* Bs = YT + 64 * XP_F32;
+#pragma unroll
+    for (int i = 0; i < NX; ++i) {
+      const uint32_t w[4] = {s.x[i].x, s.x[i].y, s.x[i].z, s.x[i].w};
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        uint16_t* dst = (uint16_t*)(XT + ((X0 + i) * 8 + e) * PC_XPB);
+        dst[lane] = (uint16_t)((e & 1) ? (w[e >> 1] >> 16) : (w[e >> 1] & 0xffffu));
+      }
+    }
+    if constexpr (NY > 0) {
+      float wt[3] = {1.f, 1.f, 1.f};
+      if constexpr (YM == X_GATHER_SUM) {
+#pragma unroll
+        for (int j = 0; j < 3; ++j) wt[j] = 1.0f / (float)(s.hi[j] - s.lo[j]);
+      } else if constexpr (YM == X_GATHER1) {
+        wt[0] = 1.0f / (float)(s.hi[0] - s.lo[0]);
+      }
+#pragma unroll
+      for (int i = 0; i < NY; ++i) {
+        float v[8];
+#pragma unroll
+        for (int j = 0; j < NYS; ++j) {
+          const uint32_t w[4] = {s.y[i][j].x, s.y[i][j].y, s.y[i][j].z, s.y[i][j].w};
+#pragma unroll
+          for (int e = 0; e < 8; ++e) {
+            const float f = (e & 1) ? bf16hi_to_f32(w[e >> 1]) : bf16lo_to_f32(w[e >> 1]);
+            if (j == 0) v[e] = (YM == X_DIRECT) ? f : f * wt[0];
+            else v[e] += f * wt[j];
+          }
+        }
+#pragma unroll
+        for (int e = 0; e < 8; ++e) YT[((Y0 + i) * 8 + e) * XP_F32 + lane] = v[e];
+      }
+    }
+    if constexpr (HASB) {
+      float x, y, z;
+      dir_finish<BM>(s.d, x, y, z);
+      const int pos = basis_pos(lane);
+      sh_eval<LT>(x, y, z, p.bs.sh, [&](int k, float v) {
+        const int kl = k - kbase;
+        if (kl >= 0 && kl < WG_KG) Bs[kl * 64 + pos] = ok ? v : 0.f;
+      });
+    }
+  };
+
+  if (n_tiles <= 0) return;
+  PcIds i0, i1;
+  Set s0, s1;
+  load_ids(0, i0);
+  load_ids(1, i1);
+  issue(0, i0, s0);
+  issue(1, i1, s1);
+  load_ids(2, i0);
+  load_ids(3, i1);
+  store(0, s0);
+  issue(2, i0, s0);
+  // barrier t: tile t is complete in buffer t&1, and the consumers are done with buffer (t+1)&1
+  for (int t = 0; t < n_tiles; t += 2) {
+    __syncthreads();
+    load_ids(t + 4, i0);
+    store(t + 1, s1);
+    issue(t + 3, i1, s1);
+    if (t + 1 < n_tiles) {
+      __syncthreads();
+      load_ids(t + 5, i1);
+      store(t + 2, s0);
+      issue(t + 4, i0, s0);
+    }
+  }
+}
+
+template <int BM, int YM, int LT>
+__global__ void __launch_bounds__(PC_THREADS) k_wgrad_pc(WgradP p) {
+  extern __shared__ uint4 lds_raw[];
+  char* lds = (char*)lds_raw;
+
+  const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, hh = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keeps the role and k tests scalar
+  const int slab = blockIdx.y;
+  const int kg = slab % p.KGn, cbp = (slab / p.KGn) % p.CBP, nbp = slab / (p.KGn * p.CBP);
+  const int kbase = kg * WG_KG;
+  const int kcount = min(WG_KG, p.K - kbase);
+  const int cbase = cbp * 64, nbase = nbp * 64;
+  const int64_t rbeg = (int64_t)blockIdx.x * p.rows_per_part;
+  const int64_t rend = min(p.R, rbeg + p.rows_per_part);
+  const int n_tiles = rbeg < rend ? (int)((rend - rbeg + WG_RT - 1) / WG_RT) : 0;
+
+  if (wave >= PC_CONS) {
+    // octets of Y cost ~50 vector instructions per row, the basis ~100, octets of X almost nothing
+    switch (wave - PC_CONS) {
+      case 0: pc_producer<BM, YM, LT, true, 1, 0, 4, 0>(p, lds, lane, rbeg, rend, n_tiles, cbase, nbase, kbase); break;
+      case 1: pc_producer<BM, YM, LT, false, 3, 1, 0, 0>(p, lds, lane, rbeg, rend, n_tiles, cbase, nbase, kbase); break;
+      case 2: pc_producer<BM, YM, LT, false, 2, 4, 2, 4>(p, lds, lane, rbeg, rend, n_tiles, cbase, nbase, kbase); break;
+      default: pc_producer<BM, YM, LT, false, 2, 6, 2, 6>(p, lds, lane, rbeg, rend, n_tiles, cbase, nbase, kbase); break;
+    }
+    return;
+  }
+
+  const int kp = wave % p.NKPW, rs = wave / p.NKPW;
+  const bool active = (rs < p.RS) && (2 * kp < kcount);
+  const bool kv[2] = {active, active && (2 * kp + 1 < kcount)};
+
+  floatx16 acc[2][2][2];  // [kk][cb][nb]
+#pragma unroll
+  for (int a = 0; a < 2; ++a)
+#pragma unroll
+    for (int b = 0; b < 2; ++b)
+#pragma unroll
+      for (int c = 0; c < 2; ++c)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[a][b][c][i] = 0.f;
+
+  for (int t = 0; t < n_tiles; ++t) {
+    __syncthreads();
+    if (!active) continue;
+    const char* XT = lds + (t & 1) * PC_BUF_BYTES;
+    const float* YT = (const float*)(XT + PC_XT_BYTES);
+    const float* Bs = YT + 64 * XP_F32;
+    for (int ss = rs; ss < WG_RT / 16; ss += p.RS) {
+      const int roff = ss * 16 + hh * 8;
+      uint4 xf[2];
+#pragma unroll
+      for (int cb = 0; cb < 2; ++cb) xf[cb] = *(const uint4*)(XT + (cb * 32 + l32) * PC_XPB + roff * 2);
+      float2 bq[2];
+#pragma unroll
+      for (int kk = 0; kk < 2; ++kk) bq[kk] = *(const float2*)(Bs + (2 * kp + kk) * 64 + roff + 2 * (lane & 3));
+#pragma unroll
+      for (int nb = 0; nb < 2; ++nb) {
+        const float4* s = (const float4*)(YT + (nb * 32 + l32) * XP_F32 + roff);
+        const float4 ya = s[0], yb = s[1];
+#pragma unroll
+        for (int kk = 0; kk < 2; ++kk) {
+          if (!kv[kk]) continue;
+          uint4 yf;
+          yf.x = pack_bf16x2(quad_bcast<0>(bq[kk].x) * ya.x, quad_bcast<1>(bq[kk].x) * ya.y);
+          yf.y = pack_bf16x2(quad_bcast<2>(bq[kk].x) * ya.z, quad_bcast<3>(bq[kk].x) * ya.w);
+          yf.z = pack_bf16x2(quad_bcast<0>(bq[kk].y) * yb.x, quad_bcast<1>(bq[kk].y) * yb.y);
+          yf.w = pack_bf16x2(quad_bcast<2>(bq[kk].y) * yb.z, quad_bcast<3>(bq[kk].y) * yb.w);
+#pragma unroll
+          for (int cb = 0; cb < 2; ++cb)
+            acc[kk][cb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                __builtin_bit_cast(bf16x8, xf[cb]), __builtin_bit_cast(bf16x8, yf), acc[kk][cb][nb], 0, 0, 0);
+        }
+      }
+    }
+  }
+
+  // ---- write this wave's partial sums ----
+  if (rs < p.RS) {
+    const int64_t slice = (int64_t)blockIdx.x * p.RS + rs;
+#pragma unroll
+    for (int kk = 0; kk < 2; ++kk) {
+      if (!kv[kk]) continue;
+      const int k = kbase + 2 * kp + kk;
+      float* dst = p.partial + (slice * p.K + k) * (int64_t)p.Cc * p.Cn;
+#pragma unroll
+      for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+        for (int nb = 0; nb < 2; ++nb) {
+          const int n = nbase + nb * 32 + l32;
+#pragma unroll
+          for (int i = 0; i < 16; ++i) {
+            const int c = cbase + cb * 32 + 8 * (i >> 2) + 4 * hh + (i & 3);
+            dst[(int64_t)c * p.Cn + n] = acc[kk][cb][nb][i];
+          }
+        }
+    }
+  }
+}
+
+bool pm_wgrad_fuses_basis(pm_dtype mt, BMode bm, XMode xm, XMode ym, int K, int Cc, int Cn, const RowSrc& xs,
+                          const RowSrc& ys) {
+  if (mt != PM_BF16 || xm != X_DIRECT || K < 1) return false;
+  if (!((bm == B_NORMAL && ym == X_GATHER_SUM) || (bm == B_DIRS && ym == X_GATHER1))) return false;
+  if (!xs.is_bf16 || !ys.is_bf16) return false;
+  if (Cc % 64 != 0 || Cn % 64 != 0 || Cc > xs.C || Cn > ys.C) return false;
+  if (xs.C % 8 != 0 || ys.C % 8 != 0) return false;  // every row starts on a 16-byte boundary
+  return pm_aligned16(xs.p) && pm_aligned16(ys.p);
+}
+
+template <int BM, int YM, int LT>
+static pm_status launch_pc(const WgradP& p, int n_part, int slabs, hipStream_t st) {
+  auto kern = k_wgrad_pc<BM, YM, LT>;
+  const size_t lds = 2 * (size_t)PC_BUF_BYTES;
+  { ProfScope ps__(st, "k_wgrad");
+    hipLaunchKernelGGL(kern, dim3((unsigned)n_part, (unsigned)slabs), dim3(PC_THREADS), lds, st, p); }
+  PM_CHECK_LAUNCH("k_wgrad_pc");
+  return PM_OK;
+}
+
+pm_status pm_launch_wgrad_pc(BMode bm, XMode ym, const WgradP& p, int n_part, int slabs, hipStream_t st) {
+  const bool l3 = p.bs.sh.L == 3;
+  if (bm == B_NORMAL && ym == X_GATHER_SUM)
+    return l3 ? launch_pc<B_NORMAL, X_GATHER_SUM, 3>(p, n_part, slabs, st)
+              : launch_pc<B_NORMAL, X_GATHER_SUM, -1>(p, n_part, slabs, st);
+  if (bm == B_DIRS && ym == X_GATHER1)
+    return l3 ? launch_pc<B_DIRS, X_GATHER1, 3>(p, n_part, slabs, st)
+              : launch_pc<B_DIRS, X_GATHER1, -1>(p, n_part, slabs, st);
+  return pm_fail(PM_ERR_UNSUPPORTED, "wgrad producer/consumer mode (%d,%d)", (int)bm, (int)ym);
+}

@@ -121,6 +121,9 @@ CASES = [  # (L, cin, cout, dtype)
     (0, 8, 8, "f32"),
     (5, 8, 40, "bf16"),
     (3, 128, 96, "bf16"),
+    (1, 64, 64, "bf16"),
+    (4, 64, 128, "bf16"),
+    (5, 64, 64, "bf16"),
 ]
 
 
