@@ -3,15 +3,17 @@
 // for bf16 rows X read directly and Y gathered (transposed sums of Eq. 5 and Eq. 7), with the basis B
 // evaluated inside the kernel from the row's direction (Eq. 3-4).
 //
-// A workgroup has 12 waves.  Waves 8..11 are producers: lane = row of a 64-row tile; they fetch the
-// row's channels, its gathered gradient rows and its corner positions two tiles ahead, combine them
-// and write the tile TRANSPOSED into LDS (channel-major, so an MFMA operand fragment -- 8 consecutive
+// A workgroup has 12 waves.  Waves 8..11 are producers: lane = row of a 64-row block; they fetch the
+// row's channels, its gathered gradient rows and its corner positions a tile ahead, combine them
+// and write the block TRANSPOSED into LDS (channel-major, so an MFMA operand fragment -- 8 consecutive
 // rows of one channel -- is one 16-byte read).  Waves 0..7 are consumers: each owns two k's of a
 // 64x64 (c,n) slab (8 accumulator blocks of 32x32); per 16 rows it scales the Y fragment by the basis
 // values (kept compactly, two registers per k, and broadcast inside lane quads by the multiply's own
-// lane-select modifier) and issues the matrix instructions.  One barrier per tile separates the two
-// LDS buffers; producers and consumers work on different tiles at the same time, so global-memory
-// latency, the gather arithmetic and the matrix pipe overlap across waves of a SIMD.
+// lane-select modifier) and issues the matrix instructions.  A tile is two 64-row blocks; one barrier
+// per tile separates the two LDS buffers; producers and consumers work on different tiles at the same
+// time, so global-memory latency, the gather arithmetic and the matrix pipe overlap across the waves
+// of a SIMD (the longer the stretch between barriers, the better the waves of a SIMD fall into
+// alternating LDS-read and matrix phases).
 //
 // Each workgroup covers a fixed contiguous range of rows and writes its partial sums to its own
 // slice; the slices are added in a fixed order afterwards (bitwise reproducible, no float atomics).
@@ -24,7 +26,9 @@
 #define PC_XT_BYTES (64 * PC_XPB)
 #define PC_YT_BYTES (64 * XP_F32 * 4)
 #define PC_BS_BYTES (WG_KG * 64 * 4)
-#define PC_BUF_BYTES (PC_XT_BYTES + PC_YT_BYTES + PC_BS_BYTES)
+#define PC_HALF_BYTES (PC_XT_BYTES + PC_YT_BYTES + PC_BS_BYTES)   /* one staged block of 64 rows */
+#define PC_HPT 2                                                    /* 64-row blocks per tile (per barrier) */
+#define PC_BUF_BYTES (PC_HPT * PC_HALF_BYTES)
 
 // value of lane (4*(lane/4) + J) of the same quad
 template <int J>
@@ -50,8 +54,9 @@ struct PcSet {
 };
 
 // One producer wave.  It moves NX channel octets of X starting at octet X0, NY octets of Y starting at
-// Y0 and (HASB) the basis values of the tile's 64 rows.  Tile i lives in register set i&1; its loads
-// are issued three barriers before it is consumed.
+// Y0 and (HASB) the basis values of each 64-row block.  Block b of the workgroup's row range lives in
+// register set b&1 and in LDS buffer (b/2)&1, slot b&1; its loads are issued one tile before it is
+// written to LDS, its ids one tile before that.
 template <int BM, int YM, int LT, bool HASB, int NY, int Y0, int NX, int X0>
 __device__ __forceinline__ void pc_producer(const WgradP& p, char* lds, const int lane, const int64_t rbeg,
                                             const int64_t rend, const int n_tiles, const int cbase, const int nbase,
@@ -60,10 +65,10 @@ __device__ __forceinline__ void pc_producer(const WgradP& p, char* lds, const in
   using Set = PcSet<NYS, NY, NX>;
   // rows past the end are clamped to the last row (every load unconditional and in bounds); their basis
   // values are written as zero, which removes them from every sum
-  auto rowc = [&](int t) { return min(rbeg + (int64_t)t * WG_RT + lane, rend - 1); };
+  auto rowc = [&](int b) { return min(rbeg + (int64_t)b * WG_RT + lane, rend - 1); };
 
-  auto load_ids = [&](int t, PcIds& d) {
-    const int64_t r = rowc(t);
+  auto load_ids = [&](int b, PcIds& d) {
+    const int64_t r = rowc(b);
     d.y[0] = d.y[1] = d.y[2] = 0;
     if constexpr (NY > 0) {
       if constexpr (YM == X_GATHER_SUM) {
@@ -76,8 +81,8 @@ __device__ __forceinline__ void pc_producer(const WgradP& p, char* lds, const in
     if constexpr (HASB) dir_ids<BM>(p.bs, r, d.g);
   };
 
-  auto issue = [&](int t, const PcIds& d, Set& s) {
-    const int64_t r = rowc(t);
+  auto issue = [&](int b, const PcIds& d, Set& s) {
+    const int64_t r = rowc(b);
 #pragma unroll
     for (int i = 0; i < NX; ++i)
       s.x[i] = *(const uint4*)((const uint16_t*)p.xs.p + r * (int64_t)p.xs.C + cbase + (X0 + i) * 8);
@@ -103,9 +108,9 @@ __device__ __forceinline__ void pc_producer(const WgradP& p, char* lds, const in
     if constexpr (HASB) dir_load<BM>(p.bs, r, d.g, s.d);
   };
 
-  auto store = [&](int t, Set& s) {
-    const bool ok = rbeg + (int64_t)t * WG_RT + lane < rend;
-    char* XT = lds + (t & 1) * PC_BUF_BYTES;
+  auto store = [&](int b, Set& s) {
+    const bool ok = rbeg + (int64_t)b * WG_RT + lane < rend;
+    char* XT = lds + ((b >> 1) & 1) * PC_BUF_BYTES + (b & 1) * PC_HALF_BYTES;
     float* YT = (float*)(XT + PC_XT_BYTES);
     float* Bs = YT + 64 * XP_F32;
 #pragma unroll
@@ -164,18 +169,20 @@ __device__ __forceinline__ void pc_producer(const WgradP& p, char* lds, const in
   load_ids(3, i1);
   store(0, s0);
   issue(2, i0, s0);
-  // barrier t: tile t is complete in buffer t&1, and the consumers are done with buffer (t+1)&1
-  for (int t = 0; t < n_tiles; t += 2) {
+  load_ids(4, i0);
+  store(1, s1);
+  issue(3, i1, s1);
+  load_ids(5, i1);
+  // barrier t: tile t (blocks 2t, 2t+1) is complete in buffer t&1 and the consumers are done with the other
+  // buffer, which now receives tile t+1; the loads of tile t+2 go out as soon as their registers are free
+  for (int t = 0; t < n_tiles; ++t) {
     __syncthreads();
-    load_ids(t + 4, i0);
-    store(t + 1, s1);
-    issue(t + 3, i1, s1);
-    if (t + 1 < n_tiles) {
-      __syncthreads();
-      load_ids(t + 5, i1);
-      store(t + 2, s0);
-      issue(t + 4, i0, s0);
-    }
+    store(2 * t + 2, s0);
+    issue(2 * t + 4, i0, s0);
+    load_ids(2 * t + 6, i0);
+    store(2 * t + 3, s1);
+    issue(2 * t + 5, i1, s1);
+    load_ids(2 * t + 7, i1);
   }
 }
 
@@ -193,7 +200,7 @@ __global__ void __launch_bounds__(PC_THREADS) k_wgrad_pc(WgradP p) {
   const int cbase = cbp * 64, nbase = nbp * 64;
   const int64_t rbeg = (int64_t)blockIdx.x * p.rows_per_part;
   const int64_t rend = min(p.R, rbeg + p.rows_per_part);
-  const int n_tiles = rbeg < rend ? (int)((rend - rbeg + WG_RT - 1) / WG_RT) : 0;
+  const int n_tiles = rbeg < rend ? (int)((rend - rbeg + PC_HPT * WG_RT - 1) / (PC_HPT * WG_RT)) : 0;
 
   if (wave >= PC_CONS) {
     // octets of Y cost ~50 vector instructions per row, the basis ~100, octets of X almost nothing
@@ -223,11 +230,11 @@ __global__ void __launch_bounds__(PC_THREADS) k_wgrad_pc(WgradP p) {
   for (int t = 0; t < n_tiles; ++t) {
     __syncthreads();
     if (!active) continue;
-    const char* XT = lds + (t & 1) * PC_BUF_BYTES;
-    const float* YT = (const float*)(XT + PC_XT_BYTES);
-    const float* Bs = YT + 64 * XP_F32;
-    for (int ss = rs; ss < WG_RT / 16; ss += p.RS) {
-      const int roff = ss * 16 + hh * 8;
+    for (int ss = rs; ss < PC_HPT * WG_RT / 16; ss += p.RS) {
+      const char* XT = lds + (t & 1) * PC_BUF_BYTES + (ss >> 2) * PC_HALF_BYTES;
+      const float* YT = (const float*)(XT + PC_XT_BYTES);
+      const float* Bs = YT + 64 * XP_F32;
+      const int roff = (ss & 3) * 16 + hh * 8;
       uint4 xf[2];
 #pragma unroll
       for (int cb = 0; cb < 2; ++cb) xf[cb] = *(const uint4*)(XT + (cb * 32 + l32) * PC_XPB + roff * 2);
@@ -292,6 +299,7 @@ template <int BM, int YM, int LT>
 static pm_status launch_pc(const WgradP& p, int n_part, int slabs, hipStream_t st) {
   auto kern = k_wgrad_pc<BM, YM, LT>;
   const size_t lds = 2 * (size_t)PC_BUF_BYTES;
+  PM_CHECK_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
   { ProfScope ps__(st, "k_wgrad");
     hipLaunchKernelGGL(kern, dim3((unsigned)n_part, (unsigned)slabs), dim3(PC_THREADS), lds, st, p); }
   PM_CHECK_LAUNCH("k_wgrad_pc");
