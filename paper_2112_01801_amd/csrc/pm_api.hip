@@ -6,6 +6,8 @@
 
 #include <vector>
 
+#include <algorithm>
+
 #include "pm_host.h"
 
 static thread_local char g_err[512] = "";
@@ -150,7 +152,9 @@ static WsPlan plan_ws(pm_op op, int64_t V, int64_t F, int64_t P, int L, int cin,
       break;
     case PM_OP_F2V_BWD:
       w.apack = pm_pack_bytes(pm_pack_geom(K, cout, cin, dt));
-      w.inter = pm_round_up((size_t)F * K * 4, 256);   // basis rows for the weight gradient
+      // basis rows for the general weight-gradient kernel, or the gathered gradient rows dy (bf16) that the
+      // producer/consumer kernel hands to the backward-data pass
+      w.inter = pm_round_up(std::max((size_t)F * K * 4, (size_t)F * cout * 2), 256);
       w.wgrad = pm_wgrad_ws_bytes(F, K, cin, cout);
       break;
     case PM_OP_V2F:
@@ -329,18 +333,28 @@ extern "C" pm_status pm_f2v_bwd(const pm_mesh* mesh, const pm_vf_adj* adj, int L
   pm_make_sh_table(L, norm, &bs.sh);
   RowSrc dys = row_src(dg_vert, dtype, cout);   // dy_f = sum_j dg[v_j] / deg(v_j)
   dys.facet = mesh->facet; dys.row_ptr = adj->row_ptr;
-  if (dh_facet) {
-    PM_TRY(pm_launch_pack(PACK_TRANS, dtype, K, cin, cout, W, nullptr, apack, st));
-    PM_TRY(pm_launch_conv_rows(dtype, B_NORMAL, X_GATHER_SUM, F, K, cout, cin, bs, dys, apack, dh_facet,
-                               dtype == PM_BF16, st));
-  }
+  RowSrc xs = row_src(h_facet, dtype, cin);
+  // With both gradients wanted and the producer/consumer weight-gradient kernel applicable, that kernel runs
+  // first and leaves the gathered rows dy (bf16: the very operand precision of the backward-data pass)
+  // in the workspace, so the backward-data pass reads plain rows.
+  const bool pc = dW && pm_wgrad_fuses_basis(dtype, B_NORMAL, X_DIRECT, X_GATHER_SUM, K, cin, cout, xs, dys);
+  void* dy = (pc && dh_facet) ? (void*)bvals : nullptr;
   if (dW) {
-    RowSrc xs = row_src(h_facet, dtype, cin);
-    if (!pm_wgrad_fuses_basis(dtype, B_NORMAL, X_DIRECT, X_GATHER_SUM, K, cin, cout, xs, dys)) {
+    if (!pc) {
       PM_TRY(pm_launch_basis_mesh(mesh, bs.sh, bvals, st));
       bs.bvals = bvals;
     }
-    PM_TRY(pm_launch_wgrad(dtype, B_NORMAL, X_DIRECT, X_GATHER_SUM, F, K, cin, cout, bs, xs, dys, dW, wg, w.wgrad, st));
+    PM_TRY(pm_launch_wgrad(dtype, B_NORMAL, X_DIRECT, X_GATHER_SUM, F, K, cin, cout, bs, xs, dys, dW, wg, w.wgrad, dy, st));
+  }
+  if (dh_facet) {
+    PM_TRY(pm_launch_pack(PACK_TRANS, dtype, K, cin, cout, W, nullptr, apack, st));
+    if (dy) {
+      RowSrc dyr = row_src(dy, PM_BF16, cout);
+      PM_TRY(pm_launch_conv_rows(dtype, B_NORMAL, X_DIRECT, F, K, cout, cin, bs, dyr, apack, dh_facet, dtype == PM_BF16, st));
+    } else {
+      PM_TRY(pm_launch_conv_rows(dtype, B_NORMAL, X_GATHER_SUM, F, K, cout, cin, bs, dys, apack, dh_facet,
+                                 dtype == PM_BF16, st));
+    }
   }
   return PM_OK;
 }
@@ -405,7 +419,7 @@ extern "C" pm_status pm_v2f_bwd(const pm_mesh* mesh, const pm_vf_adj* adj, int L
     xs.facet = mesh->facet;
     RowSrc ys = row_src(dg_facet, dtype, cout);
     PM_TRY(pm_launch_wgrad(dtype, B_ONE, X_GATHER_CAT, X_DIRECT, F, 3, cin, cout, basis_none(), xs, ys, M, wg, w.wgrad,
-                           st));
+                           nullptr, st));
     PM_TRY(pm_launch_unfold(K, cin, cout, M, &fc, dW, st));
   }
   return PM_OK;
@@ -480,7 +494,7 @@ extern "C" pm_status pm_f2f_bwd(int64_t n_facet, int64_t n_tex, const int32_t* t
       PM_TRY(pm_launch_basis_dirs(n_tex, bary, bs.sh, bvals, st));
       bs.bvals = bvals;
     }
-    PM_TRY(pm_launch_wgrad(dtype, B_DIRS, X_DIRECT, X_GATHER1, n_tex, K, cin, cout, bs, xs, dys, dW, wg, w.wgrad, st));
+    PM_TRY(pm_launch_wgrad(dtype, B_DIRS, X_DIRECT, X_GATHER1, n_tex, K, cin, cout, bs, xs, dys, dW, wg, w.wgrad, nullptr, st));
   }
   return PM_OK;
 }

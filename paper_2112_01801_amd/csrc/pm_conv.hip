@@ -125,8 +125,8 @@ PM_CONV_DECLARE(1, B_DIRS, X_GATHER1)
 PM_CONV_DECLARE(1, B_ONE, X_DIRECT)
 PM_CONV_DECLARE(1, B_ONE, X_GATHER_CAT)
 
-// Largest weight image kept resident in LDS: 128 KiB, or less when the device offers less per workgroup.
-static size_t lds_resident_max() {
+// LDS a workgroup may use on the current device (bytes)
+static size_t pm_lds_max_bytes() {
   static int cached = -1;
   if (cached < 0) {
     int dev = 0, v = 0;
@@ -135,7 +135,11 @@ static size_t lds_resident_max() {
       v = 64 * 1024;
     cached = v;
   }
-  size_t cap = (size_t)cached;
+  return (size_t)cached;
+}
+// Largest weight image kept resident in LDS: 128 KiB, or less when the device offers less per workgroup.
+static size_t lds_resident_max() {
+  const size_t cap = pm_lds_max_bytes();
   return cap < 128 * 1024 ? cap : 128 * 1024;
 }
 
@@ -182,34 +186,59 @@ struct SegP {
   void* out;
 };
 
-// SRC_BF16: the rows being reduced are bf16 (8 channels = 16 bytes per lane) instead of fp32 (4 channels)
-template <bool SRC_BF16>
+// SRC_BF16: the rows being reduced are bf16 (8 channels = 16 bytes per lane) instead of fp32 (4 channels).
+// DIV: compile-time divisor of the column entries (1, 3) or 0 for the run-time value.
+// The entries of a segment are taken NB at a time: first the column entries, then the rows they name (all
+// in flight together), then the additions, strictly in ascending entry order.
+template <bool SRC_BF16, int DIV, int NB>
 __global__ void __launch_bounds__(256) k_segreduce(SegP p) {
   constexpr int CPL = SRC_BF16 ? 8 : 4;
   const int gpb = 256 / p.lpg;  // segments per block
-  const int64_t seg = (int64_t)blockIdx.x * gpb + threadIdx.x / p.lpg;
   const int sub = threadIdx.x % p.lpg;
-  if (seg >= p.n_seg) return;
+  for (int64_t seg = (int64_t)blockIdx.x * gpb + threadIdx.x / p.lpg; seg < p.n_seg; seg += (int64_t)gridDim.x * gpb) {
   const int32_t b = p.row_ptr[seg], e = p.row_ptr[seg + 1];
   const float scale = (p.mean && e > b) ? 1.0f / (float)(e - b) : 1.0f;
-  const bool vec = (p.C % CPL) == 0;
+  const bool vec = (p.C % CPL) == 0 && pm_aligned16_dev(p.src);
+  auto row_of = [&](int32_t i) -> int64_t {
+    if (!p.col) return (int64_t)i;
+    const int32_t c = p.col[i];
+    if constexpr (DIV == 1) return (int64_t)c;
+    else if constexpr (DIV == 3) return (int64_t)(((uint64_t)(uint32_t)c * 0xAAAAAAABull) >> 33);
+    else return (int64_t)(c / p.div);
+  };
   for (int c0 = sub * CPL; c0 < p.C; c0 += p.lpg * CPL) {
     float a[CPL];
 #pragma unroll
     for (int i = 0; i < CPL; ++i) a[i] = 0.f;
-    for (int32_t i = b; i < e; ++i) {
-      const int64_t r = p.col ? (int64_t)(p.col[i] / p.div) : (int64_t)i;
-      const int64_t o = r * p.C + c0;
-      if (vec) {
-        if constexpr (SRC_BF16) {
-          const uint4 u = *(const uint4*)((const uint16_t*)p.src + o);
-          a[0] += bf16lo_to_f32(u.x); a[1] += bf16hi_to_f32(u.x); a[2] += bf16lo_to_f32(u.y); a[3] += bf16hi_to_f32(u.y);
-          a[4] += bf16lo_to_f32(u.z); a[5] += bf16hi_to_f32(u.z); a[6] += bf16lo_to_f32(u.w); a[7] += bf16hi_to_f32(u.w);
-        } else {
-          const float4 f = *(const float4*)((const float*)p.src + o);
-          a[0] += f.x; a[1] += f.y; a[2] += f.z; a[3] += f.w;
+    if (vec) {
+      for (int32_t i0 = b; i0 < e; i0 += NB) {
+        int64_t r[NB];
+#pragma unroll
+        for (int j = 0; j < NB; ++j) r[j] = row_of(min(i0 + j, e - 1));   // clamped: loads are unconditional
+        uint4 u[NB];
+#pragma unroll
+        for (int j = 0; j < NB; ++j) {
+          const int64_t o = r[j] * p.C + c0;
+          if constexpr (SRC_BF16) u[j] = *(const uint4*)((const uint16_t*)p.src + o);
+          else u[j] = *(const uint4*)((const float*)p.src + o);
         }
-      } else {
+        __builtin_amdgcn_sched_barrier(0);   // every load of the batch is out before the first addition waits
+#pragma unroll
+        for (int j = 0; j < NB; ++j) {
+          if (i0 + j >= e) u[j] = make_uint4(0, 0, 0, 0);   // a select: adding +0 leaves the sum as it is
+          if constexpr (SRC_BF16) {
+            a[0] += bf16lo_to_f32(u[j].x); a[1] += bf16hi_to_f32(u[j].x); a[2] += bf16lo_to_f32(u[j].y);
+            a[3] += bf16hi_to_f32(u[j].y); a[4] += bf16lo_to_f32(u[j].z); a[5] += bf16hi_to_f32(u[j].z);
+            a[6] += bf16lo_to_f32(u[j].w); a[7] += bf16hi_to_f32(u[j].w);
+          } else {
+            a[0] += __uint_as_float(u[j].x); a[1] += __uint_as_float(u[j].y);
+            a[2] += __uint_as_float(u[j].z); a[3] += __uint_as_float(u[j].w);
+          }
+        }
+      }
+    } else {
+      for (int32_t i = b; i < e; ++i) {
+        const int64_t o = row_of(i) * p.C + c0;
 #pragma unroll
         for (int q = 0; q < CPL; ++q)
           if (c0 + q < p.C)
@@ -219,7 +248,7 @@ __global__ void __launch_bounds__(256) k_segreduce(SegP p) {
 #pragma unroll
     for (int i = 0; i < CPL; ++i) a[i] *= scale;
     const int64_t o = seg * p.C + c0;
-    if (vec) {
+    if (vec && (p.C % 4) == 0 && pm_aligned16_dev(p.out)) {
       if (p.out_bf16) {
 #pragma unroll
         for (int q = 0; q < CPL / 4; ++q) {
@@ -241,11 +270,21 @@ __global__ void __launch_bounds__(256) k_segreduce(SegP p) {
         }
     }
   }
+  }
+}
+
+template <bool SRC_BF16>
+static void launch_segreduce_div(const SegP& p, dim3 grid, hipStream_t st) {
+  // two entries per batch measured best on MI355X (deeper batches lose more to cache pressure than they gain)
+  if (p.div == 1) hipLaunchKernelGGL((k_segreduce<SRC_BF16, 1, 2>), grid, dim3(256), 0, st, p);
+  else if (p.div == 3) hipLaunchKernelGGL((k_segreduce<SRC_BF16, 3, 2>), grid, dim3(256), 0, st, p);
+  else hipLaunchKernelGGL((k_segreduce<SRC_BF16, 0, 2>), grid, dim3(256), 0, st, p);
 }
 
 pm_status pm_launch_segreduce(int64_t n_seg, int C, const void* src, int src_is_bf16, const int32_t* row_ptr,
                               const int32_t* col, int div, int mean, void* out, int out_is_bf16, hipStream_t st) {
   if (n_seg == 0) return PM_OK;
+  if (div < 1) return pm_fail(PM_ERR_INVALID_ARG, "segreduce divisor %d", div);
   SegP p;
   p.n_seg = n_seg; p.C = C; p.div = div; p.mean = mean; p.out_bf16 = out_is_bf16;
   p.src = src; p.row_ptr = row_ptr; p.col = col; p.out = out;
@@ -254,10 +293,12 @@ pm_status pm_launch_segreduce(int64_t n_seg, int C, const void* src, int src_is_
   while (lpg < need && lpg < 64) lpg <<= 1;
   p.lpg = lpg;
   int gpb = 256 / lpg;
-  const dim3 grid((unsigned)((n_seg + gpb - 1) / gpb));
+  int64_t nblk = (n_seg + gpb - 1) / gpb;
+  if (nblk > 0x7fffffff) nblk = 0x7fffffff;   // the kernel strides over the segments
+  const dim3 grid((unsigned)nblk);
   { ProfScope ps__(st, "k_segreduce");
-    if (src_is_bf16) hipLaunchKernelGGL(k_segreduce<true>, grid, dim3(256), 0, st, p);
-    else hipLaunchKernelGGL(k_segreduce<false>, grid, dim3(256), 0, st, p); }
+    if (src_is_bf16) launch_segreduce_div<true>(p, grid, st);
+    else launch_segreduce_div<false>(p, grid, st); }
   PM_CHECK_LAUNCH("k_segreduce");
   return PM_OK;
 }

@@ -19,6 +19,7 @@ struct ShTable {
   int L;
 };
 
+__device__ __forceinline__ bool pm_aligned16_dev(const void* p) { return (((uintptr_t)p) & 15u) == 0; }
 __device__ __forceinline__ float bf16_to_f32(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
 __device__ __forceinline__ float bf16lo_to_f32(uint32_t u) { return __uint_as_float(u << 16); }
 __device__ __forceinline__ float bf16hi_to_f32(uint32_t u) { return __uint_as_float(u & 0xffff0000u); }

@@ -108,13 +108,14 @@ pm_status pm_launch_segreduce(int64_t n_seg, int C, const void* src, int src_is_
 // dWp[k][c][n] = sum_r B_r[k] X_r[c] Y_r[n], fp32, deterministic (per-workgroup partials + fixed-order sum).
 // X_GATHER_CAT here means: k indexes the corner, X^{(k)}_r = xs.p[facet[r][k]] (K must be 3, B_ONE).
 // bs.bvals must hold the basis rows [R][K] (fp32) unless B_ONE or pm_wgrad_fuses_basis() says that the kernel
-// chosen for these arguments evaluates the basis itself from bs.vert / bs.facet / bs.dirs.
+// chosen for these arguments evaluates the basis itself from bs.vert / bs.facet / bs.dirs.  Only that kernel
+// accepts y_out != NULL: it then also writes the Y operand rows (after gathering), bf16 [R][Cn].
 size_t pm_wgrad_ws_bytes(int64_t R, int K, int Cc, int Cn);
 bool pm_wgrad_fuses_basis(pm_dtype mt, BMode bm, XMode xm, XMode ym, int K, int Cc, int Cn, const RowSrc& xs,
                           const RowSrc& ys);
 pm_status pm_launch_wgrad(pm_dtype mt, BMode bm, XMode xm, XMode ym, int64_t R, int K, int Cc, int Cn,
                           const BasisSrc& bs, const RowSrc& xs, const RowSrc& ys, float* dWp, void* ws, size_t ws_bytes,
-                          hipStream_t st);
+                          void* y_out, hipStream_t st);
 // dW[k][ci][co] = sum_j fc[j][k] M[j][ci][co]
 pm_status pm_launch_unfold(int K, int cin, int cout, const float* M, const FoldCoef* fc, float* dW, hipStream_t st);
 // owner[p] = f for p in [tex_off[f], tex_off[f+1])

@@ -15,6 +15,7 @@ struct WgradP {
   BasisSrc bs;         // bs.bvals: precomputed basis rows [R][K] (unused for B_ONE)
   RowSrc xs, ys;
   float* partial;      // [n_part * RS][K][Cc][Cn]
+  void* y_out;         // optional (producer/consumer kernel): the Y operand rows [R][Cn] are also written here, bf16
 };
 
 // Producer/consumer variant (see pm_wgrad_fuses_basis for when it applies).

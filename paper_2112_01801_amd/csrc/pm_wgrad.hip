@@ -523,7 +523,7 @@ static pm_status launch_wgrad_mode(BMode bm, XMode xm, XMode ym, const WgradP& p
 
 pm_status pm_launch_wgrad(pm_dtype mt, BMode bm, XMode xm, XMode ym, int64_t R, int K, int Cc, int Cn,
                           const BasisSrc& bs, const RowSrc& xs, const RowSrc& ys, float* dWp, void* ws, size_t ws_bytes,
-                          hipStream_t st) {
+                          void* y_out, hipStream_t st) {
   WgradGeom g = wgrad_geom(R, K, Cc, Cn);
   if (ws_bytes < pm_wgrad_ws_bytes(R, K, Cc, Cn)) return pm_fail(PM_ERR_WORKSPACE, "wgrad workspace too small");
   WgradP p;
@@ -531,9 +531,12 @@ pm_status pm_launch_wgrad(pm_dtype mt, BMode bm, XMode xm, XMode ym, int64_t R, 
   p.K = K; p.Cc = Cc; p.Cn = Cn;
   p.KGn = g.KGn; p.CBP = g.CBP; p.NBP = g.NBP; p.NKPW = g.NKPW; p.RS = g.RS;
   p.bs = bs; p.xs = xs; p.ys = ys; p.partial = (float*)ws;
+  p.y_out = y_out;
   pm_status s;
   if (pm_wgrad_fuses_basis(mt, bm, xm, ym, K, Cc, Cn, xs, ys))
     s = pm_launch_wgrad_pc(bm, ym, p, g.n_part, g.slabs, st);
+  else if (y_out)
+    return pm_fail(PM_ERR_UNSUPPORTED, "the general weight-gradient kernel does not write the Y rows");
   else
     s = (mt == PM_BF16) ? launch_wgrad_mode<1>(bm, xm, ym, p, g, st) : launch_wgrad_mode<0>(bm, xm, ym, p, g, st);
   if (s != PM_OK) return s;

@@ -17,6 +17,8 @@
 //
 // Each workgroup covers a fixed contiguous range of rows and writes its partial sums to its own
 // slice; the slices are added in a fixed order afterwards (bitwise reproducible, no float atomics).
+// On request the producers also write the gathered Y rows (bf16) to global memory, so that the
+// backward-data pass of the same call can read them as plain rows instead of gathering them again.
 #include "pm_wgrad.h"
 
 #define PC_CONS 8
@@ -61,6 +63,7 @@ template <int BM, int YM, int LT, bool HASB, int NY, int Y0, int NX, int X0>
 __device__ __forceinline__ void pc_producer(const WgradP& p, char* lds, const int lane, const int64_t rbeg,
                                             const int64_t rend, const int n_tiles, const int cbase, const int nbase,
                                             const int kbase) {
+  const bool emit_y = p.y_out != nullptr && cbase == 0 && kbase == 0;   // one slab per n-range writes the rows
   constexpr int NYS = (YM == X_GATHER_SUM) ? 3 : 1;
   using Set = PcSet<NYS, NY, NX>;
   // rows past the end are clamped to the last row (every load unconditional and in bounds); their basis
@@ -145,6 +148,13 @@ __device__ __forceinline__ void pc_producer(const WgradP& p, char* lds, const in
         }
 #pragma unroll
         for (int e = 0; e < 8; ++e) YT[((Y0 + i) * 8 + e) * XP_F32 + lane] = v[e];
+        if (emit_y && ok) {
+          uint4 w;
+          w.x = pack_bf16x2(v[0], v[1]); w.y = pack_bf16x2(v[2], v[3]);
+          w.z = pack_bf16x2(v[4], v[5]); w.w = pack_bf16x2(v[6], v[7]);
+          const int64_t r = rbeg + (int64_t)b * WG_RT + lane;
+          *(uint4*)((uint16_t*)p.y_out + r * (int64_t)p.Cn + nbase + (Y0 + i) * 8) = w;
+        }
       }
     }
     if constexpr (HASB) {

@@ -184,6 +184,24 @@ def test_f2f_forward_backward(pm, L, cin, cout, dtype):
     assert rel_err(to_host(dW), rdW) < TOL[dtype]
 
 
+@pytest.mark.parametrize("L,cin,cout", [(3, 64, 64), (2, 64, 128)])
+def test_f2v_backward_single_gradients(pm, L, cin, cout):
+    """dh alone and dW alone take other kernel paths than the joint call (which shares the gathered rows)."""
+    dtype = "bf16"
+    b, rng, K, W, mesh, adj = _setup(pm, L, cin, cout, dtype, 15)
+    h = make_features(rng, b.n_facet, cin, dtype)
+    dg = make_features(rng, b.n_vert, cout, dtype)
+    args = (mesh, adj, L, to_dev(h, dtype), to_dev(W, dtype), to_dev(dg, dtype), pm_dtype(dtype))
+    rdh, rdW = oracle.f2v_bwd(b.vert, b.facet, L, h, W, dg)
+    dh, none = pm.pm_f2v_bwd(*args, want_dW=False)
+    assert none is None and rel_err(to_host(dh), rdh) < TOL[dtype]
+    none, dW = pm.pm_f2v_bwd(*args, want_dh=False)
+    assert none is None and rel_err(to_host(dW), rdW) < TOL[dtype]
+    dh2, dW2 = pm.pm_f2v_bwd(*args)
+    assert rel_err(to_host(dh2), rdh) < TOL[dtype] and rel_err(to_host(dW2), rdW) < TOL[dtype]
+    assert np.array_equal(to_host(dW2), to_host(dW))           # the weight gradient does not depend on the pairing
+
+
 def test_f2f_empty_facets_and_paper_shape(pm):
     """Cin = 3 colour channels (the paper's own shape), some facets without texture points."""
     import torch
