@@ -149,6 +149,20 @@ def main():
                     "unit": dom["unit"], "frac": dom["frac"], "traffic": read_traffic(dom["kernel"], args.grid),
                     "avg_ms": dom["avg_ms"]}
 
+    # what this device sustains in short issue loops, beside the published peaks
+    pws = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+    peaks = {}
+    for key, kind in (("mfma_bf16_ones", pm.PM_PEAK_MFMA_BF16_ONES), ("mfma_bf16_random", pm.PM_PEAK_MFMA_BF16_RANDOM),
+                      ("hbm_copy", pm.PM_PEAK_HBM_COPY)):
+        rate, clk = pm.pm_peak_probe(kind, pws)
+        peaks[key] = {"value": round(rate, 1), "unit": "GB/s" if key == "hbm_copy" else "TFLOP/s",
+                      "shader_clock_mhz": round(clk)}
+    del pws
+    if roofline:
+        ref = peaks["mfma_bf16_random"]["value"] if roofline["bound"] == "mfma" else peaks["hbm_copy"]["value"]
+        roofline["frac_of_measured_peak"] = round(roofline["achieved"] / ref, 4)
+        roofline["measured_peak"] = ref
+
     cpu_baseline = None
     if not args.no_cpu_baseline:
         cpu_baseline = oracle_baseline(cfg, min(args.oracle_rows, args.grid), h, W, dg)
@@ -163,6 +177,7 @@ def main():
                    "ops": ["pm_f2v", "pm_f2v_bwd"], "adjacency_setup_ms": round(setup_ms, 3)},
         "roofline": roofline,
         "cpu_baseline": cpu_baseline,
+        "measured_peaks": peaks,
         "kernels": kernels,
     }
     print(json.dumps(out))

@@ -146,6 +146,21 @@ int32_t pm_profile_count(void);
 pm_status pm_profile_read(int32_t i, char* name, size_t name_cap, float* ms);
 pm_status pm_profile_reset(void);
 
+/* Measurement aid (not part of the method): rates this device sustains in short issue loops, to quote beside
+ * the published peaks.  The bf16 matrix loop exists with all-ones operands and with random signs and
+ * mantissas: the shader clock is power-managed, so the rate depends on the data.  `ws` is device memory
+ * the probe may overwrite (16-byte aligned, >= 1 MiB; the copy probe moves half of it to the other half,
+ * so give it a few hundred MiB to measure HBM rather than the caches).  *value receives TFLOP/s (matrix
+ * probes) or GB/s read+written (copy); *clock_mhz (may be NULL) the shader clock observed inside the probe
+ * kernel.  The call synchronises `stream`; it allocates no device memory. */
+typedef enum {
+  PM_PEAK_MFMA_BF16_ONES = 0,
+  PM_PEAK_MFMA_BF16_RANDOM = 1,
+  PM_PEAK_MFMA_F32 = 2,
+  PM_PEAK_HBM_COPY = 3
+} pm_peak_kind;
+pm_status pm_peak_probe(pm_peak_kind kind, void* ws, size_t ws_bytes, double* value, double* clock_mhz, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

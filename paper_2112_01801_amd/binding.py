@@ -25,6 +25,7 @@ EXPORTS = [
     "pm_status_string", "pm_last_error", "pm_workspace_bytes", "pm_validate_mesh", "pm_build_vf_adjacency",
     "pm_sh_basis", "pm_sh_basis_dirs", "pm_sh_basis_bwd", "pm_f2v", "pm_f2v_bwd", "pm_v2f", "pm_v2f_bwd",
     "pm_f2f", "pm_f2f_bwd", "pm_profile_enable", "pm_profile_count", "pm_profile_read", "pm_profile_reset",
+    "pm_peak_probe",
 ]
 
 
@@ -75,7 +76,8 @@ def lib():
             "pm_f2f_bwd": [i64, i64, vp, vp, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, sz, vp],
         }
         sig.update({"pm_profile_enable": [i32], "pm_profile_count": [], "pm_profile_reset": [],
-                    "pm_profile_read": [i32, C.c_char_p, sz, C.POINTER(C.c_float)]})
+                    "pm_profile_read": [i32, C.c_char_p, sz, C.POINTER(C.c_float)],
+                    "pm_peak_probe": [i32, vp, sz, C.POINTER(C.c_double), C.POINTER(C.c_double), vp]})
         for name, args in sig.items():
             f = getattr(l, name)
             f.restype = C.c_int32
@@ -303,6 +305,17 @@ def pm_profile_enable(on: bool) -> None:
 
 def pm_profile_reset() -> None:
     _check(lib().pm_profile_reset())
+
+
+PM_PEAK_MFMA_BF16_ONES, PM_PEAK_MFMA_BF16_RANDOM, PM_PEAK_MFMA_F32, PM_PEAK_HBM_COPY = 0, 1, 2, 3
+
+
+def pm_peak_probe(kind: int, ws: torch.Tensor, stream=None):
+    """(rate, shader clock in MHz) of one issue-loop probe; rate in TFLOP/s, or GB/s for the copy."""
+    val, clk = C.c_double(), C.c_double()
+    _check(lib().pm_peak_probe(kind, _ptr(ws), ws.numel() * ws.element_size(), C.byref(val), C.byref(clk),
+                               _stream(stream)))
+    return float(val.value), float(clk.value)
 
 
 def pm_profile_read():

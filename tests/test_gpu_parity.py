@@ -267,3 +267,18 @@ def test_argument_errors(pm):
     with pytest.raises(pm.PmError) as e:
         pm.pm_f2v(mesh, adj, 3, h, torch.zeros(16 * 8 * 8 + 1, device="cuda")[1:].view(16, 8, 8), 0)
     assert e.value.status == -1
+
+
+def test_peak_probes_report_sane_rates(pm):
+    """The measurement aid: rates within the physical range of the device, clock readings present."""
+    import torch
+    ws = torch.empty(256 << 20, dtype=torch.uint8, device="cuda")
+    ones, clk1 = pm.pm_peak_probe(pm.PM_PEAK_MFMA_BF16_ONES, ws)
+    rnd, clk2 = pm.pm_peak_probe(pm.PM_PEAK_MFMA_BF16_RANDOM, ws)
+    f32, _ = pm.pm_peak_probe(pm.PM_PEAK_MFMA_F32, ws)
+    copy, _ = pm.pm_peak_probe(pm.PM_PEAK_HBM_COPY, ws)
+    assert 500 < rnd <= ones * 1.05 < 2700 and 30 < f32 < 170 and 500 < copy < 8500
+    assert 500 < clk2 <= clk1 * 1.05 < 3000
+    with pytest.raises(pm.PmError) as e:
+        pm.pm_peak_probe(pm.PM_PEAK_HBM_COPY, torch.empty(1024, dtype=torch.uint8, device="cuda"))
+    assert e.value.status == -3
