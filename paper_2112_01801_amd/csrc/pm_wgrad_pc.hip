@@ -129,9 +129,9 @@ __device__ __forceinline__ void pc_producer(const WgradP& p, char* lds, const in
       float wt[3] = {1.f, 1.f, 1.f};
       if constexpr (YM == X_GATHER_SUM) {
 #pragma unroll
-        for (int j = 0; j < 3; ++j) wt[j] = 1.0f / (float)(s.hi[j] - s.lo[j]);
+        for (int j = 0; j < 3; ++j) wt[j] = __builtin_amdgcn_rcpf((float)(s.hi[j] - s.lo[j]));   // 1 ulp
       } else if constexpr (YM == X_GATHER1) {
-        wt[0] = 1.0f / (float)(s.hi[0] - s.lo[0]);
+        wt[0] = __builtin_amdgcn_rcpf((float)(s.hi[0] - s.lo[0]));
       }
 #pragma unroll
       for (int i = 0; i < NY; ++i) {
@@ -162,8 +162,12 @@ __device__ __forceinline__ void pc_producer(const WgradP& p, char* lds, const in
       dir_finish<BM>(s.d, x, y, z);
       const int pos = basis_pos(lane);
       sh_eval<LT>(x, y, z, p.bs.sh, [&](int k, float v) {
-        const int kl = k - kbase;
-        if (kl >= 0 && kl < WG_KG) Bs[kl * 64 + pos] = ok ? v : 0.f;
+        if constexpr (LT >= 0 && (LT + 1) * (LT + 1) <= WG_KG) {   // one k group: kbase is 0
+          Bs[k * 64 + pos] = ok ? v : 0.f;
+        } else {
+          const int kl = k - kbase;
+          if (kl >= 0 && kl < WG_KG) Bs[kl * 64 + pos] = ok ? v : 0.f;
+        }
       });
     }
   };
