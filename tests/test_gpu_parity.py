@@ -282,3 +282,45 @@ def test_peak_probes_report_sane_rates(pm):
     with pytest.raises(pm.PmError) as e:
         pm.pm_peak_probe(pm.PM_PEAK_HBM_COPY, torch.empty(1024, dtype=torch.uint8, device="cuda"))
     assert e.value.status == -3
+
+
+def test_step_replays_from_a_hip_graph(pm):
+    """The entry points enqueue kernels only (no allocation, no synchronisation, caller's workspace), so a
+    forward+backward step can be captured into a HIP graph.  Replays, with eager work and synchronisations
+    in between, must reproduce the eager results bit for bit."""
+    import torch
+    L, cin, cout, dtype = 3, 64, 64, "bf16"
+    b, rng, K, W, mesh, adj = _setup(pm, L, cin, cout, dtype, 80)
+    h = to_dev(make_features(rng, b.n_facet, cin, dtype), dtype)
+    dg = to_dev(make_features(rng, b.n_vert, cout, dtype), dtype)
+    Wd = to_dev(W, dtype)
+    V, F = b.n_vert, b.n_facet
+    ws_f = pm.alloc_workspace(pm.pm_workspace_bytes(pm.PM_OP_F2V, V, F, 0, L, cin, cout, 1))
+    ws_b = pm.alloc_workspace(pm.pm_workspace_bytes(pm.PM_OP_F2V_BWD, V, F, 0, L, cin, cout, 1))
+    g = torch.empty((V, cout), dtype=torch.bfloat16, device="cuda")
+    dh = torch.empty((F, cin), dtype=torch.bfloat16, device="cuda")
+    dW = torch.empty((K, cin, cout), dtype=torch.float32, device="cuda")
+
+    def step(stream=None):
+        pm.pm_f2v(mesh, adj, L, h, Wd, 1, out=g, ws=ws_f, stream=stream)
+        pm.pm_f2v_bwd(mesh, adj, L, h, Wd, dg, 1, dh=dh, dW=dW, ws=ws_b, stream=stream)
+
+    step()
+    torch.cuda.synchronize()
+    ref = (g.clone(), dh.clone(), dW.clone())
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        step(side)                                  # warm-up on the capture stream (function attributes are set here)
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            step(side)
+    for rep in range(3):
+        for t in (g, dh, dW):
+            t.zero_()                               # eager work between replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for got, want in zip((g, dh, dW), ref):
+            assert torch.equal(got, want), "replay %d differs from the eager result" % rep
