@@ -161,14 +161,14 @@ static WsPlan plan_ws(pm_op op, int64_t V, int64_t F, int64_t P, int L, int cin,
       w.apack = pm_pack_bytes(pm_pack_geom(1, 3 * cin, cout, dt));
       break;
     case PM_OP_V2F_BWD:
-      w.apack = pm_pack_bytes(pm_pack_geom(1, cout, 3 * cin, dt));
-      w.inter = pm_round_up((size_t)F * 3 * cin * 4, 256);
+      w.apack = pm_pack_bytes(pm_pack_geom(1, 3 * cout, cin, dt));
+      w.inter = pm_round_up((size_t)V * 3 * cout * esize(dt), 256);   // per-vertex corner-slot sums of dg
       w.small = pm_round_up((size_t)3 * cin * cout * 4, 256);
       w.wgrad = pm_wgrad_ws_bytes(F, 3, cin, cout);
       break;
     case PM_OP_F2F:
       w.apack = pm_pack_bytes(pm_pack_geom(K, cin, cout, dt));
-      w.inter = pm_round_up((size_t)P * cout * 4, 256);
+      w.inter = pm_round_up((size_t)P * cout * esize(dt), 256);   // per-point summands, feature dtype
       break;
     case PM_OP_F2F_BWD:
       w.apack = pm_pack_bytes(pm_pack_geom(K, cout, cin, dt));
@@ -402,17 +402,20 @@ extern "C" pm_status pm_v2f_bwd(const pm_mesh* mesh, const pm_vf_adj* adj, int L
   PM_TRY(check_ws(w, ws, ws_bytes));
   hipStream_t st = (hipStream_t)stream;
   char* apack = (char*)ws;
-  float* dz = (float*)(apack + w.apack);               // [F][3][cin] per-corner input gradients
-  float* M = (float*)((char*)dz + w.inter);            // [3][cin][cout]
+  void* sv = apack + w.apack;                          // [V][3][cout] corner-slot sums of dg (feature dtype)
+  float* M = (float*)((char*)sv + w.inter);            // [3][cin][cout]
   void* wg = (char*)M + w.small;
   FoldCoef fc;
   fold_coef(L, norm, &fc);
   if (dh_vert) {
-    PM_TRY(pm_launch_pack(PACK_FOLD_TRANS, dtype, K, cin, cout, W, &fc, apack, st));
-    RowSrc xs = row_src(dg_facet, dtype, cout);
-    PM_TRY(pm_launch_conv_rows(dtype, B_ONE, X_DIRECT, F, 1, cout, 3 * cin, basis_none(), xs, apack, dz, 0, st));
-    // row 3f+j of dz is exactly corner slot 3f+j of the adjacency
-    PM_TRY(pm_launch_segreduce(V, cin, dz, 0, adj->row_ptr, adj->col, 1, 0, dh_vert, dtype == PM_BF16, st));
+    // dh_v = sum_j W_j (sum over the facets that have v at corner j of dg_f),  W_j = sum_k B_k(e_j) W[k]:
+    // first the corner-slot sums at the vertices (an adjacency entry 3f+j names facet and slot), then one
+    // matrix pass over the vertex rows.  No per-facet intermediate is formed.
+    const int fb = dtype == PM_BF16;
+    PM_TRY(pm_launch_segsum_slots(V, cout, dg_facet, fb, adj->row_ptr, adj->col, sv, fb, st));
+    PM_TRY(pm_launch_pack(PACK_FOLD_BWD, dtype, K, cin, cout, W, &fc, apack, st));
+    RowSrc xs = row_src(sv, dtype, 3 * cout);
+    PM_TRY(pm_launch_conv_rows(dtype, B_ONE, X_DIRECT, V, 1, 3 * cout, cin, basis_none(), xs, apack, dh_vert, fb, st));
   }
   if (dW) {
     RowSrc xs = row_src(h_vert, dtype, cin);
@@ -448,14 +451,15 @@ extern "C" pm_status pm_f2f(int64_t n_facet, int64_t n_tex, const int32_t* tex_o
   PM_TRY(check_ws(w, ws, ws_bytes));
   hipStream_t st = (hipStream_t)stream;
   char* apack = (char*)ws;
-  float* yp = (float*)(apack + w.apack);   // per-point summands of Eq. 7
+  void* yp = apack + w.apack;   // per-point summands of Eq. 7, in the feature dtype (summed in fp32)
+  const int yb = dtype == PM_BF16;
   PM_TRY(pm_launch_pack(PACK_PLAIN, dtype, K, cin, cout, W, nullptr, apack, st));
   BasisSrc bs = basis_none();
   bs.dirs = bary;
   pm_make_sh_table(L, norm, &bs.sh);
   RowSrc xs = row_src(h_tex, dtype, cin);
-  PM_TRY(pm_launch_conv_rows(dtype, B_DIRS, X_DIRECT, n_tex, K, cin, cout, bs, xs, apack, yp, 0, st));
-  return pm_launch_segreduce(n_facet, cout, yp, 0, tex_off, nullptr, 1, 1, g_facet, dtype == PM_BF16, st);
+  PM_TRY(pm_launch_conv_rows(dtype, B_DIRS, X_DIRECT, n_tex, K, cin, cout, bs, xs, apack, yp, yb, st));
+  return pm_launch_segreduce(n_facet, cout, yp, yb, tex_off, nullptr, 1, 1, g_facet, dtype == PM_BF16, st);
 }
 
 extern "C" pm_status pm_f2f_bwd(int64_t n_facet, int64_t n_tex, const int32_t* tex_off, const float* bary, int L,

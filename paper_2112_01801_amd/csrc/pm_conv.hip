@@ -34,28 +34,49 @@ __device__ __forceinline__ float pack_src(const PackP& p, int k, int ci, int co)
   return p.src_bf16 ? bf16_to_f32(((const uint16_t*)p.W)[o]) : ((const float*)p.W)[o];
 }
 
-// logical Wp[k][c][n]
-__device__ __forceinline__ float pack_value(const PackP& p, int k, int c, int n) {
-  if (c >= p.Cc || n >= p.Cn) return 0.f;
-  switch (p.mode) {
-    case PACK_PLAIN: return pack_src(p, k, c, n);
-    case PACK_TRANS: return pack_src(p, k, n, c);
-    case PACK_FOLD: {
-      int j = c / p.cin, ci = c - j * p.cin;
-      float s = 0.f;
-      for (int kk = 0; kk < p.K; ++kk) s += p.fc.c[j][kk] * pack_src(p, kk, ci, n);
-      return s;
-    }
-    default: {  // PACK_FOLD_TRANS
-      int j = n / p.cin, ci = n - j * p.cin;
-      float s = 0.f;
-      for (int kk = 0; kk < p.K; ++kk) s += p.fc.c[j][kk] * pack_src(p, kk, ci, c);
-      return s;
-    }
+// logical Wp[k][c][n], N consecutive c starting at c0.  The folded forms sum over k in ascending order; the
+// loads of all N elements for two k at a time are issued before the additions.
+//   PLAIN: W[k][c][n]   TRANS: W[k][n][c]   FOLD: sum_k fc[j][k] W[k][ci][n], c = j*cin+ci
+//   FOLD_TRANS: sum_k fc[j][k] W[k][ci][c], n = j*cin+ci      FOLD_BWD: sum_k fc[j][k] W[k][n][co], c = j*cout+co
+template <int MODE, int N>
+__device__ __forceinline__ void pack_values(const PackP& p, int k, int c0, int n, float (&v)[N]) {
+  int j[N], ci[N], co[N];
+  bool ok[N];
+#pragma unroll
+  for (int e = 0; e < N; ++e) {
+    const int c = c0 + e;
+    ok[e] = c < p.Cc && n < p.Cn;
+    j[e] = 0;
+    if (MODE == PACK_PLAIN) { ci[e] = c; co[e] = n; }
+    else if (MODE == PACK_TRANS) { ci[e] = n; co[e] = c; }
+    else if (MODE == PACK_FOLD) { j[e] = c / p.cin; ci[e] = c - j[e] * p.cin; co[e] = n; }
+    else if (MODE == PACK_FOLD_TRANS) { j[e] = n / p.cin; ci[e] = n - j[e] * p.cin; co[e] = c; }
+    else { j[e] = c / p.cout; ci[e] = n; co[e] = c - j[e] * p.cout; }
+    if (!ok[e]) { j[e] = 0; ci[e] = 0; co[e] = 0; }   // in-bounds dummy, the value is dropped
+    v[e] = 0.f;
   }
+  if (MODE == PACK_PLAIN || MODE == PACK_TRANS) {
+#pragma unroll
+    for (int e = 0; e < N; ++e) v[e] = ok[e] ? pack_src(p, k, ci[e], co[e]) : 0.f;
+    return;
+  }
+  int kk = 0;
+  for (; kk + 2 <= p.K; kk += 2) {
+    float w0[N], w1[N];
+#pragma unroll
+    for (int e = 0; e < N; ++e) { w0[e] = pack_src(p, kk, ci[e], co[e]); w1[e] = pack_src(p, kk + 1, ci[e], co[e]); }
+#pragma unroll
+    for (int e = 0; e < N; ++e) { v[e] += p.fc.c[j[e]][kk] * w0[e]; v[e] += p.fc.c[j[e]][kk + 1] * w1[e]; }
+  }
+  for (; kk < p.K; ++kk)
+#pragma unroll
+    for (int e = 0; e < N; ++e) v[e] += p.fc.c[j[e]][kk] * pack_src(p, kk, ci[e], co[e]);
+#pragma unroll
+  for (int e = 0; e < N; ++e) v[e] = ok[e] ? v[e] : 0.f;
 }
 
 // one thread per (stage, nbi, g, lane) granule
+template <int MODE>
 __global__ void __launch_bounds__(256) k_pack(PackP p, int64_t n_gran) {
   int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (t >= n_gran) return;
@@ -73,16 +94,15 @@ __global__ void __launch_bounds__(256) k_pack(PackP p, int64_t n_gran) {
   if (p.dst_bf16) {
     const int c0 = (ch * PM_GC + g) * 16 + hh * 8;
     float v[8];
-#pragma unroll
-    for (int e = 0; e < 8; ++e) v[e] = pack_value(p, k, c0 + e, n);
+    pack_values<MODE, 8>(p, k, c0, n, v);
     o.x = pack_bf16x2(v[0], v[1]); o.y = pack_bf16x2(v[2], v[3]);
     o.z = pack_bf16x2(v[4], v[5]); o.w = pack_bf16x2(v[6], v[7]);
   } else {
     const int c0 = (ch * PM_GC + g) * 8 + hh * 4;
-    o.x = __float_as_uint(pack_value(p, k, c0 + 0, n));
-    o.y = __float_as_uint(pack_value(p, k, c0 + 1, n));
-    o.z = __float_as_uint(pack_value(p, k, c0 + 2, n));
-    o.w = __float_as_uint(pack_value(p, k, c0 + 3, n));
+    float v[4];
+    pack_values<MODE, 4>(p, k, c0, n, v);
+    o.x = __float_as_uint(v[0]); o.y = __float_as_uint(v[1]);
+    o.z = __float_as_uint(v[2]); o.w = __float_as_uint(v[3]);
   }
   p.out[t] = o;
 }
@@ -96,7 +116,8 @@ pm_status pm_launch_pack(PackMode mode, pm_dtype dt, int K, int cin, int cout, c
     case PACK_PLAIN: p.Kp = K; p.Cc = cin; p.Cn = cout; break;
     case PACK_TRANS: p.Kp = K; p.Cc = cout; p.Cn = cin; break;
     case PACK_FOLD: p.Kp = 1; p.Cc = 3 * cin; p.Cn = cout; break;
-    default: p.Kp = 1; p.Cc = cout; p.Cn = 3 * cin; break;
+    case PACK_FOLD_TRANS: p.Kp = 1; p.Cc = cout; p.Cn = 3 * cin; break;
+    default: p.Kp = 1; p.Cc = 3 * cout; p.Cn = cin; break;
   }
   PackGeom g = pm_pack_geom(p.Kp, p.Cc, p.Cn, dt);
   p.NCH = g.NCH; p.NBG = g.NBG;
@@ -104,7 +125,14 @@ pm_status pm_launch_pack(PackMode mode, pm_dtype dt, int K, int cin, int cout, c
   if (fc) p.fc = *fc; else for (int j = 0; j < 3; ++j) for (int k = 0; k < PM_MAX_K; ++k) p.fc.c[j][k] = 0.f;
   int64_t n_gran = g.stages * STAGE_U4;
   { ProfScope ps__(st, "k_pack");
-    hipLaunchKernelGGL(k_pack, dim3((unsigned)((n_gran + 255) / 256)), dim3(256), 0, st, p, n_gran); }
+    const dim3 grid((unsigned)((n_gran + 255) / 256));
+    switch (mode) {
+      case PACK_PLAIN: hipLaunchKernelGGL(k_pack<PACK_PLAIN>, grid, dim3(256), 0, st, p, n_gran); break;
+      case PACK_TRANS: hipLaunchKernelGGL(k_pack<PACK_TRANS>, grid, dim3(256), 0, st, p, n_gran); break;
+      case PACK_FOLD: hipLaunchKernelGGL(k_pack<PACK_FOLD>, grid, dim3(256), 0, st, p, n_gran); break;
+      case PACK_FOLD_TRANS: hipLaunchKernelGGL(k_pack<PACK_FOLD_TRANS>, grid, dim3(256), 0, st, p, n_gran); break;
+      default: hipLaunchKernelGGL(k_pack<PACK_FOLD_BWD>, grid, dim3(256), 0, st, p, n_gran); break;
+    } }
   PM_CHECK_LAUNCH("k_pack");
   return PM_OK;
 }
@@ -300,6 +328,107 @@ pm_status pm_launch_segreduce(int64_t n_seg, int C, const void* src, int src_is_
     if (src_is_bf16) launch_segreduce_div<true>(p, grid, st);
     else launch_segreduce_div<false>(p, grid, st); }
   PM_CHECK_LAUNCH("k_segreduce");
+  return PM_OK;
+}
+
+// Corner-slot sums at the vertices (backward of Eq. 6 before the matrix): one lane group per vertex, lanes
+// span channels; an adjacency entry 3f+j adds row f to slot j.  Entries are taken two at a time (both rows
+// in flight), added in ascending order; the slot is chosen by selects, so the code has no divergent branch.
+template <bool SRC_BF16>
+__global__ void __launch_bounds__(256) k_segsum_slots(SegP p) {
+  constexpr int CPL = SRC_BF16 ? 8 : 4;
+  const int gpb = 256 / p.lpg;
+  const int sub = threadIdx.x % p.lpg;
+  const bool vec = (p.C % CPL) == 0 && pm_aligned16_dev(p.src) && pm_aligned16_dev(p.out);
+  for (int64_t seg = (int64_t)blockIdx.x * gpb + threadIdx.x / p.lpg; seg < p.n_seg; seg += (int64_t)gridDim.x * gpb) {
+    const int32_t b = p.row_ptr[seg], e = p.row_ptr[seg + 1];
+    for (int c0 = sub * CPL; c0 < p.C; c0 += p.lpg * CPL) {
+      float a[3][CPL];
+#pragma unroll
+      for (int j = 0; j < 3; ++j)
+#pragma unroll
+        for (int i = 0; i < CPL; ++i) a[j][i] = 0.f;
+      for (int32_t i0 = b; i0 < e; i0 += 2) {
+        int32_t cidx[2];
+        float x[2][CPL];
+#pragma unroll
+        for (int q = 0; q < 2; ++q) cidx[q] = p.col[min(i0 + q, e - 1)];
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+          const int64_t r = (int64_t)(((uint64_t)(uint32_t)cidx[q] * 0xAAAAAAABull) >> 33);   // / 3
+          const int64_t o = r * p.C + c0;
+          if (vec) {
+            const uint4 u = SRC_BF16 ? *(const uint4*)((const uint16_t*)p.src + o) : *(const uint4*)((const float*)p.src + o);
+            if constexpr (SRC_BF16) {
+              x[q][0] = bf16lo_to_f32(u.x); x[q][1] = bf16hi_to_f32(u.x); x[q][2] = bf16lo_to_f32(u.y); x[q][3] = bf16hi_to_f32(u.y);
+              x[q][4] = bf16lo_to_f32(u.z); x[q][5] = bf16hi_to_f32(u.z); x[q][6] = bf16lo_to_f32(u.w); x[q][7] = bf16hi_to_f32(u.w);
+            } else {
+              x[q][0] = __uint_as_float(u.x); x[q][1] = __uint_as_float(u.y); x[q][2] = __uint_as_float(u.z); x[q][3] = __uint_as_float(u.w);
+            }
+          } else {
+#pragma unroll
+            for (int i = 0; i < CPL; ++i) {
+              float t = 0.f;
+              if (c0 + i < p.C) t = SRC_BF16 ? bf16_to_f32(((const uint16_t*)p.src)[o + i]) : ((const float*)p.src)[o + i];
+              x[q][i] = t;
+            }
+          }
+        }
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+          const int slot = (i0 + q < e) ? cidx[q] - 3 * (int32_t)(((uint64_t)(uint32_t)cidx[q] * 0xAAAAAAABull) >> 33) : 3;
+#pragma unroll
+          for (int j = 0; j < 3; ++j)
+#pragma unroll
+            for (int i = 0; i < CPL; ++i) a[j][i] += (slot == j) ? x[q][i] : 0.f;
+        }
+      }
+#pragma unroll
+      for (int j = 0; j < 3; ++j) {
+        const int64_t o = (seg * 3 + j) * p.C + c0;
+        if (vec) {
+          if (p.out_bf16) {
+#pragma unroll
+            for (int q = 0; q < CPL / 4; ++q) {
+              uint2 w;
+              w.x = pack_bf16x2(a[j][4 * q], a[j][4 * q + 1]); w.y = pack_bf16x2(a[j][4 * q + 2], a[j][4 * q + 3]);
+              *(uint2*)((uint16_t*)p.out + o + 4 * q) = w;
+            }
+          } else {
+#pragma unroll
+            for (int q = 0; q < CPL / 4; ++q)
+              *(float4*)((float*)p.out + o + 4 * q) = make_float4(a[j][4 * q], a[j][4 * q + 1], a[j][4 * q + 2], a[j][4 * q + 3]);
+          }
+        } else {
+#pragma unroll
+          for (int i = 0; i < CPL; ++i)
+            if (c0 + i < p.C) {
+              if (p.out_bf16) ((uint16_t*)p.out)[o + i] = (uint16_t)f32_to_bf16_bits(a[j][i]);
+              else ((float*)p.out)[o + i] = a[j][i];
+            }
+        }
+      }
+    }
+  }
+}
+
+pm_status pm_launch_segsum_slots(int64_t n_seg, int C, const void* src, int src_is_bf16, const int32_t* row_ptr,
+                                 const int32_t* col, void* out, int out_is_bf16, hipStream_t st) {
+  if (n_seg == 0) return PM_OK;
+  SegP p;
+  p.n_seg = n_seg; p.C = C; p.div = 3; p.mean = 0; p.out_bf16 = out_is_bf16;
+  p.src = src; p.row_ptr = row_ptr; p.col = col; p.out = out;
+  const int cpl = src_is_bf16 ? 8 : 4;
+  int need = (C + cpl - 1) / cpl, lpg = 1;
+  while (lpg < need && lpg < 64) lpg <<= 1;
+  p.lpg = lpg;
+  const int gpb = 256 / lpg;
+  int64_t nblk = (n_seg + gpb - 1) / gpb;
+  if (nblk > 0x7fffffff) nblk = 0x7fffffff;
+  { ProfScope ps__(st, "k_segsum_slots");
+    if (src_is_bf16) hipLaunchKernelGGL(k_segsum_slots<true>, dim3((unsigned)nblk), dim3(256), 0, st, p);
+    else hipLaunchKernelGGL(k_segsum_slots<false>, dim3((unsigned)nblk), dim3(256), 0, st, p); }
+  PM_CHECK_LAUNCH("k_segsum_slots");
   return PM_OK;
 }
 

@@ -328,7 +328,55 @@ __global__ void __launch_bounds__(NW * 64) k_conv_rows(ConvP p) {
       pu0 = u0; pu1 = u1;
     };
 
-    if constexpr (RES) {
+    if constexpr (RES && BM == B_ONE) {
+      // No basis (K = 1): little matrix work per row, so the kernel lives on its row fetches.  Up to four
+      // 32-wide output blocks accumulate at once (loop order  n-block group -> c-chunk -> n-block), every
+      // chunk of the operand rows is fetched once per group, and the next chunk's loads are issued before
+      // the current chunk is multiplied.
+      const int NB = NBG * PM_NBS;
+      for (int nb0 = 0; nb0 * 32 < p.Cn; nb0 += 4) {
+        floatx16 y[4][2];
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+#pragma unroll
+          for (int fb = 0; fb < 2; ++fb)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) y[q][fb][i] = 0.f;
+        uint4 X[2][PM_GC];
+        fetch_chunk(0, X);
+        for (int ch = 0; ch < NCH; ++ch) {
+          uint4 Xn[2][PM_GC];
+          if (ch + 1 < NCH) fetch_chunk(ch + 1, Xn);
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            const int nb = nb0 + q;
+            if (nb < NB && nb * 32 < p.Cn) {
+              const uint4* base = lds + ((int64_t)((nb / PM_NBS) * NCH + ch)) * STAGE_U4 + (nb % PM_NBS) * PM_GC * 64 + lane;
+#pragma unroll
+              for (int g = 0; g < PM_GC; ++g) {
+                const uint4 a = base[g * 64];
+                y[q][0] = mma_group<DT>(a, X[0][g], y[q][0]);
+                y[q][1] = mma_group<DT>(a, X[1][g], y[q][1]);
+              }
+            }
+          }
+          if (ch + 1 < NCH) {
+#pragma unroll
+            for (int fb = 0; fb < 2; ++fb)
+#pragma unroll
+              for (int g = 0; g < PM_GC; ++g) X[fb][g] = Xn[fb][g];
+          }
+        }
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int nb = nb0 + q;
+          if (nb < NB && nb * 32 < p.Cn) {
+            store_block(nb, 0, y[q][0]);
+            store_block(nb, 1, y[q][1]);
+          }
+        }
+      }
+    } else if constexpr (RES) {
       // Weights resident in LDS: one 32-wide block of output channels at a time (32 accumulator
       // registers), loop order  n-block -> c-chunk -> k.
       for (int nb = 0; nb < NBG * PM_NBS; ++nb) {

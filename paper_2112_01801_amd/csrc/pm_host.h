@@ -64,11 +64,12 @@ static inline PackGeom pm_pack_geom(int K, int Cc, int Cn, pm_dtype dt) {
 static inline size_t pm_pack_bytes(const PackGeom& g) { return (size_t)g.stages * PM_STAGE_BYTES; }
 
 // ---- kernel launchers (each enqueues on `st`, returns PM_OK or PM_ERR_HIP) ----------------------
-enum PackMode { PACK_PLAIN = 0, PACK_TRANS = 1, PACK_FOLD = 2, PACK_FOLD_TRANS = 3 };
+enum PackMode { PACK_PLAIN = 0, PACK_TRANS = 1, PACK_FOLD = 2, PACK_FOLD_TRANS = 3, PACK_FOLD_BWD = 4 };
 struct FoldCoef { float c[3][PM_MAX_K]; };
 // Builds the MFMA operand image of Wp[k][c][n] from W[K][cin][cout] (src dtype = dt):
 //   PLAIN: Wp[k][ci][co] = W[k][ci][co]          TRANS: Wp[k][co][ci] = W[k][ci][co]
 //   FOLD:  Wp[0][j*cin+ci][co] = sum_k fc[j][k] W[k][ci][co]    FOLD_TRANS: Wp[0][co][j*cin+ci] = same
+//   FOLD_BWD: Wp[0][j*cout+co][ci] = same   (backward-data of the folded form, contraction over (corner, co))
 pm_status pm_launch_pack(PackMode mode, pm_dtype dt, int K, int cin, int cout, const void* W, const FoldCoef* fc,
                          void* apack, hipStream_t st);
 
@@ -118,6 +119,10 @@ pm_status pm_launch_wgrad(pm_dtype mt, BMode bm, XMode xm, XMode ym, int64_t R, 
                           void* y_out, hipStream_t st);
 // dW[k][ci][co] = sum_j fc[j][k] M[j][ci][co]
 pm_status pm_launch_unfold(int K, int cin, int cout, const float* M, const FoldCoef* fc, float* dW, hipStream_t st);
+// out[v][j][c] = sum over the entries e of segment v with col[e] % 3 == j of src[col[e] / 3][c]   (j = 0..2):
+// the facet rows adjacent to a vertex, summed separately per corner slot, ascending entry order, fp32 sums.
+pm_status pm_launch_segsum_slots(int64_t n_seg, int C, const void* src, int src_is_bf16, const int32_t* row_ptr,
+                                 const int32_t* col, void* out, int out_is_bf16, hipStream_t st);
 // owner[p] = f for p in [tex_off[f], tex_off[f+1])
 pm_status pm_launch_owner(int64_t n_facet, const int32_t* tex_off, int32_t* owner, hipStream_t st);
 
