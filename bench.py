@@ -31,6 +31,10 @@ def parse():
     ap.add_argument("--grid", type=int, default=1024, help="height-field side (1024 = the benchmark config)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--oracle-rows", type=int, default=256, help="grid rows of the mesh the oracle is timed on")
+    ap.add_argument("--ops", action="store_true",
+                    help="instead of the benchmark step: time every operator (F2V, V2F, F2F, forward and backward) on the "
+                         "same mesh and print one JSON line with per-kernel times")
+    ap.add_argument("--ops-dtype", default="bf16", choices=["bf16", "f32"])
     return ap.parse_args()
 
 
@@ -69,6 +73,9 @@ def main():
 
     cfg = mg.config3(args.grid)
     b = cfg.batch
+    if args.ops:
+        print(json.dumps(all_ops(args, cfg, pm, mg, torch)))
+        return
     F, V, K, cin, cout = b.n_facet, b.n_vert, cfg.K, cfg.cin, cfg.cout
     rng = mg.rng_for(3, 1)
     h = mg.round_to_bf16(mg.normal_features(rng, F, cin))
@@ -185,6 +192,53 @@ def main():
         "kernels": kernels,
     }
     print(json.dumps(out))
+
+
+def all_ops(args, cfg, pm, mg, torch):
+    """Per-kernel event times of every operator on the benchmark mesh (textures of Eq. 8 with (alpha, beta) = (3, 1))."""
+    b = cfg.batch
+    F, V, K, cin, cout, L = b.n_facet, b.n_vert, cfg.K, cfg.cin, cfg.cout, cfg.L
+    DT = pm.PM_BF16 if args.ops_dtype == "bf16" else pm.PM_F32
+    tdt = torch.bfloat16 if DT == pm.PM_BF16 else torch.float32
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(20211201 + 3)
+    rnd = lambda *sh: torch.randn(*sh, device="cuda", generator=gen).to(tdt)
+    W = ((torch.rand(K, cin, cout, device="cuda", generator=gen) * 2 - 1) * (6.0 / (K * cin + cout)) ** 0.5).to(tdt)
+    mesh = pm.mesh_to_device(b)
+    adj = pm.pm_build_vf_adjacency(mesh)
+    tex_off, bary = mg.texture_layout(b, 3, 1)
+    P = int(tex_off[-1])
+    t_off, t_bary = torch.from_numpy(tex_off).cuda(), torch.from_numpy(bary).cuda()
+    hF, hV, hP, dgV, dgF = rnd(F, cin), rnd(V, cin), rnd(P, cin), rnd(V, cout), rnd(F, cout)
+    ops = {
+        "f2v": (lambda: pm.pm_f2v(mesh, adj, L, hF, W, DT), F),
+        "f2v_bwd": (lambda: pm.pm_f2v_bwd(mesh, adj, L, hF, W, dgV, DT), F),
+        "v2f": (lambda: pm.pm_v2f(mesh, L, hV, W, DT), F),
+        "v2f_bwd": (lambda: pm.pm_v2f_bwd(mesh, adj, L, hV, W, dgF, DT), F),
+        "f2f": (lambda: pm.pm_f2f(t_off, t_bary, L, hP, W, DT), P),
+        "f2f_bwd": (lambda: pm.pm_f2f_bwd(t_off, t_bary, L, hP, W, dgF, DT), P),
+    }
+    out = {"workload": "config 3 mesh %dx%d: F=%d V=%d texture points=%d, L=%d, %d->%d, %s" %
+                       (args.grid, args.grid, F, V, P, L, cin, cout, args.ops_dtype),
+           "steps": args.steps, "ops": {}}
+    for name, (fn, rows) in ops.items():
+        for _ in range(max(1, args.warmup)):
+            fn()
+        torch.cuda.synchronize()
+        pm.pm_profile_reset()
+        pm.pm_profile_enable(True)
+        for _ in range(args.steps):
+            fn()
+        torch.cuda.synchronize()
+        pm.pm_profile_enable(False)
+        agg = {}
+        for label, ms in pm.pm_profile_read():
+            agg[label] = agg.get(label, 0.0) + ms / args.steps
+        pm.pm_profile_reset()
+        tot = sum(agg.values())
+        out["ops"][name] = {"kernel_ms": round(tot, 4), "rows": rows, "rows_per_s": round(rows / (tot * 1e-3)),
+                            "kernels": {k.split("/", 1)[1]: round(v, 4) for k, v in agg.items()}}
+    return out
 
 
 def board_power(step, torch):
