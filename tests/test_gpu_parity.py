@@ -234,6 +234,48 @@ def test_fan_vertex_and_orthonormal_variant(pm):
     assert np.all(g[-1] == 0)
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_v2f_backward_on_fan_and_isolated_vertices(pm, dtype):
+    """The per-vertex corner-slot sums with one segment of 5000 entries and vertices without any facet."""
+    b = mg.pack_batch([fan_mesh(5000), mg.icosphere(2)])
+    rng = np.random.default_rng(55)
+    L, cin, cout = 3, 64, 64
+    W = make_coeffs(rng, 16, cin, cout, dtype)
+    h = make_features(rng, b.n_vert, cin, dtype)
+    dg = make_features(rng, b.n_facet, cout, dtype)
+    mesh = pm.mesh_to_device(b)
+    adj = pm.pm_build_vf_adjacency(mesh)
+    dh, dW = pm.pm_v2f_bwd(mesh, adj, L, to_dev(h, dtype), to_dev(W, dtype), to_dev(dg, dtype), pm_dtype(dtype))
+    rdh, rdW = oracle.v2f_bwd(b.n_vert, b.facet, L, h, W, dg)
+    # the hub row sums 5000 facet rows and is ~50x larger than every other row: bf16 operand rounding scales
+    # with it, so it is measured against its own rms, the other rows against theirs
+    got = to_host(dh)
+    assert rel_err(got[:1], rdh[:1]) < TOL[dtype]
+    assert rel_err(got[1:], rdh[1:]) < TOL[dtype]
+    assert rel_err(to_host(dW), rdW) < TOL[dtype]
+    iso = np.setdiff1d(np.arange(b.n_vert), np.unique(b.facet))
+    assert iso.size > 0 and np.all(to_host(dh)[iso] == 0)
+
+
+def test_f2f_bf16_with_empty_facets(pm):
+    import torch
+    rng = np.random.default_rng(41)
+    res = rng.choice([0, 3, 6, 10], size=900)
+    tex_off = np.concatenate([[0], np.cumsum(res)]).astype(np.int32)
+    bary = np.concatenate([mg.bary_lattice({3: 1, 6: 2, 10: 3}[r]) for r in res if r > 0], 0)
+    L, cin, cout = 3, 64, 64
+    W = make_coeffs(rng, 16, cin, cout, "bf16")
+    h = make_features(rng, bary.shape[0], cin, "bf16")
+    dg = make_features(rng, 900, cout, "bf16")
+    t_off, t_bary = torch.from_numpy(tex_off).cuda(), torch.from_numpy(bary).cuda()
+    g = pm.pm_f2f(t_off, t_bary, L, to_dev(h, "bf16"), to_dev(W, "bf16"), 1)
+    assert rel_err(to_host(g), oracle.f2f(tex_off, bary, L, h, W)) < TOL["bf16"]
+    assert np.all(to_host(g)[res == 0] == 0)
+    dh, dW = pm.pm_f2f_bwd(t_off, t_bary, L, to_dev(h, "bf16"), to_dev(W, "bf16"), to_dev(dg, "bf16"), 1)
+    rdh, rdW = oracle.f2f_bwd(tex_off, bary, L, h, W, dg)
+    assert rel_err(to_host(dh), rdh) < TOL["bf16"] and rel_err(to_host(dW), rdW) < TOL["bf16"]
+
+
 def test_results_are_bitwise_reproducible(pm):
     import torch
     L, cin, cout, dtype = 3, 64, 64, "bf16"
