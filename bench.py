@@ -39,7 +39,7 @@ def parse():
 
 
 def kernel_models(F, V, K, cin, cout, e):
-    """Algorithmic work per launch of each kernel of the step ('Kernels')."""
+    """Algorithmic work per launch of each kernel of the step: flop of the contraction, bytes each array once."""
     flop = 2.0 * K * cin * cout * F
     w_bytes = K * cin * cout * e
     geom = F * 12 + V * 12                       # corner ids + vertex positions, each touched once

@@ -202,6 +202,23 @@ def test_f2v_backward_single_gradients(pm, L, cin, cout):
     assert np.array_equal(to_host(dW2), to_host(dW))           # the weight gradient does not depend on the pairing
 
 
+@pytest.mark.parametrize("dtype,cin,cout", [("bf16", 64, 64), ("f32", 24, 40), ("bf16", 128, 64)])
+def test_v2f_backward_single_gradients(pm, dtype, cin, cout):
+    """dW alone gathers the corner rows; together with dh it comes from the per-vertex slot sums instead."""
+    L = 3
+    b, rng, K, W, mesh, adj = _setup(pm, L, cin, cout, dtype, 25)
+    h = make_features(rng, b.n_vert, cin, dtype)
+    dg = make_features(rng, b.n_facet, cout, dtype)
+    args = (mesh, adj, L, to_dev(h, dtype), to_dev(W, dtype), to_dev(dg, dtype), pm_dtype(dtype))
+    rdh, rdW = oracle.v2f_bwd(b.n_vert, b.facet, L, h, W, dg)
+    dh, none = pm.pm_v2f_bwd(*args, want_dW=False)
+    assert none is None and rel_err(to_host(dh), rdh) < TOL[dtype]
+    none, dW = pm.pm_v2f_bwd(*args, want_dh=False)
+    assert none is None and rel_err(to_host(dW), rdW) < TOL[dtype]
+    dh2, dW2 = pm.pm_v2f_bwd(*args)
+    assert rel_err(to_host(dh2), rdh) < TOL[dtype] and rel_err(to_host(dW2), rdW) < TOL[dtype]
+
+
 def test_f2f_empty_facets_and_paper_shape(pm):
     """Cin = 3 colour channels (the paper's own shape), some facets without texture points."""
     import torch
