@@ -293,6 +293,33 @@ def test_f2f_bf16_with_empty_facets(pm):
     assert rel_err(to_host(dh), rdh) < TOL["bf16"] and rel_err(to_host(dW), rdW) < TOL["bf16"]
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_empty_inputs(pm, dtype):
+    """No facets (and no texture points): every sum is empty, so feature outputs and weight gradients are zero."""
+    import torch
+    b = mg.pack_batch([(np.random.default_rng(3).random((5, 3)).astype(np.float32), np.zeros((0, 3), np.int32))])
+    mesh = pm.mesh_to_device(b)
+    adj = pm.pm_build_vf_adjacency(mesh)
+    L, cin, cout, dt = 3, 64, 64, pm_dtype(dtype)
+    tdt = torch.bfloat16 if dt else torch.float32
+    W = torch.ones((16, cin, cout), device="cuda", dtype=tdt)
+    hF, hV = torch.zeros((0, cin), device="cuda", dtype=tdt), torch.ones((5, cin), device="cuda", dtype=tdt)
+    dgV, dgF = torch.ones((5, cout), device="cuda", dtype=tdt), torch.zeros((0, cout), device="cuda", dtype=tdt)
+    g = pm.pm_f2v(mesh, adj, L, hF, W, dt)
+    assert g.shape == (5, cout) and not g.float().abs().any()
+    dh, dW = pm.pm_f2v_bwd(mesh, adj, L, hF, W, dgV, dt)
+    assert dh.shape == (0, cin) and not dW.abs().any()
+    assert pm.pm_v2f(mesh, L, hV, W, dt).shape == (0, cout)
+    dh, dW = pm.pm_v2f_bwd(mesh, adj, L, hV, W, dgF, dt)
+    assert dh.shape == (5, cin) and not dh.float().abs().any() and not dW.abs().any()
+    t_off = torch.zeros(4, dtype=torch.int32, device="cuda")          # three facets without texture points
+    bary = torch.zeros((0, 3), device="cuda")
+    g = pm.pm_f2f(t_off, bary, L, hF, W, dt)
+    assert g.shape == (3, cout) and not g.float().abs().any()
+    dh, dW = pm.pm_f2f_bwd(t_off, bary, L, hF, W, torch.ones((3, cout), device="cuda", dtype=tdt), dt)
+    assert dh.shape == (0, cin) and not dW.abs().any()
+
+
 def test_results_are_bitwise_reproducible(pm):
     import torch
     L, cin, cout, dtype = 3, 64, 64, "bf16"
