@@ -136,6 +136,70 @@ def v2f_bwd(n_vert, facet, L, h, W, dg, norm: int = 0, rows=None, want_dh=True, 
     return dh, dW
 
 
+def f2v_sep(vert, facet, L, h, alpha, P, norm: int = 0, rows=None) -> np.ndarray:
+    """Depth-wise separable facet2vertex: per-channel SH coefficients alpha [K,cin], point-wise P [cin,cout]."""
+    vert, facet, h, alpha, P = _f32(vert), _i32(facet), _f64(h), _f64(alpha), _f64(P)
+    K, cin = alpha.shape
+    cout = P.shape[1]
+    assert K == (L + 1) ** 2 and P.shape[0] == cin and h.shape == (facet.shape[0], cin)
+    rows = _rows(rows)
+    n = vert.shape[0] if rows is None else rows.shape[0]
+    out = np.empty((n, cout), dtype=np.float64)
+    lib().orc_f2v_sep(C.c_int64(vert.shape[0]), C.c_int64(facet.shape[0]), _p(vert, C.c_float), _p(facet, C.c_int32),
+                      C.c_int(L), C.c_int(norm), C.c_int(cin), C.c_int(cout), _p(h, C.c_double), _p(alpha, C.c_double),
+                      _p(P, C.c_double), C.c_int64(n), _p(rows, C.c_int64), _p(out, C.c_double))
+    return out
+
+
+def f2v_sep_bwd(vert, facet, L, h, alpha, P, dg, norm: int = 0, rows=None, want_dh=True, want_dw=True):
+    """Returns (dh [rows or F, cin], dalpha [K,cin], dP [cin,cout]); dalpha/dP None unless want_dw."""
+    vert, facet, h, alpha, P, dg = _f32(vert), _i32(facet), _f64(h), _f64(alpha), _f64(P), _f64(dg)
+    K, cin = alpha.shape
+    cout = P.shape[1]
+    assert dg.shape == (vert.shape[0], cout)
+    rows = _rows(rows)
+    n = facet.shape[0] if rows is None else rows.shape[0]
+    dh = np.empty((n, cin), dtype=np.float64) if want_dh else None
+    da = np.empty_like(alpha) if want_dw else None
+    dP = np.empty_like(P) if want_dw else None
+    lib().orc_f2v_sep_bwd(C.c_int64(vert.shape[0]), C.c_int64(facet.shape[0]), _p(vert, C.c_float),
+                          _p(facet, C.c_int32), C.c_int(L), C.c_int(norm), C.c_int(cin), C.c_int(cout),
+                          _p(h, C.c_double), _p(alpha, C.c_double), _p(P, C.c_double), _p(dg, C.c_double),
+                          C.c_int64(n), _p(rows, C.c_int64), _p(dh, C.c_double), _p(da, C.c_double), _p(dP, C.c_double))
+    return dh, da, dP
+
+
+def v2f_sep(n_vert, facet, L, h, alpha, P, norm: int = 0, rows=None) -> np.ndarray:
+    facet, h, alpha, P = _i32(facet), _f64(h), _f64(alpha), _f64(P)
+    K, cin = alpha.shape
+    cout = P.shape[1]
+    assert K == (L + 1) ** 2 and h.shape == (n_vert, cin)
+    rows = _rows(rows)
+    n = facet.shape[0] if rows is None else rows.shape[0]
+    out = np.empty((n, cout), dtype=np.float64)
+    lib().orc_v2f_sep(C.c_int64(n_vert), C.c_int64(facet.shape[0]), _p(facet, C.c_int32), C.c_int(L), C.c_int(norm),
+                      C.c_int(cin), C.c_int(cout), _p(h, C.c_double), _p(alpha, C.c_double), _p(P, C.c_double),
+                      C.c_int64(n), _p(rows, C.c_int64), _p(out, C.c_double))
+    return out
+
+
+def v2f_sep_bwd(n_vert, facet, L, h, alpha, P, dg, norm: int = 0, rows=None, want_dh=True, want_dw=True):
+    facet, h, alpha, P, dg = _i32(facet), _f64(h), _f64(alpha), _f64(P), _f64(dg)
+    K, cin = alpha.shape
+    cout = P.shape[1]
+    assert dg.shape == (facet.shape[0], cout)
+    rows = _rows(rows)
+    n = n_vert if rows is None else rows.shape[0]
+    dh = np.empty((n, cin), dtype=np.float64) if want_dh else None
+    da = np.empty_like(alpha) if want_dw else None
+    dP = np.empty_like(P) if want_dw else None
+    lib().orc_v2f_sep_bwd(C.c_int64(n_vert), C.c_int64(facet.shape[0]), _p(facet, C.c_int32), C.c_int(L),
+                          C.c_int(norm), C.c_int(cin), C.c_int(cout), _p(h, C.c_double), _p(alpha, C.c_double),
+                          _p(P, C.c_double), _p(dg, C.c_double), C.c_int64(n), _p(rows, C.c_int64),
+                          _p(dh, C.c_double), _p(da, C.c_double), _p(dP, C.c_double))
+    return dh, da, dP
+
+
 def f2f(tex_off, bary, L, h, W, norm: int = 0, rows=None) -> np.ndarray:
     tex_off, bary, h, W = _i32(tex_off), _f32(bary), _f64(h), _f64(W)
     K, cin, cout = W.shape

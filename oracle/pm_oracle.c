@@ -16,6 +16,9 @@
  *   - facet normal = (x2-x1) x (x3-x1), normalised; if its squared length < 1e-30 use (0,0,1).
  *   - a vertex without adjacent facets gets a zero output row.
  *
+ * The depth-wise separable forms (orc_*_sep*) are pinned against the dense functions on the expanded
+ * coefficients alpha[k][ci]*P[ci][co], by finite differences and by adjoint identities.
+ *
  * Parity status: every function below is pinned by tests (quadrature Gram matrix, closed forms,
  * a library SH routine, tetrahedron / icosahedron closed forms, brute-force adjacency scans,
  * finite differences, adjoint identities) EXCEPT agreement with the authors' released code,
@@ -401,6 +404,240 @@ void orc_f2f_bwd(int64_t F, const int32_t* tex_off, const float* bary, int L, in
     free(Ball);
   }
   free(owner);
+}
+
+
+/* ------------------------------------------------------------------------------------------------
+ * Depth-wise separable form of facet2vertex / vertex2facet (Section "Mesh convolutions": Eq. 5 and
+ * Eq. 6 with one scalar coefficient set {a_l0, a_lm, b_lm} per channel, followed by a point-wise
+ * channel mixing).  alpha[k][ci] are the per-channel SH coefficients, P[ci][co] the point-wise matrix.
+ * It equals the dense form with W[k][ci][co] = alpha[k][ci] * P[ci][co]; the loops below follow the
+ * staged definition (depth-wise, aggregate, point-wise), not that expansion.
+ * ------------------------------------------------------------------------------------------------ */
+
+/* s[ci] = sum_k alpha[k][ci] B[k]: the filter value of channel ci at the direction whose basis is B */
+static void dw_filter(const double* B, int K, int cin, const double* alpha, double* s) {
+  for (int ci = 0; ci < cin; ++ci) {
+    double t = 0.0;
+    for (int k = 0; k < K; ++k) t += alpha[(int64_t)k * cin + ci] * B[k];
+    s[ci] = t;
+  }
+}
+
+/* z_v[ci] = 1/|N(v)| sum_{f in N(v)} F_ci(n_f) h_f[ci]   (depth-wise Eq. 5) for one vertex */
+static void sep_vertex_mean(int64_t v, const int32_t* rp, const int32_t* col, const float* vert, const int32_t* facet,
+                            int L, int norm, int cin, const double* h, const double* alpha, double* s, double* z) {
+  int K = (L + 1) * (L + 1);
+  for (int ci = 0; ci < cin; ++ci) z[ci] = 0.0;
+  int deg = rp[v + 1] - rp[v];
+  for (int e = rp[v]; e < rp[v + 1]; ++e) {
+    int64_t f = col[e] / 3;
+    double n[3], B[ORC_MAX_K];
+    facet_normal_one(vert, facet + 3 * f, n);
+    sh_basis_one(n, L, norm, B);
+    dw_filter(B, K, cin, alpha, s);
+    for (int ci = 0; ci < cin; ++ci) z[ci] += s[ci] * h[f * cin + ci];
+  }
+  if (deg > 0)
+    for (int ci = 0; ci < cin; ++ci) z[ci] /= (double)deg;
+}
+
+/* separable facet2vertex: g_v = z_v P.  Rows listed in `rows` (or all V). out [n_rows, cout]. */
+void orc_f2v_sep(int64_t V, int64_t F, const float* vert, const int32_t* facet, int L, int norm, int cin, int cout,
+                 const double* h, const double* alpha, const double* P, int64_t n_rows, const int64_t* rows,
+                 double* out) {
+  int32_t* rp = (int32_t*)malloc(((size_t)V + 1) * sizeof(int32_t));
+  int32_t* col = (int32_t*)malloc((size_t)(3 * F + 1) * sizeof(int32_t));
+  orc_vf_adjacency(V, F, facet, rp, col);
+#pragma omp parallel
+  {
+    double* s = (double*)malloc((size_t)cin * sizeof(double));
+    double* z = (double*)malloc((size_t)cin * sizeof(double));
+#pragma omp for schedule(dynamic, 64)
+    for (int64_t r = 0; r < n_rows; ++r) {
+      int64_t v = rows ? rows[r] : r;
+      sep_vertex_mean(v, rp, col, vert, facet, L, norm, cin, h, alpha, s, z);
+      for (int co = 0; co < cout; ++co) {
+        double t = 0.0;
+        for (int ci = 0; ci < cin; ++ci) t += z[ci] * P[(int64_t)ci * cout + co];
+        out[r * cout + co] = t;
+      }
+    }
+    free(s); free(z);
+  }
+  free(rp); free(col);
+}
+
+/*
+ * separable facet2vertex backward (transposed sums):
+ *   dz_v[ci]       = sum_co P[ci][co] dg_v[co]
+ *   dy_f[ci]       = sum_j dz_{v_j(f)}[ci] / |N(v_j(f))|
+ *   dh_f[ci]       = F_ci(n_f) dy_f[ci]                                  (rows = facets listed, or all)
+ *   dalpha[k][ci]  = sum_f B_k(n_f) h_f[ci] dy_f[ci]                      (all facets; skipped if NULL)
+ *   dP[ci][co]     = sum_v z_v[ci] dg_v[co]                               (all vertices; skipped if NULL)
+ */
+void orc_f2v_sep_bwd(int64_t V, int64_t F, const float* vert, const int32_t* facet, int L, int norm, int cin,
+                     int cout, const double* h, const double* alpha, const double* P, const double* dg,
+                     int64_t n_rows, const int64_t* rows, double* dh, double* dalpha, double* dP) {
+  int K = (L + 1) * (L + 1);
+  int64_t* deg = (int64_t*)calloc((size_t)V, sizeof(int64_t));
+  for (int64_t e = 0; e < 3 * F; ++e) deg[facet[e]]++;
+  double* dz = (double*)malloc((size_t)(V > 0 ? V : 1) * cin * sizeof(double));
+#pragma omp parallel for schedule(static)
+  for (int64_t v = 0; v < V; ++v)
+    for (int ci = 0; ci < cin; ++ci) {
+      double t = 0.0;
+      for (int co = 0; co < cout; ++co) t += P[(int64_t)ci * cout + co] * dg[v * cout + co];
+      dz[v * cin + ci] = t;
+    }
+  if (dh) {
+#pragma omp parallel
+    {
+      double* s = (double*)malloc((size_t)cin * sizeof(double));
+#pragma omp for schedule(static)
+      for (int64_t r = 0; r < n_rows; ++r) {
+        int64_t f = rows ? rows[r] : r;
+        double n[3], B[ORC_MAX_K];
+        facet_normal_one(vert, facet + 3 * f, n);
+        sh_basis_one(n, L, norm, B);
+        dw_filter(B, K, cin, alpha, s);
+        for (int ci = 0; ci < cin; ++ci) {
+          double dy = 0.0;
+          for (int j = 0; j < 3; ++j) {
+            int64_t v = facet[3 * f + j];
+            dy += dz[v * cin + ci] / (double)deg[v];
+          }
+          dh[r * cin + ci] = s[ci] * dy;
+        }
+      }
+      free(s);
+    }
+  }
+  if (dalpha) {
+    for (int64_t i = 0; i < (int64_t)K * cin; ++i) dalpha[i] = 0.0;
+    for (int64_t f = 0; f < F; ++f) {   /* ascending facet order */
+      double n[3], B[ORC_MAX_K];
+      facet_normal_one(vert, facet + 3 * f, n);
+      sh_basis_one(n, L, norm, B);
+      for (int ci = 0; ci < cin; ++ci) {
+        double dy = 0.0;
+        for (int j = 0; j < 3; ++j) {
+          int64_t v = facet[3 * f + j];
+          dy += dz[v * cin + ci] / (double)deg[v];
+        }
+        double hd = h[f * cin + ci] * dy;
+        for (int k = 0; k < K; ++k) dalpha[(int64_t)k * cin + ci] += B[k] * hd;
+      }
+    }
+  }
+  if (dP) {
+    int32_t* rp = (int32_t*)malloc(((size_t)V + 1) * sizeof(int32_t));
+    int32_t* col = (int32_t*)malloc((size_t)(3 * F + 1) * sizeof(int32_t));
+    orc_vf_adjacency(V, F, facet, rp, col);
+    double* s = (double*)malloc((size_t)cin * sizeof(double));
+    double* z = (double*)malloc((size_t)cin * sizeof(double));
+    for (int64_t i = 0; i < (int64_t)cin * cout; ++i) dP[i] = 0.0;
+    for (int64_t v = 0; v < V; ++v) {
+      sep_vertex_mean(v, rp, col, vert, facet, L, norm, cin, h, alpha, s, z);
+      for (int ci = 0; ci < cin; ++ci)
+        for (int co = 0; co < cout; ++co) dP[(int64_t)ci * cout + co] += z[ci] * dg[v * cout + co];
+    }
+    free(s); free(z); free(rp); free(col);
+  }
+  free(dz); free(deg);
+}
+
+/* separable vertex2facet: u_f[ci] = sum_j F_ci(e_j) h_{v_j(f)}[ci] (depth-wise Eq. 6),  g_f = u_f P */
+void orc_v2f_sep(int64_t V, int64_t F, const int32_t* facet, int L, int norm, int cin, int cout, const double* h,
+                 const double* alpha, const double* P, int64_t n_rows, const int64_t* rows, double* out) {
+  int K = (L + 1) * (L + 1);
+  double Bc[3][ORC_MAX_K];
+  corner_basis(L, norm, Bc);
+  double* sc = (double*)malloc((size_t)3 * cin * sizeof(double));
+  for (int j = 0; j < 3; ++j) dw_filter(Bc[j], K, cin, alpha, sc + (int64_t)j * cin);
+  (void)V; (void)F;
+#pragma omp parallel
+  {
+    double* u = (double*)malloc((size_t)cin * sizeof(double));
+#pragma omp for schedule(static)
+    for (int64_t r = 0; r < n_rows; ++r) {
+      int64_t f = rows ? rows[r] : r;
+      for (int ci = 0; ci < cin; ++ci) {
+        double t = 0.0;
+        for (int j = 0; j < 3; ++j) t += sc[(int64_t)j * cin + ci] * h[(int64_t)facet[3 * f + j] * cin + ci];
+        u[ci] = t;
+      }
+      for (int co = 0; co < cout; ++co) {
+        double t = 0.0;
+        for (int ci = 0; ci < cin; ++ci) t += u[ci] * P[(int64_t)ci * cout + co];
+        out[r * cout + co] = t;
+      }
+    }
+    free(u);
+  }
+  free(sc);
+}
+
+/*
+ * separable vertex2facet backward:
+ *   du_f[ci]      = sum_co P[ci][co] dg_f[co]
+ *   dh_v[ci]      = sum_{(f,j): v_j(f)=v} F_ci(e_j) du_f[ci]              (rows = vertices listed, or all)
+ *   dalpha[k][ci] = sum_f sum_j B_k(e_j) h_{v_j(f)}[ci] du_f[ci]
+ *   dP[ci][co]    = sum_f u_f[ci] dg_f[co]
+ */
+void orc_v2f_sep_bwd(int64_t V, int64_t F, const int32_t* facet, int L, int norm, int cin, int cout, const double* h,
+                     const double* alpha, const double* P, const double* dg, int64_t n_rows, const int64_t* rows,
+                     double* dh, double* dalpha, double* dP) {
+  int K = (L + 1) * (L + 1);
+  double Bc[3][ORC_MAX_K];
+  corner_basis(L, norm, Bc);
+  double* sc = (double*)malloc((size_t)3 * cin * sizeof(double));
+  for (int j = 0; j < 3; ++j) dw_filter(Bc[j], K, cin, alpha, sc + (int64_t)j * cin);
+  double* du = (double*)malloc((size_t)(F > 0 ? F : 1) * cin * sizeof(double));
+#pragma omp parallel for schedule(static)
+  for (int64_t f = 0; f < F; ++f)
+    for (int ci = 0; ci < cin; ++ci) {
+      double t = 0.0;
+      for (int co = 0; co < cout; ++co) t += P[(int64_t)ci * cout + co] * dg[f * cout + co];
+      du[f * cin + ci] = t;
+    }
+  if (dh) {
+    int32_t* rp = (int32_t*)malloc(((size_t)V + 1) * sizeof(int32_t));
+    int32_t* col = (int32_t*)malloc((size_t)(3 * F + 1) * sizeof(int32_t));
+    orc_vf_adjacency(V, F, facet, rp, col);
+#pragma omp parallel for schedule(dynamic, 64)
+    for (int64_t r = 0; r < n_rows; ++r) {
+      int64_t v = rows ? rows[r] : r;
+      for (int ci = 0; ci < cin; ++ci) dh[r * cin + ci] = 0.0;
+      for (int e = rp[v]; e < rp[v + 1]; ++e) {
+        int64_t f = col[e] / 3;
+        int j = col[e] % 3;
+        for (int ci = 0; ci < cin; ++ci) dh[r * cin + ci] += sc[(int64_t)j * cin + ci] * du[f * cin + ci];
+      }
+    }
+    free(rp); free(col);
+  }
+  if (dalpha) {
+    for (int64_t i = 0; i < (int64_t)K * cin; ++i) dalpha[i] = 0.0;
+    for (int64_t f = 0; f < F; ++f)
+      for (int j = 0; j < 3; ++j) {
+        int64_t v = facet[3 * f + j];
+        for (int ci = 0; ci < cin; ++ci) {
+          double hd = h[v * cin + ci] * du[f * cin + ci];
+          for (int k = 0; k < K; ++k) dalpha[(int64_t)k * cin + ci] += Bc[j][k] * hd;
+        }
+      }
+  }
+  if (dP) {
+    for (int64_t i = 0; i < (int64_t)cin * cout; ++i) dP[i] = 0.0;
+    for (int64_t f = 0; f < F; ++f)
+      for (int ci = 0; ci < cin; ++ci) {
+        double u = 0.0;
+        for (int j = 0; j < 3; ++j) u += sc[(int64_t)j * cin + ci] * h[(int64_t)facet[3 * f + j] * cin + ci];
+        for (int co = 0; co < cout; ++co) dP[(int64_t)ci * cout + co] += u * dg[f * cout + co];
+      }
+  }
+  free(sc); free(du);
 }
 
 int orc_max_l(void) { return ORC_MAX_L; }
