@@ -58,7 +58,8 @@ typedef enum { PM_SH_PAPER = 0, PM_SH_ORTHONORMAL = 1 } pm_sh_norm;
 
 typedef enum {
   PM_OP_ADJACENCY = 0, PM_OP_F2V = 1, PM_OP_F2V_BWD = 2, PM_OP_V2F = 3, PM_OP_V2F_BWD = 4,
-  PM_OP_F2F = 5, PM_OP_F2F_BWD = 6
+  PM_OP_F2F = 5, PM_OP_F2F_BWD = 6,
+  PM_OP_F2V_SEP = 7, PM_OP_F2V_SEP_BWD = 8, PM_OP_V2F_SEP = 9, PM_OP_V2F_SEP_BWD = 10
 } pm_op;
 
 /* Packed batch of triangle meshes (device arrays). */
@@ -134,6 +135,26 @@ pm_status pm_f2f(int64_t n_facet, int64_t n_tex, const int32_t* tex_off, const f
 pm_status pm_f2f_bwd(int64_t n_facet, int64_t n_tex, const int32_t* tex_off, const float* bary, int L,
                      pm_sh_norm norm, int cin, int cout, pm_dtype dtype, const void* h_tex, const void* W,
                      const void* dg_facet, void* dh_tex, float* dW, void* ws, size_t ws_bytes, void* stream);
+
+/* Depth-wise separable form of facet2vertex and vertex2facet (Section "Mesh convolutions": Eq. 5 and Eq. 6
+ * with one scalar SH coefficient set per channel, followed by a point-wise channel mixing):
+ *   facet2vertex:  g_v = ( 1/|N(v)| sum_{f in N(v)} h_f (.) s(n_f) ) P,   s(d)[ci] = sum_k alpha[k][ci] B_k(d)
+ *   vertex2facet:  g_f = ( sum_j h_{v_j(f)} (.) s(e_j) ) P
+ * which is the dense form with W[k][ci][co] = alpha[k][ci] * P[ci][co].  alpha [K,cin] is always fp32; P [cin,cout]
+ * has the feature dtype; dalpha [K,cin] and dP [cin,cout] are fp32.  Any of the three gradient outputs may be NULL
+ * (dalpha and dP only together).  Same conventions as the dense entry points otherwise. */
+pm_status pm_f2v_sep(const pm_mesh* mesh, const pm_vf_adj* adj, int L, pm_sh_norm norm, int cin, int cout,
+                     pm_dtype dtype, const void* h_facet, const float* alpha, const void* P, void* g_vert, void* ws,
+                     size_t ws_bytes, void* stream);
+pm_status pm_f2v_sep_bwd(const pm_mesh* mesh, const pm_vf_adj* adj, int L, pm_sh_norm norm, int cin, int cout,
+                         pm_dtype dtype, const void* h_facet, const float* alpha, const void* P, const void* dg_vert,
+                         void* dh_facet, float* dalpha, float* dP, void* ws, size_t ws_bytes, void* stream);
+pm_status pm_v2f_sep(const pm_mesh* mesh, int L, pm_sh_norm norm, int cin, int cout, pm_dtype dtype,
+                     const void* h_vert, const float* alpha, const void* P, void* g_facet, void* ws, size_t ws_bytes,
+                     void* stream);
+pm_status pm_v2f_sep_bwd(const pm_mesh* mesh, const pm_vf_adj* adj, int L, pm_sh_norm norm, int cin, int cout,
+                         pm_dtype dtype, const void* h_vert, const float* alpha, const void* P, const void* dg_facet,
+                         void* dh_vert, float* dalpha, float* dP, void* ws, size_t ws_bytes, void* stream);
 
 /* Measurement aid (not part of the method): per-kernel timing with HIP events.
  * After pm_profile_enable(1) every kernel this thread's calls launch is bracketed by a pair of events

@@ -19,13 +19,14 @@ LIB_PATH = os.path.join(HERE, "libpicassomesh.so")
 PM_F32, PM_BF16 = 0, 1
 PM_SH_PAPER, PM_SH_ORTHONORMAL = 0, 1
 PM_OP_ADJACENCY, PM_OP_F2V, PM_OP_F2V_BWD, PM_OP_V2F, PM_OP_V2F_BWD, PM_OP_F2F, PM_OP_F2F_BWD = range(7)
+PM_OP_F2V_SEP, PM_OP_F2V_SEP_BWD, PM_OP_V2F_SEP, PM_OP_V2F_SEP_BWD = 7, 8, 9, 10
 PM_MAX_L = 5
 
 EXPORTS = [
     "pm_status_string", "pm_last_error", "pm_workspace_bytes", "pm_validate_mesh", "pm_build_vf_adjacency",
     "pm_sh_basis", "pm_sh_basis_dirs", "pm_sh_basis_bwd", "pm_f2v", "pm_f2v_bwd", "pm_v2f", "pm_v2f_bwd",
     "pm_f2f", "pm_f2f_bwd", "pm_profile_enable", "pm_profile_count", "pm_profile_read", "pm_profile_reset",
-    "pm_peak_probe",
+    "pm_peak_probe", "pm_f2v_sep", "pm_f2v_sep_bwd", "pm_v2f_sep", "pm_v2f_sep_bwd",
 ]
 
 
@@ -74,6 +75,10 @@ def lib():
             "pm_v2f_bwd": [mp, ap, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, sz, vp],
             "pm_f2f": [i64, i64, vp, vp, i32, i32, i32, i32, i32, vp, vp, vp, vp, sz, vp],
             "pm_f2f_bwd": [i64, i64, vp, vp, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, sz, vp],
+            "pm_f2v_sep": [mp, ap, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, sz, vp],
+            "pm_f2v_sep_bwd": [mp, ap, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp],
+            "pm_v2f_sep": [mp, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, sz, vp],
+            "pm_v2f_sep_bwd": [mp, ap, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp],
         }
         sig.update({"pm_profile_enable": [i32], "pm_profile_count": [], "pm_profile_reset": [],
                     "pm_profile_read": [i32, C.c_char_p, sz, C.POINTER(C.c_float)],
@@ -297,6 +302,73 @@ def pm_f2f_bwd(tex_off, bary, L: int, h_tex, W, dg_facet, dtype: int, norm: int 
                             _ptr(h_tex) if P else None, _ptr(W), _ptr(dg_facet), _ptr(dh) if want_dh else None,
                             _ptr(dW) if want_dW else None, _ptr(ws), ws.numel(), _stream(stream)))
     return (dh if want_dh else None), (dW if want_dW else None)
+
+
+def _check_sep(alpha, P, dtype):
+    assert alpha.dtype == torch.float32, "alpha is always fp32"
+    assert P.dtype == torch_dtype(dtype) and alpha.shape[1] == P.shape[0]
+
+
+def pm_f2v_sep(mesh: Mesh, adj: Adjacency, L: int, h_facet, alpha, P, dtype: int, norm: int = PM_SH_PAPER, out=None,
+               ws=None, stream=None):
+    """Depth-wise separable facet2vertex: alpha [K,cin] fp32, P [cin,cout] in the feature dtype."""
+    _check_sep(alpha, P, dtype)
+    cin, cout = P.shape
+    dev = h_facet.device
+    if out is None:
+        out = torch.empty((mesh.n_vert, cout), dtype=torch_dtype(dtype), device=dev)
+    ws = _ws(PM_OP_F2V_SEP, mesh.n_vert, mesh.n_facet, 0, L, cin, cout, dtype, ws, dev)
+    m, a = mesh.c(), adj.c()
+    _check(lib().pm_f2v_sep(C.byref(m), C.byref(a), L, norm, cin, cout, dtype, _ptr(h_facet), _ptr(alpha), _ptr(P),
+                            C.c_void_p(out.data_ptr()), _ptr(ws), ws.numel(), _stream(stream)))
+    return out
+
+
+def pm_f2v_sep_bwd(mesh: Mesh, adj: Adjacency, L: int, h_facet, alpha, P, dg_vert, dtype: int, norm: int = PM_SH_PAPER,
+                   want_dh=True, want_dw=True, ws=None, stream=None):
+    """Returns (dh, dalpha, dP); dalpha and dP are fp32 and come together."""
+    _check_sep(alpha, P, dtype)
+    cin, cout = P.shape
+    K = alpha.shape[0]
+    dev = h_facet.device
+    dh = torch.empty((mesh.n_facet, cin), dtype=torch_dtype(dtype), device=dev) if want_dh else None
+    da = torch.empty((K, cin), dtype=torch.float32, device=dev) if want_dw else None
+    dP = torch.empty((cin, cout), dtype=torch.float32, device=dev) if want_dw else None
+    ws = _ws(PM_OP_F2V_SEP_BWD, mesh.n_vert, mesh.n_facet, 0, L, cin, cout, dtype, ws, dev)
+    m, a = mesh.c(), adj.c()
+    _check(lib().pm_f2v_sep_bwd(C.byref(m), C.byref(a), L, norm, cin, cout, dtype, _ptr(h_facet), _ptr(alpha), _ptr(P),
+                                _ptr(dg_vert), _ptr(dh), _ptr(da), _ptr(dP), _ptr(ws), ws.numel(), _stream(stream)))
+    return dh, da, dP
+
+
+def pm_v2f_sep(mesh: Mesh, L: int, h_vert, alpha, P, dtype: int, norm: int = PM_SH_PAPER, out=None, ws=None,
+               stream=None):
+    _check_sep(alpha, P, dtype)
+    cin, cout = P.shape
+    dev = h_vert.device
+    if out is None:
+        out = torch.empty((mesh.n_facet, cout), dtype=torch_dtype(dtype), device=dev)
+    ws = _ws(PM_OP_V2F_SEP, mesh.n_vert, mesh.n_facet, 0, L, cin, cout, dtype, ws, dev)
+    m = mesh.c()
+    _check(lib().pm_v2f_sep(C.byref(m), L, norm, cin, cout, dtype, _ptr(h_vert), _ptr(alpha), _ptr(P),
+                            C.c_void_p(out.data_ptr()), _ptr(ws), ws.numel(), _stream(stream)))
+    return out
+
+
+def pm_v2f_sep_bwd(mesh: Mesh, adj: Adjacency, L: int, h_vert, alpha, P, dg_facet, dtype: int, norm: int = PM_SH_PAPER,
+                   want_dh=True, want_dw=True, ws=None, stream=None):
+    _check_sep(alpha, P, dtype)
+    cin, cout = P.shape
+    K = alpha.shape[0]
+    dev = h_vert.device
+    dh = torch.empty((mesh.n_vert, cin), dtype=torch_dtype(dtype), device=dev) if want_dh else None
+    da = torch.empty((K, cin), dtype=torch.float32, device=dev) if want_dw else None
+    dP = torch.empty((cin, cout), dtype=torch.float32, device=dev) if want_dw else None
+    ws = _ws(PM_OP_V2F_SEP_BWD, mesh.n_vert, mesh.n_facet, 0, L, cin, cout, dtype, ws, dev)
+    m, a = mesh.c(), adj.c()
+    _check(lib().pm_v2f_sep_bwd(C.byref(m), C.byref(a), L, norm, cin, cout, dtype, _ptr(h_vert), _ptr(alpha), _ptr(P),
+                                _ptr(dg_facet), _ptr(dh), _ptr(da), _ptr(dP), _ptr(ws), ws.numel(), _stream(stream)))
+    return dh, da, dP
 
 
 def pm_profile_enable(on: bool) -> None:

@@ -166,6 +166,27 @@ static WsPlan plan_ws(pm_op op, int64_t V, int64_t F, int64_t P, int L, int cin,
       w.small = pm_round_up((size_t)3 * cin * cout * 4, 256);
       w.wgrad = pm_wgrad_ws_bytes(F, 3, cin, cout);
       break;
+    case PM_OP_F2V_SEP:
+      w.apack = pm_pack_bytes(pm_pack_geom(1, cin, cout, dt));
+      w.inter = pm_round_up((size_t)F * cin * esize(dt), 256);     // depth-wise facet rows y
+      w.owner = pm_round_up((size_t)V * cin * esize(dt), 256);     // their vertex means z
+      break;
+    case PM_OP_F2V_SEP_BWD:
+      w.apack = pm_pack_bytes(pm_pack_geom(1, cout, cin, dt));
+      w.inter = pm_round_up((size_t)F * cin * esize(dt), 256);     // y (for dP)
+      w.owner = pm_round_up((size_t)V * cin * esize(dt), 256);     // z (for dP), then reused never: dz has its own
+      w.small = pm_round_up((size_t)V * cin * 4, 256);             // dz = dg P^T, kept in fp32
+      w.wgrad = std::max(pm_wgrad_ws_bytes(V, 1, cin, cout), pm_sep_dalpha_ws_bytes(F, K, cin, dt == PM_BF16));
+      break;
+    case PM_OP_V2F_SEP:
+      w.apack = pm_pack_bytes(pm_pack_geom(1, 3 * cin, cout, dt));
+      break;
+    case PM_OP_V2F_SEP_BWD:
+      w.apack = pm_pack_bytes(pm_pack_geom(1, cout, cin, dt));
+      w.inter = pm_round_up((size_t)F * cin * esize(dt), 256);        // T_f = dg_f P^T
+      w.small = pm_round_up((size_t)3 * cin * cout * 4, 256);
+      w.wgrad = pm_wgrad_ws_bytes(F, 3, cin, cout);
+      break;
     case PM_OP_F2F:
       w.apack = pm_pack_bytes(pm_pack_geom(K, cin, cout, dt));
       w.inter = pm_round_up((size_t)P * cout * esize(dt), 256);   // per-point summands, feature dtype
@@ -184,7 +205,7 @@ static WsPlan plan_ws(pm_op op, int64_t V, int64_t F, int64_t P, int L, int cin,
 
 extern "C" size_t pm_workspace_bytes(pm_op op, int64_t n_vert, int64_t n_facet, int64_t n_tex, int L, int cin, int cout,
                                      pm_dtype dtype) {
-  if (op < PM_OP_ADJACENCY || op > PM_OP_F2F_BWD) return 0;
+  if (op < PM_OP_ADJACENCY || op > PM_OP_V2F_SEP_BWD) return 0;
   if (n_vert < 0 || n_facet < 0 || n_tex < 0) return 0;
   if (op != PM_OP_ADJACENCY && check_conv_common(L, PM_SH_PAPER, cin, cout, dtype) != PM_OK) return 0;
   if (op == PM_OP_ADJACENCY) { L = 0; cin = cout = 1; dtype = PM_F32; }
@@ -424,6 +445,161 @@ extern "C" pm_status pm_v2f_bwd(const pm_mesh* mesh, const pm_vf_adj* adj, int L
     PM_TRY(pm_launch_wgrad(dtype, B_ONE, X_GATHER_CAT, X_DIRECT, F, 3, cin, cout, basis_none(), xs, ys, M, wg, w.wgrad,
                            nullptr, st));
     PM_TRY(pm_launch_unfold(K, cin, cout, M, &fc, dW, st));
+  }
+  return PM_OK;
+}
+
+// ---- depth-wise separable facet2vertex / vertex2facet ---------------------------------------------
+static pm_status check_sep(const float* alpha, const void* P) {
+  if (!alpha || !pm_aligned16(alpha)) return pm_fail(PM_ERR_INVALID_ARG, "alpha is NULL or not 16-byte aligned");
+  return check_ptr(P, "P", true);
+}
+
+extern "C" pm_status pm_f2v_sep(const pm_mesh* mesh, const pm_vf_adj* adj, int L, pm_sh_norm norm, int cin, int cout,
+                                pm_dtype dtype, const void* h_facet, const float* alpha, const void* P, void* g_vert,
+                                void* ws, size_t ws_bytes, void* stream) {
+  pm_prof_set_op("f2v_sep");
+  PM_TRY(check_conv_common(L, norm, cin, cout, dtype));
+  PM_TRY(check_mesh(mesh, true));
+  if (!adj || !adj->row_ptr || (mesh->n_facet > 0 && !adj->col)) return pm_fail(PM_ERR_INVALID_ARG, "adjacency is NULL");
+  PM_TRY(check_sep(alpha, P));
+  PM_TRY(check_ptr(h_facet, "h_facet", mesh->n_facet > 0));
+  PM_TRY(check_ptr(g_vert, "g_vert", mesh->n_vert > 0));
+  const int K = (L + 1) * (L + 1);
+  const int64_t V = mesh->n_vert, F = mesh->n_facet;
+  WsPlan w = plan_ws(PM_OP_F2V_SEP, V, F, 0, L, cin, cout, dtype);
+  PM_TRY(check_ws(w, ws, ws_bytes));
+  hipStream_t st = (hipStream_t)stream;
+  char* apack = (char*)ws;
+  void* y = apack + w.apack;
+  void* z = (char*)y + w.inter;
+  const int fb = dtype == PM_BF16;
+  BasisSrc bs = basis_none();
+  bs.vert = mesh->vert; bs.facet = mesh->facet;
+  pm_make_sh_table(L, norm, &bs.sh);
+  // depth-wise stage per facet, mean over the adjacent facets, then the point-wise matrix on the vertex rows
+  // (the mean and the matrix commute, and there are half as many vertices as facets)
+  PM_TRY(pm_launch_dw_f2v(F, K, cin, fb, bs, h_facet, alpha, y, st));
+  PM_TRY(pm_launch_segreduce(V, cin, y, fb, adj->row_ptr, adj->col, 3, 1, z, fb, st));
+  PM_TRY(pm_launch_pack(PACK_PLAIN, dtype, 1, cin, cout, P, nullptr, apack, st));
+  RowSrc xs = row_src(z, dtype, cin);
+  return pm_launch_conv_rows(dtype, B_ONE, X_DIRECT, V, 1, cin, cout, basis_none(), xs, apack, g_vert, fb, st);
+}
+
+extern "C" pm_status pm_f2v_sep_bwd(const pm_mesh* mesh, const pm_vf_adj* adj, int L, pm_sh_norm norm, int cin,
+                                    int cout, pm_dtype dtype, const void* h_facet, const float* alpha, const void* P,
+                                    const void* dg_vert, void* dh_facet, float* dalpha, float* dP, void* ws,
+                                    size_t ws_bytes, void* stream) {
+  pm_prof_set_op("f2v_sep_bwd");
+  PM_TRY(check_conv_common(L, norm, cin, cout, dtype));
+  PM_TRY(check_mesh(mesh, true));
+  if (!adj || !adj->row_ptr || (mesh->n_facet > 0 && !adj->col)) return pm_fail(PM_ERR_INVALID_ARG, "adjacency is NULL");
+  PM_TRY(check_sep(alpha, P));
+  PM_TRY(check_ptr(h_facet, "h_facet", mesh->n_facet > 0));
+  PM_TRY(check_ptr(dg_vert, "dg_vert", mesh->n_vert > 0));
+  PM_TRY(check_ptr(dh_facet, "dh_facet", false));
+  PM_TRY(check_ptr(dalpha, "dalpha", false));
+  PM_TRY(check_ptr(dP, "dP", false));
+  if ((dalpha == nullptr) != (dP == nullptr)) return pm_fail(PM_ERR_INVALID_ARG, "dalpha and dP come together");
+  const int K = (L + 1) * (L + 1);
+  const int64_t V = mesh->n_vert, F = mesh->n_facet;
+  WsPlan w = plan_ws(PM_OP_F2V_SEP_BWD, V, F, 0, L, cin, cout, dtype);
+  PM_TRY(check_ws(w, ws, ws_bytes));
+  hipStream_t st = (hipStream_t)stream;
+  char* apack = (char*)ws;
+  void* y = apack + w.apack;
+  void* z = (char*)y + w.inter;
+  void* dz = (char*)z + w.owner;
+  void* wg = (char*)dz + w.small;
+  const int fb = dtype == PM_BF16;
+  BasisSrc bs = basis_none();
+  bs.vert = mesh->vert; bs.facet = mesh->facet;
+  pm_make_sh_table(L, norm, &bs.sh);
+  // dz = dg P^T on the vertex rows
+  PM_TRY(pm_launch_pack(PACK_TRANS, dtype, 1, cin, cout, P, nullptr, apack, st));
+  RowSrc gs = row_src(dg_vert, dtype, cout);
+  PM_TRY(pm_launch_conv_rows(dtype, B_ONE, X_DIRECT, V, 1, cout, cin, basis_none(), gs, apack, dz, 0, st));
+  if (dP) {
+    // dP = z^T dg with z recomputed (depth-wise stage + vertex mean): two bandwidth-bound passes instead of
+    // keeping z from the forward call
+    PM_TRY(pm_launch_dw_f2v(F, K, cin, fb, bs, h_facet, alpha, y, st));
+    PM_TRY(pm_launch_segreduce(V, cin, y, fb, adj->row_ptr, adj->col, 3, 1, z, fb, st));
+    RowSrc zs = row_src(z, dtype, cin);
+    PM_TRY(pm_launch_wgrad(dtype, B_ONE, X_DIRECT, X_DIRECT, V, 1, cin, cout, basis_none(), zs, gs, dP, wg, w.wgrad,
+                           nullptr, st));
+  }
+  if (dh_facet || dalpha)
+    PM_TRY(pm_launch_dw_f2v_bwd(F, K, cin, fb, bs, h_facet, alpha, (const float*)dz, adj->row_ptr, dh_facet, dalpha, (float*)wg, st));
+  return PM_OK;
+}
+
+extern "C" pm_status pm_v2f_sep(const pm_mesh* mesh, int L, pm_sh_norm norm, int cin, int cout, pm_dtype dtype,
+                                const void* h_vert, const float* alpha, const void* P, void* g_facet, void* ws,
+                                size_t ws_bytes, void* stream) {
+  pm_prof_set_op("v2f_sep");
+  PM_TRY(check_conv_common(L, norm, cin, cout, dtype));
+  PM_TRY(check_mesh(mesh, false));
+  PM_TRY(check_sep(alpha, P));
+  PM_TRY(check_ptr(h_vert, "h_vert", mesh->n_vert > 0));
+  PM_TRY(check_ptr(g_facet, "g_facet", mesh->n_facet > 0));
+  const int K = (L + 1) * (L + 1);
+  WsPlan w = plan_ws(PM_OP_V2F_SEP, mesh->n_vert, mesh->n_facet, 0, L, cin, cout, dtype);
+  PM_TRY(check_ws(w, ws, ws_bytes));
+  hipStream_t st = (hipStream_t)stream;
+  char* apack = (char*)ws;
+  // the three corner directions are constants: W_j = diag(s(e_j)) P, then the folded dense path
+  FoldCoef fc;
+  fold_coef(L, norm, &fc);
+  PM_TRY(pm_launch_pack(PACK_SEP_FOLD, dtype, K, cin, cout, P, &fc, apack, st, alpha));
+  RowSrc xs = row_src(h_vert, dtype, cin);
+  xs.facet = mesh->facet;
+  return pm_launch_conv_rows(dtype, B_ONE, X_GATHER_CAT, mesh->n_facet, 1, 3 * cin, cout, basis_none(), xs, apack,
+                             g_facet, dtype == PM_BF16, st);
+}
+
+extern "C" pm_status pm_v2f_sep_bwd(const pm_mesh* mesh, const pm_vf_adj* adj, int L, pm_sh_norm norm, int cin,
+                                    int cout, pm_dtype dtype, const void* h_vert, const float* alpha, const void* P,
+                                    const void* dg_facet, void* dh_vert, float* dalpha, float* dP, void* ws,
+                                    size_t ws_bytes, void* stream) {
+  pm_prof_set_op("v2f_sep_bwd");
+  PM_TRY(check_conv_common(L, norm, cin, cout, dtype));
+  PM_TRY(check_mesh(mesh, false));
+  PM_TRY(check_sep(alpha, P));
+  PM_TRY(check_ptr(h_vert, "h_vert", mesh->n_vert > 0));
+  PM_TRY(check_ptr(dg_facet, "dg_facet", mesh->n_facet > 0));
+  PM_TRY(check_ptr(dh_vert, "dh_vert", false));
+  PM_TRY(check_ptr(dalpha, "dalpha", false));
+  PM_TRY(check_ptr(dP, "dP", false));
+  if ((dalpha == nullptr) != (dP == nullptr)) return pm_fail(PM_ERR_INVALID_ARG, "dalpha and dP come together");
+  if (dh_vert && (!adj || !adj->row_ptr || (mesh->n_facet > 0 && !adj->col)))
+    return pm_fail(PM_ERR_INVALID_ARG, "dh_vert needs the adjacency");
+  const int K = (L + 1) * (L + 1);
+  const int64_t V = mesh->n_vert, F = mesh->n_facet;
+  WsPlan w = plan_ws(PM_OP_V2F_SEP_BWD, V, F, 0, L, cin, cout, dtype);
+  PM_TRY(check_ws(w, ws, ws_bytes));
+  hipStream_t st = (hipStream_t)stream;
+  char* apack = (char*)ws;
+  void* sv = apack + w.apack;
+  float* M = (float*)((char*)sv + w.inter);
+  void* wg = (char*)M + w.small;
+  const int fb = dtype == PM_BF16;
+  FoldCoef fc;
+  fold_coef(L, norm, &fc);
+  if (dh_vert) {
+    // one GEMM row per facet with P alone (the three corner matrices differ only by a channel scale), then the
+    // per-vertex sum applies the scale of each entry's corner
+    PM_TRY(pm_launch_pack(PACK_TRANS, dtype, 1, cin, cout, P, nullptr, apack, st));
+    RowSrc gs = row_src(dg_facet, dtype, cout);
+    PM_TRY(pm_launch_conv_rows(dtype, B_ONE, X_DIRECT, F, 1, cout, cin, basis_none(), gs, apack, sv, fb, st));
+    PM_TRY(pm_launch_slot_scale_sum(V, K, cin, fb, sv, adj->row_ptr, adj->col, alpha, &fc, dh_vert, st));
+  }
+  if (dP) {
+    RowSrc xs = row_src(h_vert, dtype, cin);
+    xs.facet = mesh->facet;
+    RowSrc ys = row_src(dg_facet, dtype, cout);
+    PM_TRY(pm_launch_wgrad(dtype, B_ONE, X_GATHER_CAT, X_DIRECT, F, 3, cin, cout, basis_none(), xs, ys, M, wg, w.wgrad,
+                           nullptr, st));
+    PM_TRY(pm_launch_sep_unfold(K, cin, cout, fb, M, alpha, P, &fc, dalpha, dP, st));
   }
   return PM_OK;
 }

@@ -25,6 +25,7 @@ struct PackP {
   int Kp, Cc, Cn;     // packed logical Wp[Kp][Cc][Cn]
   int NCH, NBG;
   const void* W;
+  const float* alpha;   // SEP modes: per-channel SH coefficients [K][cin]; W is then the point-wise matrix [cin][cout]
   uint4* out;
   FoldCoef fc;
 };
@@ -51,13 +52,24 @@ __device__ __forceinline__ void pack_values(const PackP& p, int k, int c0, int n
     else if (MODE == PACK_TRANS) { ci[e] = n; co[e] = c; }
     else if (MODE == PACK_FOLD) { j[e] = c / p.cin; ci[e] = c - j[e] * p.cin; co[e] = n; }
     else if (MODE == PACK_FOLD_TRANS) { j[e] = n / p.cin; ci[e] = n - j[e] * p.cin; co[e] = c; }
-    else { j[e] = c / p.cout; ci[e] = n; co[e] = c - j[e] * p.cout; }
+    else if (MODE == PACK_FOLD_BWD) { j[e] = c / p.cout; ci[e] = n; co[e] = c - j[e] * p.cout; }
+    else { j[e] = c / p.cin; ci[e] = c - j[e] * p.cin; co[e] = n; }   // PACK_SEP_FOLD
     if (!ok[e]) { j[e] = 0; ci[e] = 0; co[e] = 0; }   // in-bounds dummy, the value is dropped
     v[e] = 0.f;
   }
   if (MODE == PACK_PLAIN || MODE == PACK_TRANS) {
 #pragma unroll
     for (int e = 0; e < N; ++e) v[e] = ok[e] ? pack_src(p, k, ci[e], co[e]) : 0.f;
+    return;
+  }
+  if (MODE == PACK_SEP_FOLD) {
+    // s_j[ci] * P[ci][co],  s_j[ci] = sum_k fc[j][k] alpha[k][ci]
+#pragma unroll
+    for (int e = 0; e < N; ++e) {
+      float sj = 0.f;
+      for (int kk = 0; kk < p.K; ++kk) sj += p.fc.c[j[e]][kk] * p.alpha[(int64_t)kk * p.cin + ci[e]];
+      v[e] = ok[e] ? sj * pack_src(p, 0, ci[e], co[e]) : 0.f;
+    }
     return;
   }
   int kk = 0;
@@ -108,20 +120,20 @@ __global__ void __launch_bounds__(256) k_pack(PackP p, int64_t n_gran) {
 }
 
 pm_status pm_launch_pack(PackMode mode, pm_dtype dt, int K, int cin, int cout, const void* W, const FoldCoef* fc,
-                         void* apack, hipStream_t st) {
+                         void* apack, hipStream_t st, const float* alpha) {
   PackP p;
   p.mode = mode; p.src_bf16 = (dt == PM_BF16); p.dst_bf16 = (dt == PM_BF16);
   p.K = K; p.cin = cin; p.cout = cout;
   switch (mode) {
     case PACK_PLAIN: p.Kp = K; p.Cc = cin; p.Cn = cout; break;
     case PACK_TRANS: p.Kp = K; p.Cc = cout; p.Cn = cin; break;
-    case PACK_FOLD: p.Kp = 1; p.Cc = 3 * cin; p.Cn = cout; break;
+    case PACK_FOLD: case PACK_SEP_FOLD: p.Kp = 1; p.Cc = 3 * cin; p.Cn = cout; break;
     case PACK_FOLD_TRANS: p.Kp = 1; p.Cc = cout; p.Cn = 3 * cin; break;
     default: p.Kp = 1; p.Cc = 3 * cout; p.Cn = cin; break;
   }
   PackGeom g = pm_pack_geom(p.Kp, p.Cc, p.Cn, dt);
   p.NCH = g.NCH; p.NBG = g.NBG;
-  p.W = W; p.out = (uint4*)apack;
+  p.W = W; p.alpha = alpha; p.out = (uint4*)apack;
   if (fc) p.fc = *fc; else for (int j = 0; j < 3; ++j) for (int k = 0; k < PM_MAX_K; ++k) p.fc.c[j][k] = 0.f;
   int64_t n_gran = g.stages * STAGE_U4;
   { ProfScope ps__(st, "k_pack");
@@ -131,7 +143,8 @@ pm_status pm_launch_pack(PackMode mode, pm_dtype dt, int K, int cin, int cout, c
       case PACK_TRANS: hipLaunchKernelGGL(k_pack<PACK_TRANS>, grid, dim3(256), 0, st, p, n_gran); break;
       case PACK_FOLD: hipLaunchKernelGGL(k_pack<PACK_FOLD>, grid, dim3(256), 0, st, p, n_gran); break;
       case PACK_FOLD_TRANS: hipLaunchKernelGGL(k_pack<PACK_FOLD_TRANS>, grid, dim3(256), 0, st, p, n_gran); break;
-      default: hipLaunchKernelGGL(k_pack<PACK_FOLD_BWD>, grid, dim3(256), 0, st, p, n_gran); break;
+      case PACK_FOLD_BWD: hipLaunchKernelGGL(k_pack<PACK_FOLD_BWD>, grid, dim3(256), 0, st, p, n_gran); break;
+      default: hipLaunchKernelGGL(k_pack<PACK_SEP_FOLD>, grid, dim3(256), 0, st, p, n_gran); break;
     } }
   PM_CHECK_LAUNCH("k_pack");
   return PM_OK;

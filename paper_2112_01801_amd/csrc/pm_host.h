@@ -64,14 +64,17 @@ static inline PackGeom pm_pack_geom(int K, int Cc, int Cn, pm_dtype dt) {
 static inline size_t pm_pack_bytes(const PackGeom& g) { return (size_t)g.stages * PM_STAGE_BYTES; }
 
 // ---- kernel launchers (each enqueues on `st`, returns PM_OK or PM_ERR_HIP) ----------------------
-enum PackMode { PACK_PLAIN = 0, PACK_TRANS = 1, PACK_FOLD = 2, PACK_FOLD_TRANS = 3, PACK_FOLD_BWD = 4 };
+enum PackMode { PACK_PLAIN = 0, PACK_TRANS = 1, PACK_FOLD = 2, PACK_FOLD_TRANS = 3, PACK_FOLD_BWD = 4,
+                PACK_SEP_FOLD = 5 };
 struct FoldCoef { float c[3][PM_MAX_K]; };
 // Builds the MFMA operand image of Wp[k][c][n] from W[K][cin][cout] (src dtype = dt):
 //   PLAIN: Wp[k][ci][co] = W[k][ci][co]          TRANS: Wp[k][co][ci] = W[k][ci][co]
 //   FOLD:  Wp[0][j*cin+ci][co] = sum_k fc[j][k] W[k][ci][co]    FOLD_TRANS: Wp[0][co][j*cin+ci] = same
 //   FOLD_BWD: Wp[0][j*cout+co][ci] = same   (backward-data of the folded form, contraction over (corner, co))
+//   SEP_FOLD (separable vertex2facet): like FOLD with the folded matrices
+//   W_j[ci][co] = s_j[ci] P[ci][co],  s_j[ci] = sum_k fc[j][k] alpha[k][ci];  W is P [cin][cout], alpha [K][cin] fp32
 pm_status pm_launch_pack(PackMode mode, pm_dtype dt, int K, int cin, int cout, const void* W, const FoldCoef* fc,
-                         void* apack, hipStream_t st);
+                         void* apack, hipStream_t st, const float* alpha = nullptr);
 
 enum BMode { B_ONE = 0, B_NORMAL = 1, B_DIRS = 2 };
 enum XMode { X_DIRECT = 0, X_GATHER_SUM = 1, X_GATHER_CAT = 2, X_GATHER1 = 3 };
@@ -123,6 +126,23 @@ pm_status pm_launch_unfold(int K, int cin, int cout, const float* M, const FoldC
 // the facet rows adjacent to a vertex, summed separately per corner slot, ascending entry order, fp32 sums.
 pm_status pm_launch_segsum_slots(int64_t n_seg, int C, const void* src, int src_is_bf16, const int32_t* row_ptr,
                                  const int32_t* col, void* out, int out_is_bf16, hipStream_t st);
+// out[i] = sum over n_slice slices of partial[slice][i], added in a fixed order (bitwise reproducible)
+pm_status pm_launch_sum_slices(const float* partial, int64_t n, int n_slice, float* out, hipStream_t st);
+
+// Depth-wise stage of the separable facet2vertex form: y_f[c] = h_f[c] * sum_k alpha[k][c] B_k(n_f), and its backward
+// (dh_f[c] = dy_f[c] * filter, dy_f = gathered mean of dz;  dalpha[k][c] = sum_f B_k(n_f) h_f[c] dy_f[c]).
+size_t pm_sep_dalpha_ws_bytes(int64_t F, int K, int C, int is_bf16);
+pm_status pm_launch_dw_f2v(int64_t F, int K, int C, int is_bf16, const BasisSrc& bs, const void* h, const float* alpha,
+                           void* y, hipStream_t st);
+pm_status pm_launch_dw_f2v_bwd(int64_t F, int K, int C, int is_bf16, const BasisSrc& bs, const void* h,
+                               const float* alpha, const float* dz, const int32_t* row_ptr, void* dh, float* dalpha,
+                               float* partial, hipStream_t st);
+// separable vertex2facet backward: out[v][c] = sum over entries (f, j) of v of s_j[c] T[f][c]
+pm_status pm_launch_slot_scale_sum(int64_t V, int K, int C, int is_bf16, const void* T, const int32_t* row_ptr,
+                                   const int32_t* col, const float* alpha, const FoldCoef* fc, void* out, hipStream_t st);
+// separable vertex2facet: dP, dalpha from the three corner matrices M [3][cin][cout]
+pm_status pm_launch_sep_unfold(int K, int cin, int cout, int p_bf16, const float* M, const float* alpha, const void* P,
+                               const FoldCoef* fc, float* dalpha, float* dP, hipStream_t st);
 // owner[p] = f for p in [tex_off[f], tex_off[f+1])
 pm_status pm_launch_owner(int64_t n_facet, const int32_t* tex_off, int32_t* owner, hipStream_t st);
 

@@ -450,6 +450,13 @@ __global__ void __launch_bounds__(256) k_sum_partials(const float* __restrict__ 
   }
 }
 
+pm_status pm_launch_sum_slices(const float* partial, int64_t n, int n_slice, float* out, hipStream_t st) {
+  { ProfScope ps__(st, "k_sum_partials");
+    hipLaunchKernelGGL(k_sum_partials, dim3((unsigned)((n + 31) / 32)), dim3(256), 0, st, partial, n, n_slice, out); }
+  PM_CHECK_LAUNCH("k_sum_partials");
+  return PM_OK;
+}
+
 struct WgradGeom {
   int KGn, CBP, NBP, slabs, NKPW, RS, n_part;
   int64_t rows_per_part;
@@ -518,6 +525,8 @@ static pm_status launch_wgrad_mode(BMode bm, XMode xm, XMode ym, const WgradP& p
     return launch_wgrad_inst<DT, B_ONE, X_GATHER_CAT, X_DIRECT>(p, g, st);
   if (bm == B_DIRS && xm == X_DIRECT && ym == X_GATHER1)
     return launch_wgrad_inst<DT, B_DIRS, X_DIRECT, X_GATHER1>(p, g, st);
+  if (bm == B_ONE && xm == X_DIRECT && ym == X_DIRECT)
+    return launch_wgrad_inst<DT, B_ONE, X_DIRECT, X_DIRECT>(p, g, st);
   return pm_fail(PM_ERR_UNSUPPORTED, "wgrad mode (%d,%d,%d)", (int)bm, (int)xm, (int)ym);
 }
 
@@ -540,12 +549,7 @@ pm_status pm_launch_wgrad(pm_dtype mt, BMode bm, XMode xm, XMode ym, int64_t R, 
   else
     s = (mt == PM_BF16) ? launch_wgrad_mode<1>(bm, xm, ym, p, g, st) : launch_wgrad_mode<0>(bm, xm, ym, p, g, st);
   if (s != PM_OK) return s;
-  int64_t n = (int64_t)K * Cc * Cn;
-  { ProfScope ps__(st, "k_sum_partials");
-    hipLaunchKernelGGL(k_sum_partials, dim3((unsigned)((n + 31) / 32)), dim3(256), 0, st, (const float*)ws, n,
-                     g.n_part * g.RS, dWp); }
-  PM_CHECK_LAUNCH("k_sum_partials");
-  return PM_OK;
+  return pm_launch_sum_slices((const float*)ws, (int64_t)K * Cc * Cn, g.n_part * g.RS, dWp, st);
 }
 
 // dW[k][ci][co] = sum_j fc[j][k] * M[j][ci][co]   (vertex2facet: the three corner directions are constants)
