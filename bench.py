@@ -210,6 +210,9 @@ def all_ops(args, cfg, pm, mg, torch):
     P = int(tex_off[-1])
     t_off, t_bary = torch.from_numpy(tex_off).cuda(), torch.from_numpy(bary).cuda()
     hF, hV, hP, dgV, dgF = rnd(F, cin), rnd(V, cin), rnd(P, cin), rnd(V, cout), rnd(F, cout)
+    # separable form: W[k, ci, co] = alpha[k, ci] * Pw[ci, co]
+    alpha = (torch.rand(K, cin, device="cuda", generator=gen) * 2 - 1) / K ** 0.5
+    Pw = ((torch.rand(cin, cout, device="cuda", generator=gen) * 2 - 1) * (3.0 / cin) ** 0.5).to(tdt)
     ops = {
         "f2v": (lambda: pm.pm_f2v(mesh, adj, L, hF, W, DT), F),
         "f2v_bwd": (lambda: pm.pm_f2v_bwd(mesh, adj, L, hF, W, dgV, DT), F),
@@ -217,6 +220,10 @@ def all_ops(args, cfg, pm, mg, torch):
         "v2f_bwd": (lambda: pm.pm_v2f_bwd(mesh, adj, L, hV, W, dgF, DT), F),
         "f2f": (lambda: pm.pm_f2f(t_off, t_bary, L, hP, W, DT), P),
         "f2f_bwd": (lambda: pm.pm_f2f_bwd(t_off, t_bary, L, hP, W, dgF, DT), P),
+        "f2v_sep": (lambda: pm.pm_f2v_sep(mesh, adj, L, hF, alpha, Pw, DT), F),
+        "f2v_sep_bwd": (lambda: pm.pm_f2v_sep_bwd(mesh, adj, L, hF, alpha, Pw, dgV, DT), F),
+        "v2f_sep": (lambda: pm.pm_v2f_sep(mesh, L, hV, alpha, Pw, DT), F),
+        "v2f_sep_bwd": (lambda: pm.pm_v2f_sep_bwd(mesh, adj, L, hV, alpha, Pw, dgF, DT), F),
     }
     out = {"workload": "config 3 mesh %dx%d: F=%d V=%d texture points=%d, L=%d, %d->%d, %s" %
                        (args.grid, args.grid, F, V, P, L, cin, cout, args.ops_dtype),

@@ -184,7 +184,7 @@ static WsPlan plan_ws(pm_op op, int64_t V, int64_t F, int64_t P, int L, int cin,
     case PM_OP_V2F_SEP_BWD:
       w.apack = pm_pack_bytes(pm_pack_geom(1, cout, cin, dt));
       w.inter = pm_round_up((size_t)F * cin * esize(dt), 256);        // T_f = dg_f P^T
-      w.small = pm_round_up((size_t)3 * cin * cout * 4, 256);
+      w.small = pm_round_up((size_t)3 * cin * cout * 4, 256) + pm_round_up((size_t)3 * cin * 4, 256);   // M, corner scales
       w.wgrad = pm_wgrad_ws_bytes(F, 3, cin, cout);
       break;
     case PM_OP_F2F:
@@ -591,7 +591,8 @@ extern "C" pm_status pm_v2f_sep_bwd(const pm_mesh* mesh, const pm_vf_adj* adj, i
     PM_TRY(pm_launch_pack(PACK_TRANS, dtype, 1, cin, cout, P, nullptr, apack, st));
     RowSrc gs = row_src(dg_facet, dtype, cout);
     PM_TRY(pm_launch_conv_rows(dtype, B_ONE, X_DIRECT, F, 1, cout, cin, basis_none(), gs, apack, sv, fb, st));
-    PM_TRY(pm_launch_slot_scale_sum(V, K, cin, fb, sv, adj->row_ptr, adj->col, alpha, &fc, dh_vert, st));
+    PM_TRY(pm_launch_slot_scale_sum(V, K, cin, fb, sv, adj->row_ptr, adj->col, alpha, &fc,
+                                    (float*)((char*)M + pm_round_up((size_t)3 * cin * cout * 4, 256)), dh_vert, st));
   }
   if (dP) {
     RowSrc xs = row_src(h_vert, dtype, cin);

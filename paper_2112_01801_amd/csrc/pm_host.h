@@ -139,7 +139,8 @@ pm_status pm_launch_dw_f2v_bwd(int64_t F, int K, int C, int is_bf16, const Basis
                                float* partial, hipStream_t st);
 // separable vertex2facet backward: out[v][c] = sum over entries (f, j) of v of s_j[c] T[f][c]
 pm_status pm_launch_slot_scale_sum(int64_t V, int K, int C, int is_bf16, const void* T, const int32_t* row_ptr,
-                                   const int32_t* col, const float* alpha, const FoldCoef* fc, void* out, hipStream_t st);
+                                   const int32_t* col, const float* alpha, const FoldCoef* fc, float* sc, void* out,
+                                   hipStream_t st);
 // separable vertex2facet: dP, dalpha from the three corner matrices M [3][cin][cout]
 pm_status pm_launch_sep_unfold(int K, int cin, int cout, int p_bf16, const float* M, const float* alpha, const void* P,
                                const FoldCoef* fc, float* dalpha, float* dP, hipStream_t st);

@@ -3,20 +3,19 @@
 //     y_f[c]  = h_f[c] * s_f[c],            s_f[c] = sum_k alpha[k][c] B_k(n_f)
 //     dh_f[c] = dy_f[c] * s_f[c],           dy_f[c] = sum_j dz[v_j(f)][c] / deg(v_j(f))    (dz in fp32)
 //     dalpha[k][c] = sum_f B_k(n_f) h_f[c] dy_f[c]
-// Bound by HBM (one row read, one written per facet).  A group of lanes owns a facet row, each lane a run of
-// channels; a block walks its rows four per group at a time so that a coefficient fetched from LDS serves
-// four rows.  The SH basis of the block's rows is evaluated once per row (one thread each) into LDS.
-// dalpha is reduced without atomics: every lane group accumulates its rows in registers (a fixed
-// assignment of rows to groups) and writes its own slice; the slices are added in a fixed order.
+// Bound by HBM (one row read, one written per facet); the K multiply-adds per element run on the fp32
+// matrix cores so that the vector ALU only loads, converts and stores.
+// dalpha is reduced without atomics: every wave accumulates its rows in matrix-core tiles (a fixed assignment
+// of rows to waves), a block adds its waves in LDS one after the other and writes its own slice; the slices
+// are added in a fixed order.
 // The tail of the file holds the small fold/unfold kernels of the separable vertex2facet form (Eq. 6).
 #include "pm_rows.h"
 
-#define SEP_RPG 4      /* rows a lane group handles per step */
-#define SEP_KC 16      /* basis functions per pass of the backward kernel (register accumulators) */
+#define SEP_KC 16      /* basis functions per pass of the backward kernel (rows of one matrix-core tile) */
 
 struct SepP {
   int64_t F;
-  int K, C, lpg;          // lanes per row group (power of two), each lane CPL channels per step
+  int K, C, lpg;          // lanes per row group (16)
   int is_bf16;
   BasisSrc bs;            // vert / facet / sh table
   const void* h;          // [F][C]
@@ -29,14 +28,19 @@ struct SepP {
   int want_dalpha;
 };
 
-template <bool BF16>
-__device__ __forceinline__ void sep_load(const void* base, int64_t off, int C, int c0, float (&v)[BF16 ? 8 : 4]) {
-  constexpr int CPL = BF16 ? 8 : 4;
-  if (c0 + CPL <= C && ((((uintptr_t)base) + (uint64_t)(off + c0) * (BF16 ? 2 : 4)) & 15) == 0) {
-    if constexpr (BF16) {
+// CPL consecutive channels of one row, as fp32.  VEC: one 8- or 16-byte access (the caller has checked that
+// every run is whole and aligned); else element by element, channels past C read as zero / are not written.
+template <bool BF16, int CPL, bool VEC>
+__device__ __forceinline__ void sep_load(const void* base, int64_t off, int C, int c0, float (&v)[CPL]) {
+  static_assert((BF16 && (CPL == 8 || CPL == 4)) || (!BF16 && CPL == 4), "run width");
+  if constexpr (VEC) {
+    if constexpr (BF16 && CPL == 8) {
       const uint4 u = *(const uint4*)((const uint16_t*)base + off + c0);
       v[0] = bf16lo_to_f32(u.x); v[1] = bf16hi_to_f32(u.x); v[2] = bf16lo_to_f32(u.y); v[3] = bf16hi_to_f32(u.y);
       v[4] = bf16lo_to_f32(u.z); v[5] = bf16hi_to_f32(u.z); v[6] = bf16lo_to_f32(u.w); v[7] = bf16hi_to_f32(u.w);
+    } else if constexpr (BF16) {
+      const uint2 u = *(const uint2*)((const uint16_t*)base + off + c0);
+      v[0] = bf16lo_to_f32(u.x); v[1] = bf16hi_to_f32(u.x); v[2] = bf16lo_to_f32(u.y); v[3] = bf16hi_to_f32(u.y);
     } else {
       const float4 f = *(const float4*)((const float*)base + off + c0);
       v[0] = f.x; v[1] = f.y; v[2] = f.z; v[3] = f.w;
@@ -51,10 +55,10 @@ __device__ __forceinline__ void sep_load(const void* base, int64_t off, int C, i
   }
 }
 
-// CPL fp32 values of one row (the vertex rows dz stay fp32 in both feature dtypes)
-template <int CPL>
+// CPL fp32 values of one row (the vertex rows dz and the corner scales stay fp32 in both feature dtypes)
+template <int CPL, bool VEC>
 __device__ __forceinline__ void sep_load_f32(const float* base, int64_t off, int C, int c0, float (&v)[CPL]) {
-  if (c0 + CPL <= C && ((((uintptr_t)base) + (uint64_t)(off + c0) * 4) & 15) == 0) {
+  if constexpr (VEC) {
 #pragma unroll
     for (int q = 0; q < CPL / 4; ++q) {
       const float4 f = *(const float4*)(base + off + c0 + 4 * q);
@@ -66,15 +70,18 @@ __device__ __forceinline__ void sep_load_f32(const float* base, int64_t off, int
   }
 }
 
-template <bool BF16>
-__device__ __forceinline__ void sep_store(void* base, int64_t off, int C, int c0, const float (&v)[BF16 ? 8 : 4]) {
-  constexpr int CPL = BF16 ? 8 : 4;
-  if (c0 + CPL <= C && ((((uintptr_t)base) + (uint64_t)(off + c0) * (BF16 ? 2 : 4)) & 15) == 0) {
-    if constexpr (BF16) {
+template <bool BF16, int CPL, bool VEC>
+__device__ __forceinline__ void sep_store(void* base, int64_t off, int C, int c0, const float (&v)[CPL]) {
+  if constexpr (VEC) {
+    if constexpr (BF16 && CPL == 8) {
       uint4 u;
       u.x = pack_bf16x2(v[0], v[1]); u.y = pack_bf16x2(v[2], v[3]);
       u.z = pack_bf16x2(v[4], v[5]); u.w = pack_bf16x2(v[6], v[7]);
       *(uint4*)((uint16_t*)base + off + c0) = u;
+    } else if constexpr (BF16) {
+      uint2 u;
+      u.x = pack_bf16x2(v[0], v[1]); u.y = pack_bf16x2(v[2], v[3]);
+      *(uint2*)((uint16_t*)base + off + c0) = u;
     } else {
       *(float4*)((float*)base + off + c0) = make_float4(v[0], v[1], v[2], v[3]);
     }
@@ -88,160 +95,197 @@ __device__ __forceinline__ void sep_store(void* base, int64_t off, int C, int c0
   }
 }
 
-// LDS: alpha [kn][lanes per group * channels per lane] (this pass's k range, one channel run), basis [rows per step][kn]
-template <bool BF16, bool BWD>
+// whole, 16-byte aligned channel runs: C a multiple of 8 (bf16) or 4 (fp32) and aligned bases
+static bool sep_vec_ok(int C, int is_bf16, const void* a, const void* b, const void* c) {
+  auto al = [](const void* q) { return (((uintptr_t)q) & 15) == 0; };
+  return C % (is_bf16 ? 8 : 4) == 0 && al(a) && al(b) && al(c);
+}
+
+// Lane layout (fixed): a wave holds 4 row groups of 16 lanes, lane `sub` of a group owns channels
+// 4 sub .. 4 sub + 3 of a run of 64 channels, and each group handles four consecutive rows per sub-step, so a
+// wave covers 16 rows x 64 channels per sub-step.  Both small contractions run on the fp32 matrix cores
+// (16x16x4: A[i][kk] from lane (i = lane % 16, kk = lane / 16), B[kk][j] from lane (kk = lane / 16,
+// j = lane % 16), D[4 (lane / 16) + reg][lane % 16]) in exactly this layout, with no data movement:
+//   s = Basis alpha:      i = row of the sub-step, kk = basis function, column j of tile t = channel 4 j + t;
+//                         register q of tile t is then s[row 4 g + q][channel 4 sub + t], the lane's own element
+//   dalpha = Basis^T (h dy): i = basis function, kk = row group g (its q-th row), same columns; the lane's own
+//                         products h dy are the B operand.
+// A wave evaluates the SH basis of 64 rows at a time (one lane per row) into its own LDS rows, then walks
+// them in four sub-steps; waves never wait for each other inside the row loop.
+// LDS: alpha [4 ceil(kn/4)][64] (zero rows past kn), per wave basis [64][kn | 1], backward: block sum [16][64].
+#define SEP_RW 64
+
+template <bool BF16, bool BWD, bool VEC>
 __global__ void __launch_bounds__(256) k_dw_f2v(SepP p) {
   extern __shared__ float sep_lds[];
-  constexpr int CPL = BF16 ? 8 : 4;
-  const int tid = threadIdx.x;
-  const int G = 256 / p.lpg;                 // lane groups per block
-  const int grp = tid / p.lpg, sub = tid % p.lpg;
-  const int rows_step = G * SEP_RPG;         // rows per block step (<= 256)
-  const int RW = p.lpg * CPL;                // channels per run: one run is resident in LDS at a time
+  constexpr int CPL = 4;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int g = lane >> 4, sub = lane & 15;
   const int k0 = BWD ? p.kc0 : 0;
-  // basis functions handled in this launch: all of them, or one chunk when dalpha accumulates in registers
+  // basis functions handled in this launch: all of them, or one chunk of the dalpha rows
   const int kn = (BWD && p.want_dalpha) ? min(SEP_KC, p.K - k0) : p.K;
-  float* A = sep_lds;                        // [kn][RW]
-  float* Bs = sep_lds + (size_t)kn * RW;     // [rows_step][kn]
-  const int nchunk = (p.C + RW - 1) / RW;    // channel runs per lane (1 unless C > 64 * CPL)
+  const int nk4 = (kn + 3) >> 2;
+  const int KP = kn | 1;                                   // odd row pitch: conflict-free column reads
+  float* A = sep_lds;                                      // [4 nk4][64]
+  float* Bw = sep_lds + nk4 * 4 * SEP_RW + wave * 64 * KP;  // this wave's [64][KP]
+  float* red = sep_lds + nk4 * 4 * SEP_RW + 4 * 64 * KP;   // [SEP_KC][64] (backward)
+  const bool want_s = !BWD || (p.y != nullptr && kn == p.K);   // dh needs the whole filter value
+  const int nrun = (p.C + SEP_RW - 1) / SEP_RW;
+  const int64_t n_ss = (p.F + 63) >> 6;
 
-  // backward: this group's dalpha accumulators for one channel run at a time
-  for (int cr = 0; cr < nchunk; ++cr) {
-    const int c0 = (cr * p.lpg + sub) * CPL;
+  for (int cr = 0; cr < nrun; ++cr) {
+    const int c0 = cr * SEP_RW + sub * CPL;
+    const bool cok = c0 < p.C;
+    const int cl = VEC ? min(c0, p.C - CPL) : c0;
     __syncthreads();                          // the previous run's coefficients are no longer needed
-    for (int i = tid; i < kn * RW; i += 256) {
-      const int k = i / RW, c = cr * RW + (i - k * RW);
-      A[i] = (c < p.C) ? p.alpha[(int64_t)(k0 + k) * p.C + c] : 0.f;
+    for (int i = tid; i < nk4 * 4 * SEP_RW; i += 256) {
+      const int k = i >> 6, c = cr * SEP_RW + (i & 63);
+      A[i] = (k < kn && c < p.C) ? p.alpha[(int64_t)(k0 + k) * p.C + c] : 0.f;
     }
-    float da[BWD ? SEP_KC : 1][CPL];
-    if constexpr (BWD) {
+    __syncthreads();
+    floatx4 D[4];                             // backward: dalpha tiles of this wave
 #pragma unroll
-      for (int k = 0; k < SEP_KC; ++k)
-#pragma unroll
-        for (int i = 0; i < CPL; ++i) da[k][i] = 0.f;
-    }
-    for (int64_t r0 = (int64_t)blockIdx.x * rows_step; r0 < p.F; r0 += (int64_t)gridDim.x * rows_step) {
-      __syncthreads();                        // the previous step's basis rows are no longer needed
-      if (tid < rows_step) {
-        const int64_t r = r0 + tid;
+    for (int t = 0; t < 4; ++t) D[t] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+    for (int64_t ss = (int64_t)blockIdx.x * 4 + wave; ss < n_ss; ss += (int64_t)gridDim.x * 4) {
+      const int64_t R0 = ss << 6;
+      __builtin_amdgcn_wave_barrier();        // the previous rows' basis has been read
+      {
+        const int64_t r = R0 + lane;
         if (r < p.F) {
           float x, y, z;
           row_direction<B_NORMAL>(p.bs, r, x, y, z);
           sh_eval<-1>(x, y, z, p.bs.sh, [&](int k, float v) {
             const int kl = k - k0;
-            if (kl >= 0 && kl < kn) Bs[tid * kn + kl] = v;
+            if (kl >= 0 && kl < kn) Bw[lane * KP + kl] = v;
           });
+        } else {
+          for (int k = 0; k < kn; ++k) Bw[lane * KP + k] = 0.f;   // rows past the end add nothing to dalpha
         }
       }
-      __syncthreads();
-      // this group's rows of the step: grp * SEP_RPG + q
-      float hv[SEP_RPG][CPL], s[SEP_RPG][CPL], dyv[SEP_RPG][CPL];
-      bool ok[SEP_RPG];
+      __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      for (int s4 = 0; s4 < 4; ++s4) {
+        if (R0 + 16 * s4 >= p.F) break;       // the same for the whole wave
+        const int64_t rb = R0 + 16 * s4 + 4 * g;
+        float hv[4][CPL], dyv[BWD ? 4 : 1][CPL];
+        bool ok[4];
+        // With whole aligned runs every load is issued unconditionally at an in-range address (row and run
+        // clamped) and masked afterwards, so that the loads of all four rows are in flight together.
 #pragma unroll
-      for (int q = 0; q < SEP_RPG; ++q) {
-        const int64_t r = r0 + grp * SEP_RPG + q;
-        ok[q] = r < p.F && c0 < p.C;
+        for (int q = 0; q < 4; ++q) {
+          const int64_t r = rb + q;
+          ok[q] = r < p.F && cok;
+          const int64_t rl = min(r, p.F - 1);
 #pragma unroll
-        for (int i = 0; i < CPL; ++i) { hv[q][i] = 0.f; s[q][i] = 0.f; dyv[q][i] = 0.f; }
-        if (ok[q]) {
-          sep_load<BF16>(p.h, r * p.C, p.C, c0, hv[q]);
+          for (int i = 0; i < CPL; ++i) hv[q][i] = 0.f;
           if constexpr (BWD) {
 #pragma unroll
-            for (int j = 0; j < 3; ++j) {
-              const int32_t v = p.bs.facet[3 * r + j];
-              const float w = 1.0f / (float)(p.row_ptr[v + 1] - p.row_ptr[v]);
-              float t[CPL];
-              sep_load_f32<CPL>(p.dz, (int64_t)v * p.C, p.C, c0, t);
-#pragma unroll
-              for (int i = 0; i < CPL; ++i) dyv[q][i] += t[i] * w;
-            }
+            for (int i = 0; i < CPL; ++i) dyv[q][i] = 0.f;
           }
-        }
-      }
-      if (c0 < p.C) {
-        for (int k = 0; k < kn; ++k) {
-          float a[CPL];
+          if (VEC || ok[q]) {
+            sep_load<BF16, CPL, VEC>(p.h, rl * p.C, p.C, cl, hv[q]);
+            if constexpr (BWD) {
 #pragma unroll
-          for (int i = 0; i < CPL; ++i) a[i] = A[k * RW + sub * CPL + i];
+              for (int j = 0; j < 3; ++j) {
+                const int32_t v = p.bs.facet[3 * rl + j];
+                const float w = 1.0f / (float)(p.row_ptr[v + 1] - p.row_ptr[v]);
+                float t[CPL];
+                sep_load_f32<CPL, VEC>(p.dz, (int64_t)v * p.C, p.C, cl, t);
 #pragma unroll
-          for (int q = 0; q < SEP_RPG; ++q) {
-            const float b = Bs[(grp * SEP_RPG + q) * kn + k];
-#pragma unroll
-            for (int i = 0; i < CPL; ++i) s[q][i] += a[i] * b;
-          }
-        }
-      }
-      if constexpr (BWD) {
-        if (c0 < p.C && p.want_dalpha) {
-#pragma unroll
-          for (int k = 0; k < SEP_KC; ++k) {
-            if (k < kn) {
-#pragma unroll
-              for (int q = 0; q < SEP_RPG; ++q) {
-                const float b = ok[q] ? Bs[(grp * SEP_RPG + q) * kn + k] : 0.f;
-#pragma unroll
-                for (int i = 0; i < CPL; ++i) da[k][i] += b * (hv[q][i] * dyv[q][i]);
+                for (int i = 0; i < CPL; ++i) dyv[q][i] += t[i] * w;
               }
             }
           }
-        }
-      }
+          if constexpr (VEC) {
 #pragma unroll
-      for (int q = 0; q < SEP_RPG; ++q) {
-        if (!ok[q]) continue;
-        const int64_t r = r0 + grp * SEP_RPG + q;
-        float o[CPL];
-        if constexpr (BWD) {
-          // the whole filter value is needed for dh: only a launch that covers every k writes it
-          if (p.y && kn == p.K) {
+            for (int i = 0; i < CPL; ++i) hv[q][i] = ok[q] ? hv[q][i] : 0.f;
+            if constexpr (BWD) {
 #pragma unroll
-            for (int i = 0; i < CPL; ++i) o[i] = dyv[q][i] * s[q][i];
-            sep_store<BF16>(p.y, r * p.C, p.C, c0, o);
+              for (int i = 0; i < CPL; ++i) dyv[q][i] = ok[q] ? dyv[q][i] : 0.f;
+            }
           }
-        } else {
+        }
+        floatx4 S[4];
 #pragma unroll
-          for (int i = 0; i < CPL; ++i) o[i] = hv[q][i] * s[q][i];
-          sep_store<BF16>(p.y, r * p.C, p.C, c0, o);
+        for (int t = 0; t < 4; ++t) S[t] = floatx4{0.f, 0.f, 0.f, 0.f};
+        if (want_s) {
+          for (int ks = 0; ks < nk4; ++ks) {
+            const int k = 4 * ks + g;
+            const float bv = Bw[(16 * s4 + sub) * KP + min(k, kn - 1)];
+            const float a = k < kn ? bv : 0.f;
+            const float4 w4 = *(const float4*)&A[k * SEP_RW + sub * CPL];
+            S[0] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, w4.x, S[0], 0, 0, 0);
+            S[1] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, w4.y, S[1], 0, 0, 0);
+            S[2] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, w4.z, S[2], 0, 0, 0);
+            S[3] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, w4.w, S[3], 0, 0, 0);
+          }
+        }
+        if constexpr (BWD) {
+          if (p.want_dalpha) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+              const float bv = Bw[(16 * s4 + 4 * g + q) * KP + min(sub, kn - 1)];
+              const float a = sub < kn ? bv : 0.f;
+#pragma unroll
+              for (int t = 0; t < 4; ++t)
+                D[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, hv[q][t] * dyv[q][t], D[t], 0, 0, 0);
+            }
+          }
+        }
+        if (!BWD || (p.y != nullptr && want_s)) {
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            float o[CPL];
+#pragma unroll
+            for (int t = 0; t < 4; ++t) o[t] = (BWD ? dyv[q][t] : hv[q][t]) * S[t][q];
+            if (ok[q]) sep_store<BF16, CPL, VEC>(p.y, (rb + q) * p.C, p.C, c0, o);
+          }
         }
       }
     }
     if constexpr (BWD) {
-      if (p.want_dalpha && c0 < p.C) {
-        float* dst = p.partial + ((int64_t)blockIdx.x * G + grp) * p.K * p.C;
+      if (p.want_dalpha) {
+        // the block's sum over its four waves, one after the other (a fixed order), then one slice per block
+        for (int w = 0; w < 4; ++w) {
+          __syncthreads();
+          if (wave == w) {
 #pragma unroll
-        for (int k = 0; k < SEP_KC; ++k)
-          if (k < kn) {
+            for (int t = 0; t < 4; ++t)
 #pragma unroll
-            for (int i = 0; i < CPL; ++i)
-              if (c0 + i < p.C) dst[(int64_t)(k0 + k) * p.C + c0 + i] = da[k][i];
+              for (int r = 0; r < 4; ++r) {
+                const int o = (4 * g + r) * SEP_RW + sub * CPL + t;
+                red[o] = (w == 0 ? 0.f : red[o]) + D[t][r];
+              }
           }
+        }
+        __syncthreads();
+        float* dst = p.partial + (int64_t)blockIdx.x * p.K * p.C;
+        for (int i = tid; i < kn * SEP_RW; i += 256) {
+          const int k = i >> 6, c = cr * SEP_RW + (i & 63);
+          if (c < p.C) dst[(int64_t)(k0 + k) * p.C + c] = red[i];
+        }
       }
     }
   }
 }
 
-static void sep_geom(int C, int is_bf16, int* lpg, int* grid, int64_t F) {
-  const int cpl = is_bf16 ? 8 : 4;
-  int need = (C + cpl - 1) / cpl, l = 1;
-  while (l < need && l < 64) l <<= 1;
-  if (l < 4) l = 4;      // one thread per row evaluates the basis: at most 256 rows per block step
-  *lpg = l;
-  const int rows_step = (256 / l) * SEP_RPG;
-  int64_t nblk = (F + rows_step - 1) / rows_step;
-  if (nblk > 512) nblk = 512;
-  if (nblk < 1) nblk = 1;
-  *grid = (int)nblk;
+#define SEP_GRID_FWD 2048
+#define SEP_GRID_BWD 1024
+static int sep_grid(int64_t F, int cap) {
+  int64_t nblk = (((F + 63) >> 6) + 3) >> 2;      // four waves per block, 64 rows per wave step
+  if (nblk > cap) nblk = cap;
+  return nblk < 1 ? 1 : (int)nblk;
 }
 
 size_t pm_sep_dalpha_ws_bytes(int64_t F, int K, int C, int is_bf16) {
-  int lpg, grid;
-  sep_geom(C, is_bf16, &lpg, &grid, F);
-  return pm_round_up((size_t)grid * (256 / lpg) * K * C * sizeof(float), 256);
+  (void)is_bf16;
+  return pm_round_up((size_t)sep_grid(F, SEP_GRID_BWD) * K * C * sizeof(float), 256);
 }
 
-static size_t sep_lds_bytes(int kn, int C, int is_bf16, int lpg) {
-  (void)C;
-  return ((size_t)kn * lpg * (is_bf16 ? 8 : 4) + (size_t)(256 / lpg) * SEP_RPG * kn) * sizeof(float);
+static size_t sep_lds_bytes(int kn, bool bwd) {
+  const int nk4 = (kn + 3) / 4, KP = kn | 1;
+  return ((size_t)nk4 * 4 * SEP_RW + (size_t)4 * 64 * KP + (bwd ? (size_t)SEP_KC * SEP_RW : 0)) * sizeof(float);
 }
 
 pm_status pm_launch_dw_f2v(int64_t F, int K, int C, int is_bf16, const BasisSrc& bs, const void* h, const float* alpha,
@@ -249,11 +293,12 @@ pm_status pm_launch_dw_f2v(int64_t F, int K, int C, int is_bf16, const BasisSrc&
   if (F == 0) return PM_OK;
   SepP p;
   p.F = F; p.K = K; p.C = C; p.is_bf16 = is_bf16; p.bs = bs; p.h = h; p.alpha = alpha; p.y = y;
-  p.dz = nullptr; p.row_ptr = nullptr; p.partial = nullptr; p.kc0 = 0; p.want_dalpha = 0;
-  int grid;
-  sep_geom(C, is_bf16, &p.lpg, &grid, F);
-  const size_t lds = sep_lds_bytes(K, C, is_bf16, p.lpg);
-  auto kern = is_bf16 ? k_dw_f2v<true, false> : k_dw_f2v<false, false>;
+  p.dz = nullptr; p.row_ptr = nullptr; p.partial = nullptr; p.kc0 = 0; p.want_dalpha = 0; p.lpg = 16;
+  const int grid = sep_grid(F, SEP_GRID_FWD);
+  const size_t lds = sep_lds_bytes(K, false);
+  const bool vec = sep_vec_ok(C, is_bf16, h, y, nullptr);
+  auto kern = is_bf16 ? (vec ? k_dw_f2v<true, false, true> : k_dw_f2v<true, false, false>)
+                      : (vec ? k_dw_f2v<false, false, true> : k_dw_f2v<false, false, false>);
   PM_CHECK_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
   { ProfScope ps__(st, "k_dw_f2v");
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(256), lds, st, p); }
@@ -267,20 +312,21 @@ pm_status pm_launch_dw_f2v_bwd(int64_t F, int K, int C, int is_bf16, const Basis
                                float* partial, hipStream_t st) {
   SepP p;
   p.F = F; p.K = K; p.C = C; p.is_bf16 = is_bf16; p.bs = bs; p.h = h; p.alpha = alpha; p.y = dh;
-  p.dz = dz; p.row_ptr = row_ptr; p.partial = partial; p.want_dalpha = dalpha != nullptr;
-  int grid;
-  sep_geom(C, is_bf16, &p.lpg, &grid, F);
-  auto kern = is_bf16 ? k_dw_f2v<true, true> : k_dw_f2v<false, true>;
+  p.dz = dz; p.row_ptr = row_ptr; p.partial = partial; p.want_dalpha = dalpha != nullptr; p.lpg = 16;
+  const int grid = sep_grid(F, SEP_GRID_BWD);
+  const bool vec = sep_vec_ok(C, is_bf16, h, dz, dh);
+  auto kern = is_bf16 ? (vec ? k_dw_f2v<true, true, true> : k_dw_f2v<true, true, false>)
+                      : (vec ? k_dw_f2v<false, true, true> : k_dw_f2v<false, true, false>);
   if (F == 0) {
     if (dalpha) return pm_launch_sum_slices(partial, (int64_t)K * C, 0, dalpha, st);   // no slices: zeros
     return PM_OK;
   }
   // dh needs the whole filter value: it comes from the dalpha launch when that covers every k (K <= SEP_KC),
-  // else from a launch of its own without dalpha accumulators
+  // else from a launch of its own without dalpha tiles
   const bool fused = dalpha && K <= SEP_KC;
   if (dh && !fused) {
     p.kc0 = 0; p.want_dalpha = 0; p.y = dh;
-    const size_t lds = sep_lds_bytes(K, C, is_bf16, p.lpg);
+    const size_t lds = sep_lds_bytes(K, true);
     PM_CHECK_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
     { ProfScope ps__(st, "k_dw_f2v_bwd");
       hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(256), lds, st, p); }
@@ -292,13 +338,13 @@ pm_status pm_launch_dw_f2v_bwd(int64_t F, int K, int C, int is_bf16, const Basis
     for (int k0 = 0; k0 < K; k0 += SEP_KC) {
       p.kc0 = k0;
       const int kn = K - k0 < SEP_KC ? K - k0 : SEP_KC;
-      const size_t lds = sep_lds_bytes(kn, C, is_bf16, p.lpg);
+      const size_t lds = sep_lds_bytes(kn, true);
       PM_CHECK_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
       { ProfScope ps__(st, "k_dw_f2v_bwd");
         hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(256), lds, st, p); }
       PM_CHECK_LAUNCH("k_dw_f2v_bwd");
     }
-    return pm_launch_sum_slices(partial, (int64_t)K * C, grid * (256 / p.lpg), dalpha, st);
+    return pm_launch_sum_slices(partial, (int64_t)K * C, grid, dalpha, st);
   }
   return PM_OK;
 }
@@ -306,20 +352,30 @@ pm_status pm_launch_dw_f2v_bwd(int64_t F, int K, int C, int is_bf16, const Basis
 // ---- separable vertex2facet, backward to the vertex features.  With T_f = dg_f P^T (one row per facet),
 //   dh_v[c] = sum over the adjacency entries (f, j) of v of  s_j[c] T_f[c],     s_j[c] = sum_k fc[j][k] alpha[k][c]
 // (fc[j][k] is the SH basis at the barycentric corner j, Eq. 6).  A group of lanes owns a vertex, each lane a
-// run of channels whose three scales it keeps in registers; entries are taken two at a time in ascending
-// order, the corner chosen by selects.
+// run of channels whose three scales (from a small table built first) it keeps in registers; entries are
+// taken two at a time in ascending order into per-corner sums (the corner chosen by selects), which are
+// scaled and added at the end.
 struct SlotP {
   int64_t V;
-  int K, C, lpg, out_bf16;
+  int C, lpg, out_bf16;
   const void* T;            // [F][C] feature dtype
   const int32_t* row_ptr;   // [V+1]
   const int32_t* col;       // entries 3f + j
-  const float* alpha;       // [K][C]
-  FoldCoef fc;
+  const float* sc;          // [3][C] corner scales s_j[c]
   void* out;                // [V][C]
 };
 
-template <bool BF16>
+__global__ void __launch_bounds__(256) k_sep_slot_scales(int K, int C, const float* __restrict__ alpha, FoldCoef fc,
+                                                         float* __restrict__ sc) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i >= 3 * C) return;
+  const int j = i / C, c = i - j * C;
+  float a = 0.f;
+  for (int k = 0; k < K; ++k) a += fc.c[j][k] * alpha[(int64_t)k * C + c];
+  sc[i] = a;
+}
+
+template <bool BF16, bool VEC>
 __global__ void __launch_bounds__(256) k_slot_scale_sum(SlotP p) {
   constexpr int CPL = BF16 ? 8 : 4;
   const int gpb = 256 / p.lpg;
@@ -327,21 +383,14 @@ __global__ void __launch_bounds__(256) k_slot_scale_sum(SlotP p) {
   for (int c0 = sub * CPL; c0 < p.C; c0 += p.lpg * CPL) {
     float sc[3][CPL];
 #pragma unroll
-    for (int j = 0; j < 3; ++j)
-#pragma unroll
-      for (int i = 0; i < CPL; ++i) sc[j][i] = 0.f;
-    for (int k = 0; k < p.K; ++k)
-#pragma unroll
-      for (int i = 0; i < CPL; ++i) {
-        const float a = (c0 + i < p.C) ? p.alpha[(int64_t)k * p.C + c0 + i] : 0.f;
-#pragma unroll
-        for (int j = 0; j < 3; ++j) sc[j][i] += p.fc.c[j][k] * a;
-      }
+    for (int j = 0; j < 3; ++j) sep_load_f32<CPL, VEC>(p.sc, (int64_t)j * p.C, p.C, c0, sc[j]);
     for (int64_t seg = (int64_t)blockIdx.x * gpb + threadIdx.x / p.lpg; seg < p.V; seg += (int64_t)gridDim.x * gpb) {
       const int32_t b = p.row_ptr[seg], e = p.row_ptr[seg + 1];
-      float acc[CPL];
+      float a3[3][CPL];                      // per-corner sums; the scales are applied once at the end
 #pragma unroll
-      for (int i = 0; i < CPL; ++i) acc[i] = 0.f;
+      for (int j = 0; j < 3; ++j)
+#pragma unroll
+        for (int i = 0; i < CPL; ++i) a3[j][i] = 0.f;
       for (int32_t i0 = b; i0 < e; i0 += 2) {
         int32_t cidx[2], row[2];
         float x[2][CPL];
@@ -351,43 +400,46 @@ __global__ void __launch_bounds__(256) k_slot_scale_sum(SlotP p) {
           row[q] = (int32_t)(((uint64_t)(uint32_t)cidx[q] * 0xAAAAAAABull) >> 33);   // / 3
         }
 #pragma unroll
-        for (int q = 0; q < 2; ++q) sep_load<BF16>(p.T, (int64_t)row[q] * p.C, p.C, c0, x[q]);
+        for (int q = 0; q < 2; ++q) sep_load<BF16, CPL, VEC>(p.T, (int64_t)row[q] * p.C, p.C, c0, x[q]);
 #pragma unroll
         for (int q = 0; q < 2; ++q) {
-          const int slot = cidx[q] - 3 * row[q];
-          const bool live = i0 + q < e;
+          const int slot = (i0 + q < e) ? cidx[q] - 3 * row[q] : 3;
 #pragma unroll
-          for (int i = 0; i < CPL; ++i) {
-            const float w = slot == 0 ? sc[0][i] : (slot == 1 ? sc[1][i] : sc[2][i]);
-            acc[i] += live ? w * x[q][i] : 0.f;
-          }
+          for (int j = 0; j < 3; ++j)
+#pragma unroll
+            for (int i = 0; i < CPL; ++i) a3[j][i] += (slot == j) ? x[q][i] : 0.f;
         }
       }
-      if (p.out_bf16) {
-        if constexpr (BF16) sep_store<true>(p.out, seg * p.C, p.C, c0, acc);
-      } else {
-        if constexpr (!BF16) sep_store<false>(p.out, seg * p.C, p.C, c0, acc);
-      }
+      float acc[CPL];
+#pragma unroll
+      for (int i = 0; i < CPL; ++i) acc[i] = sc[0][i] * a3[0][i] + sc[1][i] * a3[1][i] + sc[2][i] * a3[2][i];
+      sep_store<BF16, CPL, VEC>(p.out, seg * p.C, p.C, c0, acc);
     }
   }
 }
 
+// `sc` is a scratch table of 3 * C floats
 pm_status pm_launch_slot_scale_sum(int64_t V, int K, int C, int is_bf16, const void* T, const int32_t* row_ptr,
-                                   const int32_t* col, const float* alpha, const FoldCoef* fc, void* out, hipStream_t st) {
+                                   const int32_t* col, const float* alpha, const FoldCoef* fc, float* sc, void* out,
+                                   hipStream_t st) {
   if (V == 0) return PM_OK;
+  { ProfScope ps__(st, "k_sep_slot_scales");
+    hipLaunchKernelGGL(k_sep_slot_scales, dim3((unsigned)((3 * C + 255) / 256)), dim3(256), 0, st, K, C, alpha, *fc, sc); }
+  PM_CHECK_LAUNCH("k_sep_slot_scales");
   SlotP p;
-  p.V = V; p.K = K; p.C = C; p.out_bf16 = is_bf16; p.T = T; p.row_ptr = row_ptr; p.col = col; p.alpha = alpha;
-  p.fc = *fc; p.out = out;
+  p.V = V; p.C = C; p.out_bf16 = is_bf16; p.T = T; p.row_ptr = row_ptr; p.col = col; p.sc = sc; p.out = out;
   const int cpl = is_bf16 ? 8 : 4;
   int need = (C + cpl - 1) / cpl, l = 1;
   while (l < need && l < 64) l <<= 1;
   p.lpg = l;
   const int gpb = 256 / l;
   int64_t nblk = (V + gpb - 1) / gpb;
-  if (nblk > 8192) nblk = 8192;
+  if (nblk > 0x7fffffff) nblk = 0x7fffffff;
   { ProfScope ps__(st, "k_slot_scale_sum");
-    if (is_bf16) hipLaunchKernelGGL(k_slot_scale_sum<true>, dim3((unsigned)nblk), dim3(256), 0, st, p);
-    else hipLaunchKernelGGL(k_slot_scale_sum<false>, dim3((unsigned)nblk), dim3(256), 0, st, p); }
+    const bool vec = sep_vec_ok(C, is_bf16, T, out, sc);
+    auto kern = is_bf16 ? (vec ? k_slot_scale_sum<true, true> : k_slot_scale_sum<true, false>)
+                        : (vec ? k_slot_scale_sum<false, true> : k_slot_scale_sum<false, false>);
+    hipLaunchKernelGGL(kern, dim3((unsigned)nblk), dim3(256), 0, st, p); }
   PM_CHECK_LAUNCH("k_slot_scale_sum");
   return PM_OK;
 }
