@@ -173,6 +173,44 @@ def cluster_grid_2x2(v: np.ndarray, nx: int, ny: int) -> Tuple[np.ndarray, np.nd
     return vc.reshape(-1, 3).astype(np.float32), np.ascontiguousarray(g.astype(np.int32)), cx, cy
 
 
+def grid_cluster_maps(nx: int, ny: int) -> Tuple[np.ndarray, np.ndarray]:
+    """(VCluster, IOmap) of `cluster_grid_2x2`: the representative of a 2x2 block is its vertex with even
+    grid coordinates, and it maps to the block's index in the coarse grid; every other IOmap entry is -1."""
+    assert nx % 2 == 0 and ny % 2 == 0
+    cy = ny // 2
+    i = np.arange(nx)[:, None]
+    j = np.arange(ny)[None, :]
+    vcluster = ((i // 2 * 2) * ny + (j // 2 * 2)).ravel().astype(np.int32)
+    iomap = np.full(nx * ny, -1, np.int32)
+    rep = np.unique(vcluster)
+    iomap[rep] = ((rep // ny) // 2 * cy + (rep % ny) // 2).astype(np.int32)
+    return vcluster, iomap
+
+
+def random_cluster_maps(rng: np.random.Generator, n_in: int, n_out: int, drop_frac: float = 0.0,
+                        heavy: int = 0) -> Tuple[np.ndarray, np.ndarray]:
+    """(VCluster, IOmap) of a random clustering shaped like an edge-contraction decimation: `n_out` distinct
+    representatives in random output order, every other vertex joins a random one; `heavy` extra vertices all
+    join the first representative (one long cluster); a fraction of the vertices joins a dead representative
+    whose IOmap is -1 (they reach no output vertex)."""
+    assert 0 < n_out <= n_in
+    perm = rng.permutation(n_in)
+    rep = perm[:n_out]
+    dead = perm[n_out] if n_out < n_in else -1
+    vcluster = np.empty(n_in, np.int32)
+    vcluster[rep] = rep
+    rest = perm[n_out:]
+    vcluster[rest] = rep[rng.integers(0, n_out, rest.size)]
+    vcluster[rest[:min(heavy, rest.size)]] = rep[0]
+    if dead >= 0 and drop_frac > 0:
+        d = rest[rng.random(rest.size) < drop_frac]
+        vcluster[d] = dead
+        vcluster[dead] = dead
+    iomap = np.full(n_in, -1, np.int32)
+    iomap[rep] = rng.permutation(n_out).astype(np.int32)
+    return vcluster, iomap
+
+
 # --------------------------------------------------------------------------------------
 # batching
 # --------------------------------------------------------------------------------------
