@@ -9,7 +9,7 @@
  *   - Plain C linkage.  Every pointer is a DEVICE pointer unless the comment says HOST; all are
  *     borrowed (never freed or retained).  `stream` is a hipStream_t passed as void* (NULL = the
  *     default stream).  All work is enqueued on that stream; no entry point allocates device memory
- *     and only pm_validate_mesh synchronises with the host.
+ *     and only pm_validate_mesh and pm_validate_clusters synchronise with the host.
  *   - Arrays are row-major and contiguous.  Base pointers of feature, weight, output and workspace
  *     arrays must be 16-byte aligned (checked -> PM_ERR_INVALID_ARG).
  *   - Meshes come as one packed heterogeneous batch ("Heterogeneous Batching" subsection): vertex
@@ -155,6 +155,50 @@ pm_status pm_v2f_sep(const pm_mesh* mesh, int L, pm_sh_norm norm, int cin, int c
 pm_status pm_v2f_sep_bwd(const pm_mesh* mesh, const pm_vf_adj* adj, int L, pm_sh_norm norm, int cin, int cout,
                          pm_dtype dtype, const void* h_vert, const float* alpha, const void* P, const void* dg_facet,
                          void* dh_vert, float* dalpha, float* dP, void* ws, size_t ws_bytes, void* stream);
+
+/* ---- Mesh pooling / unpooling (Section "Mesh decimation", paragraph "(Un)poolings") --------------------
+ * A decimation hands over two int32 vectors of the INPUT mesh's vertex count n_in: VCluster and IOmap.
+ * Encoding taken here (the paper gives none): vcluster[v] = input-mesh index of the representative vertex of
+ * v's cluster; iomap[u] = output-mesh index (0 <= . < n_out) of input vertex u when it is a representative,
+ * else -1.  The output vertex of v is target[v] = iomap[vcluster[v]]; -1 = v reaches no output vertex.
+ * Features are rows [n_in][C] (input mesh) and [n_out][C] (output mesh) of `dtype`, C >= 1.
+ *
+ * pm_build_cluster_map fills the three arrays every pooling call reads: target [n_in], row_ptr [n_out+1] and
+ * col [n_in] (the members of each output vertex, ascending; the first row_ptr[n_out] entries are used).
+ * An id outside its range is treated as -1, never dereferenced.  ws: pm_cluster_ws_bytes(n_in, n_out).
+ * pm_validate_clusters counts such ids and returns PM_ERR_BAD_MESH if there are any (synchronises;
+ * ws >= pm_cluster_ws_bytes(n_in, n_out)).  A pm_cluster_map not made by pm_build_cluster_map is undefined
+ * behaviour in the calls below. */
+typedef struct pm_cluster_map {
+  int64_t n_in, n_out;
+  const int32_t* target;  /* [n_in]    */
+  const int32_t* row_ptr; /* [n_out+1] */
+  const int32_t* col;     /* [n_in]    */
+} pm_cluster_map;
+typedef enum { PM_POOL_MAX = 0, PM_POOL_AVG = 1 } pm_pool_mode;
+
+size_t pm_cluster_ws_bytes(int64_t n_in, int64_t n_out); /* HOST computation; 0 on invalid sizes */
+pm_status pm_validate_clusters(int64_t n_in, int64_t n_out, const int32_t* vcluster, const int32_t* iomap, void* ws,
+                               size_t ws_bytes, void* stream);
+pm_status pm_build_cluster_map(int64_t n_in, int64_t n_out, const int32_t* vcluster, const int32_t* iomap,
+                               int32_t* target, int32_t* row_ptr, int32_t* col, void* ws, size_t ws_bytes,
+                               void* stream);
+
+/* h_out[o] = max / average of h_in[v] over the members v of o; an output vertex without members gets 0.
+ * PM_POOL_MAX: argmax (int32 [n_out][C], may be NULL) receives the input vertex each maximum came from
+ * (ties: the lowest index; -1 for no members); NaN features are not supported.  Averages accumulate in fp32
+ * in ascending member order. */
+pm_status pm_pool(const pm_cluster_map* cm, pm_pool_mode mode, int C, pm_dtype dtype, const void* h_in, void* h_out,
+                  int32_t* argmax, void* stream);
+/* dh_in [n_in][C]: average: dg_out[target[v]] / |cluster|; maximum: dg_out[t][c] where argmax[t][c] == v, else 0
+ * (argmax from pm_pool, required for PM_POOL_MAX, ignored for PM_POOL_AVG).  Rows with no output vertex are 0. */
+pm_status pm_pool_bwd(const pm_cluster_map* cm, pm_pool_mode mode, int C, pm_dtype dtype, const void* dg_out,
+                      const int32_t* argmax, void* dh_in, void* stream);
+/* h_fine[v] = h_coarse[target[v]] (0 where there is none): every member replicates its output vertex. */
+pm_status pm_unpool(const pm_cluster_map* cm, int C, pm_dtype dtype, const void* h_coarse, void* h_fine, void* stream);
+/* dh_coarse[o] = sum of dg_fine[v] over the members of o, ascending, fp32 accumulation. */
+pm_status pm_unpool_bwd(const pm_cluster_map* cm, int C, pm_dtype dtype, const void* dg_fine, void* dh_coarse,
+                        void* stream);
 
 /* Measurement aid (not part of the method): per-kernel timing with HIP events.
  * After pm_profile_enable(1) every kernel this thread's calls launch is bracketed by a pair of events

@@ -27,6 +27,8 @@ EXPORTS = [
     "pm_sh_basis", "pm_sh_basis_dirs", "pm_sh_basis_bwd", "pm_f2v", "pm_f2v_bwd", "pm_v2f", "pm_v2f_bwd",
     "pm_f2f", "pm_f2f_bwd", "pm_profile_enable", "pm_profile_count", "pm_profile_read", "pm_profile_reset",
     "pm_peak_probe", "pm_f2v_sep", "pm_f2v_sep_bwd", "pm_v2f_sep", "pm_v2f_sep_bwd",
+    "pm_cluster_ws_bytes", "pm_validate_clusters", "pm_build_cluster_map", "pm_pool", "pm_pool_bwd", "pm_unpool",
+    "pm_unpool_bwd",
 ]
 
 
@@ -43,6 +45,11 @@ class _PmMesh(C.Structure):
 
 class _PmAdj(C.Structure):
     _fields_ = [("row_ptr", C.c_void_p), ("col", C.c_void_p)]
+
+
+class _PmClusterMap(C.Structure):
+    _fields_ = [("n_in", C.c_int64), ("n_out", C.c_int64), ("target", C.c_void_p), ("row_ptr", C.c_void_p),
+                ("col", C.c_void_p)]
 
 
 _lib = None
@@ -80,6 +87,15 @@ def lib():
             "pm_v2f_sep": [mp, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, sz, vp],
             "pm_v2f_sep_bwd": [mp, ap, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp],
         }
+        cp = C.POINTER(_PmClusterMap)
+        sig.update({"pm_validate_clusters": [i64, i64, vp, vp, vp, sz, vp],
+                    "pm_build_cluster_map": [i64, i64, vp, vp, vp, vp, vp, vp, sz, vp],
+                    "pm_pool": [cp, i32, i32, i32, vp, vp, vp, vp],
+                    "pm_pool_bwd": [cp, i32, i32, i32, vp, vp, vp, vp],
+                    "pm_unpool": [cp, i32, i32, vp, vp, vp],
+                    "pm_unpool_bwd": [cp, i32, i32, vp, vp, vp]})
+        l.pm_cluster_ws_bytes.restype = C.c_size_t
+        l.pm_cluster_ws_bytes.argtypes = [i64, i64]
         sig.update({"pm_profile_enable": [i32], "pm_profile_count": [], "pm_profile_reset": [],
                     "pm_profile_read": [i32, C.c_char_p, sz, C.POINTER(C.c_float)],
                     "pm_peak_probe": [i32, vp, sz, C.POINTER(C.c_double), C.POINTER(C.c_double), vp]})
@@ -369,6 +385,93 @@ def pm_v2f_sep_bwd(mesh: Mesh, adj: Adjacency, L: int, h_vert, alpha, P, dg_face
     _check(lib().pm_v2f_sep_bwd(C.byref(m), C.byref(a), L, norm, cin, cout, dtype, _ptr(h_vert), _ptr(alpha), _ptr(P),
                                 _ptr(dg_facet), _ptr(dh), _ptr(da), _ptr(dP), _ptr(ws), ws.numel(), _stream(stream)))
     return dh, da, dP
+
+
+# ---- pooling / unpooling over vertex clusters -------------------------------------------------------
+PM_POOL_MAX, PM_POOL_AVG = 0, 1
+
+
+@dataclass
+class ClusterMap:
+    n_in: int
+    n_out: int
+    target: torch.Tensor
+    row_ptr: torch.Tensor
+    col: torch.Tensor
+
+    def c(self) -> _PmClusterMap:
+        m = _PmClusterMap()
+        m.n_in, m.n_out = self.n_in, self.n_out
+        m.target = self.target.data_ptr() if self.n_in else None
+        m.row_ptr = self.row_ptr.data_ptr()
+        m.col = self.col.data_ptr() if self.n_in else None
+        return m
+
+
+def pm_cluster_ws_bytes(n_in: int, n_out: int) -> int:
+    return int(lib().pm_cluster_ws_bytes(n_in, n_out))
+
+
+def pm_validate_clusters(vcluster: torch.Tensor, iomap: torch.Tensor, n_out: int, stream=None) -> None:
+    n_in = vcluster.shape[0]
+    ws = alloc_workspace(pm_cluster_ws_bytes(n_in, n_out), vcluster.device)
+    _check(lib().pm_validate_clusters(n_in, n_out, _ptr(vcluster), _ptr(iomap), _ptr(ws), ws.numel(), _stream(stream)))
+
+
+def pm_build_cluster_map(vcluster: torch.Tensor, iomap: torch.Tensor, n_out: int, ws=None, stream=None) -> ClusterMap:
+    assert vcluster.dtype == torch.int32 and iomap.dtype == torch.int32 and vcluster.shape == iomap.shape
+    n_in, dev = vcluster.shape[0], vcluster.device
+    target = torch.empty(n_in, dtype=torch.int32, device=dev)
+    row_ptr = torch.empty(n_out + 1, dtype=torch.int32, device=dev)
+    col = torch.empty(n_in, dtype=torch.int32, device=dev)
+    if ws is None:
+        ws = alloc_workspace(pm_cluster_ws_bytes(n_in, n_out), dev)
+    _check(lib().pm_build_cluster_map(n_in, n_out, _ptr(vcluster), _ptr(iomap), C.c_void_p(target.data_ptr()),
+                                      _ptr(row_ptr), C.c_void_p(col.data_ptr()), _ptr(ws), ws.numel(), _stream(stream)))
+    return ClusterMap(n_in, n_out, target, row_ptr, col)
+
+
+def pm_pool(cm: ClusterMap, mode: int, h_in: torch.Tensor, dtype: int, want_argmax: bool = True, stream=None):
+    """(h_out [n_out, C], argmax [n_out, C] int32 or None)."""
+    Cc = h_in.shape[1]
+    assert h_in.dtype == torch_dtype(dtype) and h_in.shape[0] == cm.n_in
+    out = torch.empty((cm.n_out, Cc), dtype=h_in.dtype, device=h_in.device)
+    arg = torch.empty((cm.n_out, Cc), dtype=torch.int32, device=h_in.device) if (mode == PM_POOL_MAX and want_argmax) else None
+    m = cm.c()
+    _check(lib().pm_pool(C.byref(m), mode, Cc, dtype, C.c_void_p(h_in.data_ptr()), C.c_void_p(out.data_ptr()),
+                         C.c_void_p(arg.data_ptr()) if arg is not None else None, _stream(stream)))
+    return out, arg
+
+
+def pm_pool_bwd(cm: ClusterMap, mode: int, dg_out: torch.Tensor, dtype: int, argmax=None, stream=None) -> torch.Tensor:
+    Cc = dg_out.shape[1]
+    assert dg_out.dtype == torch_dtype(dtype) and dg_out.shape[0] == cm.n_out
+    out = torch.empty((cm.n_in, Cc), dtype=dg_out.dtype, device=dg_out.device)
+    m = cm.c()
+    _check(lib().pm_pool_bwd(C.byref(m), mode, Cc, dtype, C.c_void_p(dg_out.data_ptr()),
+                             C.c_void_p(argmax.data_ptr()) if argmax is not None else None,
+                             C.c_void_p(out.data_ptr()), _stream(stream)))
+    return out
+
+
+def pm_unpool(cm: ClusterMap, h_coarse: torch.Tensor, dtype: int, stream=None) -> torch.Tensor:
+    Cc = h_coarse.shape[1]
+    assert h_coarse.dtype == torch_dtype(dtype) and h_coarse.shape[0] == cm.n_out
+    out = torch.empty((cm.n_in, Cc), dtype=h_coarse.dtype, device=h_coarse.device)
+    m = cm.c()
+    _check(lib().pm_unpool(C.byref(m), Cc, dtype, C.c_void_p(h_coarse.data_ptr()), C.c_void_p(out.data_ptr()),
+                           _stream(stream)))
+    return out
+
+
+def pm_unpool_bwd(cm: ClusterMap, dg_fine: torch.Tensor, dtype: int, stream=None) -> torch.Tensor:
+    Cc = dg_fine.shape[1]
+    assert dg_fine.dtype == torch_dtype(dtype) and dg_fine.shape[0] == cm.n_in
+    out = torch.empty((cm.n_out, Cc), dtype=dg_fine.dtype, device=dg_fine.device)
+    m = cm.c()
+    _check(lib().pm_unpool_bwd(C.byref(m), Cc, dtype, C.c_void_p(dg_fine.data_ptr()), C.c_void_p(out.data_ptr()),
+                               _stream(stream)))
+    return out
 
 
 def pm_profile_enable(on: bool) -> None:

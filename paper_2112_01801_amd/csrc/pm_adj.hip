@@ -16,9 +16,10 @@ __global__ void k_fill_i32(int32_t* p, int64_t n, int32_t v) {
   if (i < n) p[i] = v;
 }
 
+// entries with a negative key belong to no row
 __global__ void k_count(int64_t n3, const int32_t* __restrict__ facet, int32_t* __restrict__ cnt) {
   int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (e < n3) atomicAdd(&cnt[facet[e]], 1);
+  if (e < n3 && facet[e] >= 0) atomicAdd(&cnt[facet[e]], 1);
 }
 
 // block-wide exclusive scan of SCAN_TILE items; returns the tile total through *total (thread 0)
@@ -92,7 +93,7 @@ __global__ void __launch_bounds__(SCAN_BLOCK) k_scan_apply(const int32_t* __rest
 __global__ void k_scatter(int64_t n3, const int32_t* __restrict__ facet, int32_t* __restrict__ cursor,
                           int32_t* __restrict__ tmp) {
   int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (e < n3) {
+  if (e < n3 && facet[e] >= 0) {
     int32_t pos = atomicAdd(&cursor[facet[e]], 1);
     tmp[pos] = (int32_t)e;
   }
@@ -144,13 +145,16 @@ __global__ void __launch_bounds__(256) k_sort_long(const int32_t* __restrict__ r
   }
 }
 
-size_t pm_adj_ws_bytes(int64_t n_vert, int64_t n_facet) {
+size_t pm_adj_ws_bytes(int64_t n_vert, int64_t n_facet) { return pm_csr_ws_bytes(n_vert, 3 * n_facet); }
+
+// workspace of pm_launch_csr: n_vert rows, n3 entries
+size_t pm_csr_ws_bytes(int64_t n_vert, int64_t n3) {
   int64_t n_tiles = (n_vert + SCAN_TILE - 1) / SCAN_TILE + 1;
   size_t b = 0;
   b += pm_round_up((size_t)(n_vert + 1) * 4, 256);  // cnt
   b += pm_round_up((size_t)(n_vert + 1) * 4, 256);  // cursor
   b += pm_round_up((size_t)n_tiles * 4, 256);       // tile sums
-  b += pm_round_up((size_t)(3 * n_facet + 1) * 4, 256);  // tmp
+  b += pm_round_up((size_t)(n3 + 1) * 4, 256);      // tmp
   b += pm_round_up((size_t)(n_vert + 1) * 4, 256);  // long rows
   b += 256;                                         // n_long
   return b;
@@ -158,8 +162,21 @@ size_t pm_adj_ws_bytes(int64_t n_vert, int64_t n_facet) {
 
 static inline unsigned nblk(int64_t n, int b) { return (unsigned)((n + b - 1) / b); }
 
+pm_status pm_launch_fill_i32(int32_t* p, int64_t n, int32_t v, hipStream_t st) {
+  if (n <= 0) return PM_OK;
+  { ProfScope ps__(st, "k_fill_i32");
+    hipLaunchKernelGGL(k_fill_i32, dim3(nblk(n, 256)), dim3(256), 0, st, p, n, v); }
+  PM_CHECK_LAUNCH("k_fill_i32");
+  return PM_OK;
+}
+
 pm_status pm_launch_adjacency(const pm_mesh* mesh, int32_t* row_ptr, int32_t* col, void* ws, hipStream_t st) {
-  const int64_t V = mesh->n_vert, F = mesh->n_facet, n3 = 3 * F;
+  return pm_launch_csr(mesh->n_vert, 3 * mesh->n_facet, mesh->facet, row_ptr, col, ws, st);
+}
+
+// CSR of the entries e = 0..n3-1 grouped by key[e] in [0, V) (negative keys are skipped), ascending inside a row
+pm_status pm_launch_csr(int64_t V, int64_t n3, const int32_t* keys, int32_t* row_ptr, int32_t* col, void* ws,
+                        hipStream_t st) {
   const int64_t n_tiles = (V + SCAN_TILE - 1) / SCAN_TILE;
   char* p = (char*)ws;
   int32_t* cnt = (int32_t*)p;      p += pm_round_up((size_t)(V + 1) * 4, 256);
@@ -179,7 +196,7 @@ pm_status pm_launch_adjacency(const pm_mesh* mesh, int32_t* row_ptr, int32_t* co
     PM_CHECK_LAUNCH("adjacency(empty)");
     return PM_OK;
   }
-  if (n3 > 0) hipLaunchKernelGGL(k_count, dim3(nblk(n3, 256)), dim3(256), 0, st, n3, mesh->facet, cnt);
+  if (n3 > 0) hipLaunchKernelGGL(k_count, dim3(nblk(n3, 256)), dim3(256), 0, st, n3, keys, cnt);
   { ProfScope ps__(st, "k_scan_tile_sums");
     hipLaunchKernelGGL(k_scan_tile_sums, dim3((unsigned)n_tiles), dim3(SCAN_BLOCK), 0, st, cnt, V, tsum); }
   { ProfScope ps__(st, "k_scan_sums");
@@ -188,7 +205,7 @@ pm_status pm_launch_adjacency(const pm_mesh* mesh, int32_t* row_ptr, int32_t* co
     hipLaunchKernelGGL(k_scan_apply, dim3((unsigned)n_tiles), dim3(SCAN_BLOCK), 0, st, cnt, V, tsum, row_ptr, cursor); }
   if (n3 > 0) {
     { ProfScope ps__(st, "k_scatter");
-      hipLaunchKernelGGL(k_scatter, dim3(nblk(n3, 256)), dim3(256), 0, st, n3, mesh->facet, cursor, tmp); }
+      hipLaunchKernelGGL(k_scatter, dim3(nblk(n3, 256)), dim3(256), 0, st, n3, keys, cursor, tmp); }
     { ProfScope ps__(st, "k_sort_short");
       hipLaunchKernelGGL(k_sort_short, dim3(nblk(V, 256)), dim3(256), 0, st, V, row_ptr, tmp, col, long_rows, n_long); }
     { ProfScope ps__(st, "k_sort_long");

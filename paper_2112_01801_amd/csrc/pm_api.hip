@@ -605,6 +605,111 @@ extern "C" pm_status pm_v2f_sep_bwd(const pm_mesh* mesh, const pm_vf_adj* adj, i
   return PM_OK;
 }
 
+// ---- pooling / unpooling over vertex clusters ------------------------------------------------------
+static pm_status check_cluster_sizes(int64_t n_in, int64_t n_out) {
+  if (n_in < 0 || n_out < 0 || n_in >= kMaxIds || n_out >= kMaxIds)
+    return pm_fail(PM_ERR_INVALID_ARG, "n_in=%lld n_out=%lld", (long long)n_in, (long long)n_out);
+  return PM_OK;
+}
+
+extern "C" size_t pm_cluster_ws_bytes(int64_t n_in, int64_t n_out) {
+  if (check_cluster_sizes(n_in, n_out) != PM_OK) return 0;
+  return 256 + pm_round_up((size_t)(n_in + 1) * 4, 256) + pm_csr_ws_bytes(n_out, n_in);
+}
+
+static pm_status check_cluster_args(int64_t n_in, int64_t n_out, const int32_t* vcluster, const int32_t* iomap,
+                                    void* ws, size_t ws_bytes) {
+  PM_TRY(check_cluster_sizes(n_in, n_out));
+  if (n_in > 0 && (!vcluster || !iomap)) return pm_fail(PM_ERR_INVALID_ARG, "vcluster / iomap is NULL");
+  PM_TRY(check_ptr(ws, "ws", true));
+  if (ws_bytes < pm_cluster_ws_bytes(n_in, n_out))
+    return pm_fail(PM_ERR_WORKSPACE, "workspace %zu < required %zu bytes", ws_bytes, pm_cluster_ws_bytes(n_in, n_out));
+  return PM_OK;
+}
+
+extern "C" pm_status pm_validate_clusters(int64_t n_in, int64_t n_out, const int32_t* vcluster, const int32_t* iomap,
+                                          void* ws, size_t ws_bytes, void* stream) {
+  pm_prof_set_op("validate_clusters");
+  PM_TRY(check_cluster_args(n_in, n_out, vcluster, iomap, ws, ws_bytes));
+  hipStream_t st = (hipStream_t)stream;
+  int32_t* bad = (int32_t*)ws;
+  int32_t* target = (int32_t*)((char*)ws + 256);
+  PM_TRY(pm_launch_fill_i32(bad, 1, 0, st));
+  PM_TRY(pm_launch_cluster_target(n_in, n_out, vcluster, iomap, target, bad, st));
+  int32_t n_bad = 0;
+  PM_CHECK_HIP(hipMemcpyAsync(&n_bad, bad, sizeof(n_bad), hipMemcpyDeviceToHost, st));
+  PM_CHECK_HIP(hipStreamSynchronize(st));
+  if (n_bad) return pm_fail(PM_ERR_BAD_MESH, "%d cluster / map ids are out of range", (int)n_bad);
+  return PM_OK;
+}
+
+extern "C" pm_status pm_build_cluster_map(int64_t n_in, int64_t n_out, const int32_t* vcluster, const int32_t* iomap,
+                                          int32_t* target, int32_t* row_ptr, int32_t* col, void* ws, size_t ws_bytes,
+                                          void* stream) {
+  pm_prof_set_op("cluster_map");
+  PM_TRY(check_cluster_args(n_in, n_out, vcluster, iomap, ws, ws_bytes));
+  if (!row_ptr || (n_in > 0 && (!target || !col))) return pm_fail(PM_ERR_INVALID_ARG, "target / row_ptr / col is NULL");
+  hipStream_t st = (hipStream_t)stream;
+  PM_TRY(pm_launch_cluster_target(n_in, n_out, vcluster, iomap, target, nullptr, st));
+  return pm_launch_csr(n_out, n_in, target, row_ptr, col, (char*)ws + 256 + pm_round_up((size_t)(n_in + 1) * 4, 256), st);
+}
+
+static pm_status check_pool(const pm_cluster_map* cm, int C, pm_dtype dtype, bool need_csr) {
+  if (!cm) return pm_fail(PM_ERR_INVALID_ARG, "cluster map is NULL");
+  PM_TRY(check_cluster_sizes(cm->n_in, cm->n_out));
+  if (dtype != PM_F32 && dtype != PM_BF16) return pm_fail(PM_ERR_UNSUPPORTED, "unknown pm_dtype %d", (int)dtype);
+  if (C < 1 || C > 65536) return pm_fail(PM_ERR_INVALID_ARG, "C=%d", C);
+  if (cm->n_in > 0 && !cm->target) return pm_fail(PM_ERR_INVALID_ARG, "cluster map target is NULL");
+  if (need_csr && (!cm->row_ptr || (cm->n_in > 0 && !cm->col))) return pm_fail(PM_ERR_INVALID_ARG, "cluster map CSR is NULL");
+  return PM_OK;
+}
+
+extern "C" pm_status pm_pool(const pm_cluster_map* cm, pm_pool_mode mode, int C, pm_dtype dtype, const void* h_in,
+                             void* h_out, int32_t* argmax, void* stream) {
+  pm_prof_set_op("pool");
+  PM_TRY(check_pool(cm, C, dtype, true));
+  if (mode != PM_POOL_MAX && mode != PM_POOL_AVG) return pm_fail(PM_ERR_UNSUPPORTED, "unknown pm_pool_mode %d", (int)mode);
+  PM_TRY(check_ptr(h_in, "h_in", cm->n_in > 0));
+  PM_TRY(check_ptr(h_out, "h_out", cm->n_out > 0));
+  const int fb = dtype == PM_BF16;
+  hipStream_t st = (hipStream_t)stream;
+  if (mode == PM_POOL_AVG)
+    return pm_launch_segreduce(cm->n_out, C, h_in, fb, cm->row_ptr, cm->col, 1, 1, h_out, fb, st);
+  return pm_launch_segmax(cm->n_out, C, fb, h_in, cm->row_ptr, cm->col, h_out, argmax, st);
+}
+
+extern "C" pm_status pm_pool_bwd(const pm_cluster_map* cm, pm_pool_mode mode, int C, pm_dtype dtype,
+                                 const void* dg_out, const int32_t* argmax, void* dh_in, void* stream) {
+  pm_prof_set_op("pool_bwd");
+  PM_TRY(check_pool(cm, C, dtype, mode == PM_POOL_AVG));
+  if (mode != PM_POOL_MAX && mode != PM_POOL_AVG) return pm_fail(PM_ERR_UNSUPPORTED, "unknown pm_pool_mode %d", (int)mode);
+  PM_TRY(check_ptr(dg_out, "dg_out", cm->n_out > 0));
+  PM_TRY(check_ptr(dh_in, "dh_in", cm->n_in > 0));
+  if (mode == PM_POOL_MAX && cm->n_out > 0 && !argmax) return pm_fail(PM_ERR_INVALID_ARG, "max pooling backward needs argmax");
+  return pm_launch_cluster_gather(mode == PM_POOL_AVG ? 1 : 2, cm->n_in, C, dtype == PM_BF16, cm->target, cm->row_ptr,
+                                  argmax, dg_out, dh_in, (hipStream_t)stream);
+}
+
+extern "C" pm_status pm_unpool(const pm_cluster_map* cm, int C, pm_dtype dtype, const void* h_coarse, void* h_fine,
+                               void* stream) {
+  pm_prof_set_op("unpool");
+  PM_TRY(check_pool(cm, C, dtype, false));
+  PM_TRY(check_ptr(h_coarse, "h_coarse", cm->n_out > 0));
+  PM_TRY(check_ptr(h_fine, "h_fine", cm->n_in > 0));
+  return pm_launch_cluster_gather(0, cm->n_in, C, dtype == PM_BF16, cm->target, nullptr, nullptr, h_coarse, h_fine,
+                                  (hipStream_t)stream);
+}
+
+extern "C" pm_status pm_unpool_bwd(const pm_cluster_map* cm, int C, pm_dtype dtype, const void* dg_fine,
+                                   void* dh_coarse, void* stream) {
+  pm_prof_set_op("unpool_bwd");
+  PM_TRY(check_pool(cm, C, dtype, true));
+  PM_TRY(check_ptr(dg_fine, "dg_fine", cm->n_in > 0));
+  PM_TRY(check_ptr(dh_coarse, "dh_coarse", cm->n_out > 0));
+  const int fb = dtype == PM_BF16;
+  return pm_launch_segreduce(cm->n_out, C, dg_fine, fb, cm->row_ptr, cm->col, 1, 0, dh_coarse, fb, (hipStream_t)stream);
+}
+
 // ---- facet2facet (Eq. 7) -------------------------------------------------------------------------
 static pm_status check_f2f(int64_t n_facet, int64_t n_tex, const int32_t* tex_off, const float* bary) {
   if (n_facet < 0 || n_tex < 0 || n_facet >= kMaxIds || n_tex >= kMaxIds)

@@ -153,5 +153,17 @@ pm_status pm_launch_basis_bwd(int64_t n, const float* dirs, const ShTable& T, co
                               hipStream_t st);
 
 size_t pm_adj_ws_bytes(int64_t n_vert, int64_t n_facet);
+size_t pm_csr_ws_bytes(int64_t n_rows, int64_t n_entries);
+pm_status pm_launch_fill_i32(int32_t* p, int64_t n, int32_t v, hipStream_t st);
+pm_status pm_launch_csr(int64_t n_rows, int64_t n_entries, const int32_t* keys, int32_t* row_ptr, int32_t* col, void* ws,
+                        hipStream_t st);
+// pooling over vertex clusters
+pm_status pm_launch_cluster_target(int64_t n_in, int64_t n_out, const int32_t* vcluster, const int32_t* iomap,
+                                   int32_t* target, int32_t* bad, hipStream_t st);
+pm_status pm_launch_segmax(int64_t n_out, int C, int is_bf16, const void* h_in, const int32_t* row_ptr,
+                           const int32_t* col, void* h_out, int32_t* argmax, hipStream_t st);
+pm_status pm_launch_cluster_gather(int mode, int64_t n_in, int C, int is_bf16, const int32_t* target,
+                                   const int32_t* row_ptr, const int32_t* argmax, const void* src, void* out,
+                                   hipStream_t st);
 pm_status pm_launch_adjacency(const pm_mesh* mesh, int32_t* row_ptr, int32_t* col, void* ws, hipStream_t st);
 pm_status pm_launch_validate(const pm_mesh* mesh, int32_t* flag, hipStream_t st);

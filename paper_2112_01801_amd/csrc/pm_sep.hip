@@ -10,6 +10,7 @@
 // are added in a fixed order.
 // The tail of the file holds the small fold/unfold kernels of the separable vertex2facet form (Eq. 6).
 #include "pm_rows.h"
+#include "pm_chan.h"
 
 #define SEP_KC 16      /* basis functions per pass of the backward kernel (rows of one matrix-core tile) */
 
@@ -27,79 +28,6 @@ struct SepP {
   int kc0;                // bwd: first k of this pass
   int want_dalpha;
 };
-
-// CPL consecutive channels of one row, as fp32.  VEC: one 8- or 16-byte access (the caller has checked that
-// every run is whole and aligned); else element by element, channels past C read as zero / are not written.
-template <bool BF16, int CPL, bool VEC>
-__device__ __forceinline__ void sep_load(const void* base, int64_t off, int C, int c0, float (&v)[CPL]) {
-  static_assert((BF16 && (CPL == 8 || CPL == 4)) || (!BF16 && CPL == 4), "run width");
-  if constexpr (VEC) {
-    if constexpr (BF16 && CPL == 8) {
-      const uint4 u = *(const uint4*)((const uint16_t*)base + off + c0);
-      v[0] = bf16lo_to_f32(u.x); v[1] = bf16hi_to_f32(u.x); v[2] = bf16lo_to_f32(u.y); v[3] = bf16hi_to_f32(u.y);
-      v[4] = bf16lo_to_f32(u.z); v[5] = bf16hi_to_f32(u.z); v[6] = bf16lo_to_f32(u.w); v[7] = bf16hi_to_f32(u.w);
-    } else if constexpr (BF16) {
-      const uint2 u = *(const uint2*)((const uint16_t*)base + off + c0);
-      v[0] = bf16lo_to_f32(u.x); v[1] = bf16hi_to_f32(u.x); v[2] = bf16lo_to_f32(u.y); v[3] = bf16hi_to_f32(u.y);
-    } else {
-      const float4 f = *(const float4*)((const float*)base + off + c0);
-      v[0] = f.x; v[1] = f.y; v[2] = f.z; v[3] = f.w;
-    }
-  } else {
-#pragma unroll
-    for (int i = 0; i < CPL; ++i) {
-      float t = 0.f;
-      if (c0 + i < C) t = BF16 ? bf16_to_f32(((const uint16_t*)base)[off + c0 + i]) : ((const float*)base)[off + c0 + i];
-      v[i] = t;
-    }
-  }
-}
-
-// CPL fp32 values of one row (the vertex rows dz and the corner scales stay fp32 in both feature dtypes)
-template <int CPL, bool VEC>
-__device__ __forceinline__ void sep_load_f32(const float* base, int64_t off, int C, int c0, float (&v)[CPL]) {
-  if constexpr (VEC) {
-#pragma unroll
-    for (int q = 0; q < CPL / 4; ++q) {
-      const float4 f = *(const float4*)(base + off + c0 + 4 * q);
-      v[4 * q] = f.x; v[4 * q + 1] = f.y; v[4 * q + 2] = f.z; v[4 * q + 3] = f.w;
-    }
-  } else {
-#pragma unroll
-    for (int i = 0; i < CPL; ++i) v[i] = (c0 + i < C) ? base[off + c0 + i] : 0.f;
-  }
-}
-
-template <bool BF16, int CPL, bool VEC>
-__device__ __forceinline__ void sep_store(void* base, int64_t off, int C, int c0, const float (&v)[CPL]) {
-  if constexpr (VEC) {
-    if constexpr (BF16 && CPL == 8) {
-      uint4 u;
-      u.x = pack_bf16x2(v[0], v[1]); u.y = pack_bf16x2(v[2], v[3]);
-      u.z = pack_bf16x2(v[4], v[5]); u.w = pack_bf16x2(v[6], v[7]);
-      *(uint4*)((uint16_t*)base + off + c0) = u;
-    } else if constexpr (BF16) {
-      uint2 u;
-      u.x = pack_bf16x2(v[0], v[1]); u.y = pack_bf16x2(v[2], v[3]);
-      *(uint2*)((uint16_t*)base + off + c0) = u;
-    } else {
-      *(float4*)((float*)base + off + c0) = make_float4(v[0], v[1], v[2], v[3]);
-    }
-  } else {
-#pragma unroll
-    for (int i = 0; i < CPL; ++i)
-      if (c0 + i < C) {
-        if (BF16) ((uint16_t*)base)[off + c0 + i] = (uint16_t)f32_to_bf16_bits(v[i]);
-        else ((float*)base)[off + c0 + i] = v[i];
-      }
-  }
-}
-
-// whole, 16-byte aligned channel runs: C a multiple of 8 (bf16) or 4 (fp32) and aligned bases
-static bool sep_vec_ok(int C, int is_bf16, const void* a, const void* b, const void* c) {
-  auto al = [](const void* q) { return (((uintptr_t)q) & 15) == 0; };
-  return C % (is_bf16 ? 8 : 4) == 0 && al(a) && al(b) && al(c);
-}
 
 // Lane layout (fixed): a wave holds 4 row groups of 16 lanes, lane `sub` of a group owns channels
 // 4 sub .. 4 sub + 3 of a run of 64 channels, and each group handles four consecutive rows per sub-step, so a
@@ -184,14 +112,14 @@ __global__ void __launch_bounds__(256) k_dw_f2v(SepP p) {
             for (int i = 0; i < CPL; ++i) dyv[q][i] = 0.f;
           }
           if (VEC || ok[q]) {
-            sep_load<BF16, CPL, VEC>(p.h, rl * p.C, p.C, cl, hv[q]);
+            chan_load<BF16, CPL, VEC>(p.h, rl * p.C, p.C, cl, hv[q]);
             if constexpr (BWD) {
 #pragma unroll
               for (int j = 0; j < 3; ++j) {
                 const int32_t v = p.bs.facet[3 * rl + j];
                 const float w = 1.0f / (float)(p.row_ptr[v + 1] - p.row_ptr[v]);
                 float t[CPL];
-                sep_load_f32<CPL, VEC>(p.dz, (int64_t)v * p.C, p.C, cl, t);
+                chan_load_f32<CPL, VEC>(p.dz, (int64_t)v * p.C, p.C, cl, t);
 #pragma unroll
                 for (int i = 0; i < CPL; ++i) dyv[q][i] += t[i] * w;
               }
@@ -239,7 +167,7 @@ __global__ void __launch_bounds__(256) k_dw_f2v(SepP p) {
             float o[CPL];
 #pragma unroll
             for (int t = 0; t < 4; ++t) o[t] = (BWD ? dyv[q][t] : hv[q][t]) * S[t][q];
-            if (ok[q]) sep_store<BF16, CPL, VEC>(p.y, (rb + q) * p.C, p.C, c0, o);
+            if (ok[q]) chan_store<BF16, CPL, VEC>(p.y, (rb + q) * p.C, p.C, c0, o);
           }
         }
       }
@@ -296,7 +224,7 @@ pm_status pm_launch_dw_f2v(int64_t F, int K, int C, int is_bf16, const BasisSrc&
   p.dz = nullptr; p.row_ptr = nullptr; p.partial = nullptr; p.kc0 = 0; p.want_dalpha = 0; p.lpg = 16;
   const int grid = sep_grid(F, SEP_GRID_FWD);
   const size_t lds = sep_lds_bytes(K, false);
-  const bool vec = sep_vec_ok(C, is_bf16, h, y, nullptr);
+  const bool vec = chan_vec_ok(C, is_bf16, h, y, nullptr);
   auto kern = is_bf16 ? (vec ? k_dw_f2v<true, false, true> : k_dw_f2v<true, false, false>)
                       : (vec ? k_dw_f2v<false, false, true> : k_dw_f2v<false, false, false>);
   PM_CHECK_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
@@ -314,7 +242,7 @@ pm_status pm_launch_dw_f2v_bwd(int64_t F, int K, int C, int is_bf16, const Basis
   p.F = F; p.K = K; p.C = C; p.is_bf16 = is_bf16; p.bs = bs; p.h = h; p.alpha = alpha; p.y = dh;
   p.dz = dz; p.row_ptr = row_ptr; p.partial = partial; p.want_dalpha = dalpha != nullptr; p.lpg = 16;
   const int grid = sep_grid(F, SEP_GRID_BWD);
-  const bool vec = sep_vec_ok(C, is_bf16, h, dz, dh);
+  const bool vec = chan_vec_ok(C, is_bf16, h, dz, dh);
   auto kern = is_bf16 ? (vec ? k_dw_f2v<true, true, true> : k_dw_f2v<true, true, false>)
                       : (vec ? k_dw_f2v<false, true, true> : k_dw_f2v<false, true, false>);
   if (F == 0) {
@@ -383,7 +311,7 @@ __global__ void __launch_bounds__(256) k_slot_scale_sum(SlotP p) {
   for (int c0 = sub * CPL; c0 < p.C; c0 += p.lpg * CPL) {
     float sc[3][CPL];
 #pragma unroll
-    for (int j = 0; j < 3; ++j) sep_load_f32<CPL, VEC>(p.sc, (int64_t)j * p.C, p.C, c0, sc[j]);
+    for (int j = 0; j < 3; ++j) chan_load_f32<CPL, VEC>(p.sc, (int64_t)j * p.C, p.C, c0, sc[j]);
     for (int64_t seg = (int64_t)blockIdx.x * gpb + threadIdx.x / p.lpg; seg < p.V; seg += (int64_t)gridDim.x * gpb) {
       const int32_t b = p.row_ptr[seg], e = p.row_ptr[seg + 1];
       float a3[3][CPL];                      // per-corner sums; the scales are applied once at the end
@@ -400,7 +328,7 @@ __global__ void __launch_bounds__(256) k_slot_scale_sum(SlotP p) {
           row[q] = (int32_t)(((uint64_t)(uint32_t)cidx[q] * 0xAAAAAAABull) >> 33);   // / 3
         }
 #pragma unroll
-        for (int q = 0; q < 2; ++q) sep_load<BF16, CPL, VEC>(p.T, (int64_t)row[q] * p.C, p.C, c0, x[q]);
+        for (int q = 0; q < 2; ++q) chan_load<BF16, CPL, VEC>(p.T, (int64_t)row[q] * p.C, p.C, c0, x[q]);
 #pragma unroll
         for (int q = 0; q < 2; ++q) {
           const int slot = (i0 + q < e) ? cidx[q] - 3 * row[q] : 3;
@@ -413,7 +341,7 @@ __global__ void __launch_bounds__(256) k_slot_scale_sum(SlotP p) {
       float acc[CPL];
 #pragma unroll
       for (int i = 0; i < CPL; ++i) acc[i] = sc[0][i] * a3[0][i] + sc[1][i] * a3[1][i] + sc[2][i] * a3[2][i];
-      sep_store<BF16, CPL, VEC>(p.out, seg * p.C, p.C, c0, acc);
+      chan_store<BF16, CPL, VEC>(p.out, seg * p.C, p.C, c0, acc);
     }
   }
 }
@@ -436,7 +364,7 @@ pm_status pm_launch_slot_scale_sum(int64_t V, int K, int C, int is_bf16, const v
   int64_t nblk = (V + gpb - 1) / gpb;
   if (nblk > 0x7fffffff) nblk = 0x7fffffff;
   { ProfScope ps__(st, "k_slot_scale_sum");
-    const bool vec = sep_vec_ok(C, is_bf16, T, out, sc);
+    const bool vec = chan_vec_ok(C, is_bf16, T, out, sc);
     auto kern = is_bf16 ? (vec ? k_slot_scale_sum<true, true> : k_slot_scale_sum<true, false>)
                         : (vec ? k_slot_scale_sum<false, true> : k_slot_scale_sum<false, false>);
     hipLaunchKernelGGL(kern, dim3((unsigned)nblk), dim3(256), 0, st, p); }
