@@ -225,6 +225,23 @@ def all_ops(args, cfg, pm, mg, torch):
         "v2f_sep": (lambda: pm.pm_v2f_sep(mesh, L, hV, alpha, Pw, DT), F),
         "v2f_sep_bwd": (lambda: pm.pm_v2f_sep_bwd(mesh, adj, L, hV, alpha, Pw, dgF, DT), F),
     }
+    if args.grid % 2 == 0:
+        # pooling between this mesh and its 2x2-clustered coarse level (the hierarchy of config 5)
+        vc, io = mg.grid_cluster_maps(args.grid, args.grid)
+        Vc = (args.grid // 2) ** 2
+        cm = pm.pm_build_cluster_map(torch.from_numpy(vc).cuda(), torch.from_numpy(io).cuda(), Vc)
+        hC = rnd(Vc, cin)
+        _, amax = pm.pm_pool(cm, pm.PM_POOL_MAX, hV, DT)
+        ops.update({
+            "cluster_map": (lambda: pm.pm_build_cluster_map(cm_in[0], cm_in[1], Vc), V),
+            "pool_max": (lambda: pm.pm_pool(cm, pm.PM_POOL_MAX, hV, DT), V),
+            "pool_max_bwd": (lambda: pm.pm_pool_bwd(cm, pm.PM_POOL_MAX, hC, DT, argmax=amax), V),
+            "pool_avg": (lambda: pm.pm_pool(cm, pm.PM_POOL_AVG, hV, DT), V),
+            "pool_avg_bwd": (lambda: pm.pm_pool_bwd(cm, pm.PM_POOL_AVG, hC, DT), V),
+            "unpool": (lambda: pm.pm_unpool(cm, hC, DT), V),
+            "unpool_bwd": (lambda: pm.pm_unpool_bwd(cm, hV, DT), V),
+        })
+        cm_in = (torch.from_numpy(vc).cuda(), torch.from_numpy(io).cuda())
     out = {"workload": "config 3 mesh %dx%d: F=%d V=%d texture points=%d, L=%d, %d->%d, %s" %
                        (args.grid, args.grid, F, V, P, L, cin, cout, args.ops_dtype),
            "steps": args.steps, "ops": {}}
