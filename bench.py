@@ -225,6 +225,10 @@ def all_ops(args, cfg, pm, mg, torch):
         "v2f_sep": (lambda: pm.pm_v2f_sep(mesh, L, hV, alpha, Pw, DT), F),
         "v2f_sep_bwd": (lambda: pm.pm_v2f_sep_bwd(mesh, adj, L, hV, alpha, Pw, dgF, DT), F),
     }
+    ops.update({
+        "facet_geometry": (lambda: pm.pm_facet_geometry(mesh, DT, True), F),
+        "texture_layout": (lambda: pm.pm_texture_layout(mesh, 3, 1), F),
+    })
     if args.grid % 2 == 0:
         # pooling between this mesh and its 2x2-clustered coarse level (the hierarchy of config 5)
         vc, io = mg.grid_cluster_maps(args.grid, args.grid)

@@ -200,6 +200,29 @@ pm_status pm_unpool(const pm_cluster_map* cm, int C, pm_dtype dtype, const void*
 pm_status pm_unpool_bwd(const pm_cluster_map* cm, int C, pm_dtype dtype, const void* dg_fine, void* dh_coarse,
                         void* stream);
 
+/* ---- Input preparation ------------------------------------------------------------------------------
+ * Facet geometric features (Section "Geometric Features", Eq. 9): feat [n_facet][9 or 12] of `dtype`, row
+ * layout [l1 l2 l3, theta1 theta2 theta3, nx ny nz, (z1 z2 z3)] with l1 = |x2-x1|, l2 = |x3-x2|, l3 = |x1-x3|,
+ * theta_i the normalised inner product of the two edges at corner i (the cosine of the inner angle; 0 when an
+ * edge has zero length), n the unit normal of the stored corner order ((0,0,1) for a degenerate facet) and,
+ * when with_heights != 0, the z coordinates of the three corners. */
+pm_status pm_facet_geometry(const pm_mesh* mesh, int with_heights, pm_dtype dtype, void* feat, void* stream);
+
+/* Texture resolution of every facet (Eq. 8): gamma[f] = floor(alpha (A_f - Amin)/(Amax - Amin)) + beta with the
+ * extreme areas of the facet's own mesh (mesh->facet_off is required when n_mesh > 1; equal extremes give
+ * beta), evaluated in fp32 one IEEE operation at a time in a fixed order, and tex_off [n_facet+1] = running
+ * sum of the point counts (gamma+1)(gamma+2)/2.  0 <= alpha, beta and alpha + beta <= 255; the total must stay
+ * below 2^31 (not checked).  ws: pm_texture_ws_bytes(n_facet, n_mesh).  The caller reads tex_off[n_facet]
+ * back to size the point arrays. */
+size_t pm_texture_ws_bytes(int64_t n_facet, int32_t n_mesh); /* HOST computation; 0 on invalid sizes */
+pm_status pm_texture_layout(const pm_mesh* mesh, int alpha, int beta, int32_t* gamma, int32_t* tex_off, void* ws,
+                            size_t ws_bytes, void* stream);
+/* Barycentric interpolation points of every facet, bary [n_tex][3] fp32 (the layout pm_f2f reads): the lattice
+ * (i, j, gamma-i-j)/gamma, i descending then j descending, the centroid for gamma = 0.  Points at or past
+ * n_tex are not written. */
+pm_status pm_texture_bary(int64_t n_facet, const int32_t* gamma, const int32_t* tex_off, int64_t n_tex, float* bary,
+                          void* stream);
+
 /* Measurement aid (not part of the method): per-kernel timing with HIP events.
  * After pm_profile_enable(1) every kernel this thread's calls launch is bracketed by a pair of events
  * recorded on the call's stream (events are created on demand and reused; nothing else changes).

@@ -28,7 +28,7 @@ EXPORTS = [
     "pm_f2f", "pm_f2f_bwd", "pm_profile_enable", "pm_profile_count", "pm_profile_read", "pm_profile_reset",
     "pm_peak_probe", "pm_f2v_sep", "pm_f2v_sep_bwd", "pm_v2f_sep", "pm_v2f_sep_bwd",
     "pm_cluster_ws_bytes", "pm_validate_clusters", "pm_build_cluster_map", "pm_pool", "pm_pool_bwd", "pm_unpool",
-    "pm_unpool_bwd",
+    "pm_unpool_bwd", "pm_facet_geometry", "pm_texture_ws_bytes", "pm_texture_layout", "pm_texture_bary",
 ]
 
 
@@ -94,6 +94,11 @@ def lib():
                     "pm_pool_bwd": [cp, i32, i32, i32, vp, vp, vp, vp],
                     "pm_unpool": [cp, i32, i32, vp, vp, vp],
                     "pm_unpool_bwd": [cp, i32, i32, vp, vp, vp]})
+        sig.update({"pm_facet_geometry": [mp, i32, i32, vp, vp],
+                    "pm_texture_layout": [mp, i32, i32, vp, vp, vp, sz, vp],
+                    "pm_texture_bary": [i64, vp, vp, i64, vp, vp]})
+        l.pm_texture_ws_bytes.restype = C.c_size_t
+        l.pm_texture_ws_bytes.argtypes = [i64, C.c_int32]
         l.pm_cluster_ws_bytes.restype = C.c_size_t
         l.pm_cluster_ws_bytes.argtypes = [i64, i64]
         sig.update({"pm_profile_enable": [i32], "pm_profile_count": [], "pm_profile_reset": [],
@@ -472,6 +477,31 @@ def pm_unpool_bwd(cm: ClusterMap, dg_fine: torch.Tensor, dtype: int, stream=None
     _check(lib().pm_unpool_bwd(C.byref(m), Cc, dtype, C.c_void_p(dg_fine.data_ptr()), C.c_void_p(out.data_ptr()),
                                _stream(stream)))
     return out
+
+
+# ---- input preparation -------------------------------------------------------------------------------
+def pm_facet_geometry(mesh: Mesh, dtype: int, with_heights: bool = False, stream=None) -> torch.Tensor:
+    """[n_facet, 9 or 12]: edge lengths, inner-angle cosines, unit normal, optionally corner heights (Eq. 9)."""
+    out = torch.empty((mesh.n_facet, 12 if with_heights else 9), dtype=torch_dtype(dtype), device=mesh.facet.device)
+    m = mesh.c()
+    _check(lib().pm_facet_geometry(C.byref(m), 1 if with_heights else 0, dtype, C.c_void_p(out.data_ptr()), _stream(stream)))
+    return out
+
+
+def pm_texture_layout(mesh: Mesh, alpha: int, beta: int, stream=None):
+    """(gamma [F] int32, tex_off [F+1] int32, bary [P, 3] fp32) of Eq. 8; reads the point total back once."""
+    dev = mesh.facet.device
+    gamma = torch.empty(mesh.n_facet, dtype=torch.int32, device=dev)
+    tex_off = torch.empty(mesh.n_facet + 1, dtype=torch.int32, device=dev)
+    ws = alloc_workspace(int(lib().pm_texture_ws_bytes(mesh.n_facet, mesh.n_mesh)), dev)
+    m = mesh.c()
+    _check(lib().pm_texture_layout(C.byref(m), alpha, beta, C.c_void_p(gamma.data_ptr()), _ptr(tex_off), _ptr(ws),
+                                   ws.numel(), _stream(stream)))
+    n_tex = int(tex_off[-1].item())
+    bary = torch.empty((n_tex, 3), dtype=torch.float32, device=dev)
+    _check(lib().pm_texture_bary(mesh.n_facet, C.c_void_p(gamma.data_ptr()), _ptr(tex_off), n_tex,
+                                 C.c_void_p(bary.data_ptr()), _stream(stream)))
+    return gamma, tex_off, bary
 
 
 def pm_profile_enable(on: bool) -> None:

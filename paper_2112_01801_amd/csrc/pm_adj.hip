@@ -86,7 +86,7 @@ __global__ void __launch_bounds__(SCAN_BLOCK) k_scan_apply(const int32_t* __rest
   // cursors start at the row starts
   for (int i = 0; i < SCAN_ITEMS; ++i) {
     int64_t idx = base + (int64_t)threadIdx.x * SCAN_ITEMS + i;
-    if (idx < n) cursor[idx] = row_ptr[idx];
+    if (cursor && idx < n) cursor[idx] = row_ptr[idx];
   }
 }
 
@@ -167,6 +167,23 @@ pm_status pm_launch_fill_i32(int32_t* p, int64_t n, int32_t v, hipStream_t st) {
   { ProfScope ps__(st, "k_fill_i32");
     hipLaunchKernelGGL(k_fill_i32, dim3(nblk(n, 256)), dim3(256), 0, st, p, n, v); }
   PM_CHECK_LAUNCH("k_fill_i32");
+  return PM_OK;
+}
+
+// out[i] = sum of cnt[0..i) for i = 0..n (n + 1 outputs); tile_ws holds pm_scan_ws_bytes(n)
+size_t pm_scan_ws_bytes(int64_t n) { return pm_round_up((size_t)((n + SCAN_TILE - 1) / SCAN_TILE + 2) * 4, 256); }
+
+pm_status pm_launch_exclusive_scan(const int32_t* cnt, int64_t n, int32_t* out, void* tile_ws, hipStream_t st) {
+  if (n == 0) return pm_launch_fill_i32(out, 1, 0, st);
+  const int64_t n_tiles = (n + SCAN_TILE - 1) / SCAN_TILE;
+  int32_t* tsum = (int32_t*)tile_ws;
+  { ProfScope ps__(st, "k_scan_tile_sums");
+    hipLaunchKernelGGL(k_scan_tile_sums, dim3((unsigned)n_tiles), dim3(SCAN_BLOCK), 0, st, cnt, n, tsum); }
+  { ProfScope ps__(st, "k_scan_sums");
+    hipLaunchKernelGGL(k_scan_sums, dim3(1), dim3(SCAN_BLOCK), 0, st, tsum, n_tiles); }
+  { ProfScope ps__(st, "k_scan_apply");
+    hipLaunchKernelGGL(k_scan_apply, dim3((unsigned)n_tiles), dim3(SCAN_BLOCK), 0, st, cnt, n, tsum, out, (int32_t*)nullptr); }
+  PM_CHECK_LAUNCH("exclusive scan");
   return PM_OK;
 }
 

@@ -710,6 +710,43 @@ extern "C" pm_status pm_unpool_bwd(const pm_cluster_map* cm, int C, pm_dtype dty
   return pm_launch_segreduce(cm->n_out, C, dg_fine, fb, cm->row_ptr, cm->col, 1, 0, dh_coarse, fb, (hipStream_t)stream);
 }
 
+// ---- input preparation (Eq. 8, Eq. 9) --------------------------------------------------------------
+extern "C" pm_status pm_facet_geometry(const pm_mesh* mesh, int with_heights, pm_dtype dtype, void* feat, void* stream) {
+  pm_prof_set_op("facet_geometry");
+  PM_TRY(check_mesh(mesh, true));
+  if (dtype != PM_F32 && dtype != PM_BF16) return pm_fail(PM_ERR_UNSUPPORTED, "unknown pm_dtype %d", (int)dtype);
+  PM_TRY(check_ptr(feat, "feat", mesh->n_facet > 0));
+  return pm_launch_facet_geometry(mesh, with_heights != 0, dtype == PM_BF16, feat, (hipStream_t)stream);
+}
+
+extern "C" size_t pm_texture_ws_bytes(int64_t n_facet, int32_t n_mesh) {
+  if (n_facet < 0 || n_facet >= kMaxIds || n_mesh < 0) return 0;
+  return pm_texture_ws_bytes_host(n_facet, n_mesh);
+}
+
+extern "C" pm_status pm_texture_layout(const pm_mesh* mesh, int alpha, int beta, int32_t* gamma, int32_t* tex_off,
+                                       void* ws, size_t ws_bytes, void* stream) {
+  pm_prof_set_op("texture_layout");
+  PM_TRY(check_mesh(mesh, true));
+  if (alpha < 0 || beta < 0 || alpha + beta > 255) return pm_fail(PM_ERR_INVALID_ARG, "alpha=%d beta=%d", alpha, beta);
+  if (mesh->n_mesh > 1 && !mesh->facet_off) return pm_fail(PM_ERR_INVALID_ARG, "n_mesh > 1 needs facet_off");
+  if (!tex_off || (mesh->n_facet > 0 && !gamma)) return pm_fail(PM_ERR_INVALID_ARG, "gamma / tex_off is NULL");
+  PM_TRY(check_ptr(ws, "ws", true));
+  const size_t need = pm_texture_ws_bytes_host(mesh->n_facet, mesh->n_mesh);
+  if (ws_bytes < need) return pm_fail(PM_ERR_WORKSPACE, "workspace %zu < required %zu bytes", ws_bytes, need);
+  return pm_launch_texture_layout(mesh, alpha, beta, gamma, tex_off, ws, (hipStream_t)stream);
+}
+
+extern "C" pm_status pm_texture_bary(int64_t n_facet, const int32_t* gamma, const int32_t* tex_off, int64_t n_tex,
+                                     float* bary, void* stream) {
+  pm_prof_set_op("texture_bary");
+  if (n_facet < 0 || n_tex < 0 || n_facet >= kMaxIds || n_tex >= kMaxIds)
+    return pm_fail(PM_ERR_INVALID_ARG, "n_facet=%lld n_tex=%lld", (long long)n_facet, (long long)n_tex);
+  if (n_facet > 0 && (!gamma || !tex_off)) return pm_fail(PM_ERR_INVALID_ARG, "gamma / tex_off is NULL");
+  if (n_tex > 0 && !bary) return pm_fail(PM_ERR_INVALID_ARG, "bary is NULL");
+  return pm_launch_texture_bary(n_facet, gamma, tex_off, n_tex, bary, (hipStream_t)stream);
+}
+
 // ---- facet2facet (Eq. 7) -------------------------------------------------------------------------
 static pm_status check_f2f(int64_t n_facet, int64_t n_tex, const int32_t* tex_off, const float* bary) {
   if (n_facet < 0 || n_tex < 0 || n_facet >= kMaxIds || n_tex >= kMaxIds)

@@ -155,6 +155,15 @@ pm_status pm_launch_basis_bwd(int64_t n, const float* dirs, const ShTable& T, co
 size_t pm_adj_ws_bytes(int64_t n_vert, int64_t n_facet);
 size_t pm_csr_ws_bytes(int64_t n_rows, int64_t n_entries);
 pm_status pm_launch_fill_i32(int32_t* p, int64_t n, int32_t v, hipStream_t st);
+size_t pm_scan_ws_bytes(int64_t n);
+pm_status pm_launch_exclusive_scan(const int32_t* cnt, int64_t n, int32_t* out, void* tile_ws, hipStream_t st);
+// input preparation: facet geometric features (Eq. 9), texture resolution and interpolation lattice (Eq. 8)
+pm_status pm_launch_facet_geometry(const pm_mesh* mesh, int with_heights, int out_bf16, void* feat, hipStream_t st);
+size_t pm_texture_ws_bytes_host(int64_t n_facet, int n_mesh);
+pm_status pm_launch_texture_layout(const pm_mesh* mesh, int alpha, int beta, int32_t* gamma, int32_t* tex_off, void* ws,
+                                   hipStream_t st);
+pm_status pm_launch_texture_bary(int64_t n_facet, const int32_t* gamma, const int32_t* tex_off, int64_t n_tex, float* bary,
+                                 hipStream_t st);
 pm_status pm_launch_csr(int64_t n_rows, int64_t n_entries, const int32_t* keys, int32_t* row_ptr, int32_t* col, void* ws,
                         hipStream_t st);
 // pooling over vertex clusters
