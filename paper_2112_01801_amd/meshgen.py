@@ -211,6 +211,26 @@ def random_cluster_maps(rng: np.random.Generator, n_in: int, n_out: int, drop_fr
     return vcluster, iomap
 
 
+def range_neighbors(xq: np.ndarray, xs: np.ndarray, rho: float, max_nbr: int = 0,
+                    rng: Optional[np.random.Generator] = None) -> Tuple[np.ndarray, np.ndarray]:
+    """Neighbour lists of a range search (all sources within rho of each query), as CSR (ptr [M+1], idx) with
+    ascending source ids; lists longer than `max_nbr` (> 0) keep a random subset.  Input preparation only:
+    the search itself is not part of the library."""
+    from scipy.spatial import cKDTree
+    lists = cKDTree(np.asarray(xs, np.float64)).query_ball_point(np.asarray(xq, np.float64), rho)
+    out = []
+    for l in lists:
+        l = np.sort(np.asarray(l, dtype=np.int64))
+        if max_nbr > 0 and l.shape[0] > max_nbr:
+            l = np.sort(rng.choice(l, max_nbr, replace=False))
+        out.append(l)
+    ptr = np.zeros(len(out) + 1, np.int64)
+    np.cumsum([l.shape[0] for l in out], out=ptr[1:])
+    assert ptr[-1] < 2 ** 31
+    idx = np.concatenate(out) if out else np.zeros(0, np.int64)
+    return ptr.astype(np.int32), idx.astype(np.int32)
+
+
 # --------------------------------------------------------------------------------------
 # batching
 # --------------------------------------------------------------------------------------
