@@ -9,7 +9,7 @@
  *   - Plain C linkage.  Every pointer is a DEVICE pointer unless the comment says HOST; all are
  *     borrowed (never freed or retained).  `stream` is a hipStream_t passed as void* (NULL = the
  *     default stream).  All work is enqueued on that stream; no entry point allocates device memory
- *     and only pm_validate_mesh and pm_validate_clusters synchronise with the host.
+ *     and only the pm_validate_* calls synchronise with the host.
  *   - Arrays are row-major and contiguous.  Base pointers of feature, weight, output and workspace
  *     arrays must be 16-byte aligned (checked -> PM_ERR_INVALID_ARG).
  *   - Meshes come as one packed heterogeneous batch ("Heterogeneous Batching" subsection): vertex
@@ -199,6 +199,38 @@ pm_status pm_unpool(const pm_cluster_map* cm, int C, pm_dtype dtype, const void*
 /* dh_coarse[o] = sum of dg_fine[v] over the members of o, ascending, fp32 accumulation. */
 pm_status pm_unpool_bwd(const pm_cluster_map* cm, int C, pm_dtype dtype, const void* dg_fine, void* dh_coarse,
                         void* stream);
+
+/* ---- Point-cloud convolution with the radial term (subsection "Extension to Point Cloud Convolution") ----
+ * F(theta, phi, r) = F(theta, phi) Z(r) + c0 (1 - Z(r)), Z(r) = r / rho, depth-wise separable.  For query point i
+ * with the neighbours q_e (lists supplied by the caller; the range search is not part of this library):
+ *   delta_e = xs[q_e] - xq[i], r_e = |delta_e|, Z_e = min(r_e / rho, 1), direction delta_e / r_e,
+ *   s_e[c] = Z_e sum_k alpha[k][c] B_k(direction_e) + c0[c] (1 - Z_e),
+ *   y_i[c] = 1/|N(i)| sum_e s_e[c] h[q_e][c]   (0 for an empty list),        g_i = y_i P.
+ * xq [n_query][3], xs [n_source][3] fp32 (they may be the same array); ptr [n_query+1] and idx [nnz] int32 with
+ * ptr[0] = 0, ptr non-decreasing, ptr[n_query] = nnz, 0 <= idx < n_source; rho > 0.  alpha [K][cin] and c0 [cin]
+ * are fp32 (K + 1 numbers per channel), P [cin][cout] has the feature dtype; h [n_source][cin],
+ * g [n_query][cout].  An id outside its range is clamped, never followed; pm_validate_neighbors reports bad
+ * lists (synchronises; ws >= 16 bytes).  ws: pm_pcloud_ws_bytes(backward?, ...). */
+typedef struct pm_nbr {
+  int64_t n_query, n_source, nnz;
+  const float* xq;
+  const float* xs;
+  const int32_t* ptr;
+  const int32_t* idx;
+  float rho;
+} pm_nbr;
+size_t pm_pcloud_ws_bytes(int backward, int64_t n_query, int64_t n_source, int64_t nnz, int L, int cin, int cout,
+                          pm_dtype dtype); /* HOST computation; 0 on invalid arguments */
+pm_status pm_validate_neighbors(const pm_nbr* nb, void* ws, size_t ws_bytes, void* stream);
+pm_status pm_pcloud_conv(const pm_nbr* nb, int L, pm_sh_norm norm, int cin, int cout, pm_dtype dtype, const void* h,
+                         const float* alpha, const float* c0, const void* P, void* g, void* ws, size_t ws_bytes,
+                         void* stream);
+/* dh [n_source][cin] (feature dtype; may be NULL); dalpha [K][cin], dc0 [cin], dP [cin][cout] fp32 (all three
+ * or none).  Sums run in a fixed order over the caller's lists and over the reverse lists built here (sorted),
+ * no float atomics. */
+pm_status pm_pcloud_conv_bwd(const pm_nbr* nb, int L, pm_sh_norm norm, int cin, int cout, pm_dtype dtype,
+                             const void* h, const float* alpha, const float* c0, const void* P, const void* dg,
+                             void* dh, float* dalpha, float* dc0, float* dP, void* ws, size_t ws_bytes, void* stream);
 
 /* ---- Input preparation ------------------------------------------------------------------------------
  * Facet geometric features (Section "Geometric Features", Eq. 9): feat [n_facet][9 or 12] of `dtype`, row

@@ -28,7 +28,8 @@ EXPORTS = [
     "pm_f2f", "pm_f2f_bwd", "pm_profile_enable", "pm_profile_count", "pm_profile_read", "pm_profile_reset",
     "pm_peak_probe", "pm_f2v_sep", "pm_f2v_sep_bwd", "pm_v2f_sep", "pm_v2f_sep_bwd",
     "pm_cluster_ws_bytes", "pm_validate_clusters", "pm_build_cluster_map", "pm_pool", "pm_pool_bwd", "pm_unpool",
-    "pm_unpool_bwd", "pm_facet_geometry", "pm_texture_ws_bytes", "pm_texture_layout", "pm_texture_bary",
+    "pm_unpool_bwd", "pm_pcloud_ws_bytes", "pm_validate_neighbors", "pm_pcloud_conv", "pm_pcloud_conv_bwd",
+    "pm_facet_geometry", "pm_texture_ws_bytes", "pm_texture_layout", "pm_texture_bary",
 ]
 
 
@@ -45,6 +46,11 @@ class _PmMesh(C.Structure):
 
 class _PmAdj(C.Structure):
     _fields_ = [("row_ptr", C.c_void_p), ("col", C.c_void_p)]
+
+
+class _PmNbr(C.Structure):
+    _fields_ = [("n_query", C.c_int64), ("n_source", C.c_int64), ("nnz", C.c_int64), ("xq", C.c_void_p),
+                ("xs", C.c_void_p), ("ptr", C.c_void_p), ("idx", C.c_void_p), ("rho", C.c_float)]
 
 
 class _PmClusterMap(C.Structure):
@@ -97,6 +103,12 @@ def lib():
         sig.update({"pm_facet_geometry": [mp, i32, i32, vp, vp],
                     "pm_texture_layout": [mp, i32, i32, vp, vp, vp, sz, vp],
                     "pm_texture_bary": [i64, vp, vp, i64, vp, vp]})
+        npt = C.POINTER(_PmNbr)
+        sig.update({"pm_validate_neighbors": [npt, vp, sz, vp],
+                    "pm_pcloud_conv": [npt, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, sz, vp],
+                    "pm_pcloud_conv_bwd": [npt, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]})
+        l.pm_pcloud_ws_bytes.restype = C.c_size_t
+        l.pm_pcloud_ws_bytes.argtypes = [i32, i64, i64, i64, i32, i32, i32, i32]
         l.pm_texture_ws_bytes.restype = C.c_size_t
         l.pm_texture_ws_bytes.argtypes = [i64, C.c_int32]
         l.pm_cluster_ws_bytes.restype = C.c_size_t
@@ -477,6 +489,71 @@ def pm_unpool_bwd(cm: ClusterMap, dg_fine: torch.Tensor, dtype: int, stream=None
     _check(lib().pm_unpool_bwd(C.byref(m), Cc, dtype, C.c_void_p(dg_fine.data_ptr()), C.c_void_p(out.data_ptr()),
                                _stream(stream)))
     return out
+
+
+# ---- point-cloud convolution with the radial term ----------------------------------------------------
+@dataclass
+class Neighbors:
+    """Caller-supplied neighbour lists of a range search: xq [M,3], xs [N,3] fp32, ptr [M+1], idx [nnz] int32."""
+    xq: torch.Tensor
+    xs: torch.Tensor
+    ptr: torch.Tensor
+    idx: torch.Tensor
+    rho: float
+
+    def c(self) -> _PmNbr:
+        n = _PmNbr()
+        n.n_query, n.n_source, n.nnz = self.xq.shape[0], self.xs.shape[0], self.idx.shape[0]
+        n.xq = self.xq.data_ptr() if self.xq.numel() else None
+        n.xs = self.xs.data_ptr() if self.xs.numel() else None
+        n.ptr = self.ptr.data_ptr()
+        n.idx = self.idx.data_ptr() if self.idx.numel() else None
+        n.rho = float(self.rho)
+        return n
+
+
+def pm_validate_neighbors(nb: Neighbors, stream=None) -> None:
+    ws = alloc_workspace(256, nb.ptr.device)
+    n = nb.c()
+    _check(lib().pm_validate_neighbors(C.byref(n), _ptr(ws), ws.numel(), _stream(stream)))
+
+
+def _pc_ws(bwd, nb, L, cin, cout, dtype, ws):
+    if ws is None:
+        ws = alloc_workspace(int(lib().pm_pcloud_ws_bytes(bwd, nb.xq.shape[0], nb.xs.shape[0], nb.idx.shape[0], L, cin,
+                                                          cout, dtype)), nb.ptr.device)
+    return ws
+
+
+def pm_pcloud_conv(nb: Neighbors, L: int, h, alpha, c0, P, dtype: int, norm: int = PM_SH_PAPER, ws=None, stream=None):
+    """g [M, cout]: alpha [K,cin] and c0 [cin] fp32, P [cin,cout] and h [N,cin] in the feature dtype."""
+    _check_sep(alpha, P, dtype)
+    assert c0.dtype == torch.float32 and c0.shape[0] == P.shape[0]
+    cin, cout = P.shape
+    out = torch.empty((nb.xq.shape[0], cout), dtype=torch_dtype(dtype), device=h.device)
+    ws = _pc_ws(0, nb, L, cin, cout, dtype, ws)
+    n = nb.c()
+    _check(lib().pm_pcloud_conv(C.byref(n), L, norm, cin, cout, dtype, C.c_void_p(h.data_ptr()), _ptr(alpha), _ptr(c0),
+                                _ptr(P), C.c_void_p(out.data_ptr()), _ptr(ws), ws.numel(), _stream(stream)))
+    return out
+
+
+def pm_pcloud_conv_bwd(nb: Neighbors, L: int, h, alpha, c0, P, dg, dtype: int, norm: int = PM_SH_PAPER,
+                       want_dh: bool = True, want_dw: bool = True, ws=None, stream=None):
+    """(dh [N,cin], dalpha [K,cin], dc0 [cin], dP [cin,cout]); the parameter gradients come together or not at all."""
+    _check_sep(alpha, P, dtype)
+    cin, cout = P.shape
+    dev = h.device
+    dh = torch.empty((nb.xs.shape[0], cin), dtype=torch_dtype(dtype), device=dev) if want_dh else None
+    da = torch.empty(alpha.shape, dtype=torch.float32, device=dev) if want_dw else None
+    dc = torch.empty(c0.shape, dtype=torch.float32, device=dev) if want_dw else None
+    dP = torch.empty((cin, cout), dtype=torch.float32, device=dev) if want_dw else None
+    ws = _pc_ws(1, nb, L, cin, cout, dtype, ws)
+    n = nb.c()
+    vp = lambda t: C.c_void_p(t.data_ptr()) if t is not None else None
+    _check(lib().pm_pcloud_conv_bwd(C.byref(n), L, norm, cin, cout, dtype, vp(h), _ptr(alpha), _ptr(c0), _ptr(P), vp(dg),
+                                    vp(dh), vp(da), vp(dc), vp(dP), _ptr(ws), ws.numel(), _stream(stream)))
+    return dh, da, dc, dP
 
 
 # ---- input preparation -------------------------------------------------------------------------------

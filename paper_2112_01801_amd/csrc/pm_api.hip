@@ -710,6 +710,144 @@ extern "C" pm_status pm_unpool_bwd(const pm_cluster_map* cm, int C, pm_dtype dty
   return pm_launch_segreduce(cm->n_out, C, dg_fine, fb, cm->row_ptr, cm->col, 1, 0, dh_coarse, fb, (hipStream_t)stream);
 }
 
+// ---- point-cloud convolution with the radial term ------------------------------------------------------
+struct PcWs { size_t apack, dy, y, owner, rev_ptr, rev_col, csr, tail, total; };
+
+static PcWs plan_pc(int bwd, int64_t M, int64_t N, int64_t nnz, int L, int cin, int cout, pm_dtype dt) {
+  const int K = (L + 1) * (L + 1);
+  PcWs w = {0, 0, 0, 0, 0, 0, 0, 0, 0};
+  w.y = pm_round_up((size_t)M * cin * esize(dt), 256);
+  if (!bwd) {
+    w.apack = pm_pack_bytes(pm_pack_geom(1, cin, cout, dt));
+  } else {
+    w.apack = pm_pack_bytes(pm_pack_geom(1, cout, cin, dt));
+    w.dy = pm_round_up((size_t)M * cin * 4, 256);
+    w.owner = pm_round_up((size_t)(nnz + 1) * 4, 256);
+    w.rev_ptr = pm_round_up((size_t)(N + 1) * 4, 256);
+    w.rev_col = pm_round_up((size_t)(nnz + 1) * 4, 256);
+    w.csr = pm_csr_ws_bytes(N, nnz);
+    w.tail = std::max(pm_pc_coef_ws_bytes(M, K, cin), pm_wgrad_ws_bytes(M, 1, cin, cout));
+  }
+  w.total = w.apack + w.dy + w.y + w.owner + w.rev_ptr + w.rev_col + w.csr + w.tail;
+  return w;
+}
+
+static pm_status check_nbr(const pm_nbr* nb) {
+  if (!nb) return pm_fail(PM_ERR_INVALID_ARG, "neighbour lists are NULL");
+  if (nb->n_query < 0 || nb->n_source < 0 || nb->nnz < 0 || nb->n_query >= kMaxIds || nb->n_source >= kMaxIds ||
+      nb->nnz >= kMaxIds)
+    return pm_fail(PM_ERR_INVALID_ARG, "n_query=%lld n_source=%lld nnz=%lld", (long long)nb->n_query,
+                   (long long)nb->n_source, (long long)nb->nnz);
+  if (!nb->ptr) return pm_fail(PM_ERR_INVALID_ARG, "ptr is NULL");
+  if (nb->nnz > 0 && (!nb->idx || nb->n_source == 0)) return pm_fail(PM_ERR_INVALID_ARG, "idx is NULL or there are no sources");
+  if ((nb->n_query > 0 && !nb->xq) || (nb->n_source > 0 && !nb->xs)) return pm_fail(PM_ERR_INVALID_ARG, "xq / xs is NULL");
+  if (!(nb->rho > 0.f)) return pm_fail(PM_ERR_INVALID_ARG, "rho must be positive");
+  return PM_OK;
+}
+
+extern "C" size_t pm_pcloud_ws_bytes(int backward, int64_t n_query, int64_t n_source, int64_t nnz, int L, int cin,
+                                     int cout, pm_dtype dtype) {
+  if (n_query < 0 || n_source < 0 || nnz < 0 || n_query >= kMaxIds || n_source >= kMaxIds || nnz >= kMaxIds) return 0;
+  if (check_conv_common(L, PM_SH_PAPER, cin, cout, dtype) != PM_OK) return 0;
+  return plan_pc(backward != 0, n_query, n_source, nnz, L, cin, cout, dtype).total;
+}
+
+extern "C" pm_status pm_validate_neighbors(const pm_nbr* nb, void* ws, size_t ws_bytes, void* stream) {
+  pm_prof_set_op("validate_neighbors");
+  PM_TRY(check_nbr(nb));
+  PM_TRY(check_ptr(ws, "ws", true));
+  if (ws_bytes < 16) return pm_fail(PM_ERR_WORKSPACE, "validate needs 16 bytes of workspace");
+  hipStream_t st = (hipStream_t)stream;
+  PM_TRY(pm_launch_validate_nbr(nb->n_query, nb->n_source, nb->nnz, nb->ptr, nb->idx, (int32_t*)ws, st));
+  int32_t flag = 0;
+  PM_CHECK_HIP(hipMemcpyAsync(&flag, ws, sizeof(flag), hipMemcpyDeviceToHost, st));
+  PM_CHECK_HIP(hipStreamSynchronize(st));
+  if (flag & 1) return pm_fail(PM_ERR_BAD_MESH, "neighbour offsets are not monotone or do not span the list");
+  if (flag & 2) return pm_fail(PM_ERR_BAD_MESH, "a neighbour id is outside the source set");
+  return PM_OK;
+}
+
+extern "C" pm_status pm_pcloud_conv(const pm_nbr* nb, int L, pm_sh_norm norm, int cin, int cout, pm_dtype dtype,
+                                    const void* h, const float* alpha, const float* c0, const void* P, void* g, void* ws,
+                                    size_t ws_bytes, void* stream) {
+  pm_prof_set_op("pcloud_conv");
+  PM_TRY(check_conv_common(L, norm, cin, cout, dtype));
+  PM_TRY(check_nbr(nb));
+  PM_TRY(check_sep(alpha, P));
+  if (!c0 || !pm_aligned16(c0)) return pm_fail(PM_ERR_INVALID_ARG, "c0 is NULL or not 16-byte aligned");
+  PM_TRY(check_ptr(h, "h", nb->n_source > 0));
+  PM_TRY(check_ptr(g, "g", nb->n_query > 0));
+  const int K = (L + 1) * (L + 1);
+  const int64_t M = nb->n_query, N = nb->n_source;
+  PcWs w = plan_pc(0, M, N, nb->nnz, L, cin, cout, dtype);
+  PM_TRY(check_ptr(ws, "ws", true));
+  if (ws_bytes < w.total) return pm_fail(PM_ERR_WORKSPACE, "workspace %zu < required %zu bytes", ws_bytes, w.total);
+  hipStream_t st = (hipStream_t)stream;
+  char* apack = (char*)ws;
+  void* y = apack + w.apack;
+  const int fb = dtype == PM_BF16;
+  ShTable sh;
+  pm_make_sh_table(L, norm, &sh);
+  PM_TRY(pm_launch_pc_dw(M, N, K, cin, fb, nb->rho, sh, nb->xq, nb->xs, nb->ptr, nb->idx, h, alpha, c0, y, st));
+  PM_TRY(pm_launch_pack(PACK_PLAIN, dtype, 1, cin, cout, P, nullptr, apack, st));
+  RowSrc ys = row_src(y, dtype, cin);
+  return pm_launch_conv_rows(dtype, B_ONE, X_DIRECT, M, 1, cin, cout, basis_none(), ys, apack, g, fb, st);
+}
+
+extern "C" pm_status pm_pcloud_conv_bwd(const pm_nbr* nb, int L, pm_sh_norm norm, int cin, int cout, pm_dtype dtype,
+                                        const void* h, const float* alpha, const float* c0, const void* P,
+                                        const void* dg, void* dh, float* dalpha, float* dc0, float* dP, void* ws,
+                                        size_t ws_bytes, void* stream) {
+  pm_prof_set_op("pcloud_conv_bwd");
+  PM_TRY(check_conv_common(L, norm, cin, cout, dtype));
+  PM_TRY(check_nbr(nb));
+  PM_TRY(check_sep(alpha, P));
+  if (!c0 || !pm_aligned16(c0)) return pm_fail(PM_ERR_INVALID_ARG, "c0 is NULL or not 16-byte aligned");
+  PM_TRY(check_ptr(h, "h", nb->n_source > 0));
+  PM_TRY(check_ptr(dg, "dg", nb->n_query > 0));
+  PM_TRY(check_ptr(dh, "dh", false));
+  PM_TRY(check_ptr(dalpha, "dalpha", false));
+  PM_TRY(check_ptr(dc0, "dc0", false));
+  PM_TRY(check_ptr(dP, "dP", false));
+  if ((dalpha == nullptr) != (dP == nullptr) || (dalpha == nullptr) != (dc0 == nullptr))
+    return pm_fail(PM_ERR_INVALID_ARG, "dalpha, dc0 and dP come together");
+  const int K = (L + 1) * (L + 1);
+  const int64_t M = nb->n_query, N = nb->n_source, nnz = nb->nnz;
+  PcWs w = plan_pc(1, M, N, nnz, L, cin, cout, dtype);
+  PM_TRY(check_ptr(ws, "ws", true));
+  if (ws_bytes < w.total) return pm_fail(PM_ERR_WORKSPACE, "workspace %zu < required %zu bytes", ws_bytes, w.total);
+  hipStream_t st = (hipStream_t)stream;
+  char* apack = (char*)ws;
+  float* dy = (float*)(apack + w.apack);
+  void* y = (char*)dy + w.dy;
+  int32_t* owner = (int32_t*)((char*)y + w.y);
+  int32_t* rev_ptr = (int32_t*)((char*)owner + w.owner);
+  int32_t* rev_col = (int32_t*)((char*)rev_ptr + w.rev_ptr);
+  void* csr_ws = (char*)rev_col + w.rev_col;
+  void* tail = (char*)csr_ws + w.csr;
+  const int fb = dtype == PM_BF16;
+  ShTable sh;
+  pm_make_sh_table(L, norm, &sh);
+  // dy = dg P^T on the query rows, kept in fp32
+  PM_TRY(pm_launch_pack(PACK_TRANS, dtype, 1, cin, cout, P, nullptr, apack, st));
+  RowSrc gs = row_src(dg, dtype, cout);
+  PM_TRY(pm_launch_conv_rows(dtype, B_ONE, X_DIRECT, M, 1, cout, cin, basis_none(), gs, apack, dy, 0, st));
+  if (dalpha) {
+    PM_TRY(pm_launch_pc_dw_coef(M, N, K, cin, fb, nb->rho, sh, nb->xq, nb->xs, nb->ptr, nb->idx, h, alpha, c0, dy, y,
+                                dalpha, dc0, (float*)tail, st));
+    RowSrc ys = row_src(y, dtype, cin);
+    PM_TRY(pm_launch_wgrad(dtype, B_ONE, X_DIRECT, X_DIRECT, M, 1, cin, cout, basis_none(), ys, gs, dP, tail, w.tail,
+                           nullptr, st));
+  }
+  if (dh) {
+    PM_TRY(pm_launch_owner(M, nb->ptr, owner, st));
+    PM_TRY(pm_launch_csr(N, nnz, nb->idx, rev_ptr, rev_col, csr_ws, st));
+    PM_TRY(pm_launch_pc_dw_dh(M, N, K, cin, fb, nb->rho, sh, nb->xq, nb->xs, nb->ptr, rev_ptr, rev_col, owner, alpha, c0,
+                              dy, dh, st));
+  }
+  return PM_OK;
+}
+
 // ---- input preparation (Eq. 8, Eq. 9) --------------------------------------------------------------
 extern "C" pm_status pm_facet_geometry(const pm_mesh* mesh, int with_heights, pm_dtype dtype, void* feat, void* stream) {
   pm_prof_set_op("facet_geometry");

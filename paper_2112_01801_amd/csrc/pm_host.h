@@ -128,6 +128,8 @@ pm_status pm_launch_segsum_slots(int64_t n_seg, int C, const void* src, int src_
                                  const int32_t* col, void* out, int out_is_bf16, hipStream_t st);
 // out[i] = sum over n_slice slices of partial[slice][i], added in a fixed order (bitwise reproducible)
 pm_status pm_launch_sum_slices(const float* partial, int64_t n, int n_slice, float* out, hipStream_t st);
+pm_status pm_launch_sum_slices_strided(const float* partial, int64_t n, int64_t stride, int n_slice, float* out,
+                                       hipStream_t st);
 
 // Depth-wise stage of the separable facet2vertex form: y_f[c] = h_f[c] * sum_k alpha[k][c] B_k(n_f), and its backward
 // (dh_f[c] = dy_f[c] * filter, dy_f = gathered mean of dz;  dalpha[k][c] = sum_f B_k(n_f) h_f[c] dy_f[c]).
@@ -157,6 +159,21 @@ size_t pm_csr_ws_bytes(int64_t n_rows, int64_t n_entries);
 pm_status pm_launch_fill_i32(int32_t* p, int64_t n, int32_t v, hipStream_t st);
 size_t pm_scan_ws_bytes(int64_t n);
 pm_status pm_launch_exclusive_scan(const int32_t* cnt, int64_t n, int32_t* out, void* tile_ws, hipStream_t st);
+// point-cloud convolution with the radial term (depth-wise stage and its transposed sums)
+size_t pm_pc_coef_ws_bytes(int64_t M, int K, int C);
+pm_status pm_launch_pc_dw(int64_t M, int64_t N, int K, int C, int is_bf16, float rho, const ShTable& sh, const float* xq,
+                          const float* xs, const int32_t* nbr_ptr, const int32_t* nbr_idx, const void* h,
+                          const float* alpha, const float* c0, void* y, hipStream_t st);
+pm_status pm_launch_pc_dw_coef(int64_t M, int64_t N, int K, int C, int is_bf16, float rho, const ShTable& sh,
+                               const float* xq, const float* xs, const int32_t* nbr_ptr, const int32_t* nbr_idx,
+                               const void* h, const float* alpha, const float* c0, const float* dy, void* y,
+                               float* dalpha, float* dc0, float* partial, hipStream_t st);
+pm_status pm_launch_pc_dw_dh(int64_t M, int64_t N, int K, int C, int is_bf16, float rho, const ShTable& sh,
+                             const float* xq, const float* xs, const int32_t* nbr_ptr, const int32_t* rev_ptr,
+                             const int32_t* rev_col, const int32_t* owner, const float* alpha, const float* c0,
+                             const float* dy, void* dh, hipStream_t st);
+pm_status pm_launch_validate_nbr(int64_t M, int64_t N, int64_t nnz, const int32_t* ptr, const int32_t* idx,
+                                 int32_t* flag, hipStream_t st);
 // input preparation: facet geometric features (Eq. 9), texture resolution and interpolation lattice (Eq. 8)
 pm_status pm_launch_facet_geometry(const pm_mesh* mesh, int with_heights, int out_bf16, void* feat, hipStream_t st);
 size_t pm_texture_ws_bytes_host(int64_t n_facet, int n_mesh);

@@ -421,8 +421,8 @@ __global__ void __launch_bounds__(512) k_wgrad(WgradP p) {
 // out[i] = sum over the slices in a fixed order (bitwise reproducible): the slices are cut into eight
 // consecutive groups, each group is added sequentially by one thread (eight loads in flight), and the
 // eight group sums are then added in group order.
-__global__ void __launch_bounds__(256) k_sum_partials(const float* __restrict__ partial, int64_t n, int n_slice,
-                                                      float* __restrict__ out) {
+__global__ void __launch_bounds__(256) k_sum_partials(const float* __restrict__ partial, int64_t n, int64_t stride,
+                                                      int n_slice, float* __restrict__ out) {
   __shared__ float part[8][32];
   const int il = threadIdx.x & 31, g = threadIdx.x >> 5;
   const int64_t i = (int64_t)blockIdx.x * 32 + il;
@@ -434,11 +434,11 @@ __global__ void __launch_bounds__(256) k_sum_partials(const float* __restrict__ 
     for (; q + 8 <= q1; q += 8) {
       float v[8];
 #pragma unroll
-      for (int j = 0; j < 8; ++j) v[j] = partial[(int64_t)(q + j) * n + i];
+      for (int j = 0; j < 8; ++j) v[j] = partial[(int64_t)(q + j) * stride + i];
 #pragma unroll
       for (int j = 0; j < 8; ++j) s += v[j];
     }
-    for (; q < q1; ++q) s += partial[(int64_t)q * n + i];
+    for (; q < q1; ++q) s += partial[(int64_t)q * stride + i];
   }
   part[g][il] = s;
   __syncthreads();
@@ -451,8 +451,15 @@ __global__ void __launch_bounds__(256) k_sum_partials(const float* __restrict__ 
 }
 
 pm_status pm_launch_sum_slices(const float* partial, int64_t n, int n_slice, float* out, hipStream_t st) {
+  return pm_launch_sum_slices_strided(partial, n, n, n_slice, out, st);
+}
+
+// the slices start `stride` floats apart (stride >= n): sums a window of n floats of every slice
+pm_status pm_launch_sum_slices_strided(const float* partial, int64_t n, int64_t stride, int n_slice, float* out,
+                                       hipStream_t st) {
+  if (n <= 0) return PM_OK;
   { ProfScope ps__(st, "k_sum_partials");
-    hipLaunchKernelGGL(k_sum_partials, dim3((unsigned)((n + 31) / 32)), dim3(256), 0, st, partial, n, n_slice, out); }
+    hipLaunchKernelGGL(k_sum_partials, dim3((unsigned)((n + 31) / 32)), dim3(256), 0, st, partial, n, stride, n_slice, out); }
   PM_CHECK_LAUNCH("k_sum_partials");
   return PM_OK;
 }

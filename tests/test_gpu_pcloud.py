@@ -1,0 +1,133 @@
+"""Point-cloud convolution with the radial term: HIP path vs the fp64 oracle through the C ABI."""
+import numpy as np
+import pytest
+
+from oracle import pcloud as opc
+from paper_2112_01801_amd import meshgen as mg
+from parity_util import TOL, make_features, pm_dtype, rel_err, rel_err_rows, sample_rows, to_dev, to_host
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def pm():
+    import torch
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    from paper_2112_01801_amd import binding
+    binding.lib()
+    return binding
+
+
+def _params(rng, L, cin, cout, dtype):
+    K = (L + 1) ** 2
+    alpha = (rng.uniform(-1, 1, (K, cin)) / np.sqrt(K)).astype(np.float32)
+    c0 = rng.uniform(-1, 1, cin).astype(np.float32)
+    P = (rng.uniform(-1, 1, (cin, cout)) * np.sqrt(3.0 / cin)).astype(np.float32)
+    return alpha, c0, (mg.round_to_bf16(P) if dtype == "bf16" else P)
+
+
+def _cloud(seed, M, N, rho, same=False, max_nbr=0):
+    """Points on a bumpy sheet (the vertices of a surface), with duplicates of some sources so that r = 0 occurs."""
+    rng = np.random.default_rng(seed)
+    xs = np.stack([rng.uniform(0, 1, N), rng.uniform(0, 1, N), 0.1 * rng.standard_normal(N)], 1).astype(np.float32)
+    if same:
+        xq = xs
+    else:
+        xq = np.stack([rng.uniform(0, 1, M), rng.uniform(0, 1, M), 0.1 * rng.standard_normal(M)], 1).astype(np.float32)
+        xq[:5] = xs[:5]
+    ptr, idx = mg.range_neighbors(xq, xs, rho, max_nbr, rng)
+    return xq, xs, ptr, idx
+
+
+def _nbr(pm, xq, xs, ptr, idx, rho):
+    import torch
+    t = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    xs_d = t(xs)
+    xq_d = xs_d if xq is xs else t(xq)
+    return pm.Neighbors(xq_d, xs_d, t(ptr), t(idx), rho)
+
+
+CASES = [(3, 64, 64, "bf16"), (3, 64, 64, "f32"), (2, 20, 24, "f32"), (4, 32, 128, "bf16"), (5, 8, 40, "f32"),
+         (0, 16, 16, "bf16"), (1, 3, 5, "f32"), (3, 136, 16, "bf16")]
+
+
+@pytest.mark.parametrize("L,cin,cout,dtype", CASES)
+def test_forward_backward_against_the_oracle(pm, L, cin, cout, dtype):
+    import torch
+    rho = 0.11
+    xq, xs, ptr, idx = _cloud(300 + L, 700, 900, rho)
+    deg = np.diff(ptr)
+    assert deg.min() == 0 or deg.max() > 3 * max(deg.min(), 1)          # ragged lists
+    rng = np.random.default_rng(310 + L)
+    alpha, c0, P = _params(rng, L, cin, cout, dtype)
+    h = make_features(rng, xs.shape[0], cin, dtype)
+    dg = make_features(rng, xq.shape[0], cout, dtype)
+    nb = _nbr(pm, xq, xs, ptr, idx, rho)
+    pm.pm_validate_neighbors(nb)
+    a_d, c_d, P_d, dt = torch.from_numpy(alpha).cuda(), torch.from_numpy(c0).cuda(), to_dev(P, dtype), pm_dtype(dtype)
+    g = pm.pm_pcloud_conv(nb, L, to_dev(h, dtype), a_d, c_d, P_d, dt)
+    assert rel_err(to_host(g), opc.pcloud_conv(xq, xs, ptr, idx, rho, L, h, alpha, c0, P)) < TOL[dtype]
+    dh, da, dc, dP = pm.pm_pcloud_conv_bwd(nb, L, to_dev(h, dtype), a_d, c_d, P_d, to_dev(dg, dtype), dt)
+    rdh, rda, rdc, rdP = opc.pcloud_conv_bwd(xq, xs, ptr, idx, rho, L, h, alpha, c0, P, dg)
+    assert rel_err(to_host(dh), rdh) < TOL[dtype]
+    assert rel_err(to_host(da), rda) < TOL[dtype]
+    assert rel_err(to_host(dc)[None, :], rdc[None, :]) < TOL[dtype]
+    assert rel_err(to_host(dP), rdP) < TOL[dtype]
+    dh1, n1, n2, n3 = pm.pm_pcloud_conv_bwd(nb, L, to_dev(h, dtype), a_d, c_d, P_d, to_dev(dg, dtype), dt, want_dw=False)
+    assert n1 is None and n2 is None and n3 is None and torch.equal(dh1, dh)
+    n0, da1, dc1, dP1 = pm.pm_pcloud_conv_bwd(nb, L, to_dev(h, dtype), a_d, c_d, P_d, to_dev(dg, dtype), dt, want_dh=False)
+    assert n0 is None and torch.equal(da1, da) and torch.equal(dc1, dc) and torch.equal(dP1, dP)
+
+
+def test_vertices_of_a_coarse_mesh_level_sampled(pm):
+    """A 256x256 level of the benchmark hierarchy (65,536 points, queries = sources, ~30 neighbours each, 1 to ~70)."""
+    import torch
+    L, cin, cout, dtype = 3, 64, 64, "bf16"
+    v, _ = mg.heightfield(256, 256, np.random.default_rng(320))
+    xs = v.astype(np.float32)
+    span = float(xs[:, 0].max() - xs[:, 0].min())
+    rho = 5.0 * span / 255
+    ptr, idx = mg.range_neighbors(xs, xs, rho)
+    assert 20 < np.diff(ptr).mean() < 40
+    rng = np.random.default_rng(321)
+    alpha, c0, P = _params(rng, L, cin, cout, dtype)
+    h = make_features(rng, xs.shape[0], cin, dtype)
+    dg = make_features(rng, xs.shape[0], cout, dtype)
+    nb = _nbr(pm, xs, xs, ptr, idx, rho)
+    a_d, c_d, P_d, dt = torch.from_numpy(alpha).cuda(), torch.from_numpy(c0).cuda(), to_dev(P, dtype), pm_dtype(dtype)
+    g = pm.pm_pcloud_conv(nb, L, to_dev(h, dtype), a_d, c_d, P_d, dt)
+    dh, da, dc, dP = pm.pm_pcloud_conv_bwd(nb, L, to_dev(h, dtype), a_d, c_d, P_d, to_dev(dg, dtype), dt)
+    # the oracle on the whole set takes a few seconds (1.9 M pairs)
+    ref = opc.pcloud_conv(xs, xs, ptr, idx, rho, L, h, alpha, c0, P)
+    rows = sample_rows(rng, xs.shape[0], 4096)
+    # border points have one or two neighbours, interior points average thirty: output rows differ in scale by
+    # sqrt(30), so bf16 results are measured per row (fp32 passes the global metric at 3e-6 on the same data)
+    assert rel_err_rows(to_host(g[rows]), ref[rows]) < TOL[dtype]
+    rdh, rda, rdc, rdP = opc.pcloud_conv_bwd(xs, xs, ptr, idx, rho, L, h, alpha, c0, P, dg)
+    assert rel_err_rows(to_host(dh[rows]), rdh[rows]) < TOL[dtype]
+    assert rel_err(to_host(da), rda) < TOL[dtype] and rel_err(to_host(dP), rdP) < TOL[dtype]
+    assert rel_err(to_host(dc)[None, :], rdc[None, :]) < TOL[dtype]
+
+
+def test_empty_lists_and_bad_lists(pm):
+    import torch
+    L, cin, cout = 2, 16, 8
+    rng = np.random.default_rng(330)
+    alpha, c0, P = _params(rng, L, cin, cout, "f32")
+    a_d, c_d, P_d = torch.from_numpy(alpha).cuda(), torch.from_numpy(c0).cuda(), to_dev(P, "f32")
+    xs = rng.uniform(0, 1, (10, 3)).astype(np.float32)
+    xq = rng.uniform(0, 1, (6, 3)).astype(np.float32)
+    h = make_features(rng, 10, cin, "f32")
+    # no pairs at all
+    nb = _nbr(pm, xq, xs, np.zeros(7, np.int32), np.zeros(0, np.int32), 0.5)
+    g = pm.pm_pcloud_conv(nb, L, to_dev(h, "f32"), a_d, c_d, P_d, 0)
+    assert g.shape == (6, cout) and not g.abs().any()
+    dh, da, dc, dP = pm.pm_pcloud_conv_bwd(nb, L, to_dev(h, "f32"), a_d, c_d, P_d, torch.ones((6, cout), device="cuda"), 0)
+    assert not dh.abs().any() and not da.abs().any() and not dc.abs().any() and not dP.abs().any()
+    # lists that do not span idx / ids outside the source set are reported
+    bad = _nbr(pm, xq, xs, np.array([0, 2, 1, 3, 3, 3, 3], np.int32), np.array([1, 2, 3], np.int32), 0.5)
+    with pytest.raises(pm.PmError):
+        pm.pm_validate_neighbors(bad)
+    bad = _nbr(pm, xq, xs, np.array([0, 1, 1, 3, 3, 3, 3], np.int32), np.array([1, 10, 3], np.int32), 0.5)
+    with pytest.raises(pm.PmError):
+        pm.pm_validate_neighbors(bad)
