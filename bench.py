@@ -225,6 +225,22 @@ def all_ops(args, cfg, pm, mg, torch):
         "v2f_sep": (lambda: pm.pm_v2f_sep(mesh, L, hV, alpha, Pw, DT), F),
         "v2f_sep_bwd": (lambda: pm.pm_v2f_sep_bwd(mesh, adj, L, hV, alpha, Pw, dgF, DT), F),
     }
+    if args.grid >= 4:
+        # point-cloud convolution on the vertices of the level two decimations down (the resolution the paper's
+        # dual blocks use it at), neighbours of a range search of about six grid spacings
+        import numpy as np
+        gn = args.grid // 2
+        pv, _ = mg.heightfield(gn, gn, np.random.default_rng(20211201 + 4))
+        rho = 5.5 / (gn - 1)
+        nptr, nidx = mg.range_neighbors(pv, pv, rho)
+        pts = torch.from_numpy(np.ascontiguousarray(pv, dtype=np.float32)).cuda()
+        nb = pm.Neighbors(pts, pts, torch.from_numpy(nptr).cuda(), torch.from_numpy(nidx).cuda(), rho)
+        c0 = torch.rand(cin, device="cuda", generator=gen) * 2 - 1
+        hN, dgN = rnd(gn * gn, cin), rnd(gn * gn, cout)
+        ops.update({
+            "pcloud_conv": (lambda: pm.pm_pcloud_conv(nb, L, hN, alpha, c0, Pw, DT), int(nidx.shape[0])),
+            "pcloud_conv_bwd": (lambda: pm.pm_pcloud_conv_bwd(nb, L, hN, alpha, c0, Pw, dgN, DT), int(nidx.shape[0])),
+        })
     ops.update({
         "facet_geometry": (lambda: pm.pm_facet_geometry(mesh, DT, True), F),
         "texture_layout": (lambda: pm.pm_texture_layout(mesh, 3, 1), F),

@@ -9,7 +9,8 @@
 #define SCAN_ITEMS 8
 #define SCAN_BLOCK 256
 #define SCAN_TILE (SCAN_ITEMS * SCAN_BLOCK)
-#define SHORT_ROW 32
+#define SHORT_ROW 16
+#define MID_ROW 256
 
 __global__ void k_fill_i32(int32_t* p, int64_t n, int32_t v) {
   int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -119,6 +120,32 @@ __global__ void k_sort_short(int64_t V, const int32_t* __restrict__ row_ptr, con
   }
 }
 
+// rows of SHORT_ROW+1 .. MID_ROW entries: one wave per queued row, the row in the wave's own LDS tile, every lane
+// ranks its entries against the whole row
+__global__ void __launch_bounds__(256) k_sort_mid(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ tmp,
+                                                  int32_t* __restrict__ col, const int32_t* __restrict__ long_rows,
+                                                  const int32_t* __restrict__ n_long) {
+  __shared__ int32_t tiles[4][MID_ROW];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  int32_t* tile = tiles[wave];
+  const int32_t nl = *n_long;
+  for (int32_t q = blockIdx.x * 4 + wave; q < nl; q += gridDim.x * 4) {
+    const int32_t v = long_rows[q];
+    const int32_t b = row_ptr[v], d = row_ptr[v + 1] - b;
+    if (d > MID_ROW) continue;                     // left to k_sort_long
+    __builtin_amdgcn_wave_barrier();
+    for (int i = lane; i < d; i += 64) tile[i] = tmp[b + i];
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    for (int i = lane; i < d; i += 64) {
+      const int32_t x = tile[i];
+      int32_t rank = 0;
+      for (int j = 0; j < d; ++j) rank += (tile[j] < x) ? 1 : 0;
+      col[b + rank] = x;
+    }
+  }
+}
+
 __global__ void __launch_bounds__(256) k_sort_long(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ tmp,
                                                    int32_t* __restrict__ col, const int32_t* __restrict__ long_rows,
                                                    const int32_t* __restrict__ n_long) {
@@ -127,6 +154,7 @@ __global__ void __launch_bounds__(256) k_sort_long(const int32_t* __restrict__ r
   for (int32_t q = blockIdx.x; q < nl; q += gridDim.x) {
     int32_t v = long_rows[q];
     int32_t b = row_ptr[v], e = row_ptr[v + 1];
+    if (e - b <= MID_ROW) continue;                // done by k_sort_mid (the same for the whole workgroup)
     // every thread owns entries i = b + t, b + t + 256, ...; ranks accumulate over LDS tiles of the row
     for (int32_t i0 = b; i0 < e; i0 += 256) {
       int32_t i = i0 + threadIdx.x;
@@ -225,6 +253,8 @@ pm_status pm_launch_csr(int64_t V, int64_t n3, const int32_t* keys, int32_t* row
       hipLaunchKernelGGL(k_scatter, dim3(nblk(n3, 256)), dim3(256), 0, st, n3, keys, cursor, tmp); }
     { ProfScope ps__(st, "k_sort_short");
       hipLaunchKernelGGL(k_sort_short, dim3(nblk(V, 256)), dim3(256), 0, st, V, row_ptr, tmp, col, long_rows, n_long); }
+    { ProfScope ps__(st, "k_sort_mid");
+      hipLaunchKernelGGL(k_sort_mid, dim3(2048), dim3(256), 0, st, row_ptr, tmp, col, long_rows, n_long); }
     { ProfScope ps__(st, "k_sort_long");
       hipLaunchKernelGGL(k_sort_long, dim3(256), dim3(256), 0, st, row_ptr, tmp, col, long_rows, n_long); }
   }

@@ -97,22 +97,27 @@ __global__ void __launch_bounds__(256) k_tex_area(int64_t F, int n_mesh, const f
   const int64_t f0 = (int64_t)blockIdx.x * 256;
   const int64_t f = f0 + threadIdx.x;
   const int64_t flast = min(f0 + 255, F - 1);
-  // a block inside one mesh reduces in LDS first
   const int m0 = mesh_of_facet(facet_off, n_mesh, f0), m1 = mesh_of_facet(facet_off, n_mesh, flast);
   if (threadIdx.x == 0) { smin = 0x7f800000u; smax = 0u; }
   __syncthreads();
+  uint32_t lo = 0x7f800000u, hi = 0u;
   if (f < F) {
     const float a = facet_area(vert, facet, f);
     area[f] = a;
-    const uint32_t u = __float_as_uint(a);
-    if (m0 == m1) {
-      atomicMin(&smin, u);
-      atomicMax(&smax, u);
-    } else {
-      const int m = mesh_of_facet(facet_off, n_mesh, f);
-      atomicMin(&minmax[2 * m], u);
-      atomicMax(&minmax[2 * m + 1], u);
+    lo = hi = __float_as_uint(a);
+  }
+  if (m0 == m1) {
+    // the whole block lies in one mesh: waves reduce by shuffles, then one LDS atomic per wave
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+      lo = min(lo, (uint32_t)__shfl_xor((int)lo, o, 64));
+      hi = max(hi, (uint32_t)__shfl_xor((int)hi, o, 64));
     }
+    if ((threadIdx.x & 63) == 0) { atomicMin(&smin, lo); atomicMax(&smax, hi); }
+  } else if (f < F) {
+    const int m = mesh_of_facet(facet_off, n_mesh, f);
+    atomicMin(&minmax[2 * m], lo);
+    atomicMax(&minmax[2 * m + 1], hi);
   }
   __syncthreads();
   if (m0 == m1 && threadIdx.x == 0) {

@@ -8,12 +8,13 @@
 //
 // One kernel walks a list of (row, entries) in three modes:
 //   0  rows = queries, entries = neighbour ids:            y_i  = w_i sum_e s_e (.) h[q_e]
-//   2  the same plus the coefficient gradients:            dalpha' += B'_e^T (h[q_e] (.) dy_i w_i)
+//   2  the same walk for the coefficient gradients:        dalpha' += B'_e^T (h[q_e] (.) dy_i w_i)
 //   1  rows = sources, entries = pair ids of the reverse lists:  dh_q = sum_e s_e (.) dy_{i_e} w_{i_e}
-// (w_i = 1/|N(i)|).  Lane layout and matrix-core use as in the mesh kernel: a wave owns 64 rows, one lane per row
-// evaluates the basis of the row's j-th entry into the wave's LDS rows, then four sub-steps of 16 rows x 64
-// channels contract B' with alpha' (and B'^T with the products) in 16x16x4 fp32 tiles; the sums over a row's
-// entries stay in registers (j runs to the longest list of the wave), so nothing per pair reaches memory.
+// (w_i = 1/|N(i)|).  Lane layout and matrix-core use as in the mesh kernel, with the wave's 64 LDS basis rows
+// holding four entries of each of 16 rows: lane (row, slot) evaluates the basis of the row's (4 j + slot)-th
+// entry, then the four sub-steps (one per slot) of 16 rows x 64 channels contract B' with alpha' (and B'^T with
+// the products) in 16x16x4 fp32 tiles; the sums over a row's entries stay in 16 registers (j runs to the
+// longest list of the 16 rows), so nothing per pair reaches memory.
 #include "pm_rows.h"
 #include "pm_chan.h"
 
@@ -41,7 +42,7 @@ struct PcP {
   const float* dy;          // mode 2: dy [R][C] fp32
   const float* alpha;       // [K][C]
   const float* c0;          // [C]
-  void* out;                // [R][C] feature dtype (mode 2: may be NULL)
+  void* out;                // [R][C] feature dtype (modes 0 and 1)
   float* partial;           // mode 2: [grid][K+1][C]
 };
 
@@ -62,9 +63,9 @@ __global__ void __launch_bounds__(256) k_pc_dw(PcP p) {
   float* Wt = Bw + 64 * KP + 64;                               // [64] weight of the gathered row (mode 1)
   float* Wrow = Bw + 64 * KP + 128;                            // [64] 1/|N(row)|
   float* red = pc_lds + nk4 * 4 * PC_RW + 4 * per_wave;        // [PC_KC + 1][64] (mode 2)
-  const bool want_s = MODE != 2 || p.out != nullptr;
+  constexpr bool want_s = MODE != 2;                           // the coefficient pass needs no filter values
   const int nrun = (p.C + PC_RW - 1) / PC_RW;
-  const int64_t n_ss = (p.R + 63) >> 6;
+  const int64_t n_ss = (p.R + 15) >> 4;                        // a wave step covers 16 rows, four entries of each
 
   for (int cr = 0; cr < nrun; ++cr) {
     const int c0 = cr * PC_RW + sub * CPL;
@@ -87,8 +88,8 @@ __global__ void __launch_bounds__(256) k_pc_dw(PcP p) {
     for (int t = 0; t < 4; ++t) D[t] = floatx4{0.f, 0.f, 0.f, 0.f};
 
     for (int64_t ss = (int64_t)blockIdx.x * 4 + wave; ss < n_ss; ss += (int64_t)gridDim.x * 4) {
-      const int64_t R0 = ss << 6;
-      const int64_t row_l = R0 + lane;
+      const int64_t R0 = ss << 4;
+      const int64_t row_l = R0 + sub;          // basis evaluation: lane = (row sub, entry slot g) -> LDS slot `lane`
       int32_t b = 0, e = 0;
       float xr[3] = {0.f, 0.f, 0.f};
       if (row_l < p.R) {
@@ -99,17 +100,34 @@ __global__ void __launch_bounds__(256) k_pc_dw(PcP p) {
 #pragma unroll
       for (int o = 32; o > 0; o >>= 1) maxdeg = max(maxdeg, __shfl_xor(maxdeg, o, 64));
       __builtin_amdgcn_wave_barrier();
-      Wrow[lane] = 1.0f / (float)max(e - b, 1);
-      float acc[4][4][CPL];
+      Wrow[sub] = 1.0f / (float)max(e - b, 1);     // (the four lanes of a row write the same value)
+      __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      float acc[4][CPL], dyr[MODE == 2 ? 4 : 1][CPL];
 #pragma unroll
-      for (int s4 = 0; s4 < 4; ++s4)
+      for (int q = 0; q < 4; ++q)
 #pragma unroll
-        for (int q = 0; q < 4; ++q)
+        for (int t = 0; t < CPL; ++t) acc[q][t] = 0.f;
+      if constexpr (MODE == 2) {
+        // the rows' own gradient, weighted: (dy_i / |N(i)|)[c]
 #pragma unroll
-          for (int t = 0; t < CPL; ++t) acc[s4][q][t] = 0.f;
+        for (int q = 0; q < 4; ++q) {
+          const int64_t row = min(R0 + 4 * g + q, p.R - 1);
+          const int32_t d = p.ptr[row + 1] - p.ptr[row];
+          if (VEC || cok) chan_load_f32<CPL, VEC>(p.dy, row * p.C, p.C, cl, dyr[q]);
+          else {
+#pragma unroll
+            for (int t = 0; t < CPL; ++t) dyr[q][t] = 0.f;
+          }
+          const float wr = 1.0f / (float)max(d, 1);
+#pragma unroll
+          for (int t = 0; t < CPL; ++t) dyr[q][t] *= wr;
+        }
+      }
 
-      for (int j = 0; j < maxdeg; ++j) {
-        __builtin_amdgcn_wave_barrier();        // the previous entry's basis rows have been read
+      for (int j4 = 0; j4 < maxdeg; j4 += 4) {
+        __builtin_amdgcn_wave_barrier();        // the previous entries' basis rows have been read
+        const int j = j4 + g;                   // this lane's entry of its row
         const bool has = b + j < e;
         if (has) {
           int32_t other = p.ent[b + j];
@@ -155,7 +173,7 @@ __global__ void __launch_bounds__(256) k_pc_dw(PcP p) {
 #pragma unroll
             for (int t = 0; t < CPL; ++t) hv[q][t] = ok ? hv[q][t] * wv : 0.f;
           }
-          if (want_s) {
+          if constexpr (want_s) {
             floatx4 S[4];
 #pragma unroll
             for (int t = 0; t < 4; ++t) S[t] = floatx4{0.f, 0.f, 0.f, 0.f};
@@ -172,23 +190,15 @@ __global__ void __launch_bounds__(256) k_pc_dw(PcP p) {
 #pragma unroll
             for (int q = 0; q < 4; ++q)
 #pragma unroll
-              for (int t = 0; t < 4; ++t) acc[s4][q][t] += hv[q][t] * S[t][q];
+              for (int t = 0; t < 4; ++t) acc[q][t] += hv[q][t] * S[t][q];
           }
           if constexpr (MODE == 2) {
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
               const int rr = 16 * s4 + 4 * g + q;
-              const int64_t row = min(R0 + rr, p.R - 1);
-              float dyr[CPL];
-              if (VEC || cok) chan_load_f32<CPL, VEC>(p.dy, row * p.C, p.C, cl, dyr);
-              else {
-#pragma unroll
-                for (int t = 0; t < CPL; ++t) dyr[t] = 0.f;
-              }
-              const float wr = Wrow[rr];
               float pe[CPL];
 #pragma unroll
-              for (int t = 0; t < CPL; ++t) pe[t] = hv[q][t] * dyr[t] * wr;      // hv is 0 where there is no pair
+              for (int t = 0; t < CPL; ++t) pe[t] = hv[q][t] * dyr[q][t];      // hv is 0 where there is no pair
               const float bv = Bw[rr * KP + p.kc0 + min(sub, kn - 1)];
               const float a = sub < kn ? bv : 0.f;
 #pragma unroll
@@ -202,19 +212,16 @@ __global__ void __launch_bounds__(256) k_pc_dw(PcP p) {
           }
         }
       }
-      if (want_s && p.out) {
+      if constexpr (want_s) {
 #pragma unroll
-        for (int s4 = 0; s4 < 4; ++s4)
+        for (int q = 0; q < 4; ++q) {
+          const int64_t row = R0 + 4 * g + q;
+          const float w = MODE == 1 ? 1.f : Wrow[4 * g + q];
+          float o[CPL];
 #pragma unroll
-          for (int q = 0; q < 4; ++q) {
-            const int rr = 16 * s4 + 4 * g + q;
-            const int64_t row = R0 + rr;
-            const float w = MODE == 1 ? 1.f : Wrow[rr];
-            float o[CPL];
-#pragma unroll
-            for (int t = 0; t < CPL; ++t) o[t] = acc[s4][q][t] * w;
-            if (row < p.R && cok) chan_store<BF16, CPL, VEC>(p.out, row * p.C, p.C, c0, o);
-          }
+          for (int t = 0; t < CPL; ++t) o[t] = acc[q][t] * w;
+          if (row < p.R && cok) chan_store<BF16, CPL, VEC>(p.out, row * p.C, p.C, c0, o);
+        }
       }
     }
     if constexpr (MODE == 2) {
@@ -257,10 +264,10 @@ __global__ void __launch_bounds__(256) k_pc_dw(PcP p) {
   }
 }
 
-#define PC_GRID 2048
+#define PC_GRID 4096
 #define PC_GRID_BWD 1024
 static int pc_grid(int64_t R, int cap) {
-  int64_t nblk = (((R + 63) >> 6) + 3) >> 2;
+  int64_t nblk = (((R + 15) >> 4) + 3) >> 2;      // four waves per block, 16 rows per wave step
   if (nblk > cap) nblk = cap;
   return nblk < 1 ? 1 : (int)nblk;
 }
@@ -303,22 +310,21 @@ pm_status pm_launch_pc_dw(int64_t M, int64_t N, int K, int C, int is_bf16, float
   return pc_launch<0>(p, is_bf16, chan_vec_ok(C, is_bf16, h, y, nullptr), pc_grid(M, PC_GRID), st);
 }
 
-// dalpha [K][C], dc0 [C] (through `partial`, pm_pc_coef_ws_bytes) and y [M][C] (feature dtype, for dP);
-// dy [M][C] fp32 is the gradient of the depth-wise output before the 1/|N(i)| weight
+// dalpha [K][C], dc0 [C] (through `partial`, pm_pc_coef_ws_bytes); dy [M][C] fp32 is the gradient of the
+// depth-wise output before the 1/|N(i)| weight
 pm_status pm_launch_pc_dw_coef(int64_t M, int64_t N, int K, int C, int is_bf16, float rho, const ShTable& sh,
                                const float* xq, const float* xs, const int32_t* nbr_ptr, const int32_t* nbr_idx,
-                               const void* h, const float* alpha, const float* c0, const float* dy, void* y,
-                               float* dalpha, float* dc0, float* partial, hipStream_t st) {
+                               const void* h, const float* alpha, const float* c0, const float* dy, float* dalpha,
+                               float* dc0, float* partial, hipStream_t st) {
   const int grid = pc_grid(M, PC_GRID_BWD);
   const int64_t slice = (int64_t)(K + 1) * C;
   if (M > 0) {
     PcP p = pc_params(K, C, rho, sh, alpha, c0);
     p.R = M; p.n_other = N; p.x_row = xq; p.x_other = xs; p.ptr = nbr_ptr; p.ent = nbr_idx; p.G = h; p.dy = dy;
     p.partial = partial;
-    const bool vec = chan_vec_ok(C, is_bf16, h, y, dy);
+    const bool vec = chan_vec_ok(C, is_bf16, h, dy, nullptr);
     for (int k0 = 0; k0 < K; k0 += PC_KC) {
       p.kc0 = k0;
-      p.out = k0 == 0 ? y : nullptr;
       PC_TRY(pc_launch<2>(p, is_bf16, vec, grid, st));
     }
   }
