@@ -100,15 +100,21 @@ __global__ void k_scatter(int64_t n3, const int32_t* __restrict__ facet, int32_t
   }
 }
 
-// rank sort of short rows (entries are distinct); long rows are queued for k_sort_long
+// rank sort of short rows (entries are distinct); longer rows are queued: medium ones from the front of
+// `long_rows` (count n_long[1]) for k_sort_mid, long ones from its back (count n_long[0]) for k_sort_long
 __global__ void k_sort_short(int64_t V, const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ tmp,
                              int32_t* __restrict__ col, int32_t* __restrict__ long_rows, int32_t* __restrict__ n_long) {
   int64_t v = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (v >= V) return;
   int32_t b = row_ptr[v], e = row_ptr[v + 1];
   int32_t d = e - b;
+  if (d > MID_ROW) {
+    int32_t slot = atomicAdd(&n_long[0], 1);
+    long_rows[V - 1 - slot] = (int32_t)v;
+    return;
+  }
   if (d > SHORT_ROW) {
-    int32_t slot = atomicAdd(n_long, 1);
+    int32_t slot = atomicAdd(&n_long[1], 1);
     long_rows[slot] = (int32_t)v;
     return;
   }
@@ -128,11 +134,10 @@ __global__ void __launch_bounds__(256) k_sort_mid(const int32_t* __restrict__ ro
   __shared__ int32_t tiles[4][MID_ROW];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   int32_t* tile = tiles[wave];
-  const int32_t nl = *n_long;
+  const int32_t nl = n_long[1];
   for (int32_t q = blockIdx.x * 4 + wave; q < nl; q += gridDim.x * 4) {
     const int32_t v = long_rows[q];
     const int32_t b = row_ptr[v], d = row_ptr[v + 1] - b;
-    if (d > MID_ROW) continue;                     // left to k_sort_long
     __builtin_amdgcn_wave_barrier();
     for (int i = lane; i < d; i += 64) tile[i] = tmp[b + i];
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
@@ -146,15 +151,15 @@ __global__ void __launch_bounds__(256) k_sort_mid(const int32_t* __restrict__ ro
   }
 }
 
-__global__ void __launch_bounds__(256) k_sort_long(const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ tmp,
-                                                   int32_t* __restrict__ col, const int32_t* __restrict__ long_rows,
+__global__ void __launch_bounds__(256) k_sort_long(int64_t V, const int32_t* __restrict__ row_ptr,
+                                                   const int32_t* __restrict__ tmp, int32_t* __restrict__ col,
+                                                   const int32_t* __restrict__ long_rows,
                                                    const int32_t* __restrict__ n_long) {
   __shared__ int32_t tile[1024];
-  const int32_t nl = *n_long;
+  const int32_t nl = n_long[0];
   for (int32_t q = blockIdx.x; q < nl; q += gridDim.x) {
-    int32_t v = long_rows[q];
+    int32_t v = long_rows[V - 1 - q];
     int32_t b = row_ptr[v], e = row_ptr[v + 1];
-    if (e - b <= MID_ROW) continue;                // done by k_sort_mid (the same for the whole workgroup)
     // every thread owns entries i = b + t, b + t + 256, ...; ranks accumulate over LDS tiles of the row
     for (int32_t i0 = b; i0 < e; i0 += 256) {
       int32_t i = i0 + threadIdx.x;
@@ -234,7 +239,7 @@ pm_status pm_launch_csr(int64_t V, int64_t n3, const int32_t* keys, int32_t* row
   { ProfScope ps__(st, "k_fill_i32");
     hipLaunchKernelGGL(k_fill_i32, dim3(nblk(V + 1, 256)), dim3(256), 0, st, cnt, V + 1, 0); }
   { ProfScope ps__(st, "k_fill_i32");
-    hipLaunchKernelGGL(k_fill_i32, dim3(1), dim3(64), 0, st, n_long, (int64_t)1, 0); }
+    hipLaunchKernelGGL(k_fill_i32, dim3(1), dim3(64), 0, st, n_long, (int64_t)2, 0); }
   if (V == 0) {
     { ProfScope ps__(st, "k_fill_i32");
       hipLaunchKernelGGL(k_fill_i32, dim3(1), dim3(64), 0, st, row_ptr, (int64_t)1, 0); }
@@ -256,7 +261,7 @@ pm_status pm_launch_csr(int64_t V, int64_t n3, const int32_t* keys, int32_t* row
     { ProfScope ps__(st, "k_sort_mid");
       hipLaunchKernelGGL(k_sort_mid, dim3(2048), dim3(256), 0, st, row_ptr, tmp, col, long_rows, n_long); }
     { ProfScope ps__(st, "k_sort_long");
-      hipLaunchKernelGGL(k_sort_long, dim3(256), dim3(256), 0, st, row_ptr, tmp, col, long_rows, n_long); }
+      hipLaunchKernelGGL(k_sort_long, dim3(256), dim3(256), 0, st, V, row_ptr, tmp, col, long_rows, n_long); }
   }
   PM_CHECK_LAUNCH("adjacency");
   return PM_OK;

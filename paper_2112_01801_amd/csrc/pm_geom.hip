@@ -89,41 +89,49 @@ __device__ __forceinline__ int mesh_of_facet(const int32_t* __restrict__ facet_o
 }
 
 // areas (non-negative, so their bit patterns order like the values) and the per-mesh extremes through integer
-// atomics on the bit patterns: exact and order-independent
-__global__ void __launch_bounds__(256) k_tex_area(int64_t F, int n_mesh, const float* __restrict__ vert,
+// atomics on the bit patterns: exact and order-independent.  A block walks a contiguous chunk of facets in
+// tiles of 256; tiles inside one mesh accumulate in registers and reach memory once per block and mesh (waves
+// reduce by shuffles, then LDS, then one pair of global atomics); a tile that straddles meshes goes direct.
+__global__ void __launch_bounds__(256) k_tex_area(int64_t F, int64_t chunk, int n_mesh, const float* __restrict__ vert,
                                                   const int32_t* __restrict__ facet, const int32_t* __restrict__ facet_off,
                                                   float* __restrict__ area, uint32_t* __restrict__ minmax) {
   __shared__ uint32_t smin, smax;
-  const int64_t f0 = (int64_t)blockIdx.x * 256;
-  const int64_t f = f0 + threadIdx.x;
-  const int64_t flast = min(f0 + 255, F - 1);
-  const int m0 = mesh_of_facet(facet_off, n_mesh, f0), m1 = mesh_of_facet(facet_off, n_mesh, flast);
-  if (threadIdx.x == 0) { smin = 0x7f800000u; smax = 0u; }
-  __syncthreads();
+  const int64_t f_begin = (int64_t)blockIdx.x * chunk, f_end = min(F, f_begin + chunk);
   uint32_t lo = 0x7f800000u, hi = 0u;
-  if (f < F) {
-    const float a = facet_area(vert, facet, f);
-    area[f] = a;
-    lo = hi = __float_as_uint(a);
-  }
-  if (m0 == m1) {
-    // the whole block lies in one mesh: waves reduce by shuffles, then one LDS atomic per wave
+  int m_cur = -1;
+  auto flush = [&]() {                      // the same for the whole block
+    if (m_cur >= 0) {
+      if (threadIdx.x == 0) { smin = 0x7f800000u; smax = 0u; }
+      __syncthreads();
 #pragma unroll
-    for (int o = 32; o > 0; o >>= 1) {
-      lo = min(lo, (uint32_t)__shfl_xor((int)lo, o, 64));
-      hi = max(hi, (uint32_t)__shfl_xor((int)hi, o, 64));
+      for (int o = 32; o > 0; o >>= 1) {
+        lo = min(lo, (uint32_t)__shfl_xor((int)lo, o, 64));
+        hi = max(hi, (uint32_t)__shfl_xor((int)hi, o, 64));
+      }
+      if ((threadIdx.x & 63) == 0) { atomicMin(&smin, lo); atomicMax(&smax, hi); }
+      __syncthreads();
+      if (threadIdx.x == 0) { atomicMin(&minmax[2 * m_cur], smin); atomicMax(&minmax[2 * m_cur + 1], smax); }
+      __syncthreads();
     }
-    if ((threadIdx.x & 63) == 0) { atomicMin(&smin, lo); atomicMax(&smax, hi); }
-  } else if (f < F) {
-    const int m = mesh_of_facet(facet_off, n_mesh, f);
-    atomicMin(&minmax[2 * m], lo);
-    atomicMax(&minmax[2 * m + 1], hi);
+    lo = 0x7f800000u; hi = 0u;
+  };
+  for (int64_t t0 = f_begin; t0 < f_end; t0 += 256) {
+    const int64_t f = t0 + threadIdx.x;
+    const int m0 = mesh_of_facet(facet_off, n_mesh, t0), m1 = mesh_of_facet(facet_off, n_mesh, min(t0 + 255, f_end - 1));
+    if (m0 == m1 && m0 != m_cur) { flush(); m_cur = m0; }
+    if (f < f_end) {
+      const float a = facet_area(vert, facet, f);
+      area[f] = a;
+      const uint32_t u = __float_as_uint(a);
+      if (m0 == m1) { lo = min(lo, u); hi = max(hi, u); }
+      else {
+        const int m = mesh_of_facet(facet_off, n_mesh, f);
+        atomicMin(&minmax[2 * m], u);
+        atomicMax(&minmax[2 * m + 1], u);
+      }
+    }
   }
-  __syncthreads();
-  if (m0 == m1 && threadIdx.x == 0) {
-    atomicMin(&minmax[2 * m0], smin);
-    atomicMax(&minmax[2 * m0 + 1], smax);
-  }
+  flush();
 }
 
 __global__ void __launch_bounds__(256) k_tex_gamma(int64_t F, int n_mesh, const int32_t* __restrict__ facet_off,
@@ -191,8 +199,12 @@ pm_status pm_launch_texture_layout(const pm_mesh* mesh, int alpha, int beta, int
     const dim3 grid((unsigned)((F + 255) / 256));
     { ProfScope ps__(st, "k_tex_init_minmax");
       hipLaunchKernelGGL(k_tex_init_minmax, dim3((unsigned)((n_mesh + 255) / 256)), dim3(256), 0, st, n_mesh, minmax); }
+    int64_t nblk = (F + 255) / 256;
+    if (nblk > 1024) nblk = 1024;
+    const int64_t chunk = ((F + nblk - 1) / nblk + 255) / 256 * 256;
     { ProfScope ps__(st, "k_tex_area");
-      hipLaunchKernelGGL(k_tex_area, grid, dim3(256), 0, st, F, n_mesh, mesh->vert, mesh->facet, mesh->facet_off, area, minmax); }
+      hipLaunchKernelGGL(k_tex_area, dim3((unsigned)((F + chunk - 1) / chunk)), dim3(256), 0, st, F, chunk, n_mesh, mesh->vert,
+                         mesh->facet, mesh->facet_off, area, minmax); }
     { ProfScope ps__(st, "k_tex_gamma");
       hipLaunchKernelGGL(k_tex_gamma, grid, dim3(256), 0, st, F, n_mesh, mesh->facet_off, area, minmax, alpha, beta, gamma, cnt); }
     PM_CHECK_LAUNCH("texture layout");
