@@ -62,3 +62,43 @@ def test_argument_errors_before_any_gpu_work(pm):
     assert s == -1
     s = lib.pm_f2f(10, 5, None, None, 2, 0, 3, 8, 0, None, None, None, None, 0, None)
     assert s == -1
+
+
+def test_workspace_sizes_of_the_later_operators(pm):
+    lib = pm.lib()
+    for op in range(7, 11):                               # separable operators
+        assert pm.pm_workspace_bytes(op, 100, 200, 0, 3, 16, 24, pm.PM_BF16) > 0
+    assert pm.pm_workspace_bytes(11, 100, 200, 0, 3, 16, 24, pm.PM_BF16) == 0
+    assert 0 < lib.pm_cluster_ws_bytes(1000, 300) < lib.pm_cluster_ws_bytes(4000, 300)
+    assert lib.pm_cluster_ws_bytes(-1, 3) == 0
+    assert 0 < lib.pm_texture_ws_bytes(1000, 1) < lib.pm_texture_ws_bytes(9000, 4)
+    fwd = lib.pm_pcloud_ws_bytes(0, 1000, 1000, 30000, 3, 64, 64, pm.PM_BF16)
+    bwd = lib.pm_pcloud_ws_bytes(1, 1000, 1000, 30000, 3, 64, 64, pm.PM_BF16)
+    assert 0 < fwd < bwd
+    assert lib.pm_pcloud_ws_bytes(0, 1000, 1000, 30000, 7, 64, 64, pm.PM_BF16) == 0
+
+
+def test_argument_errors_of_the_later_operators(pm):
+    lib = pm.lib()
+    m = pm._PmMesh()
+    m.n_mesh, m.n_vert, m.n_facet = 1, 10, 10
+    a = pm._PmAdj()
+    # separable: NULL mesh arrays, then parameter gradients that do not come together
+    assert lib.pm_f2v_sep(C.byref(m), C.byref(a), 3, 0, 8, 8, 0, None, None, None, None, None, 0, None) == -1
+    assert lib.pm_v2f_sep(C.byref(m), 9, 0, 8, 8, 0, None, None, None, None, None, 0, None) == -2
+    # pooling: NULL map, unknown mode, bad channel count
+    assert lib.pm_pool(None, 0, 8, 0, None, None, None, None) == -1
+    cm = pm._PmClusterMap()
+    cm.n_in, cm.n_out = 0, 0
+    assert lib.pm_pool(C.byref(cm), 7, 8, 0, None, None, None, None) == -1 or lib.pm_pool(C.byref(cm), 7, 8, 0, None, None, None, None) == -2
+    assert lib.pm_unpool(C.byref(cm), 0, 0, None, None, None) == -1
+    assert lib.pm_build_cluster_map(-1, 3, None, None, None, None, None, None, 0, None) == -1
+    # neighbour lists: NULL struct, non-positive radius
+    assert lib.pm_pcloud_conv(None, 3, 0, 8, 8, 0, None, None, None, None, None, None, 0, None) == -1
+    nb = pm._PmNbr()
+    nb.n_query, nb.n_source, nb.nnz, nb.rho = 0, 0, 0, 0.0
+    assert lib.pm_validate_neighbors(C.byref(nb), None, 0, None) == -1
+    # input preparation: bad Eq. 8 parameters, NULL outputs
+    assert lib.pm_texture_layout(C.byref(m), -1, 0, None, None, None, 0, None) == -1
+    assert lib.pm_texture_bary(-3, None, None, 0, None, None) == -1
+    assert lib.pm_facet_geometry(C.byref(m), 0, 5, None, None) == -1 or lib.pm_facet_geometry(C.byref(m), 0, 5, None, None) == -2
