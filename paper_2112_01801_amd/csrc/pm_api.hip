@@ -833,9 +833,8 @@ extern "C" pm_status pm_pcloud_conv_bwd(const pm_nbr* nb, int L, pm_sh_norm norm
   RowSrc gs = row_src(dg, dtype, cout);
   PM_TRY(pm_launch_conv_rows(dtype, B_ONE, X_DIRECT, M, 1, cout, cin, basis_none(), gs, apack, dy, 0, st));
   if (dalpha) {
-    // the depth-wise output y is recomputed for dP; the coefficient pass walks the same lists without it
-    PM_TRY(pm_launch_pc_dw(M, N, K, cin, fb, nb->rho, sh, nb->xq, nb->xs, nb->ptr, nb->idx, h, alpha, c0, y, st));
-    PM_TRY(pm_launch_pc_dw_coef(M, N, K, cin, fb, nb->rho, sh, nb->xq, nb->xs, nb->ptr, nb->idx, h, alpha, c0, dy,
+    // one walk over the lists gives the coefficient gradients and recomputes the depth-wise output y for dP
+    PM_TRY(pm_launch_pc_dw_coef(M, N, K, cin, fb, nb->rho, sh, nb->xq, nb->xs, nb->ptr, nb->idx, h, alpha, c0, dy, y,
                                 dalpha, dc0, (float*)tail, st));
     RowSrc ys = row_src(y, dtype, cin);
     PM_TRY(pm_launch_wgrad(dtype, B_ONE, X_DIRECT, X_DIRECT, M, 1, cin, cout, basis_none(), ys, gs, dP, tail, w.tail,

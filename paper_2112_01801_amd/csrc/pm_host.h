@@ -166,8 +166,8 @@ pm_status pm_launch_pc_dw(int64_t M, int64_t N, int K, int C, int is_bf16, float
                           const float* alpha, const float* c0, void* y, hipStream_t st);
 pm_status pm_launch_pc_dw_coef(int64_t M, int64_t N, int K, int C, int is_bf16, float rho, const ShTable& sh,
                                const float* xq, const float* xs, const int32_t* nbr_ptr, const int32_t* nbr_idx,
-                               const void* h, const float* alpha, const float* c0, const float* dy, float* dalpha,
-                               float* dc0, float* partial, hipStream_t st);
+                               const void* h, const float* alpha, const float* c0, const float* dy, void* y,
+                               float* dalpha, float* dc0, float* partial, hipStream_t st);
 pm_status pm_launch_pc_dw_dh(int64_t M, int64_t N, int K, int C, int is_bf16, float rho, const ShTable& sh,
                              const float* xq, const float* xs, const int32_t* nbr_ptr, const int32_t* rev_ptr,
                              const int32_t* rev_col, const int32_t* owner, const float* alpha, const float* c0,

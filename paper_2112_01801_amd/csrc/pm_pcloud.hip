@@ -8,7 +8,7 @@
 //
 // One kernel walks a list of (row, entries) in three modes:
 //   0  rows = queries, entries = neighbour ids:            y_i  = w_i sum_e s_e (.) h[q_e]
-//   2  the same walk for the coefficient gradients:        dalpha' += B'_e^T (h[q_e] (.) dy_i w_i)
+//   2  the same walk plus the coefficient gradients:       dalpha' += B'_e^T (h[q_e] (.) dy_i w_i)
 //   1  rows = sources, entries = pair ids of the reverse lists:  dh_q = sum_e s_e (.) dy_{i_e} w_{i_e}
 // (w_i = 1/|N(i)|).  Lane layout and matrix-core use as in the mesh kernel, with the wave's 64 LDS basis rows
 // holding four entries of each of 16 rows: lane (row, slot) evaluates the basis of the row's (4 j + slot)-th
@@ -42,7 +42,7 @@ struct PcP {
   const float* dy;          // mode 2: dy [R][C] fp32
   const float* alpha;       // [K][C]
   const float* c0;          // [C]
-  void* out;                // [R][C] feature dtype (modes 0 and 1)
+  void* out;                // [R][C] feature dtype (mode 2: may be NULL)
   float* partial;           // mode 2: [grid][K+1][C]
 };
 
@@ -63,7 +63,7 @@ __global__ void __launch_bounds__(256) k_pc_dw(PcP p) {
   float* Wt = Bw + 64 * KP + 64;                               // [64] weight of the gathered row (mode 1)
   float* Wrow = Bw + 64 * KP + 128;                            // [64] 1/|N(row)|
   float* red = pc_lds + nk4 * 4 * PC_RW + 4 * per_wave;        // [PC_KC + 1][64] (mode 2)
-  constexpr bool want_s = MODE != 2;                           // the coefficient pass needs no filter values
+  const bool want_s = MODE != 2 || p.out != nullptr;           // a coefficient pass without output needs no filter values
   const int nrun = (p.C + PC_RW - 1) / PC_RW;
   const int64_t n_ss = (p.R + 15) >> 4;                        // a wave step covers 16 rows, four entries of each
 
@@ -173,7 +173,7 @@ __global__ void __launch_bounds__(256) k_pc_dw(PcP p) {
 #pragma unroll
             for (int t = 0; t < CPL; ++t) hv[q][t] = ok ? hv[q][t] * wv : 0.f;
           }
-          if constexpr (want_s) {
+          if (want_s) {
             floatx4 S[4];
 #pragma unroll
             for (int t = 0; t < 4; ++t) S[t] = floatx4{0.f, 0.f, 0.f, 0.f};
@@ -212,7 +212,7 @@ __global__ void __launch_bounds__(256) k_pc_dw(PcP p) {
           }
         }
       }
-      if constexpr (want_s) {
+      if (want_s) {
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
           const int64_t row = R0 + 4 * g + q;
@@ -310,21 +310,22 @@ pm_status pm_launch_pc_dw(int64_t M, int64_t N, int K, int C, int is_bf16, float
   return pc_launch<0>(p, is_bf16, chan_vec_ok(C, is_bf16, h, y, nullptr), pc_grid(M, PC_GRID), st);
 }
 
-// dalpha [K][C], dc0 [C] (through `partial`, pm_pc_coef_ws_bytes); dy [M][C] fp32 is the gradient of the
-// depth-wise output before the 1/|N(i)| weight
+// dalpha [K][C], dc0 [C] (through `partial`, pm_pc_coef_ws_bytes) and, in the same walk, y [M][C] (feature
+// dtype, for dP); dy [M][C] fp32 is the gradient of the depth-wise output before the 1/|N(i)| weight
 pm_status pm_launch_pc_dw_coef(int64_t M, int64_t N, int K, int C, int is_bf16, float rho, const ShTable& sh,
                                const float* xq, const float* xs, const int32_t* nbr_ptr, const int32_t* nbr_idx,
-                               const void* h, const float* alpha, const float* c0, const float* dy, float* dalpha,
-                               float* dc0, float* partial, hipStream_t st) {
+                               const void* h, const float* alpha, const float* c0, const float* dy, void* y,
+                               float* dalpha, float* dc0, float* partial, hipStream_t st) {
   const int grid = pc_grid(M, PC_GRID_BWD);
   const int64_t slice = (int64_t)(K + 1) * C;
   if (M > 0) {
     PcP p = pc_params(K, C, rho, sh, alpha, c0);
     p.R = M; p.n_other = N; p.x_row = xq; p.x_other = xs; p.ptr = nbr_ptr; p.ent = nbr_idx; p.G = h; p.dy = dy;
     p.partial = partial;
-    const bool vec = chan_vec_ok(C, is_bf16, h, dy, nullptr);
+    const bool vec = chan_vec_ok(C, is_bf16, h, dy, y);
     for (int k0 = 0; k0 < K; k0 += PC_KC) {
       p.kc0 = k0;
+      p.out = k0 == 0 ? y : nullptr;
       PC_TRY(pc_launch<2>(p, is_bf16, vec, grid, st));
     }
   }
