@@ -102,11 +102,54 @@ def main():
         pm.pm_f2v(mesh, adj, cfg.L, h_d, W_d, DT, out=g, ws=ws_f)
         pm.pm_f2v_bwd(mesh, adj, cfg.L, h_d, W_d, dg_d, DT, dh=dh, dW=dW, ws=ws_b)
 
+    models = kernel_models(F, V, K, cin, cout, 2)
+
+    def kernel_table(recs, n_steps):
+        agg = {}
+        for name, ms in recs:
+            a = agg.setdefault(name, [0.0, 0])
+            a[0] += ms
+            a[1] += 1
+        rows = []
+        for name, (tot, cnt) in agg.items():
+            avg = tot / cnt
+            ent = {"kernel": name, "launches_per_step": cnt / n_steps, "avg_ms": round(avg, 5),
+                   "ms_per_step": round(tot / n_steps, 5)}
+            m = models.get(name)
+            if m:
+                if m["bound"] == "mfma":
+                    ach = m["flop"] / (avg * 1e-3) / 1e12
+                    ent.update(bound="mfma", achieved=round(ach, 2), peak=PEAK_MFMA_TFLOPS["bf16"], unit="TFLOP/s",
+                               frac=round(ach / PEAK_MFMA_TFLOPS["bf16"], 4),
+                               hbm_gbs_algorithmic=round(m["bytes"] / (avg * 1e-3) / 1e9, 1))
+                else:
+                    ach = m["bytes"] / (avg * 1e-3) / 1e9
+                    ent.update(bound="hbm", achieved=round(ach, 1), peak=PEAK_HBM_GBS, unit="GB/s",
+                               frac=round(ach / PEAK_HBM_GBS, 4))
+            rows.append(ent)
+        rows.sort(key=lambda k: -k["ms_per_step"])
+        return rows
+
+    # Warm-up.  Every kernel of the warm-up steps is bracketed by HIP events (the `kernels` table); that finds
+    # the dominant kernel.  A pair of events costs the stream a few microseconds (14 pairs a step: ~5 % of this
+    # step), so the timed region brackets the dominant kernel alone, whose durations give `roofline`.
+    pm.pm_profile_filter("")
+    pm.pm_profile_reset()
+    pm.pm_profile_enable(True)
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-
+    pm.pm_profile_enable(False)
+    wrecs = pm.pm_profile_read()
+    wsteps = args.warmup
+    if args.warmup >= 2:                              # the first step pays one-time costs (code load, cold caches)
+        per = len(wrecs) // args.warmup
+        wrecs, wsteps = wrecs[per:], args.warmup - 1
+    warm = kernel_table(wrecs, max(wsteps, 1))
     pm.pm_profile_reset()
+    dom_name = next((k["kernel"] for k in warm if "bound" in k), "")
+
+    pm.pm_profile_filter(dom_name)
     pm.pm_profile_enable(True)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -117,38 +160,27 @@ def main():
     pm.pm_profile_enable(False)
     recs = pm.pm_profile_read()
     pm.pm_profile_reset()
+    pm.pm_profile_filter("")
     assert torch.isfinite(g.float()).all() and torch.isfinite(dW).all()
 
     ms_per_step = elapsed * 1e3 / args.steps
     value = F * args.steps / elapsed
 
-    # per-kernel averages over the timed region
-    agg = {}
-    for name, ms in recs:
-        a = agg.setdefault(name, [0.0, 0])
-        a[0] += ms
-        a[1] += 1
-    models = kernel_models(F, V, K, cin, cout, 2)
-    kernels = []
-    for name, (tot, cnt) in agg.items():
-        per_step = tot / args.steps
-        avg = tot / cnt
-        ent = {"kernel": name, "launches_per_step": cnt / args.steps, "avg_ms": round(avg, 5),
-               "ms_per_step": round(per_step, 5)}
-        m = models.get(name)
-        if m:
-            if m["bound"] == "mfma":
-                ach = m["flop"] / (avg * 1e-3) / 1e12
-                ent.update(bound="mfma", achieved=round(ach, 2), peak=PEAK_MFMA_TFLOPS["bf16"], unit="TFLOP/s",
-                           frac=round(ach / PEAK_MFMA_TFLOPS["bf16"], 4),
-                           hbm_gbs_algorithmic=round(m["bytes"] / (avg * 1e-3) / 1e9, 1))
-            else:
-                ach = m["bytes"] / (avg * 1e-3) / 1e9
-                ent.update(bound="hbm", achieved=round(ach, 1), peak=PEAK_HBM_GBS, unit="GB/s",
-                           frac=round(ach / PEAK_HBM_GBS, 4))
-        kernels.append(ent)
-    kernels.sort(key=lambda k: -k["ms_per_step"])
-    dom = next((k for k in kernels if "bound" in k), None)
+    timed = kernel_table(recs, args.steps)            # the dominant kernel over the timed region (all kernels if W = 0)
+    if warm:
+        # the other kernels: the same number of steps once more, untimed, every kernel bracketed
+        pm.pm_profile_enable(True)
+        for _ in range(args.steps):
+            step()
+        torch.cuda.synchronize()
+        pm.pm_profile_enable(False)
+        post = kernel_table(pm.pm_profile_read(), args.steps)
+        pm.pm_profile_reset()
+        kernels = [next((t for t in timed if t["kernel"] == k["kernel"]), k) for k in post]
+        kernels_from = "an untimed repeat of the timed steps with every kernel bracketed"
+    else:
+        kernels, kernels_from = timed, "timed steps"
+    dom = next((k for k in timed if "bound" in k), None)
     roofline = None
     if dom:
         roofline = {"kernel": dom["kernel"], "bound": dom["bound"], "achieved": dom["achieved"], "peak": dom["peak"],
@@ -189,6 +221,7 @@ def main():
         "cpu_baseline": cpu_baseline,
         "measured_peaks": peaks,
         "board_power": power,
+        "kernels_measured_over": kernels_from + " (the roofline kernel: timed steps)",
         "kernels": kernels,
     }
     print(json.dumps(out))

@@ -260,8 +260,11 @@ pm_status pm_texture_bary(int64_t n_facet, const int32_t* gamma, const int32_t* 
  * recorded on the call's stream (events are created on demand and reused; nothing else changes).
  * pm_profile_count() is the number of records since the last reset; pm_profile_read(i, ...) waits for
  * record i's stop event and returns its label ("<entry point>/<kernel>", truncated to name_cap-1
- * characters) and its duration in milliseconds.  pm_profile_reset() drops the records (keeps the events). */
+ * characters) and its duration in milliseconds.  pm_profile_reset() drops the records (keeps the events).
+ * pm_profile_filter(part) limits the records to kernels whose label contains `part` (NULL or "" = all): a pair
+ * of events costs the stream a few microseconds, so a timed loop brackets only the kernel it asks about. */
 pm_status pm_profile_enable(int on);
+pm_status pm_profile_filter(const char* label_part);
 int32_t pm_profile_count(void);
 pm_status pm_profile_read(int32_t i, char* name, size_t name_cap, float* ms);
 pm_status pm_profile_reset(void);

@@ -32,6 +32,7 @@ static thread_local const char* g_prof_op = "";
 static thread_local std::vector<ProfRec> g_prof_recs;
 static thread_local std::vector<hipEvent_t> g_prof_pool;
 static thread_local bool g_prof_open = false;
+static thread_local char g_prof_filter[64] = "";
 
 static hipEvent_t prof_event() {
   if (!g_prof_pool.empty()) {
@@ -51,6 +52,7 @@ void pm_prof_begin(hipStream_t st, const char* kernel) {
   if (!g_prof_on) return;
   ProfRec r;
   snprintf(r.name, sizeof(r.name), "%s/%s", g_prof_op, kernel);
+  if (g_prof_filter[0] && !strstr(r.name, g_prof_filter)) return;
   r.start = prof_event();
   r.stop = prof_event();
   if (!r.start || !r.stop) return;
@@ -67,6 +69,12 @@ void pm_prof_end(hipStream_t st) {
 
 extern "C" pm_status pm_profile_enable(int on) {
   g_prof_on = on != 0;
+  return PM_OK;
+}
+extern "C" pm_status pm_profile_filter(const char* label_part) {
+  if (!label_part) label_part = "";
+  strncpy(g_prof_filter, label_part, sizeof(g_prof_filter) - 1);
+  g_prof_filter[sizeof(g_prof_filter) - 1] = 0;
   return PM_OK;
 }
 extern "C" int32_t pm_profile_count(void) { return (int32_t)g_prof_recs.size(); }
