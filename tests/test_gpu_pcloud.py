@@ -131,3 +131,54 @@ def test_empty_lists_and_bad_lists(pm):
     bad = _nbr(pm, xq, xs, np.array([0, 1, 1, 3, 3, 3, 3], np.int32), np.array([1, 10, 3], np.int32), 0.5)
     with pytest.raises(pm.PmError):
         pm.pm_validate_neighbors(bad)
+
+
+def test_later_operators_replay_from_a_hip_graph(pm):
+    """Separable, pooling and point-cloud entry points enqueue kernels only: captured into one HIP graph (their
+    outputs and workspaces come from the graph's memory pool), replays with eager work in between reproduce
+    the eager results bit for bit -- including the sums over the reverse lists built inside the call."""
+    import torch
+    from test_gpu_parity import small_batch
+    L, cin, cout, dtype, dt = 3, 64, 64, "bf16", 1
+    rng = np.random.default_rng(340)
+    b = small_batch(34)
+    mesh = pm.mesh_to_device(b)
+    adj = pm.pm_build_vf_adjacency(mesh)
+    alpha, c0, P = _params(rng, L, cin, cout, dtype)
+    a_d, c_d, P_d = torch.from_numpy(alpha).cuda(), torch.from_numpy(c0).cuda(), to_dev(P, dtype)
+    hF = to_dev(make_features(rng, b.n_facet, cin, dtype), dtype)
+    dgV = to_dev(make_features(rng, b.n_vert, cout, dtype), dtype)
+    xq, xs, ptr, idx = _cloud(341, 500, 600, 0.12)
+    nb = _nbr(pm, xq, xs, ptr, idx, 0.12)
+    hN = to_dev(make_features(rng, 600, cin, dtype), dtype)
+    dgM = to_dev(make_features(rng, 500, cout, dtype), dtype)
+    vc, io = mg.random_cluster_maps(rng, b.n_vert, b.n_vert // 4, drop_frac=0.05, heavy=40)
+    vc_d, io_d = torch.from_numpy(vc).cuda(), torch.from_numpy(io).cuda()
+    n_used = int((io[vc] >= 0).sum())               # members that reach an output vertex: the used part of col
+
+    def work():
+        out = list(pm.pm_f2v_sep_bwd(mesh, adj, L, hF, a_d, P_d, dgV, dt))
+        out += list(pm.pm_pcloud_conv_bwd(nb, L, hN, a_d, c_d, P_d, dgM, dt))
+        cm = pm.pm_build_cluster_map(vc_d, io_d, b.n_vert // 4)
+        m, arg = pm.pm_pool(cm, pm.PM_POOL_MAX, dgV, dt)
+        out += [cm.col[:n_used], m, arg, pm.pm_unpool_bwd(cm, dgV, dt)]
+        return out
+
+    ref = [t.clone() for t in work()]
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        work()
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            res = work()
+    for rep in range(3):
+        for t in res:
+            t.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for i, (got, want) in enumerate(zip(res, ref)):
+            assert torch.equal(got, want), "replay %d, output %d differs from the eager result" % (rep, i)
