@@ -243,8 +243,8 @@ pm_status pm_facet_geometry(const pm_mesh* mesh, int with_heights, pm_dtype dtyp
 /* Texture resolution of every facet (Eq. 8): gamma[f] = floor(alpha (A_f - Amin)/(Amax - Amin)) + beta with the
  * extreme areas of the facet's own mesh (mesh->facet_off is required when n_mesh > 1; equal extremes give
  * beta), evaluated in fp32 one IEEE operation at a time in a fixed order, and tex_off [n_facet+1] = running
- * sum of the point counts (gamma+1)(gamma+2)/2.  0 <= alpha, beta and alpha + beta <= 255; the total must stay
- * below 2^31 (not checked).  ws: pm_texture_ws_bytes(n_facet, n_mesh).  The caller reads tex_off[n_facet]
+ * sum of the point counts (gamma+1)(gamma+2)/2.  0 <= alpha, beta, alpha + beta <= 255 and
+ * n_facet (alpha+beta+1)(alpha+beta+2)/2 < 2^31 (the bound on the total, checked).  ws: pm_texture_ws_bytes(n_facet, n_mesh).  The caller reads tex_off[n_facet]
  * back to size the point arrays. */
 size_t pm_texture_ws_bytes(int64_t n_facet, int32_t n_mesh); /* HOST computation; 0 on invalid sizes */
 pm_status pm_texture_layout(const pm_mesh* mesh, int alpha, int beta, int32_t* gamma, int32_t* tex_off, void* ws,

@@ -877,6 +877,13 @@ extern "C" pm_status pm_texture_layout(const pm_mesh* mesh, int alpha, int beta,
   PM_TRY(check_mesh(mesh, true));
   if (alpha < 0 || beta < 0 || alpha + beta > 255) return pm_fail(PM_ERR_INVALID_ARG, "alpha=%d beta=%d", alpha, beta);
   if (mesh->n_mesh > 1 && !mesh->facet_off) return pm_fail(PM_ERR_INVALID_ARG, "n_mesh > 1 needs facet_off");
+  {
+    // every facet may reach gamma = alpha + beta: the running point count must fit the int32 offsets
+    const int64_t gmax = alpha + beta, kmax = (gmax + 1) * (gmax + 2) / 2;
+    if (mesh->n_facet * kmax >= kMaxIds)
+      return pm_fail(PM_ERR_INVALID_ARG, "%lld facets with up to %lld points each exceed the int32 offsets",
+                     (long long)mesh->n_facet, (long long)kmax);
+  }
   if (!tex_off || (mesh->n_facet > 0 && !gamma)) return pm_fail(PM_ERR_INVALID_ARG, "gamma / tex_off is NULL");
   PM_TRY(check_ptr(ws, "ws", true));
   const size_t need = pm_texture_ws_bytes_host(mesh->n_facet, mesh->n_mesh);

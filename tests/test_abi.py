@@ -101,4 +101,8 @@ def test_argument_errors_of_the_later_operators(pm):
     # input preparation: bad Eq. 8 parameters, NULL outputs
     assert lib.pm_texture_layout(C.byref(m), -1, 0, None, None, None, 0, None) == -1
     assert lib.pm_texture_bary(-3, None, None, 0, None, None) == -1
+    big = pm._PmMesh()
+    big.n_mesh, big.n_vert, big.n_facet = 1, 10, 2_000_000_000
+    big.vert, big.facet = 256, 256                       # never dereferenced: the size check comes first
+    assert lib.pm_texture_layout(C.byref(big), 3, 1, None, None, None, 0, None) == -1 and b"int32" in lib.pm_last_error()
     assert lib.pm_facet_geometry(C.byref(m), 0, 5, None, None) == -1 or lib.pm_facet_geometry(C.byref(m), 0, 5, None, None) == -2
