@@ -246,6 +246,7 @@ def all_ops(args, cfg, pm, mg, torch):
     # separable form: W[k, ci, co] = alpha[k, ci] * Pw[ci, co]
     alpha = (torch.rand(K, cin, device="cuda", generator=gen) * 2 - 1) / K ** 0.5
     Pw = ((torch.rand(cin, cout, device="cuda", generator=gen) * 2 - 1) * (3.0 / cin) ** 0.5).to(tdt)
+    _, zV = pm.pm_f2v_sep(mesh, adj, L, hF, alpha, Pw, DT, save_z=True)
     ops = {
         "f2v": (lambda: pm.pm_f2v(mesh, adj, L, hF, W, DT), F),
         "f2v_bwd": (lambda: pm.pm_f2v_bwd(mesh, adj, L, hF, W, dgV, DT), F),
@@ -255,6 +256,7 @@ def all_ops(args, cfg, pm, mg, torch):
         "f2f_bwd": (lambda: pm.pm_f2f_bwd(t_off, t_bary, L, hP, W, dgF, DT), P),
         "f2v_sep": (lambda: pm.pm_f2v_sep(mesh, adj, L, hF, alpha, Pw, DT), F),
         "f2v_sep_bwd": (lambda: pm.pm_f2v_sep_bwd(mesh, adj, L, hF, alpha, Pw, dgV, DT), F),
+        "f2v_sep_bwd_saved_z": (lambda: pm.pm_f2v_sep_bwd(mesh, adj, L, hF, alpha, Pw, dgV, DT, z_saved=zV), F),
         "v2f_sep": (lambda: pm.pm_v2f_sep(mesh, L, hV, alpha, Pw, DT), F),
         "v2f_sep_bwd": (lambda: pm.pm_v2f_sep_bwd(mesh, adj, L, hV, alpha, Pw, dgF, DT), F),
     }
@@ -270,9 +272,13 @@ def all_ops(args, cfg, pm, mg, torch):
         nb = pm.Neighbors(pts, pts, torch.from_numpy(nptr).cuda(), torch.from_numpy(nidx).cuda(), rho)
         c0 = torch.rand(cin, device="cuda", generator=gen) * 2 - 1
         hN, dgN = rnd(gn * gn, cin), rnd(gn * gn, cout)
+        nb_rev = pm.pm_build_reverse_neighbors(nb)
+        _, yN = pm.pm_pcloud_conv(nb, L, hN, alpha, c0, Pw, DT, save_y=True)
         ops.update({
             "pcloud_conv": (lambda: pm.pm_pcloud_conv(nb, L, hN, alpha, c0, Pw, DT), int(nidx.shape[0])),
             "pcloud_conv_bwd": (lambda: pm.pm_pcloud_conv_bwd(nb, L, hN, alpha, c0, Pw, dgN, DT), int(nidx.shape[0])),
+            "pcloud_conv_bwd_saved": (lambda: pm.pm_pcloud_conv_bwd(nb_rev, L, hN, alpha, c0, Pw, dgN, DT, y_saved=yN),
+                                      int(nidx.shape[0])),
         })
     ops.update({
         "facet_geometry": (lambda: pm.pm_facet_geometry(mesh, DT, True), F),

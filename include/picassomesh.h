@@ -142,13 +142,17 @@ pm_status pm_f2f_bwd(int64_t n_facet, int64_t n_tex, const int32_t* tex_off, con
  *   vertex2facet:  g_f = ( sum_j h_{v_j(f)} (.) s(e_j) ) P
  * which is the dense form with W[k][ci][co] = alpha[k][ci] * P[ci][co].  alpha [K,cin] is always fp32; P [cin,cout]
  * has the feature dtype; dalpha [K,cin] and dP [cin,cout] are fp32.  Any of the three gradient outputs may be NULL
- * (dalpha and dP only together).  Same conventions as the dense entry points otherwise. */
+ * (dalpha and dP only together).  Same conventions as the dense entry points otherwise.
+ * z_vert (facet2vertex forward, may be NULL) receives the vertex means before the point-wise matrix,
+ * [n_vert,cin] of the feature dtype; handed back as z_saved (may be NULL) the backward pass takes dP from it
+ * instead of recomputing it (two bandwidth-bound passes fewer; the results are the same bit for bit). */
 pm_status pm_f2v_sep(const pm_mesh* mesh, const pm_vf_adj* adj, int L, pm_sh_norm norm, int cin, int cout,
-                     pm_dtype dtype, const void* h_facet, const float* alpha, const void* P, void* g_vert, void* ws,
-                     size_t ws_bytes, void* stream);
+                     pm_dtype dtype, const void* h_facet, const float* alpha, const void* P, void* g_vert, void* z_vert,
+                     void* ws, size_t ws_bytes, void* stream);
 pm_status pm_f2v_sep_bwd(const pm_mesh* mesh, const pm_vf_adj* adj, int L, pm_sh_norm norm, int cin, int cout,
                          pm_dtype dtype, const void* h_facet, const float* alpha, const void* P, const void* dg_vert,
-                         void* dh_facet, float* dalpha, float* dP, void* ws, size_t ws_bytes, void* stream);
+                         const void* z_saved, void* dh_facet, float* dalpha, float* dP, void* ws, size_t ws_bytes,
+                         void* stream);
 pm_status pm_v2f_sep(const pm_mesh* mesh, int L, pm_sh_norm norm, int cin, int cout, pm_dtype dtype,
                      const void* h_vert, const float* alpha, const void* P, void* g_facet, void* ws, size_t ws_bytes,
                      void* stream);
@@ -210,7 +214,12 @@ pm_status pm_unpool_bwd(const pm_cluster_map* cm, int C, pm_dtype dtype, const v
  * ptr[0] = 0, ptr non-decreasing, ptr[n_query] = nnz, 0 <= idx < n_source; rho > 0.  alpha [K][cin] and c0 [cin]
  * are fp32 (K + 1 numbers per channel), P [cin][cout] has the feature dtype; h [n_source][cin],
  * g [n_query][cout].  An id outside its range is clamped, never followed; pm_validate_neighbors reports bad
- * lists (synchronises; ws >= 16 bytes).  ws: pm_pcloud_ws_bytes(backward?, ...). */
+ * lists (synchronises; ws >= 16 bytes).  ws: pm_pcloud_ws_bytes(backward?, ...).
+ * The backward pass sums over the reverse lists (the pairs of every source point, sorted).  It builds them in
+ * its workspace on every call unless the caller built them once with pm_build_reverse_neighbors and set
+ * rev_ptr [n_source+1], rev_col [nnz] (pair ids) and owner [nnz] (query of every pair): all three or none.
+ * y_query (forward, may be NULL) receives the depth-wise output y [n_query,cin] of the feature dtype; handed
+ * back as y_saved (may be NULL) the backward pass takes dP from it instead of recomputing it. */
 typedef struct pm_nbr {
   int64_t n_query, n_source, nnz;
   const float* xq;
@@ -218,19 +227,26 @@ typedef struct pm_nbr {
   const int32_t* ptr;
   const int32_t* idx;
   float rho;
+  const int32_t* rev_ptr; /* optional, see above */
+  const int32_t* rev_col;
+  const int32_t* owner;
 } pm_nbr;
+size_t pm_reverse_ws_bytes(int64_t n_source, int64_t nnz); /* HOST computation; 0 on invalid sizes */
+pm_status pm_build_reverse_neighbors(const pm_nbr* nb, int32_t* rev_ptr, int32_t* rev_col, int32_t* owner, void* ws,
+                                     size_t ws_bytes, void* stream);
 size_t pm_pcloud_ws_bytes(int backward, int64_t n_query, int64_t n_source, int64_t nnz, int L, int cin, int cout,
                           pm_dtype dtype); /* HOST computation; 0 on invalid arguments */
 pm_status pm_validate_neighbors(const pm_nbr* nb, void* ws, size_t ws_bytes, void* stream);
 pm_status pm_pcloud_conv(const pm_nbr* nb, int L, pm_sh_norm norm, int cin, int cout, pm_dtype dtype, const void* h,
-                         const float* alpha, const float* c0, const void* P, void* g, void* ws, size_t ws_bytes,
-                         void* stream);
+                         const float* alpha, const float* c0, const void* P, void* g, void* y_query, void* ws,
+                         size_t ws_bytes, void* stream);
 /* dh [n_source][cin] (feature dtype; may be NULL); dalpha [K][cin], dc0 [cin], dP [cin][cout] fp32 (all three
  * or none).  Sums run in a fixed order over the caller's lists and over the reverse lists built here (sorted),
  * no float atomics. */
 pm_status pm_pcloud_conv_bwd(const pm_nbr* nb, int L, pm_sh_norm norm, int cin, int cout, pm_dtype dtype,
                              const void* h, const float* alpha, const float* c0, const void* P, const void* dg,
-                             void* dh, float* dalpha, float* dc0, float* dP, void* ws, size_t ws_bytes, void* stream);
+                             const void* y_saved, void* dh, float* dalpha, float* dc0, float* dP, void* ws,
+                             size_t ws_bytes, void* stream);
 
 /* ---- Input preparation ------------------------------------------------------------------------------
  * Facet geometric features (Section "Geometric Features", Eq. 9): feat [n_facet][9 or 12] of `dtype`, row

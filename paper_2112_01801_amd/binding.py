@@ -28,7 +28,7 @@ EXPORTS = [
     "pm_f2f", "pm_f2f_bwd", "pm_profile_enable", "pm_profile_filter", "pm_profile_count", "pm_profile_read", "pm_profile_reset",
     "pm_peak_probe", "pm_f2v_sep", "pm_f2v_sep_bwd", "pm_v2f_sep", "pm_v2f_sep_bwd",
     "pm_cluster_ws_bytes", "pm_validate_clusters", "pm_build_cluster_map", "pm_pool", "pm_pool_bwd", "pm_unpool",
-    "pm_unpool_bwd", "pm_pcloud_ws_bytes", "pm_validate_neighbors", "pm_pcloud_conv", "pm_pcloud_conv_bwd",
+    "pm_unpool_bwd", "pm_pcloud_ws_bytes", "pm_reverse_ws_bytes", "pm_build_reverse_neighbors", "pm_validate_neighbors", "pm_pcloud_conv", "pm_pcloud_conv_bwd",
     "pm_facet_geometry", "pm_texture_ws_bytes", "pm_texture_layout", "pm_texture_bary",
 ]
 
@@ -50,7 +50,8 @@ class _PmAdj(C.Structure):
 
 class _PmNbr(C.Structure):
     _fields_ = [("n_query", C.c_int64), ("n_source", C.c_int64), ("nnz", C.c_int64), ("xq", C.c_void_p),
-                ("xs", C.c_void_p), ("ptr", C.c_void_p), ("idx", C.c_void_p), ("rho", C.c_float)]
+                ("xs", C.c_void_p), ("ptr", C.c_void_p), ("idx", C.c_void_p), ("rho", C.c_float),
+                ("rev_ptr", C.c_void_p), ("rev_col", C.c_void_p), ("owner", C.c_void_p)]
 
 
 class _PmClusterMap(C.Structure):
@@ -88,8 +89,8 @@ def lib():
             "pm_v2f_bwd": [mp, ap, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, sz, vp],
             "pm_f2f": [i64, i64, vp, vp, i32, i32, i32, i32, i32, vp, vp, vp, vp, sz, vp],
             "pm_f2f_bwd": [i64, i64, vp, vp, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, sz, vp],
-            "pm_f2v_sep": [mp, ap, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, sz, vp],
-            "pm_f2v_sep_bwd": [mp, ap, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp],
+            "pm_f2v_sep": [mp, ap, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, sz, vp],
+            "pm_f2v_sep_bwd": [mp, ap, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp],
             "pm_v2f_sep": [mp, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, sz, vp],
             "pm_v2f_sep_bwd": [mp, ap, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp],
         }
@@ -105,8 +106,11 @@ def lib():
                     "pm_texture_bary": [i64, vp, vp, i64, vp, vp]})
         npt = C.POINTER(_PmNbr)
         sig.update({"pm_validate_neighbors": [npt, vp, sz, vp],
-                    "pm_pcloud_conv": [npt, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, sz, vp],
-                    "pm_pcloud_conv_bwd": [npt, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]})
+                    "pm_build_reverse_neighbors": [npt, vp, vp, vp, vp, sz, vp],
+                    "pm_pcloud_conv": [npt, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, sz, vp],
+                    "pm_pcloud_conv_bwd": [npt, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]})
+        l.pm_reverse_ws_bytes.restype = C.c_size_t
+        l.pm_reverse_ws_bytes.argtypes = [i64, i64]
         l.pm_pcloud_ws_bytes.restype = C.c_size_t
         l.pm_pcloud_ws_bytes.argtypes = [i32, i64, i64, i64, i32, i32, i32, i32]
         l.pm_texture_ws_bytes.restype = C.c_size_t
@@ -343,23 +347,26 @@ def _check_sep(alpha, P, dtype):
 
 
 def pm_f2v_sep(mesh: Mesh, adj: Adjacency, L: int, h_facet, alpha, P, dtype: int, norm: int = PM_SH_PAPER, out=None,
-               ws=None, stream=None):
-    """Depth-wise separable facet2vertex: alpha [K,cin] fp32, P [cin,cout] in the feature dtype."""
+               ws=None, stream=None, save_z: bool = False):
+    """Depth-wise separable facet2vertex: alpha [K,cin] fp32, P [cin,cout] in the feature dtype.
+    With save_z the vertex means before the point-wise matrix come back too: (g, z), z for pm_f2v_sep_bwd."""
     _check_sep(alpha, P, dtype)
     cin, cout = P.shape
     dev = h_facet.device
     if out is None:
         out = torch.empty((mesh.n_vert, cout), dtype=torch_dtype(dtype), device=dev)
+    z = torch.empty((mesh.n_vert, cin), dtype=torch_dtype(dtype), device=dev) if save_z else None
     ws = _ws(PM_OP_F2V_SEP, mesh.n_vert, mesh.n_facet, 0, L, cin, cout, dtype, ws, dev)
     m, a = mesh.c(), adj.c()
     _check(lib().pm_f2v_sep(C.byref(m), C.byref(a), L, norm, cin, cout, dtype, _ptr(h_facet), _ptr(alpha), _ptr(P),
-                            C.c_void_p(out.data_ptr()), _ptr(ws), ws.numel(), _stream(stream)))
-    return out
+                            C.c_void_p(out.data_ptr()), C.c_void_p(z.data_ptr()) if z is not None and z.numel() else None,
+                            _ptr(ws), ws.numel(), _stream(stream)))
+    return (out, z) if save_z else out
 
 
 def pm_f2v_sep_bwd(mesh: Mesh, adj: Adjacency, L: int, h_facet, alpha, P, dg_vert, dtype: int, norm: int = PM_SH_PAPER,
-                   want_dh=True, want_dw=True, ws=None, stream=None):
-    """Returns (dh, dalpha, dP); dalpha and dP are fp32 and come together."""
+                   want_dh=True, want_dw=True, ws=None, stream=None, z_saved=None):
+    """Returns (dh, dalpha, dP); dalpha and dP are fp32 and come together.  z_saved: the z of pm_f2v_sep(save_z)."""
     _check_sep(alpha, P, dtype)
     cin, cout = P.shape
     K = alpha.shape[0]
@@ -370,7 +377,8 @@ def pm_f2v_sep_bwd(mesh: Mesh, adj: Adjacency, L: int, h_facet, alpha, P, dg_ver
     ws = _ws(PM_OP_F2V_SEP_BWD, mesh.n_vert, mesh.n_facet, 0, L, cin, cout, dtype, ws, dev)
     m, a = mesh.c(), adj.c()
     _check(lib().pm_f2v_sep_bwd(C.byref(m), C.byref(a), L, norm, cin, cout, dtype, _ptr(h_facet), _ptr(alpha), _ptr(P),
-                                _ptr(dg_vert), _ptr(dh), _ptr(da), _ptr(dP), _ptr(ws), ws.numel(), _stream(stream)))
+                                _ptr(dg_vert), _ptr(z_saved) if z_saved is not None and z_saved.numel() else None,
+                                _ptr(dh), _ptr(da), _ptr(dP), _ptr(ws), ws.numel(), _stream(stream)))
     return dh, da, dP
 
 
@@ -500,6 +508,9 @@ class Neighbors:
     ptr: torch.Tensor
     idx: torch.Tensor
     rho: float
+    rev_ptr: Optional[torch.Tensor] = None      # reverse lists (pm_build_reverse_neighbors), optional
+    rev_col: Optional[torch.Tensor] = None
+    owner: Optional[torch.Tensor] = None
 
     def c(self) -> _PmNbr:
         n = _PmNbr()
@@ -509,6 +520,10 @@ class Neighbors:
         n.ptr = self.ptr.data_ptr()
         n.idx = self.idx.data_ptr() if self.idx.numel() else None
         n.rho = float(self.rho)
+        if self.rev_ptr is not None:
+            n.rev_ptr = self.rev_ptr.data_ptr()
+            n.rev_col = self.rev_col.data_ptr() if self.rev_col.numel() else None
+            n.owner = self.owner.data_ptr() if self.owner.numel() else None
         return n
 
 
@@ -518,6 +533,20 @@ def pm_validate_neighbors(nb: Neighbors, stream=None) -> None:
     _check(lib().pm_validate_neighbors(C.byref(n), _ptr(ws), ws.numel(), _stream(stream)))
 
 
+def pm_build_reverse_neighbors(nb: Neighbors, stream=None) -> Neighbors:
+    """The same lists with the reverse lists attached (built once, reused by every backward call)."""
+    dev, nnz, N = nb.ptr.device, nb.idx.shape[0], nb.xs.shape[0]
+    rev_ptr = torch.empty(N + 1, dtype=torch.int32, device=dev)
+    rev_col = torch.empty(nnz, dtype=torch.int32, device=dev)
+    owner = torch.empty(nnz, dtype=torch.int32, device=dev)
+    ws = alloc_workspace(int(lib().pm_reverse_ws_bytes(N, nnz)), dev)
+    n = nb.c()
+    vp = lambda t: C.c_void_p(t.data_ptr()) if t.numel() else None
+    _check(lib().pm_build_reverse_neighbors(C.byref(n), _ptr(rev_ptr), vp(rev_col), vp(owner), _ptr(ws), ws.numel(),
+                                            _stream(stream)))
+    return Neighbors(nb.xq, nb.xs, nb.ptr, nb.idx, nb.rho, rev_ptr, rev_col, owner)
+
+
 def _pc_ws(bwd, nb, L, cin, cout, dtype, ws):
     if ws is None:
         ws = alloc_workspace(int(lib().pm_pcloud_ws_bytes(bwd, nb.xq.shape[0], nb.xs.shape[0], nb.idx.shape[0], L, cin,
@@ -525,22 +554,28 @@ def _pc_ws(bwd, nb, L, cin, cout, dtype, ws):
     return ws
 
 
-def pm_pcloud_conv(nb: Neighbors, L: int, h, alpha, c0, P, dtype: int, norm: int = PM_SH_PAPER, ws=None, stream=None):
-    """g [M, cout]: alpha [K,cin] and c0 [cin] fp32, P [cin,cout] and h [N,cin] in the feature dtype."""
+def pm_pcloud_conv(nb: Neighbors, L: int, h, alpha, c0, P, dtype: int, norm: int = PM_SH_PAPER, ws=None, stream=None,
+                   save_y: bool = False):
+    """g [M, cout]: alpha [K,cin] and c0 [cin] fp32, P [cin,cout] and h [N,cin] in the feature dtype.
+    With save_y the depth-wise output comes back too: (g, y), y for pm_pcloud_conv_bwd."""
     _check_sep(alpha, P, dtype)
     assert c0.dtype == torch.float32 and c0.shape[0] == P.shape[0]
     cin, cout = P.shape
     out = torch.empty((nb.xq.shape[0], cout), dtype=torch_dtype(dtype), device=h.device)
+    y = torch.empty((nb.xq.shape[0], cin), dtype=torch_dtype(dtype), device=h.device) if save_y else None
     ws = _pc_ws(0, nb, L, cin, cout, dtype, ws)
     n = nb.c()
     _check(lib().pm_pcloud_conv(C.byref(n), L, norm, cin, cout, dtype, C.c_void_p(h.data_ptr()), _ptr(alpha), _ptr(c0),
-                                _ptr(P), C.c_void_p(out.data_ptr()), _ptr(ws), ws.numel(), _stream(stream)))
-    return out
+                                _ptr(P), C.c_void_p(out.data_ptr()),
+                                C.c_void_p(y.data_ptr()) if y is not None and y.numel() else None, _ptr(ws), ws.numel(),
+                                _stream(stream)))
+    return (out, y) if save_y else out
 
 
 def pm_pcloud_conv_bwd(nb: Neighbors, L: int, h, alpha, c0, P, dg, dtype: int, norm: int = PM_SH_PAPER,
-                       want_dh: bool = True, want_dw: bool = True, ws=None, stream=None):
-    """(dh [N,cin], dalpha [K,cin], dc0 [cin], dP [cin,cout]); the parameter gradients come together or not at all."""
+                       want_dh: bool = True, want_dw: bool = True, ws=None, stream=None, y_saved=None):
+    """(dh [N,cin], dalpha [K,cin], dc0 [cin], dP [cin,cout]); the parameter gradients come together or not at all.
+    y_saved: the y of pm_pcloud_conv(save_y)."""
     _check_sep(alpha, P, dtype)
     cin, cout = P.shape
     dev = h.device
@@ -552,6 +587,7 @@ def pm_pcloud_conv_bwd(nb: Neighbors, L: int, h, alpha, c0, P, dg, dtype: int, n
     n = nb.c()
     vp = lambda t: C.c_void_p(t.data_ptr()) if t is not None else None
     _check(lib().pm_pcloud_conv_bwd(C.byref(n), L, norm, cin, cout, dtype, vp(h), _ptr(alpha), _ptr(c0), _ptr(P), vp(dg),
+                                    vp(y_saved) if y_saved is not None and y_saved.numel() else None,
                                     vp(dh), vp(da), vp(dc), vp(dP), _ptr(ws), ws.numel(), _stream(stream)))
     return dh, da, dc, dP
 

@@ -465,7 +465,7 @@ static pm_status check_sep(const float* alpha, const void* P) {
 
 extern "C" pm_status pm_f2v_sep(const pm_mesh* mesh, const pm_vf_adj* adj, int L, pm_sh_norm norm, int cin, int cout,
                                 pm_dtype dtype, const void* h_facet, const float* alpha, const void* P, void* g_vert,
-                                void* ws, size_t ws_bytes, void* stream) {
+                                void* z_vert, void* ws, size_t ws_bytes, void* stream) {
   pm_prof_set_op("f2v_sep");
   PM_TRY(check_conv_common(L, norm, cin, cout, dtype));
   PM_TRY(check_mesh(mesh, true));
@@ -473,6 +473,7 @@ extern "C" pm_status pm_f2v_sep(const pm_mesh* mesh, const pm_vf_adj* adj, int L
   PM_TRY(check_sep(alpha, P));
   PM_TRY(check_ptr(h_facet, "h_facet", mesh->n_facet > 0));
   PM_TRY(check_ptr(g_vert, "g_vert", mesh->n_vert > 0));
+  PM_TRY(check_ptr(z_vert, "z_vert", false));
   const int K = (L + 1) * (L + 1);
   const int64_t V = mesh->n_vert, F = mesh->n_facet;
   WsPlan w = plan_ws(PM_OP_F2V_SEP, V, F, 0, L, cin, cout, dtype);
@@ -480,7 +481,7 @@ extern "C" pm_status pm_f2v_sep(const pm_mesh* mesh, const pm_vf_adj* adj, int L
   hipStream_t st = (hipStream_t)stream;
   char* apack = (char*)ws;
   void* y = apack + w.apack;
-  void* z = (char*)y + w.inter;
+  void* z = z_vert ? z_vert : (void*)((char*)y + w.inter);
   const int fb = dtype == PM_BF16;
   BasisSrc bs = basis_none();
   bs.vert = mesh->vert; bs.facet = mesh->facet;
@@ -496,8 +497,8 @@ extern "C" pm_status pm_f2v_sep(const pm_mesh* mesh, const pm_vf_adj* adj, int L
 
 extern "C" pm_status pm_f2v_sep_bwd(const pm_mesh* mesh, const pm_vf_adj* adj, int L, pm_sh_norm norm, int cin,
                                     int cout, pm_dtype dtype, const void* h_facet, const float* alpha, const void* P,
-                                    const void* dg_vert, void* dh_facet, float* dalpha, float* dP, void* ws,
-                                    size_t ws_bytes, void* stream) {
+                                    const void* dg_vert, const void* z_saved, void* dh_facet, float* dalpha, float* dP,
+                                    void* ws, size_t ws_bytes, void* stream) {
   pm_prof_set_op("f2v_sep_bwd");
   PM_TRY(check_conv_common(L, norm, cin, cout, dtype));
   PM_TRY(check_mesh(mesh, true));
@@ -505,6 +506,7 @@ extern "C" pm_status pm_f2v_sep_bwd(const pm_mesh* mesh, const pm_vf_adj* adj, i
   PM_TRY(check_sep(alpha, P));
   PM_TRY(check_ptr(h_facet, "h_facet", mesh->n_facet > 0));
   PM_TRY(check_ptr(dg_vert, "dg_vert", mesh->n_vert > 0));
+  PM_TRY(check_ptr(z_saved, "z_saved", false));
   PM_TRY(check_ptr(dh_facet, "dh_facet", false));
   PM_TRY(check_ptr(dalpha, "dalpha", false));
   PM_TRY(check_ptr(dP, "dP", false));
@@ -528,11 +530,13 @@ extern "C" pm_status pm_f2v_sep_bwd(const pm_mesh* mesh, const pm_vf_adj* adj, i
   RowSrc gs = row_src(dg_vert, dtype, cout);
   PM_TRY(pm_launch_conv_rows(dtype, B_ONE, X_DIRECT, V, 1, cout, cin, basis_none(), gs, apack, dz, 0, st));
   if (dP) {
-    // dP = z^T dg with z recomputed (depth-wise stage + vertex mean): two bandwidth-bound passes instead of
-    // keeping z from the forward call
-    PM_TRY(pm_launch_dw_f2v(F, K, cin, fb, bs, h_facet, alpha, y, st));
-    PM_TRY(pm_launch_segreduce(V, cin, y, fb, adj->row_ptr, adj->col, 3, 1, z, fb, st));
-    RowSrc zs = row_src(z, dtype, cin);
+    // dP = z^T dg with the vertex means z the forward call handed out, or recomputed here (depth-wise stage +
+    // vertex mean: two bandwidth-bound passes)
+    if (!z_saved) {
+      PM_TRY(pm_launch_dw_f2v(F, K, cin, fb, bs, h_facet, alpha, y, st));
+      PM_TRY(pm_launch_segreduce(V, cin, y, fb, adj->row_ptr, adj->col, 3, 1, z, fb, st));
+    }
+    RowSrc zs = row_src(z_saved ? z_saved : z, dtype, cin);
     PM_TRY(pm_launch_wgrad(dtype, B_ONE, X_DIRECT, X_DIRECT, V, 1, cin, cout, basis_none(), zs, gs, dP, wg, w.wgrad,
                            nullptr, st));
   }
@@ -750,6 +754,8 @@ static pm_status check_nbr(const pm_nbr* nb) {
   if (nb->nnz > 0 && (!nb->idx || nb->n_source == 0)) return pm_fail(PM_ERR_INVALID_ARG, "idx is NULL or there are no sources");
   if ((nb->n_query > 0 && !nb->xq) || (nb->n_source > 0 && !nb->xs)) return pm_fail(PM_ERR_INVALID_ARG, "xq / xs is NULL");
   if (!(nb->rho > 0.f)) return pm_fail(PM_ERR_INVALID_ARG, "rho must be positive");
+  if ((nb->rev_ptr || nb->rev_col || nb->owner) && (!nb->rev_ptr || (nb->nnz > 0 && (!nb->rev_col || !nb->owner))))
+    return pm_fail(PM_ERR_INVALID_ARG, "rev_ptr, rev_col and owner come together");
   return PM_OK;
 }
 
@@ -758,6 +764,24 @@ extern "C" size_t pm_pcloud_ws_bytes(int backward, int64_t n_query, int64_t n_so
   if (n_query < 0 || n_source < 0 || nnz < 0 || n_query >= kMaxIds || n_source >= kMaxIds || nnz >= kMaxIds) return 0;
   if (check_conv_common(L, PM_SH_PAPER, cin, cout, dtype) != PM_OK) return 0;
   return plan_pc(backward != 0, n_query, n_source, nnz, L, cin, cout, dtype).total;
+}
+
+extern "C" size_t pm_reverse_ws_bytes(int64_t n_source, int64_t nnz) {
+  if (n_source < 0 || nnz < 0 || n_source >= kMaxIds || nnz >= kMaxIds) return 0;
+  return pm_csr_ws_bytes(n_source, nnz);
+}
+
+extern "C" pm_status pm_build_reverse_neighbors(const pm_nbr* nb, int32_t* rev_ptr, int32_t* rev_col, int32_t* owner,
+                                                void* ws, size_t ws_bytes, void* stream) {
+  pm_prof_set_op("reverse_neighbors");
+  PM_TRY(check_nbr(nb));
+  if (!rev_ptr || (nb->nnz > 0 && (!rev_col || !owner))) return pm_fail(PM_ERR_INVALID_ARG, "rev_ptr / rev_col / owner is NULL");
+  PM_TRY(check_ptr(ws, "ws", true));
+  const size_t need = pm_csr_ws_bytes(nb->n_source, nb->nnz);
+  if (ws_bytes < need) return pm_fail(PM_ERR_WORKSPACE, "workspace %zu < required %zu bytes", ws_bytes, need);
+  hipStream_t st = (hipStream_t)stream;
+  PM_TRY(pm_launch_owner(nb->n_query, nb->ptr, owner, st));
+  return pm_launch_csr(nb->n_source, nb->nnz, nb->idx, rev_ptr, rev_col, ws, st);
 }
 
 extern "C" pm_status pm_validate_neighbors(const pm_nbr* nb, void* ws, size_t ws_bytes, void* stream) {
@@ -776,8 +800,8 @@ extern "C" pm_status pm_validate_neighbors(const pm_nbr* nb, void* ws, size_t ws
 }
 
 extern "C" pm_status pm_pcloud_conv(const pm_nbr* nb, int L, pm_sh_norm norm, int cin, int cout, pm_dtype dtype,
-                                    const void* h, const float* alpha, const float* c0, const void* P, void* g, void* ws,
-                                    size_t ws_bytes, void* stream) {
+                                    const void* h, const float* alpha, const float* c0, const void* P, void* g,
+                                    void* y_query, void* ws, size_t ws_bytes, void* stream) {
   pm_prof_set_op("pcloud_conv");
   PM_TRY(check_conv_common(L, norm, cin, cout, dtype));
   PM_TRY(check_nbr(nb));
@@ -785,6 +809,7 @@ extern "C" pm_status pm_pcloud_conv(const pm_nbr* nb, int L, pm_sh_norm norm, in
   if (!c0 || !pm_aligned16(c0)) return pm_fail(PM_ERR_INVALID_ARG, "c0 is NULL or not 16-byte aligned");
   PM_TRY(check_ptr(h, "h", nb->n_source > 0));
   PM_TRY(check_ptr(g, "g", nb->n_query > 0));
+  PM_TRY(check_ptr(y_query, "y_query", false));
   const int K = (L + 1) * (L + 1);
   const int64_t M = nb->n_query, N = nb->n_source;
   PcWs w = plan_pc(0, M, N, nb->nnz, L, cin, cout, dtype);
@@ -792,7 +817,7 @@ extern "C" pm_status pm_pcloud_conv(const pm_nbr* nb, int L, pm_sh_norm norm, in
   if (ws_bytes < w.total) return pm_fail(PM_ERR_WORKSPACE, "workspace %zu < required %zu bytes", ws_bytes, w.total);
   hipStream_t st = (hipStream_t)stream;
   char* apack = (char*)ws;
-  void* y = apack + w.apack;
+  void* y = y_query ? y_query : (void*)(apack + w.apack);
   const int fb = dtype == PM_BF16;
   ShTable sh;
   pm_make_sh_table(L, norm, &sh);
@@ -804,8 +829,8 @@ extern "C" pm_status pm_pcloud_conv(const pm_nbr* nb, int L, pm_sh_norm norm, in
 
 extern "C" pm_status pm_pcloud_conv_bwd(const pm_nbr* nb, int L, pm_sh_norm norm, int cin, int cout, pm_dtype dtype,
                                         const void* h, const float* alpha, const float* c0, const void* P,
-                                        const void* dg, void* dh, float* dalpha, float* dc0, float* dP, void* ws,
-                                        size_t ws_bytes, void* stream) {
+                                        const void* dg, const void* y_saved, void* dh, float* dalpha, float* dc0,
+                                        float* dP, void* ws, size_t ws_bytes, void* stream) {
   pm_prof_set_op("pcloud_conv_bwd");
   PM_TRY(check_conv_common(L, norm, cin, cout, dtype));
   PM_TRY(check_nbr(nb));
@@ -813,6 +838,7 @@ extern "C" pm_status pm_pcloud_conv_bwd(const pm_nbr* nb, int L, pm_sh_norm norm
   if (!c0 || !pm_aligned16(c0)) return pm_fail(PM_ERR_INVALID_ARG, "c0 is NULL or not 16-byte aligned");
   PM_TRY(check_ptr(h, "h", nb->n_source > 0));
   PM_TRY(check_ptr(dg, "dg", nb->n_query > 0));
+  PM_TRY(check_ptr(y_saved, "y_saved", false));
   PM_TRY(check_ptr(dh, "dh", false));
   PM_TRY(check_ptr(dalpha, "dalpha", false));
   PM_TRY(check_ptr(dc0, "dc0", false));
@@ -841,18 +867,22 @@ extern "C" pm_status pm_pcloud_conv_bwd(const pm_nbr* nb, int L, pm_sh_norm norm
   RowSrc gs = row_src(dg, dtype, cout);
   PM_TRY(pm_launch_conv_rows(dtype, B_ONE, X_DIRECT, M, 1, cout, cin, basis_none(), gs, apack, dy, 0, st));
   if (dalpha) {
-    // one walk over the lists gives the coefficient gradients and recomputes the depth-wise output y for dP
-    PM_TRY(pm_launch_pc_dw_coef(M, N, K, cin, fb, nb->rho, sh, nb->xq, nb->xs, nb->ptr, nb->idx, h, alpha, c0, dy, y,
-                                dalpha, dc0, (float*)tail, st));
-    RowSrc ys = row_src(y, dtype, cin);
+    // one walk over the lists gives the coefficient gradients and, unless the forward call handed it out,
+    // recomputes the depth-wise output y for dP
+    PM_TRY(pm_launch_pc_dw_coef(M, N, K, cin, fb, nb->rho, sh, nb->xq, nb->xs, nb->ptr, nb->idx, h, alpha, c0, dy,
+                                y_saved ? nullptr : y, dalpha, dc0, (float*)tail, st));
+    RowSrc ys = row_src(y_saved ? y_saved : y, dtype, cin);
     PM_TRY(pm_launch_wgrad(dtype, B_ONE, X_DIRECT, X_DIRECT, M, 1, cin, cout, basis_none(), ys, gs, dP, tail, w.tail,
                            nullptr, st));
   }
   if (dh) {
-    PM_TRY(pm_launch_owner(M, nb->ptr, owner, st));
-    PM_TRY(pm_launch_csr(N, nnz, nb->idx, rev_ptr, rev_col, csr_ws, st));
-    PM_TRY(pm_launch_pc_dw_dh(M, N, K, cin, fb, nb->rho, sh, nb->xq, nb->xs, nb->ptr, rev_ptr, rev_col, owner, alpha, c0,
-                              dy, dh, st));
+    const int32_t *rp = nb->rev_ptr, *rc = nb->rev_col, *ow = nb->owner;
+    if (!rp) {                                  // reverse lists: the caller's, or built here
+      PM_TRY(pm_launch_owner(M, nb->ptr, owner, st));
+      PM_TRY(pm_launch_csr(N, nnz, nb->idx, rev_ptr, rev_col, csr_ws, st));
+      rp = rev_ptr; rc = rev_col; ow = owner;
+    }
+    PM_TRY(pm_launch_pc_dw_dh(M, N, K, cin, fb, nb->rho, sh, nb->xq, nb->xs, nb->ptr, rp, rc, ow, alpha, c0, dy, dh, st));
   }
   return PM_OK;
 }

@@ -84,7 +84,7 @@ def test_argument_errors_of_the_later_operators(pm):
     m.n_mesh, m.n_vert, m.n_facet = 1, 10, 10
     a = pm._PmAdj()
     # separable: NULL mesh arrays, then parameter gradients that do not come together
-    assert lib.pm_f2v_sep(C.byref(m), C.byref(a), 3, 0, 8, 8, 0, None, None, None, None, None, 0, None) == -1
+    assert lib.pm_f2v_sep(C.byref(m), C.byref(a), 3, 0, 8, 8, 0, None, None, None, None, None, None, 0, None) == -1
     assert lib.pm_v2f_sep(C.byref(m), 9, 0, 8, 8, 0, None, None, None, None, None, 0, None) == -2
     # pooling: NULL map, unknown mode, bad channel count
     assert lib.pm_pool(None, 0, 8, 0, None, None, None, None) == -1
@@ -94,7 +94,8 @@ def test_argument_errors_of_the_later_operators(pm):
     assert lib.pm_unpool(C.byref(cm), 0, 0, None, None, None) == -1
     assert lib.pm_build_cluster_map(-1, 3, None, None, None, None, None, None, 0, None) == -1
     # neighbour lists: NULL struct, non-positive radius
-    assert lib.pm_pcloud_conv(None, 3, 0, 8, 8, 0, None, None, None, None, None, None, 0, None) == -1
+    assert lib.pm_pcloud_conv(None, 3, 0, 8, 8, 0, None, None, None, None, None, None, None, 0, None) == -1
+    assert lib.pm_reverse_ws_bytes(100, 3000) > 0 and lib.pm_reverse_ws_bytes(-1, 5) == 0
     nb = pm._PmNbr()
     nb.n_query, nb.n_source, nb.nnz, nb.rho = 0, 0, 0, 0.0
     assert lib.pm_validate_neighbors(C.byref(nb), None, 0, None) == -1

@@ -77,6 +77,12 @@ def test_forward_backward_against_the_oracle(pm, L, cin, cout, dtype):
     assert n1 is None and n2 is None and n3 is None and torch.equal(dh1, dh)
     n0, da1, dc1, dP1 = pm.pm_pcloud_conv_bwd(nb, L, to_dev(h, dtype), a_d, c_d, P_d, to_dev(dg, dtype), dt, want_dh=False)
     assert n0 is None and torch.equal(da1, da) and torch.equal(dc1, dc) and torch.equal(dP1, dP)
+    # reverse lists built once and the depth-wise output handed out by the forward call: the same bits
+    nb2 = pm.pm_build_reverse_neighbors(nb)
+    g2, y = pm.pm_pcloud_conv(nb2, L, to_dev(h, dtype), a_d, c_d, P_d, dt, save_y=True)
+    assert torch.equal(g2, g) and y.shape == (xq.shape[0], cin)
+    dh2, da2, dc2, dP2 = pm.pm_pcloud_conv_bwd(nb2, L, to_dev(h, dtype), a_d, c_d, P_d, to_dev(dg, dtype), dt, y_saved=y)
+    assert torch.equal(dh2, dh) and torch.equal(da2, da) and torch.equal(dc2, dc) and torch.equal(dP2, dP)
 
 
 def test_vertices_of_a_coarse_mesh_level_sampled(pm):

@@ -56,6 +56,12 @@ def test_f2v_sep_forward_backward(pm, L, cin, cout, dtype):
     none, da1, dP1 = pm.pm_f2v_sep_bwd(mesh, adj, L, to_dev(h, dtype), a_d, P_d, to_dev(dg, dtype), pm_dtype(dtype),
                                        want_dh=False)
     assert none is None and torch.equal(da1, da) and torch.equal(dP1, dP)
+    # the vertex means handed out by the forward call give the same gradients, bit for bit, without the recompute
+    g2, z = pm.pm_f2v_sep(mesh, adj, L, to_dev(h, dtype), a_d, P_d, pm_dtype(dtype), save_z=True)
+    assert torch.equal(g2, g) and z.shape == (b.n_vert, cin)
+    dh2, da2, dP2 = pm.pm_f2v_sep_bwd(mesh, adj, L, to_dev(h, dtype), a_d, P_d, to_dev(dg, dtype), pm_dtype(dtype),
+                                      z_saved=z)
+    assert torch.equal(dh2, dh) and torch.equal(da2, da) and torch.equal(dP2, dP)
 
 
 @pytest.mark.parametrize("L,cin,cout,dtype", CASES)
