@@ -308,6 +308,13 @@ static void fold_coef(int L, pm_sh_norm norm, FoldCoef* fc) {
 }
 
 // ---- facet2vertex (Eq. 5) ------------------------------------------------------------------------
+static int g_f2v_order = 1;   // 1: facet-side (default), 0: vertex-side where its kernel applies
+extern "C" pm_status pm_f2v_order(int order) {
+  if (order != 0 && order != 1) return pm_fail(PM_ERR_INVALID_ARG, "order %d", order);
+  g_f2v_order = order;
+  return PM_OK;
+}
+
 extern "C" pm_status pm_f2v(const pm_mesh* mesh, const pm_vf_adj* adj, int L, pm_sh_norm norm, int cin, int cout,
                             pm_dtype dtype, const void* h_facet, const void* W, void* g_vert, void* ws, size_t ws_bytes,
                             void* stream) {
@@ -330,6 +337,10 @@ extern "C" pm_status pm_f2v(const pm_mesh* mesh, const pm_vf_adj* adj, int L, pm
   BasisSrc bs = basis_none();
   bs.vert = mesh->vert; bs.facet = mesh->facet;
   pm_make_sh_table(L, norm, &bs.sh);
+  // vertex-side order (mean before the contraction) on request, where its kernel applies: half the matrix work
+  // and no per-facet intermediate, but slower as measured; otherwise the facet-side order below
+  if (g_f2v_order == 0 && F > 0 && pm_f2v_vs_applies(dtype, K, cin, cout, h_facet, g_vert))
+    return pm_launch_f2v_vs(mesh, adj->row_ptr, adj->col, K, cout, bs.sh, h_facet, apack, g_vert, st);
   RowSrc xs = row_src(h_facet, dtype, cin);
   const int yb = dtype == PM_BF16;
   PM_TRY(pm_launch_conv_rows(dtype, B_NORMAL, X_DIRECT, F, K, cin, cout, bs, xs, apack, y, yb, st));

@@ -183,6 +183,10 @@ pm_status pm_launch_texture_bary(int64_t n_facet, const int32_t* gamma, const in
                                  hipStream_t st);
 pm_status pm_launch_csr(int64_t n_rows, int64_t n_entries, const int32_t* keys, int32_t* row_ptr, int32_t* col, void* ws,
                         hipStream_t st);
+// facet2vertex forward in the vertex-side order (bf16, Cin = 64)
+bool pm_f2v_vs_applies(pm_dtype dt, int K, int cin, int cout, const void* h, const void* out);
+pm_status pm_launch_f2v_vs(const pm_mesh* mesh, const int32_t* row_ptr, const int32_t* col, int K, int cout,
+                           const ShTable& sh, const void* h, const void* apack, void* out, hipStream_t st);
 // pooling over vertex clusters
 pm_status pm_launch_cluster_target(int64_t n_in, int64_t n_out, const int32_t* vcluster, const int32_t* iomap,
                                    int32_t* target, int32_t* bad, hipStream_t st);
