@@ -72,19 +72,51 @@ __device__ __forceinline__ void pack_values(const PackP& p, int k, int c0, int n
     }
     return;
   }
+  // KB values of k per batch: their loads are issued together, the additions follow in ascending k
+  constexpr int KB = N == 1 ? 8 : 2;
   int kk = 0;
-  for (; kk + 2 <= p.K; kk += 2) {
-    float w0[N], w1[N];
+  for (; kk + KB <= p.K; kk += KB) {
+    float w[KB][N];
 #pragma unroll
-    for (int e = 0; e < N; ++e) { w0[e] = pack_src(p, kk, ci[e], co[e]); w1[e] = pack_src(p, kk + 1, ci[e], co[e]); }
+    for (int q = 0; q < KB; ++q)
 #pragma unroll
-    for (int e = 0; e < N; ++e) { v[e] += p.fc.c[j[e]][kk] * w0[e]; v[e] += p.fc.c[j[e]][kk + 1] * w1[e]; }
+      for (int e = 0; e < N; ++e) w[q][e] = pack_src(p, kk + q, ci[e], co[e]);
+#pragma unroll
+    for (int q = 0; q < KB; ++q)
+#pragma unroll
+      for (int e = 0; e < N; ++e) v[e] += p.fc.c[j[e]][kk + q] * w[q][e];
   }
   for (; kk < p.K; ++kk)
 #pragma unroll
     for (int e = 0; e < N; ++e) v[e] += p.fc.c[j[e]][kk] * pack_src(p, kk, ci[e], co[e]);
 #pragma unroll
   for (int e = 0; e < N; ++e) v[e] = ok[e] ? v[e] : 0.f;
+}
+
+// the folded forms (a sum over k per element): one thread per element, so that the K loads of an element are
+// spread over eight times as many threads
+template <int MODE>
+__global__ void __launch_bounds__(256) k_pack_elem(PackP p, int64_t n_elem) {
+  const int64_t te = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (te >= n_elem) return;
+  const int EPG = p.dst_bf16 ? 8 : 4;
+  const int e = (int)(te % EPG);
+  const int64_t t = te / EPG;
+  const int lane = (int)(t & 63);
+  int64_t q = t >> 6;
+  const int g = (int)(q % PM_GC); q /= PM_GC;
+  const int nbi = (int)(q % PM_NBS); q /= PM_NBS;
+  const int64_t stage = q;
+  const int k = (int)(stage % p.Kp);
+  const int ch = (int)((stage / p.Kp) % p.NCH);
+  const int nbg = (int)(stage / ((int64_t)p.Kp * p.NCH));
+  const int n = (nbg * PM_NBS + nbi) * 32 + (lane & 31);
+  const int hh = lane >> 5;
+  const int c0 = ((ch * PM_GC + g) * 2 + hh) * EPG + e;
+  float v[1];
+  pack_values<MODE, 1>(p, k, c0, n, v);
+  if (p.dst_bf16) ((uint16_t*)p.out)[te] = (uint16_t)f32_to_bf16_bits(v[0]);
+  else ((float*)p.out)[te] = v[0];
 }
 
 // one thread per (stage, nbi, g, lane) granule
@@ -141,10 +173,16 @@ pm_status pm_launch_pack(PackMode mode, pm_dtype dt, int K, int cin, int cout, c
     switch (mode) {
       case PACK_PLAIN: hipLaunchKernelGGL(k_pack<PACK_PLAIN>, grid, dim3(256), 0, st, p, n_gran); break;
       case PACK_TRANS: hipLaunchKernelGGL(k_pack<PACK_TRANS>, grid, dim3(256), 0, st, p, n_gran); break;
-      case PACK_FOLD: hipLaunchKernelGGL(k_pack<PACK_FOLD>, grid, dim3(256), 0, st, p, n_gran); break;
-      case PACK_FOLD_TRANS: hipLaunchKernelGGL(k_pack<PACK_FOLD_TRANS>, grid, dim3(256), 0, st, p, n_gran); break;
-      case PACK_FOLD_BWD: hipLaunchKernelGGL(k_pack<PACK_FOLD_BWD>, grid, dim3(256), 0, st, p, n_gran); break;
-      default: hipLaunchKernelGGL(k_pack<PACK_SEP_FOLD>, grid, dim3(256), 0, st, p, n_gran); break;
+      default: {
+        const int64_t n_elem = n_gran * (p.dst_bf16 ? 8 : 4);
+        const dim3 ge((unsigned)((n_elem + 255) / 256));
+        switch (mode) {
+          case PACK_FOLD: hipLaunchKernelGGL(k_pack_elem<PACK_FOLD>, ge, dim3(256), 0, st, p, n_elem); break;
+          case PACK_FOLD_TRANS: hipLaunchKernelGGL(k_pack_elem<PACK_FOLD_TRANS>, ge, dim3(256), 0, st, p, n_elem); break;
+          case PACK_FOLD_BWD: hipLaunchKernelGGL(k_pack_elem<PACK_FOLD_BWD>, ge, dim3(256), 0, st, p, n_elem); break;
+          default: hipLaunchKernelGGL(k_pack_elem<PACK_SEP_FOLD>, ge, dim3(256), 0, st, p, n_elem); break;
+        }
+      } break;
     } }
   PM_CHECK_LAUNCH("k_pack");
   return PM_OK;
