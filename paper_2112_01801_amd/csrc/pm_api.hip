@@ -418,7 +418,7 @@ extern "C" pm_status pm_v2f(const pm_mesh* mesh, int L, pm_sh_norm norm, int cin
   // the three corner directions are constants => three folded cin x cout matrices W_j = sum_k B_k(e_j) W[k]
   PM_TRY(pm_launch_pack(PACK_FOLD, dtype, K, cin, cout, W, &fc, ws, st));
   if (pm_v2f_stage_applies(dtype, cin, cout, h_vert, g_facet))       // the memory-bound shape: LDS-staged facet tiles
-    return pm_launch_v2f_stage(F, cout, mesh->facet, h_vert, ws, g_facet, st);
+    return pm_launch_v2f_stage(F, cin, cout, mesh->facet, h_vert, ws, g_facet, st);
   RowSrc xs = row_src(h_vert, dtype, cin);
   xs.facet = mesh->facet;
   return pm_launch_conv_rows(dtype, B_ONE, X_GATHER_CAT, F, 1, 3 * cin, cout, basis_none(), xs, ws, g_facet,
@@ -577,7 +577,7 @@ extern "C" pm_status pm_v2f_sep(const pm_mesh* mesh, int L, pm_sh_norm norm, int
   fold_coef(L, norm, &fc);
   PM_TRY(pm_launch_pack(PACK_SEP_FOLD, dtype, K, cin, cout, P, &fc, apack, st, alpha));
   if (pm_v2f_stage_applies(dtype, cin, cout, h_vert, g_facet))
-    return pm_launch_v2f_stage(mesh->n_facet, cout, mesh->facet, h_vert, apack, g_facet, st);
+    return pm_launch_v2f_stage(mesh->n_facet, cin, cout, mesh->facet, h_vert, apack, g_facet, st);
   RowSrc xs = row_src(h_vert, dtype, cin);
   xs.facet = mesh->facet;
   return pm_launch_conv_rows(dtype, B_ONE, X_GATHER_CAT, mesh->n_facet, 1, 3 * cin, cout, basis_none(), xs, apack,

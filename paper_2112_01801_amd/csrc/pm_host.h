@@ -183,10 +183,10 @@ pm_status pm_launch_texture_bary(int64_t n_facet, const int32_t* gamma, const in
                                  hipStream_t st);
 pm_status pm_launch_csr(int64_t n_rows, int64_t n_entries, const int32_t* keys, int32_t* row_ptr, int32_t* col, void* ws,
                         hipStream_t st);
-// vertex2facet forward with LDS-staged facet tiles (bf16, Cin = 64)
+// vertex2facet forward with LDS-staged facet tiles (bf16, Cin = 32 or 64)
 bool pm_v2f_stage_applies(pm_dtype dt, int cin, int cout, const void* h, const void* out);
-pm_status pm_launch_v2f_stage(int64_t F, int cout, const int32_t* facet, const void* h, const void* apack, void* out,
-                              hipStream_t st);
+pm_status pm_launch_v2f_stage(int64_t F, int cin, int cout, const int32_t* facet, const void* h, const void* apack,
+                              void* out, hipStream_t st);
 // facet2vertex forward in the vertex-side order (bf16, Cin = 64)
 bool pm_f2v_vs_applies(pm_dtype dt, int K, int cin, int cout, const void* h, const void* out);
 pm_status pm_launch_f2v_vs(const pm_mesh* mesh, const int32_t* row_ptr, const int32_t* col, int K, int cout,

@@ -124,6 +124,9 @@ CASES = [  # (L, cin, cout, dtype)
     (1, 64, 64, "bf16"),
     (4, 64, 128, "bf16"),
     (5, 64, 64, "bf16"),
+    (3, 32, 32, "bf16"),     # staged vertex2facet tiles: 32-channel rows, operand row zero-padded to two chunks
+    (2, 32, 96, "bf16"),
+    (3, 64, 32, "bf16"),
 ]
 
 
