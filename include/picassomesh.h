@@ -168,6 +168,40 @@ pm_status pm_v2f_sep_bwd(const pm_mesh* mesh, const pm_vf_adj* adj, int L, pm_sh
                          pm_dtype dtype, const void* h_vert, const float* alpha, const void* P, const void* dg_facet,
                          void* dh_vert, float* dalpha, float* dP, void* ws, size_t ws_bytes, void* stream);
 
+/* Separable vertex2vertex block (subsection "Angular Arguments in Different Convolutions", end of the vertex2facet
+ * paragraph, and the figure of the four mesh convolutions: a vertex2facet convolution followed by a facet2vertex
+ * convolution, normalisation on the facet and on the vertex features, ReLU as the activation):
+ *   u_f = ( sum_j h_{v_j(f)} (.) s1(e_j) ) P1,                 g_f = act1(a1 (.) u_f + b1)          [n_facet,cmid]
+ *   z_v = 1/|N(v)| sum_{f in N(v)} g_f (.) s2(n_f),            o_v = act2(a2 (.) (z_v P2) + b2)      [n_vert,cout]
+ * with s1, s2 the per-channel SH filters of alpha1 [K,cin], alpha2 [K,cmid] (fp32) as in the separable entry
+ * points above, P1 [cin,cmid], P2 [cmid,cout] of the feature dtype.  An epilogue is a per-channel affine map with
+ * fixed coefficients (normalisation with frozen statistics; device fp32 vectors, either may be NULL = 1 / 0)
+ * and an optional ReLU; a NULL pm_epilogue pointer means none.  For bf16 rows with cin in {32, 64} and cmid a
+ * multiple of 32 up to 128 the facet features never reach memory (unless g_facet asks for them); other shapes
+ * run the same arithmetic through the separable entry points' kernels.
+ * g_facet [n_facet,cmid] and z_vert [n_vert,cmid] (both optional, feature dtype) receive the activated facet
+ * features and the vertex means: the backward pass needs both (g_saved, z_saved) and, when act2 is a ReLU, the
+ * output rows (out_saved).  It returns dh_vert [n_vert,cin] (feature dtype), dalpha1 [K,cin], dP1 [cin,cmid],
+ * dalpha2 [K,cmid], dP2 [cmid,cout] (fp32) for fixed affine coefficients; any may be NULL (dalpha_i and dP_i only
+ * together).  Workspace from pm_v2v_sep_ws_bytes (0 on invalid arguments). */
+typedef struct pm_epilogue {
+  const float* scale;   /* [C] or NULL */
+  const float* shift;   /* [C] or NULL */
+  int relu;             /* 0 / 1 */
+} pm_epilogue;
+size_t pm_v2v_sep_ws_bytes(int backward, int64_t n_vert, int64_t n_facet, int L, int cin, int cmid, int cout,
+                           pm_dtype dtype);
+pm_status pm_v2v_sep(const pm_mesh* mesh, const pm_vf_adj* adj, int L, pm_sh_norm norm, int cin, int cmid, int cout,
+                     pm_dtype dtype, const void* h_vert, const float* alpha1, const void* P1, const pm_epilogue* ep1,
+                     const float* alpha2, const void* P2, const pm_epilogue* ep2, void* out_vert, void* g_facet,
+                     void* z_vert, void* ws, size_t ws_bytes, void* stream);
+pm_status pm_v2v_sep_bwd(const pm_mesh* mesh, const pm_vf_adj* adj, int L, pm_sh_norm norm, int cin, int cmid,
+                         int cout, pm_dtype dtype, const void* h_vert, const float* alpha1, const void* P1,
+                         const pm_epilogue* ep1, const float* alpha2, const void* P2, const pm_epilogue* ep2,
+                         const void* g_saved, const void* z_saved, const void* out_saved, const void* d_out,
+                         void* dh_vert, float* dalpha1, float* dP1, float* dalpha2, float* dP2, void* ws,
+                         size_t ws_bytes, void* stream);
+
 /* ---- Mesh pooling / unpooling (Section "Mesh decimation", paragraph "(Un)poolings") --------------------
  * A decimation hands over two int32 vectors of the INPUT mesh's vertex count n_in: VCluster and IOmap.
  * Encoding taken here (the paper gives none): vcluster[v] = input-mesh index of the representative vertex of

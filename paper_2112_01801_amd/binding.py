@@ -30,6 +30,7 @@ EXPORTS = [
     "pm_cluster_ws_bytes", "pm_validate_clusters", "pm_build_cluster_map", "pm_pool", "pm_pool_bwd", "pm_unpool",
     "pm_unpool_bwd", "pm_pcloud_ws_bytes", "pm_reverse_ws_bytes", "pm_build_reverse_neighbors", "pm_validate_neighbors", "pm_pcloud_conv", "pm_pcloud_conv_bwd",
     "pm_facet_geometry", "pm_texture_ws_bytes", "pm_texture_layout", "pm_texture_bary",
+    "pm_v2v_sep_ws_bytes", "pm_v2v_sep", "pm_v2v_sep_bwd",
 ]
 
 
@@ -109,6 +110,12 @@ def lib():
                     "pm_build_reverse_neighbors": [npt, vp, vp, vp, vp, sz, vp],
                     "pm_pcloud_conv": [npt, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, sz, vp],
                     "pm_pcloud_conv_bwd": [npt, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]})
+        ep = C.POINTER(_PmEpilogue)
+        sig.update({"pm_v2v_sep": [mp, ap, i32, i32, i32, i32, i32, i32, vp, vp, vp, ep, vp, vp, ep, vp, vp, vp, vp, sz, vp],
+                    "pm_v2v_sep_bwd": [mp, ap, i32, i32, i32, i32, i32, i32, vp, vp, vp, ep, vp, vp, ep, vp, vp, vp, vp,
+                                       vp, vp, vp, vp, vp, vp, sz, vp]})
+        l.pm_v2v_sep_ws_bytes.restype = C.c_size_t
+        l.pm_v2v_sep_ws_bytes.argtypes = [i32, i64, i64, i32, i32, i32, i32, i32]
         l.pm_reverse_ws_bytes.restype = C.c_size_t
         l.pm_reverse_ws_bytes.argtypes = [i64, i64]
         l.pm_pcloud_ws_bytes.restype = C.c_size_t
@@ -410,6 +417,76 @@ def pm_v2f_sep_bwd(mesh: Mesh, adj: Adjacency, L: int, h_vert, alpha, P, dg_face
     _check(lib().pm_v2f_sep_bwd(C.byref(m), C.byref(a), L, norm, cin, cout, dtype, _ptr(h_vert), _ptr(alpha), _ptr(P),
                                 _ptr(dg_facet), _ptr(dh), _ptr(da), _ptr(dP), _ptr(ws), ws.numel(), _stream(stream)))
     return dh, da, dP
+
+
+class _PmEpilogue(C.Structure):
+    _fields_ = [("scale", C.c_void_p), ("shift", C.c_void_p), ("relu", C.c_int)]
+
+
+class Epilogue:
+    """Per-channel affine map (fp32 device vectors or None) and optional ReLU after a stage of pm_v2v_sep."""
+
+    def __init__(self, scale=None, shift=None, relu=False):
+        for t in (scale, shift):
+            assert t is None or (t.is_cuda and t.dtype == torch.float32 and t.is_contiguous())
+        self.scale, self.shift, self.relu = scale, shift, bool(relu)
+
+    def c(self):
+        return _PmEpilogue(self.scale.data_ptr() if self.scale is not None else None,
+                           self.shift.data_ptr() if self.shift is not None else None, int(self.relu))
+
+
+def _ep(e):
+    return C.byref(e.c()) if e is not None else None
+
+
+def pm_v2v_sep(mesh: Mesh, adj: Adjacency, L: int, h_vert, alpha1, P1, ep1, alpha2, P2, ep2, dtype: int,
+               norm: int = PM_SH_PAPER, ws=None, stream=None, save: bool = False):
+    """Separable vertex2vertex block (vertex2facet -> epilogue -> facet2vertex -> epilogue); ep1 / ep2: Epilogue or None.
+    With save the activated facet features and the vertex means come back too, (out, g, z), for pm_v2v_sep_bwd."""
+    _check_sep(alpha1, P1, dtype)
+    _check_sep(alpha2, P2, dtype)
+    cin, cmid = P1.shape
+    cout = P2.shape[1]
+    assert P2.shape[0] == cmid
+    dev, td = h_vert.device, torch_dtype(dtype)
+    out = torch.empty((mesh.n_vert, cout), dtype=td, device=dev)
+    g = torch.empty((mesh.n_facet, cmid), dtype=td, device=dev) if save else None
+    z = torch.empty((mesh.n_vert, cmid), dtype=td, device=dev) if save else None
+    if ws is None:
+        ws = alloc_workspace(lib().pm_v2v_sep_ws_bytes(0, mesh.n_vert, mesh.n_facet, L, cin, cmid, cout, dtype), dev)
+    m, a = mesh.c(), adj.c()
+    opt = lambda t: _ptr(t) if t is not None and t.numel() else None
+    _check(lib().pm_v2v_sep(C.byref(m), C.byref(a), L, norm, cin, cmid, cout, dtype, _ptr(h_vert), _ptr(alpha1), _ptr(P1),
+                            _ep(ep1), _ptr(alpha2), _ptr(P2), _ep(ep2), C.c_void_p(out.data_ptr()), opt(g), opt(z),
+                            _ptr(ws), ws.numel(), _stream(stream)))
+    return (out, g, z) if save else out
+
+
+def pm_v2v_sep_bwd(mesh: Mesh, adj: Adjacency, L: int, h_vert, alpha1, P1, ep1, alpha2, P2, ep2, g_saved, z_saved,
+                   out_saved, d_out, dtype: int, norm: int = PM_SH_PAPER, want_dh=True, want_dw=True, ws=None, stream=None):
+    """Returns (dh, dalpha1, dP1, dalpha2, dP2) for fixed epilogue coefficients; the weight gradients are fp32."""
+    _check_sep(alpha1, P1, dtype)
+    _check_sep(alpha2, P2, dtype)
+    cin, cmid = P1.shape
+    cout = P2.shape[1]
+    K = alpha1.shape[0]
+    dev = h_vert.device
+    f32 = dict(dtype=torch.float32, device=dev)
+    dh = torch.empty((mesh.n_vert, cin), dtype=torch_dtype(dtype), device=dev) if want_dh else None
+    da1 = torch.empty((K, cin), **f32) if want_dw else None
+    dP1 = torch.empty((cin, cmid), **f32) if want_dw else None
+    da2 = torch.empty((K, cmid), **f32) if want_dw else None
+    dP2 = torch.empty((cmid, cout), **f32) if want_dw else None
+    if ws is None:
+        ws = alloc_workspace(lib().pm_v2v_sep_ws_bytes(1, mesh.n_vert, mesh.n_facet, L, cin, cmid, cout, dtype), dev)
+    m, a = mesh.c(), adj.c()
+    opt = lambda t: _ptr(t) if t is not None and t.numel() else None
+    _check(lib().pm_v2v_sep_bwd(C.byref(m), C.byref(a), L, norm, cin, cmid, cout, dtype, _ptr(h_vert), _ptr(alpha1),
+                                _ptr(P1), _ep(ep1), _ptr(alpha2), _ptr(P2), _ep(ep2), opt(g_saved), opt(z_saved),
+                                opt(out_saved), opt(d_out), opt(dh), _ptr(da1), _ptr(dP1), _ptr(da2), _ptr(dP2),
+                                _ptr(ws), ws.numel(), _stream(stream)))
+    return dh, da1, dP1, da2, dP2
 
 
 # ---- pooling / unpooling over vertex clusters -------------------------------------------------------

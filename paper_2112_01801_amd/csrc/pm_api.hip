@@ -476,6 +476,17 @@ static pm_status check_sep(const float* alpha, const void* P) {
   return check_ptr(P, "P", true);
 }
 
+// out = rows P on directly addressed rows (apack: the plain or transposed image of P): the staged-tile kernel for
+// the bf16 shapes it covers, else the general row kernel
+static pm_status pointwise_rows(pm_dtype dtype, int64_t R, int cin, int cout, const void* rows, const void* apack,
+                                void* out, int out_bf16, hipStream_t st) {
+  if (out_bf16 && pm_v2f_stage_applies(dtype, cin, cout, rows, out))
+    return pm_launch_v2v_stage(R, cin, cout, nullptr, rows, apack, nullptr, nullptr, 0, nullptr, nullptr, 0, nullptr,
+                               nullptr, out, st);
+  RowSrc xs = row_src(rows, dtype, cin);
+  return pm_launch_conv_rows(dtype, B_ONE, X_DIRECT, R, 1, cin, cout, basis_none(), xs, apack, out, out_bf16, st);
+}
+
 extern "C" pm_status pm_f2v_sep(const pm_mesh* mesh, const pm_vf_adj* adj, int L, pm_sh_norm norm, int cin, int cout,
                                 pm_dtype dtype, const void* h_facet, const float* alpha, const void* P, void* g_vert,
                                 void* z_vert, void* ws, size_t ws_bytes, void* stream) {
@@ -504,8 +515,7 @@ extern "C" pm_status pm_f2v_sep(const pm_mesh* mesh, const pm_vf_adj* adj, int L
   PM_TRY(pm_launch_dw_f2v(F, K, cin, fb, bs, h_facet, alpha, y, st));
   PM_TRY(pm_launch_segreduce(V, cin, y, fb, adj->row_ptr, adj->col, 3, 1, z, fb, st));
   PM_TRY(pm_launch_pack(PACK_PLAIN, dtype, 1, cin, cout, P, nullptr, apack, st));
-  RowSrc xs = row_src(z, dtype, cin);
-  return pm_launch_conv_rows(dtype, B_ONE, X_DIRECT, V, 1, cin, cout, basis_none(), xs, apack, g_vert, fb, st);
+  return pointwise_rows(dtype, V, cin, cout, z, apack, g_vert, fb, st);
 }
 
 extern "C" pm_status pm_f2v_sep_bwd(const pm_mesh* mesh, const pm_vf_adj* adj, int L, pm_sh_norm norm, int cin,
@@ -616,8 +626,7 @@ extern "C" pm_status pm_v2f_sep_bwd(const pm_mesh* mesh, const pm_vf_adj* adj, i
     // one GEMM row per facet with P alone (the three corner matrices differ only by a channel scale), then the
     // per-vertex sum applies the scale of each entry's corner
     PM_TRY(pm_launch_pack(PACK_TRANS, dtype, 1, cin, cout, P, nullptr, apack, st));
-    RowSrc gs = row_src(dg_facet, dtype, cout);
-    PM_TRY(pm_launch_conv_rows(dtype, B_ONE, X_DIRECT, F, 1, cout, cin, basis_none(), gs, apack, sv, fb, st));
+    PM_TRY(pointwise_rows(dtype, F, cout, cin, dg_facet, apack, sv, fb, st));
     PM_TRY(pm_launch_slot_scale_sum(V, K, cin, fb, sv, adj->row_ptr, adj->col, alpha, &fc,
                                     (float*)((char*)M + pm_round_up((size_t)3 * cin * cout * 4, 256)), dh_vert, st));
   }
@@ -630,6 +639,142 @@ extern "C" pm_status pm_v2f_sep_bwd(const pm_mesh* mesh, const pm_vf_adj* adj, i
     PM_TRY(pm_launch_sep_unfold(K, cin, cout, fb, M, alpha, P, &fc, dalpha, dP, st));
   }
   return PM_OK;
+}
+
+// ---- separable vertex2vertex block ---------------------------------------------------------------------
+struct V2vWs { size_t ap1, ap2, gbuf, dq, sub, total; };
+
+static V2vWs plan_v2v(int bwd, int64_t V, int64_t F, int L, int cin, int cmid, int cout, pm_dtype dt) {
+  V2vWs w = {0, 0, 0, 0, 0, 0};
+  if (!bwd) {
+    w.ap1 = pm_pack_bytes(pm_pack_geom(1, 3 * cin, cmid, dt));
+    w.ap2 = pm_pack_bytes(pm_pack_geom(1, cmid, cout, dt));
+    w.gbuf = pm_round_up((size_t)F * cmid * esize(dt), 256);      // facet rows: g (general path) or g (.) s2 (fused)
+    w.sub = std::max(plan_ws(PM_OP_V2F_SEP, V, F, 0, L, cin, cmid, dt).total,
+                     plan_ws(PM_OP_F2V_SEP, V, F, 0, L, cmid, cout, dt).total);
+  } else {
+    w.dq = pm_round_up((size_t)V * cout * esize(dt), 256);        // gradient at z P2
+    w.gbuf = pm_round_up((size_t)F * cmid * esize(dt), 256);      // gradient at g, then at u
+    w.sub = std::max(plan_ws(PM_OP_V2F_SEP_BWD, V, F, 0, L, cin, cmid, dt).total,
+                     plan_ws(PM_OP_F2V_SEP_BWD, V, F, 0, L, cmid, cout, dt).total);
+  }
+  w.total = w.ap1 + w.ap2 + w.gbuf + w.dq + w.sub;
+  return w;
+}
+
+static pm_status check_v2v(const pm_mesh* mesh, const pm_vf_adj* adj, int L, pm_sh_norm norm, int cin, int cmid, int cout,
+                           pm_dtype dtype, const float* alpha1, const void* P1, const float* alpha2, const void* P2) {
+  PM_TRY(check_conv_common(L, norm, cin, cmid, dtype));
+  PM_TRY(check_conv_common(L, norm, cmid, cout, dtype));
+  PM_TRY(check_mesh(mesh, true));
+  if (!adj || !adj->row_ptr || (mesh->n_facet > 0 && !adj->col)) return pm_fail(PM_ERR_INVALID_ARG, "adjacency is NULL");
+  PM_TRY(check_sep(alpha1, P1));
+  return check_sep(alpha2, P2);
+}
+
+extern "C" size_t pm_v2v_sep_ws_bytes(int backward, int64_t n_vert, int64_t n_facet, int L, int cin, int cmid, int cout,
+                                      pm_dtype dtype) {
+  if (n_vert < 0 || n_facet < 0) return 0;
+  if (check_conv_common(L, PM_SH_PAPER, cin, cmid, dtype) != PM_OK) return 0;
+  if (check_conv_common(L, PM_SH_PAPER, cmid, cout, dtype) != PM_OK) return 0;
+  return plan_v2v(backward != 0, n_vert, n_facet, L, cin, cmid, cout, dtype).total;
+}
+
+extern "C" pm_status pm_v2v_sep(const pm_mesh* mesh, const pm_vf_adj* adj, int L, pm_sh_norm norm, int cin, int cmid,
+                                int cout, pm_dtype dtype, const void* h_vert, const float* alpha1, const void* P1,
+                                const pm_epilogue* ep1, const float* alpha2, const void* P2, const pm_epilogue* ep2,
+                                void* out_vert, void* g_facet, void* z_vert, void* ws, size_t ws_bytes, void* stream) {
+  PM_TRY(check_v2v(mesh, adj, L, norm, cin, cmid, cout, dtype, alpha1, P1, alpha2, P2));
+  PM_TRY(check_ptr(h_vert, "h_vert", mesh->n_vert > 0));
+  PM_TRY(check_ptr(out_vert, "out_vert", mesh->n_vert > 0));
+  PM_TRY(check_ptr(g_facet, "g_facet", false));
+  PM_TRY(check_ptr(z_vert, "z_vert", false));
+  const int K = (L + 1) * (L + 1);
+  const int64_t V = mesh->n_vert, F = mesh->n_facet;
+  V2vWs w = plan_v2v(0, V, F, L, cin, cmid, cout, dtype);
+  PM_TRY(check_ptr(ws, "ws", true));
+  if (ws_bytes < w.total) return pm_fail(PM_ERR_WORKSPACE, "workspace %zu < required %zu bytes", ws_bytes, w.total);
+  hipStream_t st = (hipStream_t)stream;
+  char* ap1 = (char*)ws;
+  char* ap2 = ap1 + w.ap1;
+  void* gbuf = ap2 + w.ap2;
+  char* sub = (char*)gbuf + w.gbuf;
+  const int fb = dtype == PM_BF16;
+  const pm_epilogue none = {nullptr, nullptr, 0};
+  const pm_epilogue e1 = ep1 ? *ep1 : none, e2 = ep2 ? *ep2 : none;
+  if (F > 0 && pm_v2f_stage_applies(dtype, cin, cmid, h_vert, gbuf) && (!g_facet || pm_aligned16(g_facet))) {
+    // fused: gather, fold, epilogue and depth-wise filter per facet tile; vertex means; point-wise matrix + epilogue
+    pm_prof_set_op("v2v_sep");
+    FoldCoef fc;
+    fold_coef(L, norm, &fc);
+    ShTable sh;
+    pm_make_sh_table(L, norm, &sh);
+    PM_TRY(pm_launch_pack(PACK_SEP_FOLD, dtype, K, cin, cmid, P1, &fc, ap1, st, alpha1));
+    PM_TRY(pm_launch_v2v_stage(F, cin, cmid, mesh->facet, h_vert, ap1, e1.scale, e1.shift, e1.relu, g_facet, alpha2, K,
+                               mesh->vert, &sh, gbuf, st));
+    void* z = z_vert ? z_vert : (void*)sub;
+    PM_TRY(pm_launch_segreduce(V, cmid, gbuf, fb, adj->row_ptr, adj->col, 3, 1, z, fb, st));
+    PM_TRY(pm_launch_pack(PACK_PLAIN, dtype, 1, cmid, cout, P2, nullptr, ap2, st));
+    if (pm_v2f_stage_applies(dtype, cmid, cout, z, out_vert))
+      return pm_launch_v2v_stage(V, cmid, cout, nullptr, z, ap2, e2.scale, e2.shift, e2.relu, nullptr, nullptr, 0, nullptr,
+                                 nullptr, out_vert, st);
+    RowSrc xs = row_src(z, dtype, cmid);
+    PM_TRY(pm_launch_conv_rows(dtype, B_ONE, X_DIRECT, V, 1, cmid, cout, basis_none(), xs, ap2, out_vert, fb, st));
+    return pm_launch_affine_act(V, cout, fb, out_vert, e2.scale, e2.shift, e2.relu, st);
+  }
+  // general shapes: the separable entry points with the element-wise epilogues in between
+  void* g = g_facet ? g_facet : gbuf;
+  PM_TRY(pm_v2f_sep(mesh, L, norm, cin, cmid, dtype, h_vert, alpha1, P1, g, sub, w.sub, stream));
+  pm_prof_set_op("v2v_sep");
+  PM_TRY(pm_launch_affine_act(F, cmid, fb, g, e1.scale, e1.shift, e1.relu, st));
+  PM_TRY(pm_f2v_sep(mesh, adj, L, norm, cmid, cout, dtype, g, alpha2, P2, out_vert, z_vert, sub, w.sub, stream));
+  pm_prof_set_op("v2v_sep");
+  return pm_launch_affine_act(V, cout, fb, out_vert, e2.scale, e2.shift, e2.relu, st);
+}
+
+extern "C" pm_status pm_v2v_sep_bwd(const pm_mesh* mesh, const pm_vf_adj* adj, int L, pm_sh_norm norm, int cin, int cmid,
+                                    int cout, pm_dtype dtype, const void* h_vert, const float* alpha1, const void* P1,
+                                    const pm_epilogue* ep1, const float* alpha2, const void* P2, const pm_epilogue* ep2,
+                                    const void* g_saved, const void* z_saved, const void* out_saved, const void* d_out,
+                                    void* dh_vert, float* dalpha1, float* dP1, float* dalpha2, float* dP2, void* ws,
+                                    size_t ws_bytes, void* stream) {
+  PM_TRY(check_v2v(mesh, adj, L, norm, cin, cmid, cout, dtype, alpha1, P1, alpha2, P2));
+  const int64_t V = mesh->n_vert, F = mesh->n_facet;
+  const pm_epilogue none = {nullptr, nullptr, 0};
+  const pm_epilogue e1 = ep1 ? *ep1 : none, e2 = ep2 ? *ep2 : none;
+  PM_TRY(check_ptr(h_vert, "h_vert", V > 0));
+  PM_TRY(check_ptr(g_saved, "g_saved", F > 0));
+  PM_TRY(check_ptr(z_saved, "z_saved", V > 0));
+  PM_TRY(check_ptr(out_saved, "out_saved", V > 0 && e2.relu));
+  PM_TRY(check_ptr(d_out, "d_out", V > 0));
+  PM_TRY(check_ptr(dh_vert, "dh_vert", false));
+  if ((dalpha1 == nullptr) != (dP1 == nullptr) || (dalpha2 == nullptr) != (dP2 == nullptr))
+    return pm_fail(PM_ERR_INVALID_ARG, "dalpha and dP come together");
+  V2vWs w = plan_v2v(1, V, F, L, cin, cmid, cout, dtype);
+  PM_TRY(check_ptr(ws, "ws", true));
+  if (ws_bytes < w.total) return pm_fail(PM_ERR_WORKSPACE, "workspace %zu < required %zu bytes", ws_bytes, w.total);
+  hipStream_t st = (hipStream_t)stream;
+  void* dg = ws;                                  // gradient at the facet features, then at u
+  void* dq = (char*)dg + w.gbuf;
+  char* sub = (char*)dq + w.dq;
+  const int fb = dtype == PM_BF16;
+  // gradient at z P2 (the epilogue of the vertex stage), then the facet2vertex stage
+  pm_prof_set_op("v2v_sep_bwd");
+  const void* dq_in = d_out;
+  if (e2.scale || e2.relu) {
+    PM_TRY(pm_launch_affine_act_bwd(V, cout, fb, d_out, out_saved, e2.scale, e2.relu, dq, st));
+    dq_in = dq;
+  }
+  const bool need_dg = dh_vert || dP1;
+  PM_TRY(pm_f2v_sep_bwd(mesh, adj, L, norm, cmid, cout, dtype, g_saved, alpha2, P2, dq_in, z_saved, need_dg ? dg : nullptr,
+                        dalpha2, dP2, sub, w.sub, stream));
+  if (!need_dg) return PM_OK;
+  pm_prof_set_op("v2v_sep_bwd");
+  if (e1.scale || e1.relu) PM_TRY(pm_launch_affine_act_bwd(F, cmid, fb, dg, g_saved, e1.scale, e1.relu, dg, st));
+  pm_status rc = pm_v2f_sep_bwd(mesh, adj, L, norm, cin, cmid, dtype, h_vert, alpha1, P1, dg, dh_vert, dalpha1, dP1, sub,
+                                w.sub, stream);
+  pm_prof_set_op("v2v_sep_bwd");
+  return rc;
 }
 
 // ---- pooling / unpooling over vertex clusters ------------------------------------------------------

@@ -187,6 +187,15 @@ pm_status pm_launch_csr(int64_t n_rows, int64_t n_entries, const int32_t* keys, 
 bool pm_v2f_stage_applies(pm_dtype dt, int cin, int cout, const void* h, const void* out);
 pm_status pm_launch_v2f_stage(int64_t F, int cin, int cout, const int32_t* facet, const void* h, const void* apack,
                               void* out, hipStream_t st);
+// the same kernel with the fused stages of the separable vertex2vertex block (see pm_v2f_stage.hip)
+pm_status pm_launch_v2v_stage(int64_t R, int cin, int cout, const int32_t* facet, const void* h, const void* apack,
+                              const float* ep_scale, const float* ep_shift, int relu, void* save, const float* alpha2,
+                              int K2, const float* vert, const ShTable* sh, void* out, hipStream_t st);
+// x <- act(scale x + shift) in place, and its backward out = dy scale [y_saved > 0]   (scale / shift may be NULL)
+pm_status pm_launch_affine_act(int64_t n_rows, int C, int is_bf16, void* x, const float* scale, const float* shift,
+                               int relu, hipStream_t st);
+pm_status pm_launch_affine_act_bwd(int64_t n_rows, int C, int is_bf16, const void* dy, const void* y_saved,
+                                   const float* scale, int relu, void* out, hipStream_t st);
 // facet2vertex forward in the vertex-side order (bf16, Cin = 64)
 bool pm_f2v_vs_applies(pm_dtype dt, int K, int cin, int cout, const void* h, const void* out);
 pm_status pm_launch_f2v_vs(const pm_mesh* mesh, const int32_t* row_ptr, const int32_t* col, int K, int cout,

@@ -1,56 +1,96 @@
 // vertex2facet forward (Eq. 6) with LDS-staged facet tiles, for the memory-bound shapes bf16, Cin = 32 or 64:
 //     g_f = sum_j W_j^T h_{v_j(f)},   W_j = sum_k B_k(e_j) W[k]   (the three folded matrices of the packed image)
-// The work per facet is three gathered vertex rows (64 or 128 bytes), a 3 Cin x Cout contraction and one output row, so the
-// kernel lives on its memory system.  A workgroup of 4 waves walks tiles of 128 facets: the 384 vertex rows of a
-// tile are fetched with whole-row accesses (16 bytes a lane) into a padded LDS tile (the three rows of a facet side
-// by side, as the concatenated operand row of the folded form), one tile
-// ahead of the arithmetic (ids two tiles ahead), the matrix core takes its operand granules from LDS, and the
-// output tile goes back through LDS so that it leaves in whole rows.  The folded weights (up to 48 KB) stay in LDS.
+// The work per facet is three gathered vertex rows (64 or 128 bytes), a 3 Cin x Cout contraction and one output
+// row, so the kernel lives on its memory system.  A workgroup of 4 waves walks tiles of 128 facets: the 384 vertex
+// rows of a tile are fetched with whole-row accesses (16 bytes a lane) into a padded LDS tile (the three rows of a
+// facet side by side, as the concatenated operand row of the folded form), one tile ahead of the arithmetic (ids
+// two tiles ahead), the matrix core takes its operand granules from LDS, and the output tile goes back through
+// LDS so that it leaves in whole rows.  The folded weights (up to 48 KB) stay in LDS.
+//
+// The same kernel serves, by template arguments,
+//   * a point-wise matrix on directly addressed rows (NJ = 1: the tile is 128 consecutive rows), and
+//   * the fused stages of the separable vertex2vertex block (FUSE): a per-channel affine map and ReLU on the
+//     accumulators, an optional copy of these activated rows, and the depth-wise facet2vertex filter
+//     s_f[c] = sum_k alpha2[k][c] B_k(n_f) (Eq. 5) multiplied in before the store.  The filter values come from the
+//     fp32 matrix core in the accumulators' own layout: D[c][row] = sum_k alpha2[k][c] B_k(n_row) with
+//     32x32x2 tiles (A[c][kk] = alpha2[k0 + kk][c] from lane (c, kk), B[kk][row] = the basis value k0 + kk of the
+//     lane's own row), so the vector ALU only evaluates the basis of its row and multiplies.
 #include "pm_host.h"
 #include "pm_device.h"
+#include "pm_rows.h"
 
-#define VT_ROWS 128                 /* facets per tile */
+#define VT_ROWS 128                 /* rows per tile */
 #define VT_STAGE_U4 (PM_STAGE_BYTES / 16)
 
 struct VtP {
-  int64_t F;
+  int64_t F;                // rows: facets (NJ = 3) or directly addressed rows (NJ = 1)
   int cout;
-  const int32_t* facet;     // [F][3]
-  const uint16_t* h;        // [V][CIN] bf16
-  const uint4* apack;       // folded image: stage (nbg * NCH + ch)
+  const int32_t* facet;     // NJ = 3: [F][3]
+  const uint16_t* h;        // [.][CIN] bf16
+  const uint4* apack;       // packed image with one basis slot: stage (nbg * NCH + ch)
   uint16_t* out;            // [F][cout] bf16
+  int tile_bytes;           // LDS bytes of the tile buffer
+  // FUSE only
+  const float* ep_scale;    // [cout] or NULL (1)
+  const float* ep_shift;    // [cout] or NULL (0)
+  int relu;
+  uint16_t* save;           // [F][cout] activated rows, or NULL
+  const float* alpha2;      // [K2][cout] depth-wise coefficients, or NULL (no depth-wise stage)
+  int K2;
+  const float* vert;        // vertex positions (facet normals)
+  ShTable sh;
 };
 
-// CIN: 32 or 64.  NB: 32-wide output blocks (cout = 32 NB, 1..4).
-template <int CIN, int NB>
+__host__ __device__ constexpr int vt_nch(int cin, int nj) { return (nj * cin + 63) / 64; }
+__host__ __device__ constexpr int vt_pitch(int cin, int nj) { return vt_nch(cin, nj) * 128 + 16; }
+__host__ __device__ constexpr int vt_out_pitch(int nb) { return 64 * nb + 16; }
+
+// CIN: 32 or 64.  NB: 32-wide output blocks (cout = 32 NB, 1..4).  NJ: 3 gathered corner rows or 1 direct row.
+template <int CIN, int NB, int NJ, bool FUSE>
 __global__ void __launch_bounds__(256) k_v2f_stage(VtP p) {
   extern __shared__ uint4 vt_lds[];
   constexpr int NBG = (NB + 1) / 2;                 // weight stages hold two 32-wide blocks
-  constexpr int NCH = (3 * CIN + 63) / 64;          // 64-channel chunks of the concatenated operand row
-  constexpr int PPR = CIN / 8;                      // 16-byte pieces per vertex row
-  constexpr int ROWB = NCH * 128;                   // operand row bytes (zero beyond 3 CIN channels)
-  constexpr int PITCH = ROWB + 16;                  // + 16 of padding (bank spread)
-  constexpr int ITEMS = VT_ROWS * 3 * PPR;          // 16-byte pieces per tile
-  constexpr int PT = (ITEMS + 255) / 256;
-  constexpr int TILE_BYTES = VT_ROWS * PITCH;
+  constexpr int NCH = vt_nch(CIN, NJ);              // 64-channel chunks of the concatenated operand row
+  constexpr int PPR = CIN / 8;                      // 16-byte pieces per source row
+  constexpr int IPR = NJ * PPR;                     // pieces per tile row
+  constexpr int ROWB = NCH * 128;                   // operand row bytes (zero beyond NJ CIN channels)
+  constexpr int PITCH = vt_pitch(CIN, NJ);          // + 16 of padding (bank spread)
+  constexpr int ITEMS = VT_ROWS * IPR;              // 16-byte pieces per tile
+  constexpr int PT = ITEMS / 256;
+  constexpr int CO = 32 * NB;
+  constexpr int OP = vt_out_pitch(NB);              // padded output row pitch (bytes)
+  static_assert(ITEMS % 256 == 0, "whole passes of the workgroup");
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int r = lane & 31, hh = lane >> 5;
+  const int K2P = FUSE ? ((p.K2 + 1) & ~1) : 0;     // basis slots padded to the matrix tile's depth of 2
+  const int KP = p.K2 | 1;                          // odd pitch of a basis row: conflict-free reads
   uint4* Wl = vt_lds;                                              // [NBG * NCH][VT_STAGE_U4]
-  char* tile_lds = (char*)(vt_lds + NBG * NCH * VT_STAGE_U4);      // [VT_ROWS][PITCH]
+  float* Al = (float*)(vt_lds + NBG * NCH * VT_STAGE_U4);         // FUSE: [K2P][CO] coefficients, then [2][CO] affine
+  float* Ep = Al + K2P * CO;
+  char* tile_lds = (char*)(Ep + (FUSE ? 2 * CO : 0));             // [VT_ROWS][PITCH], reused for the output tile
+  float* Bw = (float*)(tile_lds + VT_ROWS * OP) + wave * 32 * KP;  // FUSE: this wave's basis rows [32][KP]
   const int64_t n_tiles = (p.F + VT_ROWS - 1) / VT_ROWS;
 
   for (int i = tid; i < NBG * NCH * VT_STAGE_U4; i += 256) Wl[i] = p.apack[i];
-  for (int i = tid; i < TILE_BYTES / 16; i += 256) ((uint4*)tile_lds)[i] = make_uint4(0, 0, 0, 0);   // the pad stays zero
+  if constexpr (FUSE) {
+    for (int i = tid; i < K2P * CO; i += 256) Al[i] = (i / CO < p.K2 && p.alpha2) ? p.alpha2[i] : 0.f;
+    for (int i = tid; i < CO; i += 256) {
+      Ep[i] = p.ep_scale ? p.ep_scale[i] : 1.f;
+      Ep[CO + i] = p.ep_shift ? p.ep_shift[i] : 0.f;
+    }
+  }
+  for (int i = tid; i < p.tile_bytes / 16; i += 256) ((uint4*)tile_lds)[i] = make_uint4(0, 0, 0, 0);   // the pad stays zero
   __syncthreads();
 
-  // piece i of this thread: item = tid + 256 i -> (facet of the tile, corner, 16-byte piece of the vertex row)
+  // piece i of this thread: item = tid + 256 i -> (row of the tile, corner, 16-byte piece of the source row)
   auto load_ids = [&](int64_t tile, int32_t (&vid)[PT]) {
 #pragma unroll
     for (int i = 0; i < PT; ++i) {
       const int item = tid + 256 * i;
-      const int64_t f = tile * VT_ROWS + item / (3 * PPR);
-      const int j = (item % (3 * PPR)) / PPR;
-      vid[i] = (item < ITEMS && tile < n_tiles && f < p.F) ? p.facet[3 * f + j] : -1;
+      const int64_t f = tile * VT_ROWS + item / IPR;
+      const int j = (item % IPR) / PPR;
+      vid[i] = -1;
+      if (tile < n_tiles && f < p.F) vid[i] = (NJ == 3) ? p.facet[3 * f + j] : (int32_t)f;
     }
   };
   auto load_rows = [&](const int32_t (&vid)[PT], uint4 (&x)[PT]) {
@@ -65,24 +105,42 @@ __global__ void __launch_bounds__(256) k_v2f_stage(VtP p) {
 #pragma unroll
     for (int i = 0; i < PT; ++i) {
       const int item = tid + 256 * i;
-      if (item < ITEMS) *(uint4*)(tile_lds + (item / (3 * PPR)) * PITCH + (item % (3 * PPR)) * 16) = x[i];
+      *(uint4*)(tile_lds + (item / IPR) * PITCH + (item % IPR) * 16) = x[i];
     }
+  };
+  // FUSE with the depth-wise stage: corner ids of the lane's own facet (one tile ahead), then its corner positions
+  const bool dw = FUSE && p.alpha2 != nullptr;
+  int32_t fid[3] = {0, 0, 0};
+  auto load_fid = [&](int64_t tile) {
+    const int64_t f = min(tile * VT_ROWS + wave * 32 + r, p.F - 1);
+#pragma unroll
+    for (int j = 0; j < 3; ++j) fid[j] = p.facet[3 * f + j];
   };
 
   int32_t vid[PT];
   uint4 x[PT];
   int64_t tile = blockIdx.x;
   load_ids(tile, vid);
+  if (dw) load_fid(tile);
   load_rows(vid, x);
   load_ids(tile + gridDim.x, vid);
   stage_rows(x);
   __syncthreads();
   for (; tile < n_tiles; tile += gridDim.x) {
+    DirRaw dr;
+    if (dw) {
+#pragma unroll
+      for (int j = 0; j < 3; ++j) {
+        const float* q = p.vert + 3 * (int64_t)fid[j];
+        dr.v[3 * j] = q[0]; dr.v[3 * j + 1] = q[1]; dr.v[3 * j + 2] = q[2];
+      }
+    }
     // next tile's rows and the ids of the one after: in flight during this tile's arithmetic
     load_rows(vid, x);
     load_ids(tile + 2 * (int64_t)gridDim.x, vid);
+    if (dw) load_fid(tile + gridDim.x);
 
-    // ---- this wave's 32 facets: operand granules from the staged tile, folded weights from LDS
+    // ---- this wave's 32 rows: operand granules from the staged tile, weights from LDS
     floatx16 y[NB];
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb)
@@ -103,11 +161,11 @@ __global__ void __launch_bounds__(256) k_v2f_stage(VtP p) {
       }
     }
     __syncthreads();                            // every wave is done with the staged rows of this tile
-    // ---- output tile through the same LDS buffer: lane (r, hh) holds, per 32-wide block, channels
-    //      q4 * 8 + hh * 4 + i of its facet; then whole rows leave in 16-byte pieces
-    {
-      constexpr int OP = 64 * NB + 16;          // padded output row pitch (bytes)
-      static_assert(VT_ROWS * OP <= TILE_BYTES, "the output tile fits the staging buffer");
+
+    // the tile of accumulators leaves through the LDS buffer: lane (r, hh) holds, per 32-wide block, channels
+    // q4 * 8 + hh * 4 + i of its row; whole rows then go out in 16-byte pieces
+    const int64_t f0 = tile * VT_ROWS;
+    auto store_tile = [&](uint16_t* dst) {
 #pragma unroll
       for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
@@ -118,22 +176,65 @@ __global__ void __launch_bounds__(256) k_v2f_stage(VtP p) {
           *(uint2*)(tile_lds + (wave * 32 + r) * OP + (nb * 32 + q4 * 8 + hh * 4) * 2) = w;
         }
       __syncthreads();
-      const int64_t f0 = tile * VT_ROWS;
       constexpr int OPR = 4 * NB;               // 16-byte pieces per output row
 #pragma unroll
       for (int i = 0; i < (VT_ROWS * OPR) / 256; ++i) {
         const int item = tid + 256 * i;
         const int row = item / OPR, piece = item % OPR;
-        if (f0 + row < p.F)
-          *(uint4*)(p.out + (f0 + row) * (32 * NB) + piece * 8) = *(const uint4*)(tile_lds + row * OP + piece * 16);
+        if (f0 + row < p.F) *(uint4*)(dst + (f0 + row) * CO + piece * 8) = *(const uint4*)(tile_lds + row * OP + piece * 16);
       }
       __syncthreads();
-      // the output overwrote the zero pad of the rows it touched: restore it where the staged rows do not reach
-      if (3 * CIN * 2 < ROWB) {
-        constexpr int PADP = (ROWB - 3 * CIN * 2) / 16;   // 16-byte pieces of pad per row
-        for (int i = tid; i < VT_ROWS * PADP; i += 256)
-          *(uint4*)(tile_lds + (i / PADP) * PITCH + 3 * CIN * 2 + (i % PADP) * 16) = make_uint4(0, 0, 0, 0);
+    };
+
+    if constexpr (FUSE) {
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) {
+          const int co = nb * 32 + q4 * 8 + hh * 4;
+          const float4 sc = *(const float4*)(Ep + co), sh = *(const float4*)(Ep + CO + co);
+          const float scv[4] = {sc.x, sc.y, sc.z, sc.w}, shv[4] = {sh.x, sh.y, sh.z, sh.w};
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            float v = y[nb][q4 * 4 + i] * scv[i] + shv[i];
+            y[nb][q4 * 4 + i] = p.relu ? fmaxf(v, 0.f) : v;
+          }
+        }
+      if (p.save) store_tile(p.save);
+      if (dw) {
+        // basis of the wave's 32 facets into its own LDS rows (both half-waves hold the same rows), then the
+        // filter values of every accumulator element from the fp32 matrix core
+        float nx, ny, nz;
+        dir_finish<B_NORMAL>(dr, nx, ny, nz);
+        sh_eval<-1>(nx, ny, nz, p.sh, [&](int k, float v) {
+          if (hh == 0) Bw[r * KP + k] = v;
+        });
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) {
+          floatx16 S;
+#pragma unroll
+          for (int i = 0; i < 16; ++i) S[i] = 0.f;
+          for (int k0 = 0; k0 < K2P; k0 += 2) {
+            const int k = k0 + hh;
+            const float a = Al[k * CO + nb * 32 + r];
+            const float b = (k < p.K2) ? Bw[r * KP + k] : 0.f;
+            S = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, S, 0, 0, 0);
+          }
+#pragma unroll
+          for (int i = 0; i < 16; ++i) y[nb][i] *= S[i];
+        }
+        __builtin_amdgcn_wave_barrier();        // the basis rows have been read
       }
+    }
+    store_tile(p.out);
+    // the output and the basis rows overwrote the zero pad of the rows they touched: restore it where the staged
+    // rows do not reach
+    if constexpr (NJ * CIN * 2 < ROWB) {
+      constexpr int PADP = (ROWB - NJ * CIN * 2) / 16;   // 16-byte pieces of pad per row
+      for (int i = tid; i < VT_ROWS * PADP; i += 256)
+        *(uint4*)(tile_lds + (i / PADP) * PITCH + NJ * CIN * 2 + (i % PADP) * 16) = make_uint4(0, 0, 0, 0);
     }
     stage_rows(x);                              // the next tile goes into the vacated buffer ...
     __syncthreads();                            // ... and is visible to every wave
@@ -145,39 +246,65 @@ bool pm_v2f_stage_applies(pm_dtype dt, int cin, int cout, const void* h, const v
          pm_aligned16(out);
 }
 
-template <int CIN, int NB>
-static pm_status v2f_stage_launch(const VtP& p, hipStream_t st) {
-  constexpr int NBG = (NB + 1) / 2, NCH = (3 * CIN + 63) / 64;
-  const size_t lds = (size_t)NBG * NCH * PM_STAGE_BYTES + (size_t)VT_ROWS * (NCH * 128 + 16);
+template <int CIN, int NB, int NJ, bool FUSE>
+static pm_status v2f_stage_launch(VtP& p, hipStream_t st, const char* label) {
+  constexpr int NBG = (NB + 1) / 2, NCH = vt_nch(CIN, NJ);
+  const int k2p = FUSE ? ((p.K2 + 1) & ~1) : 0;
+  const int bw = (FUSE && p.alpha2) ? 4 * 32 * (p.K2 | 1) * 4 : 0;
+  p.tile_bytes = (int)pm_round_up((size_t)std::max(VT_ROWS * vt_pitch(CIN, NJ), VT_ROWS * vt_out_pitch(NB) + bw), 16);
+  const size_t lds = (size_t)NBG * NCH * PM_STAGE_BYTES + (FUSE ? (size_t)(k2p + 2) * 32 * NB * 4 : 0) + p.tile_bytes;
+  if (lds > 160 * 1024) return pm_fail(PM_ERR_UNSUPPORTED, "staged tiles: %zu bytes of LDS", lds);
   int64_t grid = (p.F + VT_ROWS - 1) / VT_ROWS;
   if (grid > 512) grid = 512;
-  auto kern = k_v2f_stage<CIN, NB>;
+  auto kern = k_v2f_stage<CIN, NB, NJ, FUSE>;
   PM_CHECK_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-  { ProfScope ps__(st, "k_v2f_stage");
+  { ProfScope ps__(st, label);
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(256), lds, st, p); }
-  PM_CHECK_LAUNCH("k_v2f_stage");
+  PM_CHECK_LAUNCH(label);
   return PM_OK;
+}
+
+template <int NJ, bool FUSE>
+static pm_status v2f_stage_dispatch(int cin, VtP& p, hipStream_t st, const char* label) {
+  const int nb = p.cout / 32;
+  if (cin == 32) {
+    switch (nb) {
+      case 1: return v2f_stage_launch<32, 1, NJ, FUSE>(p, st, label);
+      case 2: return v2f_stage_launch<32, 2, NJ, FUSE>(p, st, label);
+      case 3: return v2f_stage_launch<32, 3, NJ, FUSE>(p, st, label);
+      default: return v2f_stage_launch<32, 4, NJ, FUSE>(p, st, label);
+    }
+  }
+  switch (nb) {
+    case 1: return v2f_stage_launch<64, 1, NJ, FUSE>(p, st, label);
+    case 2: return v2f_stage_launch<64, 2, NJ, FUSE>(p, st, label);
+    case 3: return v2f_stage_launch<64, 3, NJ, FUSE>(p, st, label);
+    default: return v2f_stage_launch<64, 4, NJ, FUSE>(p, st, label);
+  }
 }
 
 // apack: the folded packed image (pm_launch_pack with PACK_FOLD or PACK_SEP_FOLD), already enqueued on `st`
 pm_status pm_launch_v2f_stage(int64_t F, int cin, int cout, const int32_t* facet, const void* h, const void* apack,
                               void* out, hipStream_t st) {
   if (F == 0) return PM_OK;
-  VtP p;
+  VtP p = {};
   p.F = F; p.cout = cout; p.facet = facet; p.h = (const uint16_t*)h; p.apack = (const uint4*)apack; p.out = (uint16_t*)out;
-  const int nb = cout / 32;
-  if (cin == 32) {
-    switch (nb) {
-      case 1: return v2f_stage_launch<32, 1>(p, st);
-      case 2: return v2f_stage_launch<32, 2>(p, st);
-      case 3: return v2f_stage_launch<32, 3>(p, st);
-      default: return v2f_stage_launch<32, 4>(p, st);
-    }
-  }
-  switch (nb) {
-    case 1: return v2f_stage_launch<64, 1>(p, st);
-    case 2: return v2f_stage_launch<64, 2>(p, st);
-    case 3: return v2f_stage_launch<64, 3>(p, st);
-    default: return v2f_stage_launch<64, 4>(p, st);
-  }
+  return v2f_stage_dispatch<3, false>(cin, p, st, "k_v2f_stage");
+}
+
+// Fused stages of the separable vertex2vertex block.  facet != NULL: gathered corner rows (apack = folded image of
+// 3 cin x cout), optional depth-wise facet2vertex filter (alpha2, K2 = (L+1)^2 of sh, vert).  facet == NULL: a
+// point-wise matrix on R consecutive rows (apack = plain image of cin x cout).  Either way the accumulators pass
+// through scale/shift (NULL: 1 / 0) and ReLU (relu != 0) first, and `save` (optional) receives them at that point.
+pm_status pm_launch_v2v_stage(int64_t R, int cin, int cout, const int32_t* facet, const void* h, const void* apack,
+                              const float* ep_scale, const float* ep_shift, int relu, void* save, const float* alpha2,
+                              int K2, const float* vert, const ShTable* sh, void* out, hipStream_t st) {
+  if (R == 0) return PM_OK;
+  VtP p = {};
+  p.F = R; p.cout = cout; p.facet = facet; p.h = (const uint16_t*)h; p.apack = (const uint4*)apack; p.out = (uint16_t*)out;
+  p.ep_scale = ep_scale; p.ep_shift = ep_shift; p.relu = relu; p.save = (uint16_t*)save;
+  p.alpha2 = facet ? alpha2 : nullptr; p.K2 = p.alpha2 ? K2 : 0; p.vert = vert;
+  if (sh) p.sh = *sh;
+  if (facet) return v2f_stage_dispatch<3, true>(cin, p, st, "k_v2v_facet");
+  return v2f_stage_dispatch<1, true>(cin, p, st, "k_v2v_point");
 }
