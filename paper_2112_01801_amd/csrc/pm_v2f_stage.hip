@@ -12,9 +12,10 @@
 //   * the fused stages of the separable vertex2vertex block (FUSE): a per-channel affine map and ReLU on the
 //     accumulators, an optional copy of these activated rows, and the depth-wise facet2vertex filter
 //     s_f[c] = sum_k alpha2[k][c] B_k(n_f) (Eq. 5) multiplied in before the store.  The filter values come from the
-//     fp32 matrix core in the accumulators' own layout: D[c][row] = sum_k alpha2[k][c] B_k(n_row) with
-//     32x32x2 tiles (A[c][kk] = alpha2[k0 + kk][c] from lane (c, kk), B[kk][row] = the basis value k0 + kk of the
-//     lane's own row), so the vector ALU only evaluates the basis of its row and multiplies.
+//     matrix core in the accumulators' own layout, D[c][row] = sum_k alpha2[k][c] B_k(n_row), 16 basis functions
+//     per 32x32x16 tile.  Both operands are split into a bf16 head and a bf16 remainder (x = hi + lo, |lo| <=
+//     2^-9 |x|) and the three leading products hi hi + hi lo + lo hi are accumulated in fp32: the dropped lo lo
+//     term is below 2^-16 of a product, so the filter keeps fp32 accuracy at a fifth of the fp32 tiles' cost.
 #include "pm_host.h"
 #include "pm_device.h"
 #include "pm_rows.h"
@@ -46,8 +47,10 @@ __host__ __device__ constexpr int vt_pitch(int cin, int nj) { return vt_nch(cin,
 __host__ __device__ constexpr int vt_out_pitch(int nb) { return 64 * nb + 16; }
 
 // CIN: 32 or 64.  NB: 32-wide output blocks (cout = 32 NB, 1..4).  NJ: 3 gathered corner rows or 1 direct row.
+// Gathered rows: two workgroups share a CU (two waves per SIMD, 256 registers each) unless weights and tile leave
+// LDS for one only.  Direct rows need fewer registers and are left to the compiler's own choice.
 template <int CIN, int NB, int NJ, bool FUSE>
-__global__ void __launch_bounds__(256) k_v2f_stage(VtP p) {
+__global__ void __launch_bounds__(256, (NJ == 1 || (CIN == 64 && NB >= 3)) ? 1 : 2) k_v2f_stage(VtP p) {
   extern __shared__ uint4 vt_lds[];
   constexpr int NBG = (NB + 1) / 2;                 // weight stages hold two 32-wide blocks
   constexpr int NCH = vt_nch(CIN, NJ);              // 64-channel chunks of the concatenated operand row
@@ -62,18 +65,29 @@ __global__ void __launch_bounds__(256) k_v2f_stage(VtP p) {
   static_assert(ITEMS % 256 == 0, "whole passes of the workgroup");
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int r = lane & 31, hh = lane >> 5;
-  const int K2P = FUSE ? ((p.K2 + 1) & ~1) : 0;     // basis slots padded to the matrix tile's depth of 2
+  const int NKC = FUSE ? (p.K2 + 15) >> 4 : 0;      // chunks of 16 basis functions
   const int KP = p.K2 | 1;                          // odd pitch of a basis row: conflict-free reads
   uint4* Wl = vt_lds;                                              // [NBG * NCH][VT_STAGE_U4]
-  float* Al = (float*)(vt_lds + NBG * NCH * VT_STAGE_U4);         // FUSE: [K2P][CO] coefficients, then [2][CO] affine
-  float* Ep = Al + K2P * CO;
+  uint4* Aw = vt_lds + NBG * NCH * VT_STAGE_U4;                    // FUSE: [NKC][NB][hi, lo][64] coefficient operands
+  float* Ep = (float*)(Aw + NKC * NB * 2 * 64);                    // FUSE: [2][CO] affine
   char* tile_lds = (char*)(Ep + (FUSE ? 2 * CO : 0));             // [VT_ROWS][PITCH], reused for the output tile
   float* Bw = (float*)(tile_lds + VT_ROWS * OP) + wave * 32 * KP;  // FUSE: this wave's basis rows [32][KP]
   const int64_t n_tiles = (p.F + VT_ROWS - 1) / VT_ROWS;
 
   for (int i = tid; i < NBG * NCH * VT_STAGE_U4; i += 256) Wl[i] = p.apack[i];
   if constexpr (FUSE) {
-    for (int i = tid; i < K2P * CO; i += 256) Al[i] = (i / CO < p.K2 && p.alpha2) ? p.alpha2[i] : 0.f;
+    // operand of lane (c = lane % 32, half = lane / 32) for chunk kc, block nb: alpha2[16 kc + 8 half + i][32 nb + c]
+    for (int idx = tid; idx < NKC * NB * 2 * 64; idx += 256) {
+      const int ln = idx & 63, part = (idx >> 6) & 1, nb = (idx >> 7) % NB, kc = (idx >> 7) / NB;
+      float v[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const int k = kc * 16 + 8 * (ln >> 5) + i;
+        const float a = (k < p.K2) ? p.alpha2[k * CO + nb * 32 + (ln & 31)] : 0.f;
+        v[i] = part ? a - bf16_to_f32((uint16_t)f32_to_bf16_bits(a)) : a;
+      }
+      Aw[idx] = make_uint4(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]), pack_bf16x2(v[4], v[5]), pack_bf16x2(v[6], v[7]));
+    }
     for (int i = tid; i < CO; i += 256) {
       Ep[i] = p.ep_scale ? p.ep_scale[i] : 1.f;
       Ep[CO + i] = p.ep_shift ? p.ep_shift[i] : 0.f;
@@ -211,16 +225,36 @@ __global__ void __launch_bounds__(256) k_v2f_stage(VtP p) {
         });
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
         __builtin_amdgcn_wave_barrier();
+        // per 32-wide block and chunk of 16 basis functions: the lane's basis operand (functions 16 kc + 8 hh + i
+        // of its row) split into head and remainder, then the three leading products
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) {
           floatx16 S;
 #pragma unroll
           for (int i = 0; i < 16; ++i) S[i] = 0.f;
-          for (int k0 = 0; k0 < K2P; k0 += 2) {
-            const int k = k0 + hh;
-            const float a = Al[k * CO + nb * 32 + r];
-            const float b = (k < p.K2) ? Bw[r * KP + k] : 0.f;
-            S = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, S, 0, 0, 0);
+#pragma unroll 1
+          for (int kc = 0; kc < NKC; ++kc) {
+            float v[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+              const int k = kc * 16 + 8 * hh + i;
+              v[i] = (k < p.K2) ? Bw[r * KP + k] : 0.f;
+            }
+            const uint4 bh = make_uint4(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]), pack_bf16x2(v[4], v[5]),
+                                        pack_bf16x2(v[6], v[7]));
+            const uint32_t hw[4] = {bh.x, bh.y, bh.z, bh.w};
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+              v[2 * i] -= bf16lo_to_f32(hw[i]);
+              v[2 * i + 1] -= bf16hi_to_f32(hw[i]);
+            }
+            const uint4 bl = make_uint4(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]), pack_bf16x2(v[4], v[5]),
+                                        pack_bf16x2(v[6], v[7]));
+            const bf16x8 ah = __builtin_bit_cast(bf16x8, Aw[((kc * NB + nb) * 2 + 0) * 64 + lane]);
+            const bf16x8 al = __builtin_bit_cast(bf16x8, Aw[((kc * NB + nb) * 2 + 1) * 64 + lane]);
+            S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al, __builtin_bit_cast(bf16x8, bh), S, 0, 0, 0);
+            S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, __builtin_bit_cast(bf16x8, bl), S, 0, 0, 0);
+            S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, __builtin_bit_cast(bf16x8, bh), S, 0, 0, 0);
           }
 #pragma unroll
           for (int i = 0; i < 16; ++i) y[nb][i] *= S[i];
@@ -249,10 +283,10 @@ bool pm_v2f_stage_applies(pm_dtype dt, int cin, int cout, const void* h, const v
 template <int CIN, int NB, int NJ, bool FUSE>
 static pm_status v2f_stage_launch(VtP& p, hipStream_t st, const char* label) {
   constexpr int NBG = (NB + 1) / 2, NCH = vt_nch(CIN, NJ);
-  const int k2p = FUSE ? ((p.K2 + 1) & ~1) : 0;
+  const int nkc = FUSE ? (p.K2 + 15) / 16 : 0;
   const int bw = (FUSE && p.alpha2) ? 4 * 32 * (p.K2 | 1) * 4 : 0;
   p.tile_bytes = (int)pm_round_up((size_t)std::max(VT_ROWS * vt_pitch(CIN, NJ), VT_ROWS * vt_out_pitch(NB) + bw), 16);
-  const size_t lds = (size_t)NBG * NCH * PM_STAGE_BYTES + (FUSE ? (size_t)(k2p + 2) * 32 * NB * 4 : 0) + p.tile_bytes;
+  const size_t lds = (size_t)NBG * NCH * PM_STAGE_BYTES + (FUSE ? (size_t)nkc * NB * 2 * 1024 + 2 * 32 * NB * 4 : 0) + p.tile_bytes;
   if (lds > 160 * 1024) return pm_fail(PM_ERR_UNSUPPORTED, "staged tiles: %zu bytes of LDS", lds);
   int64_t grid = (p.F + VT_ROWS - 1) / VT_ROWS;
   if (grid > 512) grid = 512;
