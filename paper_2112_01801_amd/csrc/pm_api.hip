@@ -518,11 +518,11 @@ extern "C" pm_status pm_f2v_sep(const pm_mesh* mesh, const pm_vf_adj* adj, int L
   return pointwise_rows(dtype, V, cin, cout, z, apack, g_vert, fb, st);
 }
 
-extern "C" pm_status pm_f2v_sep_bwd(const pm_mesh* mesh, const pm_vf_adj* adj, int L, pm_sh_norm norm, int cin,
-                                    int cout, pm_dtype dtype, const void* h_facet, const float* alpha, const void* P,
-                                    const void* dg_vert, const void* z_saved, void* dh_facet, float* dalpha, float* dP,
-                                    void* ws, size_t ws_bytes, void* stream) {
-  pm_prof_set_op("f2v_sep_bwd");
+// mask_scale / mask_relu: dh_facet leaves through the epilogue that produced h_facet (vertex2vertex block)
+static pm_status f2v_sep_bwd_impl(const pm_mesh* mesh, const pm_vf_adj* adj, int L, pm_sh_norm norm, int cin,
+                                  int cout, pm_dtype dtype, const void* h_facet, const float* alpha, const void* P,
+                                  const void* dg_vert, const void* z_saved, void* dh_facet, float* dalpha, float* dP,
+                                  void* ws, size_t ws_bytes, void* stream, const float* mask_scale, int mask_relu) {
   PM_TRY(check_conv_common(L, norm, cin, cout, dtype));
   PM_TRY(check_mesh(mesh, true));
   if (!adj || !adj->row_ptr || (mesh->n_facet > 0 && !adj->col)) return pm_fail(PM_ERR_INVALID_ARG, "adjacency is NULL");
@@ -564,8 +564,18 @@ extern "C" pm_status pm_f2v_sep_bwd(const pm_mesh* mesh, const pm_vf_adj* adj, i
                            nullptr, st));
   }
   if (dh_facet || dalpha)
-    PM_TRY(pm_launch_dw_f2v_bwd(F, K, cin, fb, bs, h_facet, alpha, (const float*)dz, adj->row_ptr, dh_facet, dalpha, (float*)wg, st));
+    PM_TRY(pm_launch_dw_f2v_bwd(F, K, cin, fb, bs, h_facet, alpha, (const float*)dz, adj->row_ptr, dh_facet, dalpha,
+                                (float*)wg, mask_scale, mask_relu, st));
   return PM_OK;
+}
+
+extern "C" pm_status pm_f2v_sep_bwd(const pm_mesh* mesh, const pm_vf_adj* adj, int L, pm_sh_norm norm, int cin,
+                                    int cout, pm_dtype dtype, const void* h_facet, const float* alpha, const void* P,
+                                    const void* dg_vert, const void* z_saved, void* dh_facet, float* dalpha, float* dP,
+                                    void* ws, size_t ws_bytes, void* stream) {
+  pm_prof_set_op("f2v_sep_bwd");
+  return f2v_sep_bwd_impl(mesh, adj, L, norm, cin, cout, dtype, h_facet, alpha, P, dg_vert, z_saved, dh_facet, dalpha, dP, ws,
+                          ws_bytes, stream, nullptr, 0);
 }
 
 extern "C" pm_status pm_v2f_sep(const pm_mesh* mesh, int L, pm_sh_norm norm, int cin, int cout, pm_dtype dtype,
@@ -765,12 +775,12 @@ extern "C" pm_status pm_v2v_sep_bwd(const pm_mesh* mesh, const pm_vf_adj* adj, i
     PM_TRY(pm_launch_affine_act_bwd(V, cout, fb, d_out, out_saved, e2.scale, e2.relu, dq, st));
     dq_in = dq;
   }
+  // the depth-wise backward kernel holds g in registers: it hands the gradient on through the facet epilogue,
+  // du = dg a1 [g > 0]
   const bool need_dg = dh_vert || dP1;
-  PM_TRY(pm_f2v_sep_bwd(mesh, adj, L, norm, cmid, cout, dtype, g_saved, alpha2, P2, dq_in, z_saved, need_dg ? dg : nullptr,
-                        dalpha2, dP2, sub, w.sub, stream));
+  PM_TRY(f2v_sep_bwd_impl(mesh, adj, L, norm, cmid, cout, dtype, g_saved, alpha2, P2, dq_in, z_saved, need_dg ? dg : nullptr,
+                          dalpha2, dP2, sub, w.sub, stream, e1.scale, e1.relu));
   if (!need_dg) return PM_OK;
-  pm_prof_set_op("v2v_sep_bwd");
-  if (e1.scale || e1.relu) PM_TRY(pm_launch_affine_act_bwd(F, cmid, fb, dg, g_saved, e1.scale, e1.relu, dg, st));
   pm_status rc = pm_v2f_sep_bwd(mesh, adj, L, norm, cin, cmid, dtype, h_vert, alpha1, P1, dg, dh_vert, dalpha1, dP1, sub,
                                 w.sub, stream);
   pm_prof_set_op("v2v_sep_bwd");

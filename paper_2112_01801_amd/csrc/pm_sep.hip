@@ -3,6 +3,8 @@
 //     y_f[c]  = h_f[c] * s_f[c],            s_f[c] = sum_k alpha[k][c] B_k(n_f)
 //     dh_f[c] = dy_f[c] * s_f[c],           dy_f[c] = sum_j dz[v_j(f)][c] / deg(v_j(f))    (dz in fp32)
 //     dalpha[k][c] = sum_f B_k(n_f) h_f[c] dy_f[c]
+// The backward kernel can also take dh through the epilogue that produced h (vertex2vertex block: h = relu(a u + b),
+// so du = dh a [h > 0]): h is in registers anyway.
 // Bound by HBM (one row read, one written per facet); the K multiply-adds per element run on the fp32
 // matrix cores so that the vector ALU only loads, converts and stores.
 // dalpha is reduced without atomics: every wave accumulates its rows in matrix-core tiles (a fixed assignment
@@ -27,6 +29,8 @@ struct SepP {
   float* partial;         // bwd: [slices][K][C]
   int kc0;                // bwd: first k of this pass
   int want_dalpha;
+  const float* mask_scale; // bwd, optional: dh[c] *= mask_scale[c]          (the affine map that produced h)
+  int mask_relu;           // bwd, optional: dh[c] = 0 where h[c] <= 0       (the ReLU that produced h)
 };
 
 // Lane layout (fixed): a wave holds 4 row groups of 16 lanes, lane `sub` of a group owns channels
@@ -43,7 +47,7 @@ struct SepP {
 // LDS: alpha [4 ceil(kn/4)][64] (zero rows past kn), per wave basis [64][kn | 1], backward: block sum [16][64].
 #define SEP_RW 64
 
-template <bool BF16, bool BWD, bool VEC>
+template <bool BF16, bool BWD, bool VEC, bool MASK = false>
 __global__ void __launch_bounds__(256) k_dw_f2v(SepP p) {
   extern __shared__ float sep_lds[];
   constexpr int CPL = 4;
@@ -71,6 +75,9 @@ __global__ void __launch_bounds__(256) k_dw_f2v(SepP p) {
       A[i] = (k < kn && c < p.C) ? p.alpha[(int64_t)(k0 + k) * p.C + c] : 0.f;
     }
     __syncthreads();
+    float msc[CPL];                           // backward: the epilogue's scale for the lane's channels
+#pragma unroll
+    for (int i = 0; i < CPL; ++i) msc[i] = (MASK && p.mask_scale) ? p.mask_scale[min(c0 + i, p.C - 1)] : 1.f;
     floatx4 D[4];                             // backward: dalpha tiles of this wave
 #pragma unroll
     for (int t = 0; t < 4; ++t) D[t] = floatx4{0.f, 0.f, 0.f, 0.f};
@@ -167,6 +174,10 @@ __global__ void __launch_bounds__(256) k_dw_f2v(SepP p) {
             float o[CPL];
 #pragma unroll
             for (int t = 0; t < 4; ++t) o[t] = (BWD ? dyv[q][t] : hv[q][t]) * S[t][q];
+            if constexpr (MASK) {
+#pragma unroll
+              for (int t = 0; t < 4; ++t) o[t] = (p.mask_relu && !(hv[q][t] > 0.f)) ? 0.f : o[t] * msc[t];
+            }
             if (ok[q]) chan_store<BF16, CPL, VEC>(p.y, (rb + q) * p.C, p.C, c0, o);
           }
         }
@@ -222,6 +233,7 @@ pm_status pm_launch_dw_f2v(int64_t F, int K, int C, int is_bf16, const BasisSrc&
   SepP p;
   p.F = F; p.K = K; p.C = C; p.is_bf16 = is_bf16; p.bs = bs; p.h = h; p.alpha = alpha; p.y = y;
   p.dz = nullptr; p.row_ptr = nullptr; p.partial = nullptr; p.kc0 = 0; p.want_dalpha = 0; p.lpg = 16;
+  p.mask_scale = nullptr; p.mask_relu = 0;
   const int grid = sep_grid(F, SEP_GRID_FWD);
   const size_t lds = sep_lds_bytes(K, false);
   const bool vec = chan_vec_ok(C, is_bf16, h, y, nullptr);
@@ -234,17 +246,23 @@ pm_status pm_launch_dw_f2v(int64_t F, int K, int C, int is_bf16, const BasisSrc&
   return PM_OK;
 }
 
-// dh [F][C] (may be NULL) and dalpha [K][C] (may be NULL; `partial` must then hold pm_sep_dalpha_ws_bytes)
+// dh [F][C] (may be NULL) and dalpha [K][C] (may be NULL; `partial` must then hold pm_sep_dalpha_ws_bytes).
+// mask_scale [C] (may be NULL) / mask_relu: dh leaves as dh * mask_scale * [h > 0].
 pm_status pm_launch_dw_f2v_bwd(int64_t F, int K, int C, int is_bf16, const BasisSrc& bs, const void* h,
                                const float* alpha, const float* dz, const int32_t* row_ptr, void* dh, float* dalpha,
-                               float* partial, hipStream_t st) {
+                               float* partial, const float* mask_scale, int mask_relu, hipStream_t st) {
   SepP p;
+  p.mask_scale = mask_scale; p.mask_relu = mask_relu;
   p.F = F; p.K = K; p.C = C; p.is_bf16 = is_bf16; p.bs = bs; p.h = h; p.alpha = alpha; p.y = dh;
   p.dz = dz; p.row_ptr = row_ptr; p.partial = partial; p.want_dalpha = dalpha != nullptr; p.lpg = 16;
   const int grid = sep_grid(F, SEP_GRID_BWD);
   const bool vec = chan_vec_ok(C, is_bf16, h, dz, dh);
+  const bool mask = mask_scale != nullptr || mask_relu != 0;
   auto kern = is_bf16 ? (vec ? k_dw_f2v<true, true, true> : k_dw_f2v<true, true, false>)
                       : (vec ? k_dw_f2v<false, true, true> : k_dw_f2v<false, true, false>);
+  if (mask)
+    kern = is_bf16 ? (vec ? k_dw_f2v<true, true, true, true> : k_dw_f2v<true, true, false, true>)
+                   : (vec ? k_dw_f2v<false, true, true, true> : k_dw_f2v<false, true, false, true>);
   if (F == 0) {
     if (dalpha) return pm_launch_sum_slices(partial, (int64_t)K * C, 0, dalpha, st);   // no slices: zeros
     return PM_OK;
