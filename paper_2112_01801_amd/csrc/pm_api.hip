@@ -480,9 +480,11 @@ static pm_status check_sep(const float* alpha, const void* P) {
 // the bf16 shapes it covers, else the general row kernel
 static pm_status pointwise_rows(pm_dtype dtype, int64_t R, int cin, int cout, const void* rows, const void* apack,
                                 void* out, int out_bf16, hipStream_t st) {
-  if (out_bf16 && pm_v2f_stage_applies(dtype, cin, cout, rows, out))
+  if (pm_v2f_stage_applies(dtype, cin, cout, rows, out)) {
+    if (!out_bf16) return pm_launch_point_stage_f32(R, cin, cout, rows, apack, (float*)out, st);
     return pm_launch_v2v_stage(R, cin, cout, nullptr, rows, apack, nullptr, nullptr, 0, nullptr, nullptr, 0, nullptr,
                                nullptr, out, st);
+  }
   RowSrc xs = row_src(rows, dtype, cin);
   return pm_launch_conv_rows(dtype, B_ONE, X_DIRECT, R, 1, cin, cout, basis_none(), xs, apack, out, out_bf16, st);
 }
@@ -551,7 +553,7 @@ static pm_status f2v_sep_bwd_impl(const pm_mesh* mesh, const pm_vf_adj* adj, int
   // dz = dg P^T on the vertex rows
   PM_TRY(pm_launch_pack(PACK_TRANS, dtype, 1, cin, cout, P, nullptr, apack, st));
   RowSrc gs = row_src(dg_vert, dtype, cout);
-  PM_TRY(pm_launch_conv_rows(dtype, B_ONE, X_DIRECT, V, 1, cout, cin, basis_none(), gs, apack, dz, 0, st));
+  PM_TRY(pointwise_rows(dtype, V, cout, cin, dg_vert, apack, dz, 0, st));
   if (dP) {
     // dP = z^T dg with the vertex means z the forward call handed out, or recomputed here (depth-wise stage +
     // vertex mean: two bandwidth-bound passes)

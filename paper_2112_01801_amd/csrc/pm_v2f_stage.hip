@@ -44,12 +44,13 @@ struct VtP {
 
 __host__ __device__ constexpr int vt_nch(int cin, int nj) { return (nj * cin + 63) / 64; }
 __host__ __device__ constexpr int vt_pitch(int cin, int nj) { return vt_nch(cin, nj) * 128 + 16; }
-__host__ __device__ constexpr int vt_out_pitch(int nb) { return 64 * nb + 16; }
+__host__ __device__ constexpr int vt_out_pitch(int nb, bool f32 = false) { return (f32 ? 128 : 64) * nb + 16; }
 
 // CIN: 32 or 64.  NB: 32-wide output blocks (cout = 32 NB, 1..4).  NJ: 3 gathered corner rows or 1 direct row.
 // Gathered rows: two workgroups share a CU (two waves per SIMD, 256 registers each) unless weights and tile leave
 // LDS for one only.  Direct rows need fewer registers and are left to the compiler's own choice.
-template <int CIN, int NB, int NJ, bool FUSE>
+// OF32: the output rows are fp32 instead of bf16 (direct rows only).
+template <int CIN, int NB, int NJ, bool FUSE, bool OF32 = false>
 __global__ void __launch_bounds__(256, (NJ == 1 || (CIN == 64 && NB >= 3)) ? 1 : 2) k_v2f_stage(VtP p) {
   extern __shared__ uint4 vt_lds[];
   constexpr int NBG = (NB + 1) / 2;                 // weight stages hold two 32-wide blocks
@@ -61,7 +62,7 @@ __global__ void __launch_bounds__(256, (NJ == 1 || (CIN == 64 && NB >= 3)) ? 1 :
   constexpr int ITEMS = VT_ROWS * IPR;              // 16-byte pieces per tile
   constexpr int PT = ITEMS / 256;
   constexpr int CO = 32 * NB;
-  constexpr int OP = vt_out_pitch(NB);              // padded output row pitch (bytes)
+  constexpr int OP = vt_out_pitch(NB, OF32);        // padded output row pitch (bytes)
   static_assert(ITEMS % 256 == 0, "whole passes of the workgroup");
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int r = lane & 31, hh = lane >> 5;
@@ -180,22 +181,29 @@ __global__ void __launch_bounds__(256, (NJ == 1 || (CIN == 64 && NB >= 3)) ? 1 :
     // q4 * 8 + hh * 4 + i of its row; whole rows then go out in 16-byte pieces
     const int64_t f0 = tile * VT_ROWS;
     auto store_tile = [&](uint16_t* dst) {
+      constexpr int ESZ = OF32 ? 4 : 2;
 #pragma unroll
       for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
         for (int q4 = 0; q4 < 4; ++q4) {
-          uint2 w;
-          w.x = pack_bf16x2(y[nb][q4 * 4], y[nb][q4 * 4 + 1]);
-          w.y = pack_bf16x2(y[nb][q4 * 4 + 2], y[nb][q4 * 4 + 3]);
-          *(uint2*)(tile_lds + (wave * 32 + r) * OP + (nb * 32 + q4 * 8 + hh * 4) * 2) = w;
+          char* q = tile_lds + (wave * 32 + r) * OP + (nb * 32 + q4 * 8 + hh * 4) * ESZ;
+          if constexpr (OF32) {
+            *(float4*)q = make_float4(y[nb][q4 * 4], y[nb][q4 * 4 + 1], y[nb][q4 * 4 + 2], y[nb][q4 * 4 + 3]);
+          } else {
+            uint2 w;
+            w.x = pack_bf16x2(y[nb][q4 * 4], y[nb][q4 * 4 + 1]);
+            w.y = pack_bf16x2(y[nb][q4 * 4 + 2], y[nb][q4 * 4 + 3]);
+            *(uint2*)q = w;
+          }
         }
       __syncthreads();
-      constexpr int OPR = 4 * NB;               // 16-byte pieces per output row
+      constexpr int OPR = 4 * NB * (ESZ / 2);   // 16-byte pieces per output row
 #pragma unroll
       for (int i = 0; i < (VT_ROWS * OPR) / 256; ++i) {
         const int item = tid + 256 * i;
         const int row = item / OPR, piece = item % OPR;
-        if (f0 + row < p.F) *(uint4*)(dst + (f0 + row) * CO + piece * 8) = *(const uint4*)(tile_lds + row * OP + piece * 16);
+        if (f0 + row < p.F)
+          *(uint4*)((char*)dst + ((f0 + row) * CO * ESZ + piece * 16)) = *(const uint4*)(tile_lds + row * OP + piece * 16);
       }
       __syncthreads();
     };
@@ -280,17 +288,17 @@ bool pm_v2f_stage_applies(pm_dtype dt, int cin, int cout, const void* h, const v
          pm_aligned16(out);
 }
 
-template <int CIN, int NB, int NJ, bool FUSE>
+template <int CIN, int NB, int NJ, bool FUSE, bool OF32 = false>
 static pm_status v2f_stage_launch(VtP& p, hipStream_t st, const char* label) {
   constexpr int NBG = (NB + 1) / 2, NCH = vt_nch(CIN, NJ);
   const int nkc = FUSE ? (p.K2 + 15) / 16 : 0;
   const int bw = (FUSE && p.alpha2) ? 4 * 32 * (p.K2 | 1) * 4 : 0;
-  p.tile_bytes = (int)pm_round_up((size_t)std::max(VT_ROWS * vt_pitch(CIN, NJ), VT_ROWS * vt_out_pitch(NB) + bw), 16);
+  p.tile_bytes = (int)pm_round_up((size_t)std::max(VT_ROWS * vt_pitch(CIN, NJ), VT_ROWS * vt_out_pitch(NB, OF32) + bw), 16);
   const size_t lds = (size_t)NBG * NCH * PM_STAGE_BYTES + (FUSE ? (size_t)nkc * NB * 2 * 1024 + 2 * 32 * NB * 4 : 0) + p.tile_bytes;
   if (lds > 160 * 1024) return pm_fail(PM_ERR_UNSUPPORTED, "staged tiles: %zu bytes of LDS", lds);
   int64_t grid = (p.F + VT_ROWS - 1) / VT_ROWS;
   if (grid > 512) grid = 512;
-  auto kern = k_v2f_stage<CIN, NB, NJ, FUSE>;
+  auto kern = k_v2f_stage<CIN, NB, NJ, FUSE, OF32>;
   PM_CHECK_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
   { ProfScope ps__(st, label);
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(256), lds, st, p); }
@@ -298,22 +306,22 @@ static pm_status v2f_stage_launch(VtP& p, hipStream_t st, const char* label) {
   return PM_OK;
 }
 
-template <int NJ, bool FUSE>
+template <int NJ, bool FUSE, bool OF32 = false>
 static pm_status v2f_stage_dispatch(int cin, VtP& p, hipStream_t st, const char* label) {
   const int nb = p.cout / 32;
   if (cin == 32) {
     switch (nb) {
-      case 1: return v2f_stage_launch<32, 1, NJ, FUSE>(p, st, label);
-      case 2: return v2f_stage_launch<32, 2, NJ, FUSE>(p, st, label);
-      case 3: return v2f_stage_launch<32, 3, NJ, FUSE>(p, st, label);
-      default: return v2f_stage_launch<32, 4, NJ, FUSE>(p, st, label);
+      case 1: return v2f_stage_launch<32, 1, NJ, FUSE, OF32>(p, st, label);
+      case 2: return v2f_stage_launch<32, 2, NJ, FUSE, OF32>(p, st, label);
+      case 3: return v2f_stage_launch<32, 3, NJ, FUSE, OF32>(p, st, label);
+      default: return v2f_stage_launch<32, 4, NJ, FUSE, OF32>(p, st, label);
     }
   }
   switch (nb) {
-    case 1: return v2f_stage_launch<64, 1, NJ, FUSE>(p, st, label);
-    case 2: return v2f_stage_launch<64, 2, NJ, FUSE>(p, st, label);
-    case 3: return v2f_stage_launch<64, 3, NJ, FUSE>(p, st, label);
-    default: return v2f_stage_launch<64, 4, NJ, FUSE>(p, st, label);
+    case 1: return v2f_stage_launch<64, 1, NJ, FUSE, OF32>(p, st, label);
+    case 2: return v2f_stage_launch<64, 2, NJ, FUSE, OF32>(p, st, label);
+    case 3: return v2f_stage_launch<64, 3, NJ, FUSE, OF32>(p, st, label);
+    default: return v2f_stage_launch<64, 4, NJ, FUSE, OF32>(p, st, label);
   }
 }
 
@@ -341,4 +349,13 @@ pm_status pm_launch_v2v_stage(int64_t R, int cin, int cout, const int32_t* facet
   if (sh) p.sh = *sh;
   if (facet) return v2f_stage_dispatch<3, true>(cin, p, st, "k_v2v_facet");
   return v2f_stage_dispatch<1, true>(cin, p, st, "k_v2v_point");
+}
+
+// Point-wise matrix on R consecutive bf16 rows with fp32 output rows (apack: plain or transposed image of cin x cout)
+pm_status pm_launch_point_stage_f32(int64_t R, int cin, int cout, const void* rows, const void* apack, float* out,
+                                    hipStream_t st) {
+  if (R == 0) return PM_OK;
+  VtP p = {};
+  p.F = R; p.cout = cout; p.h = (const uint16_t*)rows; p.apack = (const uint4*)apack; p.out = (uint16_t*)out;
+  return v2f_stage_dispatch<1, false, true>(cin, p, st, "k_point_stage");
 }
