@@ -140,7 +140,7 @@ def test_empty_lists_and_bad_lists(pm):
 
 
 def test_later_operators_replay_from_a_hip_graph(pm):
-    """Separable, pooling and point-cloud entry points enqueue kernels only: captured into one HIP graph (their
+    """Separable, vertex2vertex, pooling and point-cloud entry points enqueue kernels only: captured into one HIP graph (their
     outputs and workspaces come from the graph's memory pool), replays with eager work in between reproduce
     the eager results bit for bit -- including the sums over the reverse lists built inside the call."""
     import torch
@@ -162,8 +162,12 @@ def test_later_operators_replay_from_a_hip_graph(pm):
     vc_d, io_d = torch.from_numpy(vc).cuda(), torch.from_numpy(io).cuda()
     n_used = int((io[vc] >= 0).sum())               # members that reach an output vertex: the used part of col
 
+    ep = pm.Epilogue(torch.rand(cout, device="cuda") + 0.5, torch.randn(cout, device="cuda") * 0.3, True)
+
     def work():
         out = list(pm.pm_f2v_sep_bwd(mesh, adj, L, hF, a_d, P_d, dgV, dt))
+        o, g, z = pm.pm_v2v_sep(mesh, adj, L, dgV, a_d, P_d, ep, a_d, P_d, ep, dt, save=True)
+        out += [o, g, z] + list(pm.pm_v2v_sep_bwd(mesh, adj, L, dgV, a_d, P_d, ep, a_d, P_d, ep, g, z, o, dgV, dt))
         out += list(pm.pm_pcloud_conv_bwd(nb, L, hN, a_d, c_d, P_d, dgM, dt))
         cm = pm.pm_build_cluster_map(vc_d, io_d, b.n_vert // 4)
         m, arg = pm.pm_pool(cm, pm.PM_POOL_MAX, dgV, dt)
