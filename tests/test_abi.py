@@ -76,6 +76,11 @@ def test_workspace_sizes_of_the_later_operators(pm):
     bwd = lib.pm_pcloud_ws_bytes(1, 1000, 1000, 30000, 3, 64, 64, pm.PM_BF16)
     assert 0 < fwd < bwd
     assert lib.pm_pcloud_ws_bytes(0, 1000, 1000, 30000, 7, 64, 64, pm.PM_BF16) == 0
+    vf = lib.pm_v2v_sep_ws_bytes(0, 1000, 2000, 3, 64, 64, 64, pm.PM_BF16)
+    vb = lib.pm_v2v_sep_ws_bytes(1, 1000, 2000, 3, 64, 64, 64, pm.PM_BF16)
+    assert 0 < vf < lib.pm_v2v_sep_ws_bytes(0, 1000, 8000, 3, 64, 64, 64, pm.PM_BF16) and 0 < vb
+    assert lib.pm_v2v_sep_ws_bytes(0, 1000, 2000, 3, 64, 0, 64, pm.PM_BF16) == 0
+    assert lib.pm_v2v_sep_ws_bytes(0, -1, 2000, 3, 64, 64, 64, pm.PM_BF16) == 0
 
 
 def test_argument_errors_of_the_later_operators(pm):
@@ -86,6 +91,12 @@ def test_argument_errors_of_the_later_operators(pm):
     # separable: NULL mesh arrays, then parameter gradients that do not come together
     assert lib.pm_f2v_sep(C.byref(m), C.byref(a), 3, 0, 8, 8, 0, None, None, None, None, None, None, 0, None) == -1
     assert lib.pm_v2f_sep(C.byref(m), 9, 0, 8, 8, 0, None, None, None, None, None, 0, None) == -2
+    # vertex2vertex block: NULL mesh arrays; degree out of range
+    nul = [None] * 3
+    assert lib.pm_v2v_sep(C.byref(m), C.byref(a), 3, 0, 8, 8, 8, 0, *nul, None, None, None, None, None, None, None, None, 0,
+                          None) == -1
+    assert lib.pm_v2v_sep_bwd(C.byref(m), C.byref(a), 9, 0, 8, 8, 8, 0, *nul, None, None, None, None, *([None] * 10), 0,
+                              None) == -2
     # pooling: NULL map, unknown mode, bad channel count
     assert lib.pm_pool(None, 0, 8, 0, None, None, None, None) == -1
     cm = pm._PmClusterMap()

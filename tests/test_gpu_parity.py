@@ -207,7 +207,7 @@ def test_f2v_backward_single_gradients(pm, L, cin, cout):
 
 @pytest.mark.parametrize("dtype,cin,cout", [("bf16", 64, 64), ("f32", 24, 40), ("bf16", 128, 64)])
 def test_v2f_backward_single_gradients(pm, dtype, cin, cout):
-    """dW alone gathers the corner rows; together with dh it comes from the per-vertex slot sums instead."""
+    """Each gradient alone and both together (dW gathers the corner rows either way; dh goes through the per-vertex slot sums)."""
     L = 3
     b, rng, K, W, mesh, adj = _setup(pm, L, cin, cout, dtype, 25)
     h = make_features(rng, b.n_vert, cin, dtype)
