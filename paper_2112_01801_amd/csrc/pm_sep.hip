@@ -364,6 +364,48 @@ __global__ void __launch_bounds__(256) k_slot_scale_sum(SlotP p) {
   }
 }
 
+// The same sum with the corner scales looked up in LDS (a table [4][C], row 3 = zeros for the masked entry of an
+// odd-length list): one multiply-add per element, s_j[c] T[c] added in ascending entry order.  For whole aligned
+// channel runs and tables that fit LDS.
+#define SLOT_LDS_MAX_C 2048
+template <bool BF16>
+__global__ void __launch_bounds__(256) k_slot_scale_sum_lds(SlotP p) {
+  extern __shared__ float slot_sc[];          // [4][C]
+  constexpr int CPL = BF16 ? 8 : 4;
+  for (int i = threadIdx.x; i < 4 * p.C; i += 256) slot_sc[i] = (i < 3 * p.C) ? p.sc[i] : 0.f;
+  __syncthreads();
+  const int gpb = 256 / p.lpg;
+  const int sub = threadIdx.x % p.lpg;
+  for (int c0 = sub * CPL; c0 < p.C; c0 += p.lpg * CPL) {
+    for (int64_t seg = (int64_t)blockIdx.x * gpb + threadIdx.x / p.lpg; seg < p.V; seg += (int64_t)gridDim.x * gpb) {
+      const int32_t b = p.row_ptr[seg], e = p.row_ptr[seg + 1];
+      float acc[CPL];
+#pragma unroll
+      for (int i = 0; i < CPL; ++i) acc[i] = 0.f;
+      for (int32_t i0 = b; i0 < e; i0 += 2) {
+        int32_t cidx[2], row[2];
+        float x[2][CPL];
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+          cidx[q] = p.col[min(i0 + q, e - 1)];
+          row[q] = (int32_t)(((uint64_t)(uint32_t)cidx[q] * 0xAAAAAAABull) >> 33);   // / 3
+        }
+#pragma unroll
+        for (int q = 0; q < 2; ++q) chan_load<BF16, CPL, true>(p.T, (int64_t)row[q] * p.C, p.C, c0, x[q]);
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+          const int slot = (i0 + q < e) ? cidx[q] - 3 * row[q] : 3;
+          float w[CPL];
+          chan_load_f32<CPL, true>(slot_sc, (int64_t)slot * p.C, p.C, c0, w);
+#pragma unroll
+          for (int i = 0; i < CPL; ++i) acc[i] += w[i] * x[q][i];
+        }
+      }
+      chan_store<BF16, CPL, true>(p.out, seg * p.C, p.C, c0, acc);
+    }
+  }
+}
+
 // `sc` is a scratch table of 3 * C floats
 pm_status pm_launch_slot_scale_sum(int64_t V, int K, int C, int is_bf16, const void* T, const int32_t* row_ptr,
                                    const int32_t* col, const float* alpha, const FoldCoef* fc, float* sc, void* out,
@@ -383,9 +425,14 @@ pm_status pm_launch_slot_scale_sum(int64_t V, int K, int C, int is_bf16, const v
   if (nblk > 0x7fffffff) nblk = 0x7fffffff;
   { ProfScope ps__(st, "k_slot_scale_sum");
     const bool vec = chan_vec_ok(C, is_bf16, T, out, sc);
-    auto kern = is_bf16 ? (vec ? k_slot_scale_sum<true, true> : k_slot_scale_sum<true, false>)
-                        : (vec ? k_slot_scale_sum<false, true> : k_slot_scale_sum<false, false>);
-    hipLaunchKernelGGL(kern, dim3((unsigned)nblk), dim3(256), 0, st, p); }
+    if (vec && C <= SLOT_LDS_MAX_C) {
+      auto kern = is_bf16 ? k_slot_scale_sum_lds<true> : k_slot_scale_sum_lds<false>;
+      hipLaunchKernelGGL(kern, dim3((unsigned)nblk), dim3(256), (size_t)4 * C * sizeof(float), st, p);
+    } else {
+      auto kern = is_bf16 ? (vec ? k_slot_scale_sum<true, true> : k_slot_scale_sum<true, false>)
+                          : (vec ? k_slot_scale_sum<false, true> : k_slot_scale_sum<false, false>);
+      hipLaunchKernelGGL(kern, dim3((unsigned)nblk), dim3(256), 0, st, p);
+    } }
   PM_CHECK_LAUNCH("k_slot_scale_sum");
   return PM_OK;
 }
