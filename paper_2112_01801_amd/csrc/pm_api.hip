@@ -456,8 +456,12 @@ extern "C" pm_status pm_v2f_bwd(const pm_mesh* mesh, const pm_vf_adj* adj, int L
     const int fb = dtype == PM_BF16;
     PM_TRY(pm_launch_segsum_slots(V, cout, dg_facet, fb, adj->row_ptr, adj->col, sv, fb, st));
     PM_TRY(pm_launch_pack(PACK_FOLD_BWD, dtype, K, cin, cout, W, &fc, apack, st));
-    RowSrc xs = row_src(sv, dtype, 3 * cout);
-    PM_TRY(pm_launch_conv_rows(dtype, B_ONE, X_DIRECT, V, 1, 3 * cout, cin, basis_none(), xs, apack, dh_vert, fb, st));
+    if (pm_point_stage_wide_applies(dtype, 3 * cout, cin, sv, dh_vert)) {
+      PM_TRY(pm_launch_point_stage_wide(V, 3 * cout, cin, sv, apack, dh_vert, st));
+    } else {
+      RowSrc xs = row_src(sv, dtype, 3 * cout);
+      PM_TRY(pm_launch_conv_rows(dtype, B_ONE, X_DIRECT, V, 1, 3 * cout, cin, basis_none(), xs, apack, dh_vert, fb, st));
+    }
   }
   if (dW) {
     RowSrc xs = row_src(h_vert, dtype, cin);

@@ -428,10 +428,14 @@ __global__ void __launch_bounds__(256) k_segsum_slots(SegP p) {
 #pragma unroll
         for (int q = 0; q < 2; ++q) {
           const int slot = (i0 + q < e) ? cidx[q] - 3 * (int32_t)(((uint64_t)(uint32_t)cidx[q] * 0xAAAAAAABull) >> 33) : 3;
+          // one 0/1 weight per slot and a multiply-add per element (a + 1 x and a + 0 x are exact: the sums are the
+          // plain ascending-order sums of each slot); cheaper than a select and an add per element
 #pragma unroll
-          for (int j = 0; j < 3; ++j)
+          for (int j = 0; j < 3; ++j) {
+            const float m = (slot == j) ? 1.f : 0.f;
 #pragma unroll
-            for (int i = 0; i < CPL; ++i) a[j][i] += (slot == j) ? x[q][i] : 0.f;
+            for (int i = 0; i < CPL; ++i) a[j][i] = fmaf(m, x[q][i], a[j][i]);
+          }
         }
       }
 #pragma unroll

@@ -192,6 +192,9 @@ pm_status pm_launch_v2f_stage(int64_t F, int cin, int cout, const int32_t* facet
 pm_status pm_launch_v2v_stage(int64_t R, int cin, int cout, const int32_t* facet, const void* h, const void* apack,
                               const float* ep_scale, const float* ep_shift, int relu, void* save, const float* alpha2,
                               int K2, const float* vert, const ShTable* sh, void* out, hipStream_t st);
+bool pm_point_stage_wide_applies(pm_dtype dt, int cin, int cout, const void* rows, const void* out);
+pm_status pm_launch_point_stage_wide(int64_t R, int cin, int cout, const void* rows, const void* apack, void* out,
+                                     hipStream_t st);
 pm_status pm_launch_point_stage_f32(int64_t R, int cin, int cout, const void* rows, const void* apack, float* out,
                                     hipStream_t st);
 // x <- act(scale x + shift) in place, and its backward out = dy scale [y_saved > 0]   (scale / shift may be NULL)

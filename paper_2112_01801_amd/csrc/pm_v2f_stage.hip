@@ -46,7 +46,8 @@ __host__ __device__ constexpr int vt_nch(int cin, int nj) { return (nj * cin + 6
 __host__ __device__ constexpr int vt_pitch(int cin, int nj) { return vt_nch(cin, nj) * 128 + 16; }
 __host__ __device__ constexpr int vt_out_pitch(int nb, bool f32 = false) { return (f32 ? 128 : 64) * nb + 16; }
 
-// CIN: 32 or 64.  NB: 32-wide output blocks (cout = 32 NB, 1..4).  NJ: 3 gathered corner rows or 1 direct row.
+// CIN: 32 or 64 (direct rows also 96, 192).  NB: 32-wide output blocks (cout = 32 NB, 1..4).  NJ: 3 gathered corner
+// rows or 1 direct row.
 // Gathered rows: two workgroups share a CU (two waves per SIMD, 256 registers each) unless weights and tile leave
 // LDS for one only.  Direct rows need fewer registers and are left to the compiler's own choice.
 // OF32: the output rows are fp32 instead of bf16 (direct rows only).
@@ -358,4 +359,34 @@ pm_status pm_launch_point_stage_f32(int64_t R, int cin, int cout, const void* ro
   VtP p = {};
   p.F = R; p.cout = cout; p.h = (const uint16_t*)rows; p.apack = (const uint4*)apack; p.out = (uint16_t*)out;
   return v2f_stage_dispatch<1, false, true>(cin, p, st, "k_point_stage");
+}
+
+// Point-wise matrix on R consecutive bf16 rows of 96 or 192 channels (the three corner-slot sums of a vertex side
+// by side: dense vertex2facet backward), bf16 output rows of cout = 32 .. 128 channels
+bool pm_point_stage_wide_applies(pm_dtype dt, int cin, int cout, const void* rows, const void* out) {
+  return dt == PM_BF16 && (cin == 96 || cin == 192) && cout % 32 == 0 && cout >= 32 && cout <= 128 && pm_aligned16(rows) &&
+         pm_aligned16(out);
+}
+
+pm_status pm_launch_point_stage_wide(int64_t R, int cin, int cout, const void* rows, const void* apack, void* out,
+                                     hipStream_t st) {
+  if (R == 0) return PM_OK;
+  VtP p = {};
+  p.F = R; p.cout = cout; p.h = (const uint16_t*)rows; p.apack = (const uint4*)apack; p.out = (uint16_t*)out;
+  const char* label = "k_point_stage";
+  const int nb = cout / 32;
+  if (cin == 96) {
+    switch (nb) {
+      case 1: return v2f_stage_launch<96, 1, 1, false>(p, st, label);
+      case 2: return v2f_stage_launch<96, 2, 1, false>(p, st, label);
+      case 3: return v2f_stage_launch<96, 3, 1, false>(p, st, label);
+      default: return v2f_stage_launch<96, 4, 1, false>(p, st, label);
+    }
+  }
+  switch (nb) {
+    case 1: return v2f_stage_launch<192, 1, 1, false>(p, st, label);
+    case 2: return v2f_stage_launch<192, 2, 1, false>(p, st, label);
+    case 3: return v2f_stage_launch<192, 3, 1, false>(p, st, label);
+    default: return v2f_stage_launch<192, 4, 1, false>(p, st, label);
+  }
 }
