@@ -93,8 +93,8 @@ __device__ __forceinline__ void pack_values(const PackP& p, int k, int c0, int n
   for (int e = 0; e < N; ++e) v[e] = ok[e] ? v[e] : 0.f;
 }
 
-// the folded forms (a sum over k per element): one thread per element, so that the K loads of an element are
-// spread over eight times as many threads
+// one thread per element of the image: the image is small (128 KB at K = 16, 64 x 64), so the kernel lives on its
+// launch and on how many threads share the strided reads (and, in the folded forms, the K loads of an element)
 template <int MODE>
 __global__ void __launch_bounds__(256) k_pack_elem(PackP p, int64_t n_elem) {
   const int64_t te = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -119,38 +119,6 @@ __global__ void __launch_bounds__(256) k_pack_elem(PackP p, int64_t n_elem) {
   else ((float*)p.out)[te] = v[0];
 }
 
-// one thread per (stage, nbi, g, lane) granule
-template <int MODE>
-__global__ void __launch_bounds__(256) k_pack(PackP p, int64_t n_gran) {
-  int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (t >= n_gran) return;
-  const int lane = (int)(t & 63);
-  int64_t q = t >> 6;
-  const int g = (int)(q % PM_GC); q /= PM_GC;
-  const int nbi = (int)(q % PM_NBS); q /= PM_NBS;
-  const int64_t stage = q;
-  const int k = (int)(stage % p.Kp);
-  const int ch = (int)((stage / p.Kp) % p.NCH);
-  const int nbg = (int)(stage / ((int64_t)p.Kp * p.NCH));
-  const int n = (nbg * PM_NBS + nbi) * 32 + (lane & 31);
-  const int hh = lane >> 5;
-  uint4 o;
-  if (p.dst_bf16) {
-    const int c0 = (ch * PM_GC + g) * 16 + hh * 8;
-    float v[8];
-    pack_values<MODE, 8>(p, k, c0, n, v);
-    o.x = pack_bf16x2(v[0], v[1]); o.y = pack_bf16x2(v[2], v[3]);
-    o.z = pack_bf16x2(v[4], v[5]); o.w = pack_bf16x2(v[6], v[7]);
-  } else {
-    const int c0 = (ch * PM_GC + g) * 8 + hh * 4;
-    float v[4];
-    pack_values<MODE, 4>(p, k, c0, n, v);
-    o.x = __float_as_uint(v[0]); o.y = __float_as_uint(v[1]);
-    o.z = __float_as_uint(v[2]); o.w = __float_as_uint(v[3]);
-  }
-  p.out[t] = o;
-}
-
 pm_status pm_launch_pack(PackMode mode, pm_dtype dt, int K, int cin, int cout, const void* W, const FoldCoef* fc,
                          void* apack, hipStream_t st, const float* alpha) {
   PackP p;
@@ -167,22 +135,17 @@ pm_status pm_launch_pack(PackMode mode, pm_dtype dt, int K, int cin, int cout, c
   p.NCH = g.NCH; p.NBG = g.NBG;
   p.W = W; p.alpha = alpha; p.out = (uint4*)apack;
   if (fc) p.fc = *fc; else for (int j = 0; j < 3; ++j) for (int k = 0; k < PM_MAX_K; ++k) p.fc.c[j][k] = 0.f;
-  int64_t n_gran = g.stages * STAGE_U4;
+  // one thread per element of the image
+  const int64_t n_elem = g.stages * STAGE_U4 * (p.dst_bf16 ? 8 : 4);
   { ProfScope ps__(st, "k_pack");
-    const dim3 grid((unsigned)((n_gran + 255) / 256));
+    const dim3 ge((unsigned)((n_elem + 255) / 256));
     switch (mode) {
-      case PACK_PLAIN: hipLaunchKernelGGL(k_pack<PACK_PLAIN>, grid, dim3(256), 0, st, p, n_gran); break;
-      case PACK_TRANS: hipLaunchKernelGGL(k_pack<PACK_TRANS>, grid, dim3(256), 0, st, p, n_gran); break;
-      default: {
-        const int64_t n_elem = n_gran * (p.dst_bf16 ? 8 : 4);
-        const dim3 ge((unsigned)((n_elem + 255) / 256));
-        switch (mode) {
-          case PACK_FOLD: hipLaunchKernelGGL(k_pack_elem<PACK_FOLD>, ge, dim3(256), 0, st, p, n_elem); break;
-          case PACK_FOLD_TRANS: hipLaunchKernelGGL(k_pack_elem<PACK_FOLD_TRANS>, ge, dim3(256), 0, st, p, n_elem); break;
-          case PACK_FOLD_BWD: hipLaunchKernelGGL(k_pack_elem<PACK_FOLD_BWD>, ge, dim3(256), 0, st, p, n_elem); break;
-          default: hipLaunchKernelGGL(k_pack_elem<PACK_SEP_FOLD>, ge, dim3(256), 0, st, p, n_elem); break;
-        }
-      } break;
+      case PACK_PLAIN: hipLaunchKernelGGL(k_pack_elem<PACK_PLAIN>, ge, dim3(256), 0, st, p, n_elem); break;
+      case PACK_TRANS: hipLaunchKernelGGL(k_pack_elem<PACK_TRANS>, ge, dim3(256), 0, st, p, n_elem); break;
+      case PACK_FOLD: hipLaunchKernelGGL(k_pack_elem<PACK_FOLD>, ge, dim3(256), 0, st, p, n_elem); break;
+      case PACK_FOLD_TRANS: hipLaunchKernelGGL(k_pack_elem<PACK_FOLD_TRANS>, ge, dim3(256), 0, st, p, n_elem); break;
+      case PACK_FOLD_BWD: hipLaunchKernelGGL(k_pack_elem<PACK_FOLD_BWD>, ge, dim3(256), 0, st, p, n_elem); break;
+      default: hipLaunchKernelGGL(k_pack_elem<PACK_SEP_FOLD>, ge, dim3(256), 0, st, p, n_elem); break;
     } }
   PM_CHECK_LAUNCH("k_pack");
   return PM_OK;
