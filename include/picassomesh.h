@@ -177,8 +177,10 @@ pm_status pm_v2f_sep_bwd(const pm_mesh* mesh, const pm_vf_adj* adj, int L, pm_sh
  * points above, P1 [cin,cmid], P2 [cmid,cout] of the feature dtype.  An epilogue is a per-channel affine map with
  * fixed coefficients (normalisation with frozen statistics; device fp32 vectors, either may be NULL = 1 / 0)
  * and an optional ReLU; a NULL pm_epilogue pointer means none.  For bf16 rows with cin in {32, 64} and cmid a
- * multiple of 32 up to 128 the facet features never reach memory (unless g_facet asks for them); other shapes
- * run the same arithmetic through the separable entry points' kernels.
+ * multiple of 32 up to 128 one kernel per facet tile gathers, contracts, applies the epilogue and the second
+ * filter: the facet features g are not written (unless g_facet asks for them), only the filtered rows g (.) s2
+ * pass through the workspace on their way to the vertex mean; other shapes run the same arithmetic through the
+ * separable entry points' kernels.
  * g_facet [n_facet,cmid] and z_vert [n_vert,cmid] (both optional, feature dtype) receive the activated facet
  * features and the vertex means: the backward pass needs both (g_saved, z_saved) and, when act2 is a ReLU, the
  * output rows (out_saved).  It returns dh_vert [n_vert,cin] (feature dtype), dalpha1 [K,cin], dP1 [cin,cmid],
