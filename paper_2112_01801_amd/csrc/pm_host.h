@@ -120,6 +120,12 @@ bool pm_wgrad_fuses_basis(pm_dtype mt, BMode bm, XMode xm, XMode ym, int K, int 
 pm_status pm_launch_wgrad(pm_dtype mt, BMode bm, XMode xm, XMode ym, int64_t R, int K, int Cc, int Cn,
                           const BasisSrc& bs, const RowSrc& xs, const RowSrc& ys, float* dWp, void* ws, size_t ws_bytes,
                           void* y_out, hipStream_t st);
+// The same without a basis for bf16 rows of 32 / 64 channels (K = 3 gathered corner rows, or K = 1 direct rows):
+// row-major LDS tiles and transposing LDS reads (pm_wgrad_stage.hip); pm_launch_wgrad takes it where it applies
+bool pm_wgrad_stage_applies(pm_dtype mt, BMode bm, XMode xm, XMode ym, int K, int Cc, int Cn, const RowSrc& xs,
+                            const RowSrc& ys);
+pm_status pm_launch_wgrad_stage(XMode xm, int64_t R, int K, int Cc, int Cn, const RowSrc& xs, const RowSrc& ys, float* dWp,
+                                void* ws, size_t ws_bytes, hipStream_t st);
 // dW[k][ci][co] = sum_j fc[j][k] M[j][ci][co]
 pm_status pm_launch_unfold(int K, int cin, int cout, const float* M, const FoldCoef* fc, float* dW, hipStream_t st);
 // out[v][j][c] = sum over the entries e of segment v with col[e] % 3 == j of src[col[e] / 3][c]   (j = 0..2):

@@ -542,6 +542,8 @@ pm_status pm_launch_wgrad(pm_dtype mt, BMode bm, XMode xm, XMode ym, int64_t R, 
                           void* y_out, hipStream_t st) {
   WgradGeom g = wgrad_geom(R, K, Cc, Cn);
   if (ws_bytes < pm_wgrad_ws_bytes(R, K, Cc, Cn)) return pm_fail(PM_ERR_WORKSPACE, "wgrad workspace too small");
+  if (!y_out && pm_wgrad_stage_applies(mt, bm, xm, ym, K, Cc, Cn, xs, ys))
+    return pm_launch_wgrad_stage(xm, R, K, Cc, Cn, xs, ys, dWp, ws, ws_bytes, st);
   WgradP p;
   p.R = R; p.rows_per_part = g.rows_per_part;
   p.K = K; p.Cc = Cc; p.Cn = Cn;
