@@ -483,9 +483,15 @@ static pm_status check_sep(const float* alpha, const void* P) {
 // out = rows P on directly addressed rows (apack: the plain or transposed image of P): the staged-tile kernel for
 // the bf16 shapes it covers, else the general row kernel
 static pm_status pointwise_rows(pm_dtype dtype, int64_t R, int cin, int cout, const void* rows, const void* apack,
-                                void* out, int out_bf16, hipStream_t st) {
+                                void* out, int out_bf16, hipStream_t st, const int32_t* mean_row_ptr = nullptr,
+                                int* prescaled = nullptr) {
+  if (prescaled) *prescaled = 0;
   if (pm_v2f_stage_applies(dtype, cin, cout, rows, out)) {
-    if (!out_bf16) return pm_launch_point_stage_f32(R, cin, cout, rows, apack, (float*)out, st);
+    if (!out_bf16) {
+      // fp32 rows; on request each leaves divided by the length of its segment (told back through `prescaled`)
+      if (prescaled && mean_row_ptr) *prescaled = 1;
+      return pm_launch_point_stage_f32(R, cin, cout, rows, apack, (float*)out, prescaled ? mean_row_ptr : nullptr, st);
+    }
     return pm_launch_v2v_stage(R, cin, cout, nullptr, rows, apack, nullptr, nullptr, 0, nullptr, nullptr, 0, nullptr,
                                nullptr, out, st);
   }
@@ -554,10 +560,12 @@ static pm_status f2v_sep_bwd_impl(const pm_mesh* mesh, const pm_vf_adj* adj, int
   BasisSrc bs = basis_none();
   bs.vert = mesh->vert; bs.facet = mesh->facet;
   pm_make_sh_table(L, norm, &bs.sh);
-  // dz = dg P^T on the vertex rows
   PM_TRY(pm_launch_pack(PACK_TRANS, dtype, 1, cin, cout, P, nullptr, apack, st));
   RowSrc gs = row_src(dg_vert, dtype, cout);
-  PM_TRY(pointwise_rows(dtype, V, cout, cin, dg_vert, apack, dz, 0, st));
+  // dz = dg P^T on the vertex rows; where the staged kernel runs, each row leaves divided by its vertex degree, so
+  // the depth-wise backward gathers plain sums
+  int dz_prescaled = 0;
+  PM_TRY(pointwise_rows(dtype, V, cout, cin, dg_vert, apack, dz, 0, st, adj->row_ptr, &dz_prescaled));
   if (dP) {
     // dP = z^T dg with the vertex means z the forward call handed out, or recomputed here (depth-wise stage +
     // vertex mean: two bandwidth-bound passes)
@@ -571,7 +579,7 @@ static pm_status f2v_sep_bwd_impl(const pm_mesh* mesh, const pm_vf_adj* adj, int
   }
   if (dh_facet || dalpha)
     PM_TRY(pm_launch_dw_f2v_bwd(F, K, cin, fb, bs, h_facet, alpha, (const float*)dz, adj->row_ptr, dh_facet, dalpha,
-                                (float*)wg, mask_scale, mask_relu, st));
+                                (float*)wg, mask_scale, mask_relu, dz_prescaled, st));
   return PM_OK;
 }
 

@@ -139,13 +139,14 @@ pm_status pm_launch_sum_slices_strided(const float* partial, int64_t n, int64_t 
 
 // Depth-wise stage of the separable facet2vertex form: y_f[c] = h_f[c] * sum_k alpha[k][c] B_k(n_f), and its backward
 // (dh_f[c] = dy_f[c] * filter, dy_f = gathered mean of dz;  dalpha[k][c] = sum_f B_k(n_f) h_f[c] dy_f[c]);
-// optionally dh leaves as dh * mask_scale * [h > 0] (the epilogue that produced h).
+// optionally dh leaves as dh * mask_scale * [h > 0] (the epilogue that produced h).  dz_prescaled: the rows of dz
+// already carry their 1/deg(v).
 size_t pm_sep_dalpha_ws_bytes(int64_t F, int K, int C, int is_bf16);
 pm_status pm_launch_dw_f2v(int64_t F, int K, int C, int is_bf16, const BasisSrc& bs, const void* h, const float* alpha,
                            void* y, hipStream_t st);
 pm_status pm_launch_dw_f2v_bwd(int64_t F, int K, int C, int is_bf16, const BasisSrc& bs, const void* h,
                                const float* alpha, const float* dz, const int32_t* row_ptr, void* dh, float* dalpha,
-                               float* partial, const float* mask_scale, int mask_relu, hipStream_t st);
+                               float* partial, const float* mask_scale, int mask_relu, int dz_prescaled, hipStream_t st);
 // separable vertex2facet backward: out[v][c] = sum over entries (f, j) of v of s_j[c] T[f][c]
 pm_status pm_launch_slot_scale_sum(int64_t V, int K, int C, int is_bf16, const void* T, const int32_t* row_ptr,
                                    const int32_t* col, const float* alpha, const FoldCoef* fc, float* sc, void* out,
@@ -202,7 +203,7 @@ bool pm_point_stage_wide_applies(pm_dtype dt, int cin, int cout, const void* row
 pm_status pm_launch_point_stage_wide(int64_t R, int cin, int cout, const void* rows, const void* apack, void* out,
                                      hipStream_t st);
 pm_status pm_launch_point_stage_f32(int64_t R, int cin, int cout, const void* rows, const void* apack, float* out,
-                                    hipStream_t st);
+                                    const int32_t* row_ptr, hipStream_t st);
 // x <- act(scale x + shift) in place, and its backward out = dy scale [y_saved > 0]   (scale / shift may be NULL)
 pm_status pm_launch_affine_act(int64_t n_rows, int C, int is_bf16, void* x, const float* scale, const float* shift,
                                int relu, hipStream_t st);

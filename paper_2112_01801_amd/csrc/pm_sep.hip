@@ -47,7 +47,7 @@ struct SepP {
 // LDS: alpha [4 ceil(kn/4)][64] (zero rows past kn), per wave basis [64][kn | 1], backward: block sum [16][64].
 #define SEP_RW 64
 
-template <bool BF16, bool BWD, bool VEC, bool MASK = false>
+template <bool BF16, bool BWD, bool VEC, bool MASK = false, bool PRE = false>
 __global__ void __launch_bounds__(256) k_dw_f2v(SepP p) {
   extern __shared__ float sep_lds[];
   constexpr int CPL = 4;
@@ -124,11 +124,16 @@ __global__ void __launch_bounds__(256) k_dw_f2v(SepP p) {
 #pragma unroll
               for (int j = 0; j < 3; ++j) {
                 const int32_t v = p.bs.facet[3 * rl + j];
-                const float w = 1.0f / (float)(p.row_ptr[v + 1] - p.row_ptr[v]);
                 float t[CPL];
                 chan_load_f32<CPL, VEC>(p.dz, (int64_t)v * p.C, p.C, cl, t);
+                if constexpr (PRE) {             // the rows of dz carry their 1/deg(v) already
 #pragma unroll
-                for (int i = 0; i < CPL; ++i) dyv[q][i] += t[i] * w;
+                  for (int i = 0; i < CPL; ++i) dyv[q][i] += t[i];
+                } else {
+                  const float w = 1.0f / (float)(p.row_ptr[v + 1] - p.row_ptr[v]);
+#pragma unroll
+                  for (int i = 0; i < CPL; ++i) dyv[q][i] += t[i] * w;
+                }
               }
             }
           }
@@ -250,7 +255,7 @@ pm_status pm_launch_dw_f2v(int64_t F, int K, int C, int is_bf16, const BasisSrc&
 // mask_scale [C] (may be NULL) / mask_relu: dh leaves as dh * mask_scale * [h > 0].
 pm_status pm_launch_dw_f2v_bwd(int64_t F, int K, int C, int is_bf16, const BasisSrc& bs, const void* h,
                                const float* alpha, const float* dz, const int32_t* row_ptr, void* dh, float* dalpha,
-                               float* partial, const float* mask_scale, int mask_relu, hipStream_t st) {
+                               float* partial, const float* mask_scale, int mask_relu, int dz_prescaled, hipStream_t st) {
   SepP p;
   p.mask_scale = mask_scale; p.mask_relu = mask_relu;
   p.F = F; p.K = K; p.C = C; p.is_bf16 = is_bf16; p.bs = bs; p.h = h; p.alpha = alpha; p.y = dh;
@@ -263,6 +268,11 @@ pm_status pm_launch_dw_f2v_bwd(int64_t F, int K, int C, int is_bf16, const Basis
   if (mask)
     kern = is_bf16 ? (vec ? k_dw_f2v<true, true, true, true> : k_dw_f2v<true, true, false, true>)
                    : (vec ? k_dw_f2v<false, true, true, true> : k_dw_f2v<false, true, false, true>);
+  if (dz_prescaled) {   // only the staged point-wise pass (bf16 rows) prescales
+    if (!is_bf16) return pm_fail(PM_ERR_UNSUPPORTED, "prescaled dz rows with fp32 features");
+    kern = vec ? (mask ? k_dw_f2v<true, true, true, true, true> : k_dw_f2v<true, true, true, false, true>)
+               : (mask ? k_dw_f2v<true, true, false, true, true> : k_dw_f2v<true, true, false, false, true>);
+  }
   if (F == 0) {
     if (dalpha) return pm_launch_sum_slices(partial, (int64_t)K * C, 0, dalpha, st);   // no slices: zeros
     return PM_OK;

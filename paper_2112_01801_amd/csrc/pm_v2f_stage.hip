@@ -31,6 +31,7 @@ struct VtP {
   const uint4* apack;       // packed image with one basis slot: stage (nbg * NCH + ch)
   uint16_t* out;            // [F][cout] bf16
   int tile_bytes;           // LDS bytes of the tile buffer
+  const int32_t* row_ptr;   // optional (direct rows): output row r is divided by row_ptr[r + 1] - row_ptr[r]
   // FUSE only
   const float* ep_scale;    // [cout] or NULL (1)
   const float* ep_shift;    // [cout] or NULL (0)
@@ -271,6 +272,17 @@ __global__ void __launch_bounds__(256, (NJ == 1 || (CIN == 64 && NB >= 3)) ? 1 :
         __builtin_amdgcn_wave_barrier();        // the basis rows have been read
       }
     }
+    if constexpr (NJ == 1 && !FUSE) {
+      if (p.row_ptr) {                          // the mean's weight of the row, applied once here for its consumers
+        const int64_t row = min(f0 + wave * 32 + r, p.F - 1);
+        const int32_t deg = p.row_ptr[row + 1] - p.row_ptr[row];
+        const float w = deg > 0 ? 1.0f / (float)deg : 0.f;
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) y[nb][i] *= w;
+      }
+    }
     store_tile(p.out);
     // the output and the basis rows overwrote the zero pad of the rows they touched: restore it where the staged
     // rows do not reach
@@ -352,12 +364,14 @@ pm_status pm_launch_v2v_stage(int64_t R, int cin, int cout, const int32_t* facet
   return v2f_stage_dispatch<1, true>(cin, p, st, "k_v2v_point");
 }
 
-// Point-wise matrix on R consecutive bf16 rows with fp32 output rows (apack: plain or transposed image of cin x cout)
+// Point-wise matrix on R consecutive bf16 rows with fp32 output rows (apack: plain or transposed image of cin x cout);
+// row_ptr (optional): row r leaves divided by row_ptr[r + 1] - row_ptr[r] (0 for an empty segment)
 pm_status pm_launch_point_stage_f32(int64_t R, int cin, int cout, const void* rows, const void* apack, float* out,
-                                    hipStream_t st) {
+                                    const int32_t* row_ptr, hipStream_t st) {
   if (R == 0) return PM_OK;
   VtP p = {};
   p.F = R; p.cout = cout; p.h = (const uint16_t*)rows; p.apack = (const uint4*)apack; p.out = (uint16_t*)out;
+  p.row_ptr = row_ptr;
   return v2f_stage_dispatch<1, false, true>(cin, p, st, "k_point_stage");
 }
 
