@@ -173,6 +173,33 @@ def test_v2v_config3_full_size(pm):
     assert rel_err(to_host(o), ref) < TOL[dtype]
 
 
+def test_v2v_config3_backward_adjoint(pm):
+    """Full size, no activation (the block is then linear in h and in each parameter set): every gradient against
+    the forward pass through <grad, direction> = <forward(direction), d_out>."""
+    import torch
+    cfg = mg.config3(1024)
+    L, c, dtype = 3, 64, "bf16"
+    b, rng, (a1, P1, ep1, a2, P2, ep2), h, mesh, adj, d = _setup(pm, L, c, c, c, dtype, "none", 37, batch=cfg.batch)
+    d_out = to_dev(make_features(rng, b.n_vert, c, dtype), dtype)
+    fwd = lambda **kw: pm.pm_v2v_sep(mesh, adj, L, kw.get("h", d["h"]), kw.get("a1", d["a1"]), kw.get("P1", d["P1"]), None,
+                                     kw.get("a2", d["a2"]), kw.get("P2", d["P2"]), None, 1)
+    o, g, z = pm.pm_v2v_sep(mesh, adj, L, d["h"], d["a1"], d["P1"], None, d["a2"], d["P2"], None, 1, save=True)
+    dh, da1, dP1, da2, dP2 = pm.pm_v2v_sep_bwd(mesh, adj, L, d["h"], d["a1"], d["P1"], None, d["a2"], d["P2"], None, g, z, o,
+                                               d_out, 1)
+    r2 = np.random.default_rng(38)
+    h2 = to_dev(make_features(r2, b.n_vert, c, dtype), dtype)
+    a1b, P1b = _params(r2, L, c, c, dtype)
+    a2b, P2b = _params(r2, L, c, c, dtype)
+    cases = [("h", dh, h2), ("a1", da1, torch.from_numpy(a1b).cuda()), ("P1", dP1, to_dev(P1b, dtype)),
+             ("a2", da2, torch.from_numpy(a2b).cuda()), ("P2", dP2, to_dev(P2b, dtype))]
+    for name, grad, direction in cases:
+        od = fwd(**{name: direction})
+        lhs = float((grad.double() * direction.double()).sum())
+        rhs = float((od.double() * d_out.double()).sum())
+        scale = float((od.double() * d_out.double()).abs().sum())
+        assert abs(lhs - rhs) <= 2e-3 * scale, (name, lhs, rhs, scale)
+
+
 def test_v2v_argument_errors(pm):
     import torch
     b, rng, prm, h, mesh, adj, d = _setup(pm, 2, 16, 16, 16, "f32", "none", 36)
