@@ -110,14 +110,6 @@ pm_status pm_sh_basis_bwd(int64_t n, const float* dirs, int L, pm_sh_norm norm, 
  * h_facet [F,cin], W [K,cin,cout], g_vert [V,cout] (dtype).  Vertices with empty N(v) get zeros. */
 pm_status pm_f2v(const pm_mesh* mesh, const pm_vf_adj* adj, int L, pm_sh_norm norm, int cin, int cout, pm_dtype dtype,
                  const void* h_facet, const void* W, void* g_vert, void* ws, size_t ws_bytes, void* stream);
-/* The sums of Eq. 5 commute: the mean over the adjacent facets can be taken after the contraction (facet-side
- * order, the default) or before it (vertex-side order: half the matrix work, no per-facet intermediate, but the
- * outer products run on the vector ALU; measured slower on MI355X).  pm_f2v_order(0) makes every later pm_f2v
- * call of the process take the vertex-side order where its kernel applies (bf16, cin = 64, cout in {64, 128},
- * L <= 3), pm_f2v_order(1) restores the default.  Both orders meet the same tolerances; their roundings differ
- * (the vertex-side order rounds the basis values to bf16). */
-pm_status pm_f2v_order(int order);
-
 /* Backward of Eq. 5.  dg_vert [V,cout] (dtype) -> dh_facet [F,cin] (dtype, may be NULL),
  * dW [K,cin,cout] fp32 (may be NULL). */
 pm_status pm_f2v_bwd(const pm_mesh* mesh, const pm_vf_adj* adj, int L, pm_sh_norm norm, int cin, int cout,

@@ -228,6 +228,46 @@ def f2f_bwd(tex_off, bary, L, h, W, dg, norm: int = 0, rows=None, want_dh=True, 
     return dh, dW
 
 
+def _wrows(wrows, K, cin):
+    w = np.ascontiguousarray(wrows, dtype=np.int64)
+    assert w.ndim == 1 and (w.size == 0 or (w.min() >= 0 and w.max() < K * cin))
+    return w
+
+
+def f2v_dW_rows(vert, facet, L, h, dg, wrows, norm: int = 0) -> np.ndarray:
+    """Rows dW[k, ci, :] of the facet2vertex coefficient gradient, wrows[i] = k*cin + ci (sum over all facets)."""
+    vert, facet, h, dg = _f32(vert), _i32(facet), _f64(h), _f64(dg)
+    cin, cout = h.shape[1], dg.shape[1]
+    w = _wrows(wrows, (L + 1) ** 2, cin)
+    out = np.empty((w.shape[0], cout), dtype=np.float64)
+    lib().orc_f2v_dW_rows(C.c_int64(vert.shape[0]), C.c_int64(facet.shape[0]), _p(vert, C.c_float), _p(facet, C.c_int32),
+                          C.c_int(L), C.c_int(norm), C.c_int(cin), C.c_int(cout), _p(h, C.c_double), _p(dg, C.c_double),
+                          C.c_int64(w.shape[0]), _p(w, C.c_int64), _p(out, C.c_double))
+    return out
+
+
+def v2f_dW_rows(n_vert, facet, L, h, dg, wrows, norm: int = 0) -> np.ndarray:
+    facet, h, dg = _i32(facet), _f64(h), _f64(dg)
+    cin, cout = h.shape[1], dg.shape[1]
+    w = _wrows(wrows, (L + 1) ** 2, cin)
+    out = np.empty((w.shape[0], cout), dtype=np.float64)
+    lib().orc_v2f_dW_rows(C.c_int64(n_vert), C.c_int64(facet.shape[0]), _p(facet, C.c_int32), C.c_int(L), C.c_int(norm),
+                          C.c_int(cin), C.c_int(cout), _p(h, C.c_double), _p(dg, C.c_double), C.c_int64(w.shape[0]),
+                          _p(w, C.c_int64), _p(out, C.c_double))
+    return out
+
+
+def f2f_dW_rows(tex_off, bary, L, h, dg, wrows, norm: int = 0) -> np.ndarray:
+    tex_off, bary, h, dg = _i32(tex_off), _f32(bary), _f64(h), _f64(dg)
+    cin, cout = h.shape[1], dg.shape[1]
+    w = _wrows(wrows, (L + 1) ** 2, cin)
+    out = np.empty((w.shape[0], cout), dtype=np.float64)
+    lib().orc_f2f_dW_rows(C.c_int64(tex_off.shape[0] - 1), _p(tex_off, C.c_int32), _p(bary, C.c_float), C.c_int(L),
+                          C.c_int(norm), C.c_int(cin), C.c_int(cout), _p(h, C.c_double), _p(dg, C.c_double),
+                          C.c_int64(w.shape[0]), _p(w, C.c_int64), _p(out, C.c_double))
+    return out
+
+
 def sh_basis_bwd(dirs, L: int, dbasis, norm: int = 0) -> np.ndarray:
     """Gradient of <dbasis, B(d/|d|)> with respect to the (unnormalised) directions d.
 

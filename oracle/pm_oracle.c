@@ -640,4 +640,93 @@ void orc_v2f_sep_bwd(int64_t V, int64_t F, const int32_t* facet, int L, int norm
   free(sc); free(du);
 }
 
+/* ------------------------------------------------------------------------------------------------
+ * Selected rows of the coefficient gradients.  dW is a sum over every facet (point), so at sizes where
+ * the whole tensor takes the oracle too long it evaluates the rows dW[k][ci][0..cout) named by
+ * wrows[i] = k*cin + ci, each by the same ascending sum over all facets as the full functions above
+ * (same definitions, transposed sums of Eq. 5 / 6 / 7; the results agree bit for bit with those rows).
+ * out is [n_wrows, cout].
+ * ------------------------------------------------------------------------------------------------ */
+void orc_f2v_dW_rows(int64_t V, int64_t F, const float* vert, const int32_t* facet, int L, int norm, int cin, int cout,
+                     const double* h, const double* dg, int64_t n_wrows, const int64_t* wrows, double* out) {
+  int K = (L + 1) * (L + 1);
+  int64_t* deg = (int64_t*)calloc((size_t)V, sizeof(int64_t));
+  for (int64_t e = 0; e < 3 * F; ++e) deg[facet[e]]++;
+  double* Ball = (double*)malloc((size_t)(F + 1) * K * sizeof(double));
+#pragma omp parallel for schedule(static)
+  for (int64_t f = 0; f < F; ++f) {
+    double n[3];
+    facet_normal_one(vert, facet + 3 * f, n);
+    sh_basis_one(n, L, norm, Ball + f * K);
+  }
+#pragma omp parallel
+  {
+    double* dy = (double*)malloc((size_t)cout * sizeof(double));
+#pragma omp for schedule(dynamic, 1)
+    for (int64_t i = 0; i < n_wrows; ++i) {
+      int k = (int)(wrows[i] / cin), ci = (int)(wrows[i] % cin);
+      double* d = out + i * cout;
+      for (int co = 0; co < cout; ++co) d[co] = 0.0;
+      for (int64_t f = 0; f < F; ++f) {
+        for (int co = 0; co < cout; ++co) dy[co] = 0.0;
+        for (int j = 0; j < 3; ++j) {
+          int64_t v = facet[3 * f + j];
+          for (int co = 0; co < cout; ++co) dy[co] += dg[v * cout + co] / (double)deg[v];
+        }
+        double bh = Ball[f * K + k] * h[f * cin + ci];
+        for (int co = 0; co < cout; ++co) d[co] += bh * dy[co];
+      }
+    }
+    free(dy);
+  }
+  free(Ball); free(deg);
+}
+
+void orc_v2f_dW_rows(int64_t V, int64_t F, const int32_t* facet, int L, int norm, int cin, int cout, const double* h,
+                     const double* dg, int64_t n_wrows, const int64_t* wrows, double* out) {
+  (void)V;
+  double Bc[3][ORC_MAX_K];
+  corner_basis(L, norm, Bc);
+#pragma omp parallel for schedule(dynamic, 1)
+  for (int64_t i = 0; i < n_wrows; ++i) {
+    int k = (int)(wrows[i] / cin), ci = (int)(wrows[i] % cin);
+    double* d = out + i * cout;
+    for (int co = 0; co < cout; ++co) d[co] = 0.0;
+    for (int64_t f = 0; f < F; ++f)
+      for (int j = 0; j < 3; ++j) {
+        int64_t v = facet[3 * f + j];
+        double bh = Bc[j][k] * h[v * cin + ci];
+        for (int co = 0; co < cout; ++co) d[co] += bh * dg[f * cout + co];
+      }
+  }
+}
+
+void orc_f2f_dW_rows(int64_t F, const int32_t* tex_off, const float* bary, int L, int norm, int cin, int cout,
+                     const double* h, const double* dg, int64_t n_wrows, const int64_t* wrows, double* out) {
+  int K = (L + 1) * (L + 1);
+  int64_t P = tex_off[F];
+  int32_t* owner = (int32_t*)malloc((size_t)(P + 1) * sizeof(int32_t));
+  for (int64_t f = 0; f < F; ++f)
+    for (int64_t p = tex_off[f]; p < tex_off[f + 1]; ++p) owner[p] = (int32_t)f;
+  double* Ball = (double*)malloc((size_t)(P + 1) * K * sizeof(double));
+#pragma omp parallel for schedule(static)
+  for (int64_t p = 0; p < P; ++p) {
+    double d[3] = {(double)bary[3 * p], (double)bary[3 * p + 1], (double)bary[3 * p + 2]};
+    sh_basis_one(d, L, norm, Ball + p * K);
+  }
+#pragma omp parallel for schedule(dynamic, 1)
+  for (int64_t i = 0; i < n_wrows; ++i) {
+    int k = (int)(wrows[i] / cin), ci = (int)(wrows[i] % cin);
+    double* dd = out + i * cout;
+    for (int co = 0; co < cout; ++co) dd[co] = 0.0;
+    for (int64_t p = 0; p < P; ++p) {
+      int64_t f = owner[p];
+      double R = (double)(tex_off[f + 1] - tex_off[f]);
+      double bh = Ball[p * K + k] * h[p * cin + ci] / R;
+      for (int co = 0; co < cout; ++co) dd[co] += bh * dg[f * cout + co];
+    }
+  }
+  free(Ball); free(owner);
+}
+
 int orc_max_l(void) { return ORC_MAX_L; }

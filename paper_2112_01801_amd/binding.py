@@ -25,7 +25,7 @@ PM_MAX_L = 5
 EXPORTS = [
     "pm_status_string", "pm_last_error", "pm_workspace_bytes", "pm_validate_mesh", "pm_build_vf_adjacency",
     "pm_sh_basis", "pm_sh_basis_dirs", "pm_sh_basis_bwd", "pm_f2v", "pm_f2v_bwd", "pm_v2f", "pm_v2f_bwd",
-    "pm_f2f", "pm_f2f_bwd", "pm_f2v_order", "pm_profile_enable", "pm_profile_filter", "pm_profile_count", "pm_profile_read", "pm_profile_reset",
+    "pm_f2f", "pm_f2f_bwd", "pm_profile_enable", "pm_profile_filter", "pm_profile_count", "pm_profile_read", "pm_profile_reset",
     "pm_peak_probe", "pm_f2v_sep", "pm_f2v_sep_bwd", "pm_v2f_sep", "pm_v2f_sep_bwd",
     "pm_cluster_ws_bytes", "pm_validate_clusters", "pm_build_cluster_map", "pm_pool", "pm_pool_bwd", "pm_unpool",
     "pm_unpool_bwd", "pm_pcloud_ws_bytes", "pm_reverse_ws_bytes", "pm_build_reverse_neighbors", "pm_validate_neighbors", "pm_pcloud_conv", "pm_pcloud_conv_bwd",
@@ -124,7 +124,7 @@ def lib():
         l.pm_texture_ws_bytes.argtypes = [i64, C.c_int32]
         l.pm_cluster_ws_bytes.restype = C.c_size_t
         l.pm_cluster_ws_bytes.argtypes = [i64, i64]
-        sig.update({"pm_f2v_order": [i32], "pm_profile_enable": [i32], "pm_profile_filter": [C.c_char_p], "pm_profile_count": [], "pm_profile_reset": [],
+        sig.update({"pm_profile_enable": [i32], "pm_profile_filter": [C.c_char_p], "pm_profile_count": [], "pm_profile_reset": [],
                     "pm_profile_read": [i32, C.c_char_p, sz, C.POINTER(C.c_float)],
                     "pm_peak_probe": [i32, vp, sz, C.POINTER(C.c_double), C.POINTER(C.c_double), vp]})
         for name, args in sig.items():
@@ -696,11 +696,6 @@ def pm_texture_layout(mesh: Mesh, alpha: int, beta: int, stream=None):
 
 def pm_profile_enable(on: bool) -> None:
     _check(lib().pm_profile_enable(1 if on else 0))
-
-
-def pm_f2v_order(order: int) -> None:
-    """1: facet2vertex forward in the facet-side order (default); 0: vertex-side order where its kernel applies."""
-    _check(lib().pm_f2v_order(order))
 
 
 def pm_profile_filter(label_part: str = "") -> None:

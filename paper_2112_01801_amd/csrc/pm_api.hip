@@ -4,6 +4,9 @@
 
 #include <string.h>
 
+#include <map>
+#include <mutex>
+#include <utility>
 #include <vector>
 
 #include <algorithm>
@@ -21,6 +24,21 @@ pm_status pm_fail(pm_status s, const char* fmt, ...) {
 }
 
 extern "C" const char* pm_last_error(void) { return g_err; }
+
+// The dynamic-LDS limit of a kernel is a property of the loaded code object on a device: set it when a
+// (kernel, device) pair is first launched with a given size, remember that, and skip the runtime call afterwards.
+pm_status pm_set_dyn_lds(const void* kernel, size_t bytes) {
+  static std::mutex mu;
+  static std::map<std::pair<const void*, int>, size_t> done;
+  int dev = 0;
+  PM_CHECK_HIP(hipGetDevice(&dev));
+  std::lock_guard<std::mutex> lock(mu);
+  auto it = done.find({kernel, dev});
+  if (it != done.end() && it->second == bytes) return PM_OK;
+  PM_CHECK_HIP(hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes));
+  done[{kernel, dev}] = bytes;
+  return PM_OK;
+}
 
 // ---- per-kernel event timing ------------------------------------------------------------------
 struct ProfRec {
@@ -109,12 +127,6 @@ extern "C" const char* pm_status_string(pm_status s) {
     default: return "PM_ERR_UNKNOWN";
   }
 }
-
-#define PM_TRY(expr)                 \
-  do {                               \
-    pm_status s__ = (expr);          \
-    if (s__ != PM_OK) return s__;    \
-  } while (0)
 
 static const int64_t kMaxIds = 2147483647LL;
 
@@ -308,13 +320,6 @@ static void fold_coef(int L, pm_sh_norm norm, FoldCoef* fc) {
 }
 
 // ---- facet2vertex (Eq. 5) ------------------------------------------------------------------------
-static int g_f2v_order = 1;   // 1: facet-side (default), 0: vertex-side where its kernel applies
-extern "C" pm_status pm_f2v_order(int order) {
-  if (order != 0 && order != 1) return pm_fail(PM_ERR_INVALID_ARG, "order %d", order);
-  g_f2v_order = order;
-  return PM_OK;
-}
-
 extern "C" pm_status pm_f2v(const pm_mesh* mesh, const pm_vf_adj* adj, int L, pm_sh_norm norm, int cin, int cout,
                             pm_dtype dtype, const void* h_facet, const void* W, void* g_vert, void* ws, size_t ws_bytes,
                             void* stream) {
@@ -337,10 +342,6 @@ extern "C" pm_status pm_f2v(const pm_mesh* mesh, const pm_vf_adj* adj, int L, pm
   BasisSrc bs = basis_none();
   bs.vert = mesh->vert; bs.facet = mesh->facet;
   pm_make_sh_table(L, norm, &bs.sh);
-  // vertex-side order (mean before the contraction) on request, where its kernel applies: half the matrix work
-  // and no per-facet intermediate, but slower as measured; otherwise the facet-side order below
-  if (g_f2v_order == 0 && F > 0 && pm_f2v_vs_applies(dtype, K, cin, cout, h_facet, g_vert))
-    return pm_launch_f2v_vs(mesh, adj->row_ptr, adj->col, K, cout, bs.sh, h_facet, apack, g_vert, st);
   RowSrc xs = row_src(h_facet, dtype, cin);
   const int yb = dtype == PM_BF16;
   PM_TRY(pm_launch_conv_rows(dtype, B_NORMAL, X_DIRECT, F, K, cin, cout, bs, xs, apack, y, yb, st));

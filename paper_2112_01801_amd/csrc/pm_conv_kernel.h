@@ -509,7 +509,7 @@ template <int DT, int BM, int XM, int LT, int NW, bool RES, bool FAST>
 static pm_status launch_conv_fast(const ConvP& p, int64_t S, hipStream_t st) {
   auto kern = k_conv_rows<DT, BM, XM, LT, NW, RES, FAST>;
   size_t lds = RES ? (size_t)S * PM_STAGE_BYTES : 2 * (size_t)PM_STAGE_BYTES;
-  PM_CHECK_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+  PM_TRY(pm_set_dyn_lds((const void*)kern, lds));
   const int NT = NW * 64;
   int64_t n_tiles = (p.R + NT - 1) / NT;
   int64_t grid = n_tiles < 256 ? (n_tiles + 7) / 8 * 8 : 256;

@@ -19,6 +19,12 @@ pm_status pm_fail(pm_status s, const char* fmt, ...);
     if (e__ != hipSuccess) return pm_fail(PM_ERR_HIP, "launch %s: %s", name, hipGetErrorString(e__)); \
   } while (0)
 
+#define PM_TRY(expr)                 \
+  do {                               \
+    pm_status s__ = (expr);          \
+    if (s__ != PM_OK) return s__;    \
+  } while (0)
+
 // ---- optional per-kernel event timing (see pm_profile_* in the public header) -----------------
 void pm_prof_begin(hipStream_t st, const char* kernel);
 void pm_prof_end(hipStream_t st);
@@ -28,6 +34,10 @@ struct ProfScope {
   ProfScope(hipStream_t s, const char* kernel) : st(s) { pm_prof_begin(st, kernel); }
   ~ProfScope() { pm_prof_end(st); }
 };
+
+// Raises a kernel's dynamic-LDS limit; the runtime call is made once per (kernel, device) and size, later calls
+// are a table lookup.
+pm_status pm_set_dyn_lds(const void* kernel, size_t bytes);
 
 static inline bool pm_aligned16(const void* p) { return (((uintptr_t)p) & 15u) == 0; }
 static inline size_t pm_round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
@@ -209,10 +219,6 @@ pm_status pm_launch_affine_act(int64_t n_rows, int C, int is_bf16, void* x, cons
                                int relu, hipStream_t st);
 pm_status pm_launch_affine_act_bwd(int64_t n_rows, int C, int is_bf16, const void* dy, const void* y_saved,
                                    const float* scale, int relu, void* out, hipStream_t st);
-// facet2vertex forward in the vertex-side order (bf16, Cin = 64)
-bool pm_f2v_vs_applies(pm_dtype dt, int K, int cin, int cout, const void* h, const void* out);
-pm_status pm_launch_f2v_vs(const pm_mesh* mesh, const int32_t* row_ptr, const int32_t* col, int K, int cout,
-                           const ShTable& sh, const void* h, const void* apack, void* out, hipStream_t st);
 // pooling over vertex clusters
 pm_status pm_launch_cluster_target(int64_t n_in, int64_t n_out, const int32_t* vcluster, const int32_t* iomap,
                                    int32_t* target, int32_t* bad, hipStream_t st);

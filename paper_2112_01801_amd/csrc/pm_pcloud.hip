@@ -286,7 +286,7 @@ static pm_status pc_launch(const PcP& p, int is_bf16, bool vec, int grid, hipStr
   auto kern = is_bf16 ? (vec ? k_pc_dw<true, MODE, true> : k_pc_dw<true, MODE, false>)
                       : (vec ? k_pc_dw<false, MODE, true> : k_pc_dw<false, MODE, false>);
   const size_t lds = pc_lds_bytes(p.K);
-  PM_CHECK_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+  PM_TRY(pm_set_dyn_lds((const void*)kern, lds));
   { ProfScope ps__(st, MODE == 0 ? "k_pc_dw" : (MODE == 1 ? "k_pc_dw_dh" : "k_pc_dw_coef"));
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(256), lds, st, p); }
   PM_CHECK_LAUNCH("k_pc_dw");

@@ -244,7 +244,7 @@ pm_status pm_launch_dw_f2v(int64_t F, int K, int C, int is_bf16, const BasisSrc&
   const bool vec = chan_vec_ok(C, is_bf16, h, y, nullptr);
   auto kern = is_bf16 ? (vec ? k_dw_f2v<true, false, true> : k_dw_f2v<true, false, false>)
                       : (vec ? k_dw_f2v<false, false, true> : k_dw_f2v<false, false, false>);
-  PM_CHECK_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+  PM_TRY(pm_set_dyn_lds((const void*)kern, lds));
   { ProfScope ps__(st, "k_dw_f2v");
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(256), lds, st, p); }
   PM_CHECK_LAUNCH("k_dw_f2v");
@@ -283,7 +283,7 @@ pm_status pm_launch_dw_f2v_bwd(int64_t F, int K, int C, int is_bf16, const Basis
   if (dh && !fused) {
     p.kc0 = 0; p.want_dalpha = 0; p.y = dh;
     const size_t lds = sep_lds_bytes(K, true);
-    PM_CHECK_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    PM_TRY(pm_set_dyn_lds((const void*)kern, lds));
     { ProfScope ps__(st, "k_dw_f2v_bwd");
       hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(256), lds, st, p); }
     PM_CHECK_LAUNCH("k_dw_f2v_bwd");
@@ -295,7 +295,7 @@ pm_status pm_launch_dw_f2v_bwd(int64_t F, int K, int C, int is_bf16, const Basis
       p.kc0 = k0;
       const int kn = K - k0 < SEP_KC ? K - k0 : SEP_KC;
       const size_t lds = sep_lds_bytes(kn, true);
-      PM_CHECK_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+      PM_TRY(pm_set_dyn_lds((const void*)kern, lds));
       { ProfScope ps__(st, "k_dw_f2v_bwd");
         hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(256), lds, st, p); }
       PM_CHECK_LAUNCH("k_dw_f2v_bwd");

@@ -312,7 +312,7 @@ static pm_status v2f_stage_launch(VtP& p, hipStream_t st, const char* label) {
   int64_t grid = (p.F + VT_ROWS - 1) / VT_ROWS;
   if (grid > 512) grid = 512;
   auto kern = k_v2f_stage<CIN, NB, NJ, FUSE, OF32>;
-  PM_CHECK_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+  PM_TRY(pm_set_dyn_lds((const void*)kern, lds));
   { ProfScope ps__(st, label);
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(256), lds, st, p); }
   PM_CHECK_LAUNCH(label);

@@ -503,7 +503,7 @@ static pm_status launch_wgrad_fast(const WgradP& p, const WgradGeom& g, hipStrea
   const int nsub = (XM == X_GATHER_CAT) ? 3 : 1;
   const int xpb = (DT == 1) ? XP_BF16 * 2 : XP_F32 * 4;
   size_t lds = 2 * ((size_t)nsub * 64 * xpb + (size_t)64 * XP_F32 * 4 + (size_t)WG_KG * XP_F32 * 4);
-  PM_CHECK_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+  PM_TRY(pm_set_dyn_lds((const void*)kern, lds));
   { ProfScope ps__(st, "k_wgrad");
     hipLaunchKernelGGL(kern, dim3((unsigned)g.n_part, (unsigned)g.slabs), dim3(512), lds, st, p); }
   PM_CHECK_LAUNCH("k_wgrad");

@@ -313,7 +313,7 @@ template <int BM, int YM, int LT>
 static pm_status launch_pc(const WgradP& p, int n_part, int slabs, hipStream_t st) {
   auto kern = k_wgrad_pc<BM, YM, LT>;
   const size_t lds = 2 * (size_t)PC_BUF_BYTES;
-  PM_CHECK_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+  PM_TRY(pm_set_dyn_lds((const void*)kern, lds));
   { ProfScope ps__(st, "k_wgrad");
     hipLaunchKernelGGL(kern, dim3((unsigned)n_part, (unsigned)slabs), dim3(PC_THREADS), lds, st, p); }
   PM_CHECK_LAUNCH("k_wgrad_pc");

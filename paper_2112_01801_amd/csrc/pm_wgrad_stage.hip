@@ -170,7 +170,7 @@ template <int CIN, int NB, int NJ>
 static pm_status wgrad_stage_launch(const WsP& p, int grid, hipStream_t st) {
   const size_t lds = (size_t)WS_ROWS * (NJ * CIN * 2 + 16) + (size_t)WS_ROWS * (64 * NB + 16);
   auto kern = k_wgrad_stage<CIN, NB, NJ>;
-  PM_CHECK_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+  PM_TRY(pm_set_dyn_lds((const void*)kern, lds));
   { ProfScope ps__(st, "k_wgrad_stage");
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(256), lds, st, p); }
   PM_CHECK_LAUNCH("k_wgrad_stage");

@@ -6,6 +6,8 @@ import numpy as np
 from paper_2112_01801_amd import meshgen as mg
 
 TOL = {"f32": 1e-4, "bf16": 2e-2}
+NW = 48            # sampled rows dW[k, ci, :] of the weight gradient
+ADJ_TOL = {"bf16": 1e-2, "f32": 2e-5}
 
 
 def rel_err_rows(got: np.ndarray, ref: np.ndarray) -> float:
@@ -66,3 +68,30 @@ def sample_rows(rng, n, k):
     if n <= k:
         return np.arange(n, dtype=np.int64)
     return np.sort(rng.choice(n, size=k, replace=False)).astype(np.int64)
+
+
+def _adjoint_gap(Wp, dW, gp, dg_d):
+    """|<W', dW> - <g', dg>| over the 2-norm of the terms g'*dg (the size of a sum of terms of random sign)."""
+    import torch
+    lhs = float((torch.from_numpy(Wp).cuda().double() * dW.double()).sum())
+    terms = gp.double() * dg_d.double()
+    rhs = float(terms.sum())
+    return abs(lhs - rhs) / float(terms.pow(2).sum().sqrt())
+
+
+def adjoint_ok(Wp, dW, gp, dg_d, dtype):
+    """bf16: g' carries two roundings of relative size 2^-9 per element, independent between elements, so the gap
+    is about 2e-3 of the 2-norm; fp32: accumulation error only."""
+    gap = _adjoint_gap(Wp, dW, gp, dg_d)
+    assert gap <= ADJ_TOL[dtype], gap
+    # negative controls: the identity has to see a wrong dW
+    bad = dW.clone()
+    bad[dW.shape[0] // 2] = 0
+    assert _adjoint_gap(Wp, bad, gp, dg_d) > 3 * ADJ_TOL[dtype]
+    assert _adjoint_gap(Wp, dW * 1.05, gp, dg_d) > 3 * ADJ_TOL[dtype]
+
+
+def sample_wrows(rng, K, cin):
+    w = np.sort(rng.choice(K * cin, size=min(NW, K * cin), replace=False)).astype(np.int64)
+    w[0], w[-1] = 0, K * cin - 1
+    return w

@@ -2,6 +2,7 @@
 import numpy as np
 import pytest
 
+import rounding_model as rm
 from oracle import pcloud as opc
 from paper_2112_01801_amd import meshgen as mg
 from parity_util import TOL, make_features, pm_dtype, rel_err, rel_err_rows, sample_rows, to_dev, to_host
@@ -105,12 +106,25 @@ def test_vertices_of_a_coarse_mesh_level_sampled(pm):
     dh, da, dc, dP = pm.pm_pcloud_conv_bwd(nb, L, to_dev(h, dtype), a_d, c_d, P_d, to_dev(dg, dtype), dt)
     # the oracle on the whole set takes a few seconds (1.9 M pairs)
     ref = opc.pcloud_conv(xs, xs, ptr, idx, rho, L, h, alpha, c0, P)
-    rows = sample_rows(rng, xs.shape[0], 4096)
-    # border points have one or two neighbours, interior points average thirty: output rows differ in scale by
-    # sqrt(30), so bf16 results are measured per row (fp32 passes the global metric at 3e-6 on the same data)
-    assert rel_err_rows(to_host(g[rows]), ref[rows]) < TOL[dtype]
+    # border points have one or two neighbours, interior points average thirty: the depth-wise rows y (the bf16
+    # operand of the point-wise matrix) differ in scale by sqrt(30), and half a bf16 unit of the large rows, measured
+    # against the global rms, exceeds 2e-2 in ANY bf16 data path: rounding_model (the oracle with y and the output
+    # rounded to bf16; tests/test_rounding_bounds.py pins it at 4.5e-2 on this very input) gives the bound.  The
+    # result is held to that bound, to 1e-2 from the model itself, to the stated 2e-2 on the rows the scale argument
+    # does not touch (own rms within twice the global one), and to 2e-2 of its own rms on every row.
+    got = to_host(g)
+    model = rm.pcloud_forward_bf16(xs, xs, ptr, idx, rho, L, h, alpha, c0, P)
+    e, em, d = rel_err(got, ref), rel_err(model, ref), rel_err(got, model)
+    print("pcloud forward: err %.2e  model %.2e  from model %.2e" % (e, em, d))
+    assert e < rm.derived_bound(TOL[dtype], em) and d < 1e-2
+    row_rms, rms = np.sqrt(np.mean(ref ** 2, axis=1)), np.sqrt(np.mean(ref ** 2))
+    plain = row_rms <= 2.0 * rms
+    assert plain.mean() > 0.9
+    den = np.maximum(np.abs(ref[plain]), rms)
+    assert float(np.max(np.abs(got[plain] - ref[plain]) / den)) < TOL[dtype]
+    assert rel_err_rows(got, ref) < TOL[dtype]
     rdh, rda, rdc, rdP = opc.pcloud_conv_bwd(xs, xs, ptr, idx, rho, L, h, alpha, c0, P, dg)
-    assert rel_err_rows(to_host(dh[rows]), rdh[rows]) < TOL[dtype]
+    assert rel_err(to_host(dh), rdh) < TOL[dtype]              # one store: the stated metric
     assert rel_err(to_host(da), rda) < TOL[dtype] and rel_err(to_host(dP), rdP) < TOL[dtype]
     assert rel_err(to_host(dc)[None, :], rdc[None, :]) < TOL[dtype]
 

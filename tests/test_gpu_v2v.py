@@ -6,21 +6,38 @@ the feature dtype), so that both sides take the ReLU decisions from the same val
 pre-activation is within rounding of zero may be cut on one side and kept on the other otherwise, which is a
 different (equally valid) subgradient, not an error.  The forward test checks the saved tensors themselves.
 
-Tolerance: the block is two convolutions in sequence, each held to 1e-4 (fp32) / 2e-2 (bf16) on its own; their
-rounding errors add, so the block's outputs and gradients are held to the sum, 2e-4 / 4e-2, in the same metric
-(the facet features g, the output of the first convolution alone, keep the single-convolution tolerance).
+Tolerance: fp32 is held to the stated 1e-4 throughout.  In bf16 the block chains several bf16 stores (two
+convolutions in sequence), so each tensor is held (a) to max(2e-2, 1.25 x the error of rounding_model) against the
+oracle -- rounding_model is the oracle with exactly the stored tensors rounded to bf16, tests/test_rounding_bounds.py
+pins it and the bound it gives -- and (b) to 1e-2 from that model itself.  The facet features g, the output of the
+first convolution alone, keep the stated 2e-2, and so does the second convolution alone: the block's output against
+the oracle's second stage applied to the g the library saved.
 """
 import numpy as np
 import pytest
 
+import oracle
+import rounding_model as rm
 from oracle import v2v
 from paper_2112_01801_amd import meshgen as mg
-from parity_util import TOL as TOL1, make_features, pm_dtype, rel_err, to_dev, to_host
+from parity_util import TOL, make_features, pm_dtype, rel_err, to_dev, to_host
 from test_gpu_parity import small_batch
 
 pytestmark = pytest.mark.gpu
 
-TOL = {k: 2 * v for k, v in TOL1.items()}     # two convolutions in sequence
+NEAR_MODEL = 1e-2      # distance of a bf16 result from the oracle-side model of its stores
+
+
+def _held(got, ref, model, dtype, name=""):
+    """fp32: the stated tolerance.  bf16: the bound its stores imply, and close to the model of those stores."""
+    e = rel_err(got, ref)
+    if dtype != "bf16":
+        assert e < TOL[dtype], (name, e)
+        return
+    em, d = rel_err(model, ref), rel_err(got, model)
+    print("%s: err %.2e  model %.2e  from model %.2e" % (name, e, em, d))
+    assert e < rm.derived_bound(TOL[dtype], em), (name, e, em)
+    assert d < NEAR_MODEL, (name, d)
 
 
 @pytest.fixture(scope="module")
@@ -93,13 +110,18 @@ def test_v2v_forward(pm, L, cin, cmid, cout, dtype, mode):
     import torch
     b, rng, (a1, P1, ep1, a2, P2, ep2), h, mesh, adj, d = _setup(pm, L, cin, cmid, cout, dtype, mode, 31)
     ro, rg, rz = v2v.v2v_sep(b.vert, b.facet, L, h, a1, P1, ep1, a2, P2, ep2, parts=True)
+    mo, mgg, mz = rm.v2v_forward_bf16(b.vert, b.facet, L, h, a1, P1, ep1, a2, P2, ep2) if dtype == "bf16" else (None,) * 3
     o = pm.pm_v2v_sep(mesh, adj, L, d["h"], d["a1"], d["P1"], d["ep1"], d["a2"], d["P2"], d["ep2"], pm_dtype(dtype))
-    assert rel_err(to_host(o), ro) < TOL[dtype]
+    _held(to_host(o), ro, mo, dtype, "o")
     o2, g, z = pm.pm_v2v_sep(mesh, adj, L, d["h"], d["a1"], d["P1"], d["ep1"], d["a2"], d["P2"], d["ep2"], pm_dtype(dtype),
                              save=True)
     assert torch.equal(o2, o)
-    assert rel_err(to_host(g), rg) < TOL1[dtype]
-    assert rel_err(to_host(z), rz) < TOL[dtype]
+    assert rel_err(to_host(g), rg) < TOL[dtype]                 # the first convolution alone: the stated tolerance
+    _held(to_host(z), rz, mz, dtype, "z")
+    # the second convolution alone, at the stated tolerance: the oracle's facet2vertex stage on the saved g
+    o_from_g = oracle.f2v_sep(b.vert, b.facet, L, to_host(g), a2, P2)
+    a, sh, relu = v2v._ep(ep2, cout)
+    assert rel_err(to_host(o), v2v._act(a * o_from_g + sh, relu)) < TOL[dtype]
     if mode != "none":
         assert float(g.float().min()) >= 0 and float(o.float().min()) >= 0
 
@@ -114,8 +136,10 @@ def test_v2v_backward(pm, L, cin, cmid, cout, dtype, mode):
     args = (mesh, adj, L, d["h"], d["a1"], d["P1"], d["ep1"], d["a2"], d["P2"], d["ep2"], to_dev(rg.astype(np.float32), dtype),
             to_dev(rz.astype(np.float32), dtype), to_dev(ro.astype(np.float32), dtype), to_dev(d_out, dtype), pm_dtype(dtype))
     got = pm.pm_v2v_sep_bwd(*args)
-    for name, x, r in zip(["dh", "dalpha1", "dP1", "dalpha2", "dP2"], got, ref):
-        assert rel_err(to_host(x), r) < TOL[dtype], name
+    model = (rm.v2v_backward_bf16(b.vert, b.facet, L, h, a1, P1, ep1, a2, P2, ep2, rm.r16(rg), rm.r16(rz), rm.r16(ro), d_out)
+             if dtype == "bf16" else (None,) * 5)
+    for name, x, r, m in zip(["dh", "dalpha1", "dP1", "dalpha2", "dP2"], got, ref, model):
+        _held(to_host(x), r, m, dtype, name)
     # each group alone gives the same values
     dh1, *rest = pm.pm_v2v_sep_bwd(*args, want_dw=False)
     assert all(t is None for t in rest) and torch.equal(dh1, got[0])
@@ -157,7 +181,7 @@ def test_v2v_degenerate_meshes(pm, dtype, c):
                             save=True)
     ref = v2v.v2v_sep(be.vert, be.facet, L, h, a1, P1, ep1, a2, P2, ep2)
     assert g.shape == (0, c) and not z.float().abs().any()
-    assert rel_err(to_host(o), ref) < TOL[dtype]
+    assert rel_err(to_host(o), ref) < TOL[dtype]                # act2(b2), rounded once
     got = pm.pm_v2v_sep_bwd(mesh, adj, L, d["h"], d["a1"], d["P1"], d["ep1"], d["a2"], d["P2"], d["ep2"], g, z, o,
                             torch.ones_like(o), pm_dtype(dtype))
     assert all(not x.float().abs().any() for x in got)
@@ -170,7 +194,26 @@ def test_v2v_config3_full_size(pm):
     b, rng, (a1, P1, ep1, a2, P2, ep2), h, mesh, adj, d = _setup(pm, L, c, c, c, dtype, "affine", 35, batch=cfg.batch)
     o = pm.pm_v2v_sep(mesh, adj, L, d["h"], d["a1"], d["P1"], d["ep1"], d["a2"], d["P2"], d["ep2"], 1)
     ref = v2v.v2v_sep(b.vert, b.facet, L, h, a1, P1, ep1, a2, P2, ep2)
-    assert rel_err(to_host(o), ref) < TOL[dtype]
+    model = rm.v2v_forward_bf16(b.vert, b.facet, L, h, a1, P1, ep1, a2, P2, ep2)[0]
+    _held(to_host(o), ref, model, dtype, "o at config 3")
+
+
+def test_v2v_backward_at_a_hierarchy_level_against_the_oracle(pm):
+    """The 512 x 512 level of the decimation hierarchy (522,242 facets, 64 channels, bf16, both epilogues): all five
+    gradients, every element, against the oracle (the full-size test below compares the library with its own forward)."""
+    cfg = mg.config5_levels()[1]
+    L, c, dtype = 3, 64, "bf16"
+    b, rng, (a1, P1, ep1, a2, P2, ep2), h, mesh, adj, d = _setup(pm, L, c, c, c, dtype, "affine", 39, batch=cfg.batch)
+    assert b.n_facet == 522242
+    d_out = make_features(rng, b.n_vert, c, dtype)
+    ro, rg, rz = v2v.v2v_sep(b.vert, b.facet, L, h, a1, P1, ep1, a2, P2, ep2, parts=True)
+    ref = v2v.v2v_sep_bwd(b.vert, b.facet, L, h, a1, P1, ep1, a2, P2, ep2, d_out)
+    got = pm.pm_v2v_sep_bwd(mesh, adj, L, d["h"], d["a1"], d["P1"], d["ep1"], d["a2"], d["P2"], d["ep2"],
+                            to_dev(rg.astype(np.float32), dtype), to_dev(rz.astype(np.float32), dtype),
+                            to_dev(ro.astype(np.float32), dtype), to_dev(d_out, dtype), 1)
+    model = rm.v2v_backward_bf16(b.vert, b.facet, L, h, a1, P1, ep1, a2, P2, ep2, rm.r16(rg), rm.r16(rz), rm.r16(ro), d_out)
+    for name, x, r, m in zip(["dh", "dalpha1", "dP1", "dalpha2", "dP2"], got, ref, model):
+        _held(to_host(x), r, m, dtype, name + " at 512x512")
 
 
 def test_v2v_config3_backward_adjoint(pm):

@@ -388,3 +388,34 @@ def test_v2f_and_f2f_take_no_geometry():
     import inspect
     assert "vert" not in inspect.signature(oracle.v2f).parameters
     assert "vert" not in inspect.signature(oracle.f2f).parameters
+
+
+def test_dW_rows_equal_the_rows_of_the_full_gradients():
+    """The row-wise gradient functions (used where the whole dW takes the oracle too long) against the full
+    backward functions, themselves pinned above by finite differences: same sums, so bit for bit; and one row
+    written out in numpy from the transposed sum of Eq. 5 with the separately pinned basis."""
+    v, f = mg.icosphere(2)
+    v = np.concatenate([v, [[3, 3, 3]]], 0).astype(np.float32)         # one isolated vertex
+    V, F, L, K, cin, cout = v.shape[0], f.shape[0], 3, 16, 5, 7
+    rng = np.random.default_rng(31)
+    wrows = np.array([0, 3, K * cin - 1, 17, 17, 42], dtype=np.int64)
+    h, dg, W = rng.standard_normal((F, cin)), rng.standard_normal((V, cout)), rng.uniform(-1, 1, (K, cin, cout))
+    _, dW = oracle.f2v_bwd(v, f, L, h, W, dg, want_dh=False)
+    got = oracle.f2v_dW_rows(v, f, L, h, dg, wrows)
+    np.testing.assert_array_equal(got, dW.reshape(K * cin, cout)[wrows])
+    B = oracle.sh_basis(oracle.facet_normals(v, f), L)
+    deg = np.bincount(f.ravel(), minlength=V).astype(np.float64)
+    dy = sum(dg[f[:, j]] / deg[f[:, j], None] for j in range(3))
+    k, ci = 3, 2
+    np.testing.assert_allclose(got[3], (B[:, k] * h[:, ci]) @ dy, rtol=1e-12, atol=1e-13)
+
+    h, dg = rng.standard_normal((V, cin)), rng.standard_normal((F, cout))
+    _, dW = oracle.v2f_bwd(V, f, L, h, W, dg, want_dh=False)
+    np.testing.assert_array_equal(oracle.v2f_dW_rows(V, f, L, h, dg, wrows), dW.reshape(K * cin, cout)[wrows])
+
+    batch = mg.pack_batch([(v * np.array([1, 2, 3], dtype=np.float32), f)])
+    tex_off, bary = mg.texture_layout(batch, 3, 1)
+    P = int(tex_off[-1])
+    h, dg = rng.standard_normal((P, cin)), rng.standard_normal((F, cout))
+    _, dW = oracle.f2f_bwd(tex_off, bary, L, h, W, dg, want_dh=False)
+    np.testing.assert_array_equal(oracle.f2f_dW_rows(tex_off, bary, L, h, dg, wrows), dW.reshape(K * cin, cout)[wrows])
