@@ -30,7 +30,11 @@ def parse():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--grid", type=int, default=1024, help="height-field side (1024 = the benchmark config)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--oracle-rows", type=int, default=256, help="grid rows of the mesh the oracle is timed on")
+    ap.add_argument("--oracle-rows", type=int, default=0,
+                    help="grid rows of the mesh the oracle is timed on (0 = the whole mesh, about 40 s on 16 cores)")
+    ap.add_argument("--config", type=int, default=3, choices=[1, 2, 3, 4, 5],
+                    help="3 (default): the benchmark step.  1, 2, 4, 5: the op set of that configuration, one JSON line "
+                         "with per-operator times, rates and roofline fractions (not the driver's line)")
     ap.add_argument("--ops", action="store_true",
                     help="instead of the benchmark step: time every operator (F2V, V2F, F2F, forward and backward) on the "
                          "same mesh and print one JSON line with per-kernel times")
@@ -71,6 +75,9 @@ def main():
     torch.cuda.set_device(0)
     pm.lib()
 
+    if args.config != 3:
+        print(json.dumps(config_ops(args, pm, mg, torch)))
+        return
     cfg = mg.config3(args.grid)
     b = cfg.batch
     if args.ops:
@@ -183,8 +190,12 @@ def main():
     dom = next((k for k in timed if "bound" in k), None)
     roofline = None
     if dom:
+        traffic = read_traffic(dom["kernel"], args.grid)
         roofline = {"kernel": dom["kernel"], "bound": dom["bound"], "achieved": dom["achieved"], "peak": dom["peak"],
-                    "unit": dom["unit"], "frac": dom["frac"], "traffic": read_traffic(dom["kernel"], args.grid),
+                    "unit": dom["unit"], "frac": dom["frac"], "traffic": traffic,
+                    "traffic_source": None if traffic is None else
+                    "stored, not measured in this run: profiles/hbm_traffic_c3.txt (rocprofv3 --pmc FETCH_SIZE and "
+                    "WRITE_SIZE runs of this command, bytes per launch of this kernel)",
                     "avg_ms": dom["avg_ms"]}
 
     # board power while the same step runs back to back for ~1.5 s (untimed; the sensor is slow).  The
@@ -207,7 +218,7 @@ def main():
 
     cpu_baseline = None
     if not args.no_cpu_baseline:
-        cpu_baseline = oracle_baseline(cfg, min(args.oracle_rows, args.grid), h, W, dg)
+        cpu_baseline = oracle_baseline(cfg, min(args.oracle_rows, args.grid) if args.oracle_rows > 0 else args.grid, h, W, dg)
 
     out = {
         "metric": "mesh-conv facets/sec (fwd+bwd) at 1 MI355X",
@@ -225,6 +236,114 @@ def main():
         "kernels": kernels,
     }
     print(json.dumps(out))
+
+
+def op_model(op, F, V, P, K, cin, cout, e):
+    """Algorithmic work of one operator call: matrix flop as executed, and the bytes of every array touched once
+    (ids 12 B per facet, positions 12 B per vertex, CSR 12 B per facet + 4 B per vertex, features e bytes per element)."""
+    kcc = K * cin * cout
+    csr = 12 * F + 4 * V
+    geom = 12 * F + 12 * V
+    m = {
+        "f2v": (2 * kcc * F, geom + F * cin * e + csr + V * cout * e),
+        "f2v_bwd": (4 * kcc * F, geom + 4 * V + V * cout * e + 2 * F * cin * e + kcc * 4),
+        "v2f": (2 * 3 * cin * cout * F, 12 * F + V * cin * e + F * cout * e),
+        "v2f_bwd": (4 * 3 * cin * cout * F, 12 * F + csr + F * cout * e + 2 * V * cin * e + kcc * 4),
+        "f2f": (2 * kcc * P, P * (12 + cin * e) + 4 * F + F * cout * e),
+        "f2f_bwd": (4 * kcc * P, P * (12 + 2 * cin * e) + 4 * F + F * cout * e + kcc * 4),
+    }
+    flop, byts = m[op]
+    return float(flop), float(byts)
+
+
+def config_ops(args, pm, mg, torch):
+    """The op set of configuration 1, 2, 4 or 5 on its own synthetic meshes: per operator the kernel time (HIP events
+    inside the library), rows/s, matrix TFLOP/s and algorithmic GB/s with their fractions of the published peaks."""
+    n = args.config
+    if n == 1:
+        c = mg.config1()
+        runs = [("config 1", c.batch, c.L, "f32", [("f2v", c.cin, c.cout), ("v2f", c.cin, c.cout)])]
+    elif n == 2:
+        c = mg.config2(16)
+        both = lambda op: [(op, c.cin, c.cout), (op + "_bwd", c.cin, c.cout)]
+        runs = [("config 2", c.batch, c.L, "f32", both("f2v") + both("v2f") + both("f2f"))]
+    elif n == 4:
+        c = mg.config4()
+        ops = [("v2f", 32, 128), ("v2f_bwd", 32, 128), ("f2v", 128, 128), ("f2v_bwd", 128, 128), ("f2f", 32, 128),
+               ("f2f_bwd", 32, 128)]
+        runs = [("config 4", c.batch, c.L, "f32", ops)]
+    else:
+        runs = []
+        for lvl, c in enumerate(mg.config5_levels()):
+            ops = [(op + sfx, c.cin, c.cout) for op in ("f2v", "v2f", "f2f") for sfx in ("", "_bwd")]
+            runs.append(("config 5 level %d" % lvl, c.batch, c.L, "bf16", ops))
+    out = {"metric": "mesh-conv facets/sec (fwd+bwd) at 1 MI355X", "unit": "facets/s", "config": n, "steps": args.steps,
+           "note": "kernel times from HIP events inside the library; one operator at a time, inputs resident in HBM; "
+                   "adjacency and workspaces prepared before; an extra row times facet2facet at the paper's own "
+                   "shape (3 colour channels in, Eq. 7)", "runs": []}
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(20211201 + n)
+    tot_ms_all, tot_F_all = 0.0, 0
+    for name, b, L, dtype, ops in runs:
+        F, V, K = b.n_facet, b.n_vert, (L + 1) ** 2
+        DT = pm.PM_BF16 if dtype == "bf16" else pm.PM_F32
+        tdt, e = (torch.bfloat16, 2) if dtype == "bf16" else (torch.float32, 4)
+        peak = PEAK_MFMA_TFLOPS[dtype]
+        rnd = lambda *sh: torch.randn(*sh, device="cuda", generator=gen).to(tdt)
+        mesh = pm.mesh_to_device(b)
+        adj = pm.pm_build_vf_adjacency(mesh)
+        tex_off, bary = mg.texture_layout(b, 3, 1)
+        P = int(tex_off[-1])
+        t_off, t_bary = torch.from_numpy(tex_off).cuda(), torch.from_numpy(bary).cuda()
+        rows = []
+        for op, cin, cout in ops + [("f2f", 3, 32), ("f2f_bwd", 3, 32)]:
+            W = ((torch.rand(K, cin, cout, device="cuda", generator=gen) * 2 - 1) * (6.0 / (K * cin + cout)) ** 0.5).to(tdt)
+            if op == "f2v":
+                x = rnd(F, cin); fn = lambda: pm.pm_f2v(mesh, adj, L, x, W, DT)
+            elif op == "f2v_bwd":
+                x, d = rnd(F, cin), rnd(V, cout); fn = lambda: pm.pm_f2v_bwd(mesh, adj, L, x, W, d, DT)
+            elif op == "v2f":
+                x = rnd(V, cin); fn = lambda: pm.pm_v2f(mesh, L, x, W, DT)
+            elif op == "v2f_bwd":
+                x, d = rnd(V, cin), rnd(F, cout); fn = lambda: pm.pm_v2f_bwd(mesh, adj, L, x, W, d, DT)
+            elif op == "f2f":
+                x = rnd(P, cin); fn = lambda: pm.pm_f2f(t_off, t_bary, L, x, W, DT)
+            else:
+                x, d = rnd(P, cin), rnd(F, cout); fn = lambda: pm.pm_f2f_bwd(t_off, t_bary, L, x, W, d, DT)
+            for _ in range(max(1, args.warmup)):
+                fn()
+            torch.cuda.synchronize()
+            pm.pm_profile_reset()
+            pm.pm_profile_enable(True)
+            for _ in range(args.steps):
+                fn()
+            torch.cuda.synchronize()
+            pm.pm_profile_enable(False)
+            kern = {}
+            for label, ms in pm.pm_profile_read():
+                k = label.split("/", 1)[1]
+                kern[k] = kern.get(k, 0.0) + ms / args.steps
+            pm.pm_profile_reset()
+            ms = sum(kern.values())
+            flop, byts = op_model(op, F, V, P, K, cin, cout, e)
+            tf, gbs = flop / (ms * 1e-3) / 1e12, byts / (ms * 1e-3) / 1e9
+            extra = cin == 3
+            rows.append({"op": op + (" (paper shape)" if extra else ""), "cin": cin, "cout": cout, "ms": round(ms, 4),
+                         "facets_per_s": round(F / (ms * 1e-3)), "tflops": round(tf, 2), "frac_mfma": round(tf / peak, 4),
+                         "gbs_algorithmic": round(gbs, 1), "frac_hbm": round(gbs / PEAK_HBM_GBS, 4),
+                         "kernels_ms": {k: round(v, 4) for k, v in sorted(kern.items(), key=lambda kv: -kv[1])}})
+            del x
+            if not extra:
+                tot_ms_all += ms
+        tot_F_all += F
+        named = [r for r in rows if "paper shape" not in r["op"]]
+        out["runs"].append({"workload": "%s: F=%d V=%d meshes=%d texture points=%d, L=%d, %s" %
+                                        (name, F, V, b.n_mesh, P, L, dtype),
+                            "facets_per_s_op_set": round(F / (sum(r["ms"] for r in named) * 1e-3)),
+                            "ms_op_set": round(sum(r["ms"] for r in named), 4), "peak_tflops": peak, "ops": rows})
+    out["value"] = tot_F_all / (tot_ms_all * 1e-3)
+    out["ms_per_step"] = tot_ms_all
+    return out
 
 
 def all_ops(args, cfg, pm, mg, torch):
@@ -408,9 +527,9 @@ def oracle_baseline(cfg, rows, h, W, dg):
     oracle.f2v(sub.vert, sub.facet, cfg.L, hs, W)
     oracle.f2v_bwd(sub.vert, sub.facet, cfg.L, hs, W, dgs)
     dt = time.perf_counter() - t0
+    what = "the whole mesh" if rows == nx else "the first %d of %d grid rows of the same mesh" % (rows, nx)
     return {"value": Fs / dt, "unit": "facets/s", "cores": oracle.num_threads(), "kind": "oracle",
-            "sample": "facet2vertex forward + backward (dh, dW) in fp64 on the first %d of %d grid rows of the "
-                      "same mesh (%d facets), %.1f s" % (rows, nx, Fs, dt)}
+            "sample": "facet2vertex forward + backward (dh, dW) in fp64 on %s (%d facets), %.1f s" % (what, Fs, dt)}
 
 
 if __name__ == "__main__":

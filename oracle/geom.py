@@ -9,12 +9,13 @@ Readings: a corner whose two edges have a zero length product gets theta = 0; a 
 squared length < 1e-30 gets the normal (0, 0, 1).
 
 Eq. 8: gamma = floor(alpha (A - Amin) / (Amax - Amin)) + beta with the extreme areas taken per mesh of the
-batch, K = (gamma+1)(gamma+2)/2 points per facet.  A floating-point value decides an integer here, so the
-decision is taken in the kernel's precision: fp32, one IEEE operation at a time, in this order:
-  e1 = x2-x1, e2 = x3-x1, c = e1 x e2 (each component a*b - c*d as two products and a difference),
-  A = 0.5 * sqrt((cx*cx + cy*cy) + cz*cz),  q = (float(alpha) * (A - Amin)) / (Amax - Amin),  gamma = floor(q) + beta;
-Amax == Amin (or a mesh with one facet) gives gamma = beta.  The interpolation points of a facet are the
-lattice (i, j, gamma-i-j)/gamma, i descending then j descending, and the centroid for gamma = 0.
+batch, K = (gamma+1)(gamma+2)/2 points per facet.  Evaluated as written, in fp64, from the fp32 vertex positions:
+A = |(x2-x1) x (x3-x1)| / 2, q = alpha ((A - Amin) / (Amax - Amin)), gamma = floor(q) + beta; Amax == Amin (or a mesh
+with one facet) gives gamma = beta.  A floor of a real number has no tolerance: a data path that evaluates q in
+lower precision may land on the other side of an integer when q is within its rounding error of one, and both
+values are then valid -- texture_ratio returns q so that a comparison can tell those facets apart (the extreme
+facets, q = 0 and q = alpha, are exact in any precision).  The interpolation points of a facet are the lattice
+(i, j, gamma-i-j)/gamma, i descending then j descending, and the centroid for gamma = 0.
 
 Parity status: pinned by tests/test_oracle_geom.py.
 """
@@ -48,23 +49,17 @@ def facet_geometry(vert, facet, with_heights: bool = False) -> np.ndarray:
     return np.stack(cols, axis=1)
 
 
-def facet_area_f32(vert, facet) -> np.ndarray:
-    """Facet areas in fp32, one rounding per operation, in the order the header states."""
-    v = np.asarray(vert, dtype=np.float32)
+def facet_area(vert, facet) -> np.ndarray:
+    """Facet areas |(x2-x1) x (x3-x1)| / 2 in fp64."""
+    v = np.asarray(vert, dtype=np.float64)
     f = np.asarray(facet, dtype=np.int64)
-    e1 = v[f[:, 1]] - v[f[:, 0]]
-    e2 = v[f[:, 2]] - v[f[:, 0]]
-    cx = e1[:, 1] * e2[:, 2] - e1[:, 2] * e2[:, 1]
-    cy = e1[:, 2] * e2[:, 0] - e1[:, 0] * e2[:, 2]
-    cz = e1[:, 0] * e2[:, 1] - e1[:, 1] * e2[:, 0]
-    s = (cx * cx + cy * cy) + cz * cz
-    return (np.float32(0.5) * np.sqrt(s)).astype(np.float32)
+    return 0.5 * np.linalg.norm(np.cross(v[f[:, 1]] - v[f[:, 0]], v[f[:, 2]] - v[f[:, 0]]), axis=1)
 
 
-def texture_resolution(vert, facet, facet_off, alpha: int, beta: int) -> np.ndarray:
-    """gamma [F] int32 of Eq. 8, extreme areas per mesh (facet_off [n_mesh+1])."""
-    A = facet_area_f32(vert, facet)
-    gamma = np.full(A.shape[0], beta, dtype=np.int32)
+def texture_ratio(vert, facet, facet_off, alpha: int) -> np.ndarray:
+    """q [F] = alpha (A - Amin) / (Amax - Amin) of Eq. 8 in fp64, extreme areas per mesh; 0 where Amax == Amin."""
+    A = facet_area(vert, facet)
+    q = np.zeros(A.shape[0], dtype=np.float64)
     off = np.asarray(facet_off, dtype=np.int64)
     for m in range(off.shape[0] - 1):
         a = A[off[m]:off[m + 1]]
@@ -72,9 +67,13 @@ def texture_resolution(vert, facet, facet_off, alpha: int, beta: int) -> np.ndar
             continue
         lo, hi = a.min(), a.max()
         if hi > lo:
-            q = (np.float32(alpha) * (a - lo)) / (hi - lo)
-            gamma[off[m]:off[m + 1]] = np.floor(q).astype(np.int32) + beta
-    return gamma
+            q[off[m]:off[m + 1]] = alpha * ((a - lo) / (hi - lo))
+    return q
+
+
+def texture_resolution(vert, facet, facet_off, alpha: int, beta: int) -> np.ndarray:
+    """gamma [F] int32 of Eq. 8."""
+    return np.floor(texture_ratio(vert, facet, facet_off, alpha)).astype(np.int32) + np.int32(beta)
 
 
 def texture_offsets(gamma) -> np.ndarray:

@@ -8,9 +8,11 @@
 // A zero product of edge lengths gives theta = 0; the normal of a degenerate facet is (0, 0, 1).
 //
 // Eq. 8: gamma = floor(alpha (A - Amin)/(Amax - Amin)) + beta, extremes per mesh of the batch.  The floor of a
-// floating-point value decides an integer, so the arithmetic is pinned down: fp32, one IEEE operation at a time
-// (no contraction into fused multiply-adds) in the order written in facet_area() and k_tex_gamma below; any
-// implementation that follows the same order gets the same integers.
+// floating-point value decides an integer: the arithmetic is fp32, one IEEE operation at a time (no contraction
+// into fused multiply-adds) in the order written in facet_area() and k_tex_gamma below, so the result does not
+// depend on the compiler; the ratio (A - Amin)/(Amax - Amin) is formed before the multiplication by alpha, which
+// makes the two extreme facets of a mesh exact (0 and alpha).  A facet whose exact ratio times alpha lies within
+// fp32 rounding of an integer may get either neighbouring value.
 #include "pm_host.h"
 #include "pm_device.h"
 
@@ -145,9 +147,9 @@ __global__ void __launch_bounds__(256) k_tex_gamma(int64_t F, int n_mesh, const 
   const float lo = __uint_as_float(minmax[2 * m]), hi = __uint_as_float(minmax[2 * m + 1]);
   int32_t g = beta;
   if (hi > lo) {
-    const float num = (float)alpha * (area[f] - lo);
-    const float den = hi - lo;
-    g = (int32_t)floorf(__fdiv_rn(num, den)) + beta;
+    // the ratio first: it is exactly 1 for the largest facet, so that facet gets alpha + beta whatever the rounding
+    const float ratio = __fdiv_rn(area[f] - lo, hi - lo);
+    g = (int32_t)floorf((float)alpha * ratio) + beta;
   }
   gamma[f] = g;
   cnt[f] = (g + 1) * (g + 2) / 2;

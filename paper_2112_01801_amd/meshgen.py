@@ -4,7 +4,15 @@ This module only *creates inputs* (geometry, index arrays, random features, rand
 filter coefficients, host-side rounding of inputs to bf16).  It holds none of the
 arithmetic of the mesh convolutions: no spherical harmonics, no adjacency, no
 contraction.  Both the CPU oracle's tests and the HIP path's tests draw their inputs
-from here so that the two sides see bit-identical arrays.
+from here so that the two sides see bit-identical arrays.  Neither the HIP library nor
+its Python binding imports it.
+
+Two input recipes follow rules the paper states, because the synthetic inputs are meant
+to have the structure of the paper's: the facet2facet texture layouts are drawn by the
+area rule of Eq. 8 (`texture_layout`), and the coarse levels of the hierarchy by a 2x2
+vertex clustering with mean positions (`cluster_grid_2x2`).  They shape inputs only: the
+device-side Eq. 8 (`pm_texture_layout`) is checked against the oracle in `oracle/geom.py`,
+never against this module, and the library takes any layout a caller supplies.
 
 Meshes are returned in the packed heterogeneous-batch layout of the paper's
 "Heterogeneous Batching" subsection: vertex arrays concatenated, facet index arrays
@@ -298,7 +306,7 @@ def texture_layout(batch: MeshBatch, alpha: int, beta: int) -> Tuple[np.ndarray,
             continue
         lo, hi = a.min(), a.max()
         if hi > lo:
-            gamma[f0:f1] = np.floor(alpha * (a - lo) / (hi - lo)).astype(np.int64) + beta
+            gamma[f0:f1] = np.floor(alpha * ((a - lo) / (hi - lo))).astype(np.int64) + beta
         else:
             gamma[f0:f1] = beta
     res = (gamma + 1) * (gamma + 2) // 2

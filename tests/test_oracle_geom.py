@@ -56,7 +56,7 @@ def test_texture_resolution_extremes_counts_and_lattice():
     b = mg.pack_batch([mg.heightfield(9, 7, rng), mg.icosphere(1), mg.heightfield(4, 4, rng)])
     alpha, beta = 3, 1
     gamma = og.texture_resolution(b.vert, b.facet, b.facet_off, alpha, beta)
-    A = og.facet_area_f32(b.vert, b.facet)
+    A = og.facet_area(b.vert, b.facet)
     for m in range(b.n_mesh):
         s = slice(int(b.facet_off[m]), int(b.facet_off[m + 1]))
         a, g = A[s], gamma[s]
@@ -64,10 +64,10 @@ def test_texture_resolution_extremes_counts_and_lattice():
         assert g.min() >= beta and g.max() <= alpha + beta
         order = np.argsort(a, kind="stable")
         assert np.all(np.diff(g[order]) >= 0)                                    # monotone in the area
-    # the area itself against the fp64 cross product
-    v64 = b.vert.astype(np.float64)
-    ref = 0.5 * np.linalg.norm(np.cross(v64[b.facet[:, 1]] - v64[b.facet[:, 0]], v64[b.facet[:, 2]] - v64[b.facet[:, 0]]), axis=1)
-    assert np.allclose(A, ref, rtol=1e-5)
+    # the area against Heron's formula on the edge lengths of the separately pinned Eq. 9 oracle
+    l1, l2, l3 = og.facet_geometry(b.vert, b.facet)[:, :3].T
+    sp = 0.5 * (l1 + l2 + l3)
+    assert np.allclose(A, np.sqrt(np.maximum(sp * (sp - l1) * (sp - l2) * (sp - l3), 0)), rtol=1e-9)
     off = og.texture_offsets(gamma)
     bary = og.texture_bary(gamma)
     assert off[-1] == bary.shape[0] and np.array_equal(np.diff(off), (gamma + 1) * (gamma + 2) // 2)
@@ -77,17 +77,28 @@ def test_texture_resolution_extremes_counts_and_lattice():
         assert np.unique(np.round(pts * gamma[fi]).astype(int), axis=0).shape[0] == pts.shape[0]   # all distinct
         for corner in np.eye(3):
             assert (np.abs(pts - corner).sum(axis=1) < 1e-6).any()                                # corners included
-    # gamma values away from a rounding boundary agree with the generator's independent fp64 evaluation
+    # the input generator of the facet2facet tests draws its layouts by the same rule (a check of the generator)
     tex_off, bary_gen = mg.texture_layout(b, alpha, beta)
-    safe = np.ones(b.n_facet, bool)
-    for m in range(b.n_mesh):
-        s = slice(int(b.facet_off[m]), int(b.facet_off[m + 1]))
-        q = alpha * (ref[s] - ref[s].min()) / (ref[s].max() - ref[s].min())
-        safe[s] = (np.abs(q - np.round(q)) > 1e-4) | (np.round(q) == 0)     # q >= 0: near 0 the floor is 0 either way
-    assert safe.mean() > 0.7
-    assert np.array_equal(np.diff(tex_off)[safe], np.diff(off)[safe])
-    if np.array_equal(tex_off, off):
-        assert np.array_equal(bary_gen, bary)
+    assert np.array_equal(tex_off, off) and np.array_equal(bary_gen, bary)
+
+
+def test_texture_resolution_worked_by_hand():
+    """Right triangles with legs (1, a) in the plane: areas a/2 = 0.5, 0.75, 1.0, 1.25, 1.7, 2.0.  With alpha = 3:
+    q = 3 (A - 0.5) / 1.5 = 0, 0.5, 1, 1.5, 2.4, 3 and gamma - beta = 0, 0, 1, 1, 2, 3 (q = 1 exactly: floor keeps it)."""
+    legs = [1.0, 1.5, 2.0, 2.5, 3.4, 4.0]
+    v, f = [], []
+    for i, a in enumerate(legs):
+        o = 10.0 * i
+        v += [[o, 0, 0], [o + 1, 0, 0], [o, a, 0]]
+        f.append([3 * i, 3 * i + 1, 3 * i + 2])
+    v, f = np.array(v, np.float32), np.array(f)
+    assert np.allclose(og.facet_area(v, f), [0.5, 0.75, 1.0, 1.25, 1.7, 2.0], rtol=1e-6)
+    assert np.allclose(og.texture_ratio(v, f, [0, 6], 3), [0, 0.5, 1, 1.5, 2.4, 3], atol=1e-6)
+    assert list(og.texture_resolution(v, f, [0, 6], 3, 1)) == [1, 1, 2, 2, 3, 4]
+    assert list(og.texture_resolution(v, f, [0, 6], 3, 0)) == [0, 0, 1, 1, 2, 3]
+    # two meshes: each takes its own extremes (facets 0-2: areas 0.5..1.0 -> q = 0, 1.5, 3; facets 3-5: 1.25..2.0 -> 0, 1.8, 3)
+    assert list(og.texture_resolution(v, f, [0, 3, 6], 3, 1)) == [1, 2, 4, 1, 2, 4]
+    assert list(np.diff(og.texture_offsets(og.texture_resolution(v, f, [0, 6], 3, 1)))) == [3, 3, 6, 6, 10, 15]
 
 
 def test_single_area_mesh_and_the_point_count_formula():
