@@ -120,6 +120,18 @@ pm_status pm_f2v_bwd(const pm_mesh* mesh, const pm_vf_adj* adj, int L, pm_sh_nor
  * h_vert [V,cin], g_facet [F,cout].  Geometry is not read (mesh->vert may be NULL). */
 pm_status pm_v2f(const pm_mesh* mesh, int L, pm_sh_norm norm, int cin, int cout, pm_dtype dtype, const void* h_vert,
                  const void* W, void* g_facet, void* ws, size_t ws_bytes, void* stream);
+/* For callers that cannot allocate or pass a workspace: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same operation and same result, bit for bit, as pm_v2f; the folded coefficient
+ * image (the only scratch memory of the forward pass) is kept in a static device array of
+ * PM_V2F_NOALLOC_SCRATCH_BYTES that every GPU the library runs on holds until the process ends.  The call
+ * allocates nothing and frees nothing.  Shapes whose image does not fit (roughly 3*cin*cout*sizeof(dtype), rounded
+ * up to 8 KiB blocks) are refused with PM_ERR_WORKSPACE.  All calls on one GPU share the array: calls that
+ * overlap on different streams of the same GPU race on it; calls on one stream are ordered and safe.  The first
+ * call on a device looks up the array's address (no stream work); make one call outside a capture first. */
+#define PM_V2F_NOALLOC_SCRATCH_BYTES (4u << 20)
+pm_status pm_v2f_noalloc(const pm_mesh* mesh, int L, pm_sh_norm norm, int cin, int cout, pm_dtype dtype,
+                         const void* h_vert, const void* W, void* g_facet, void* stream);
+
 /* Backward of Eq. 6.  dg_facet [F,cout] -> dh_vert [V,cin] (may be NULL; needs adj), dW fp32 (may be NULL). */
 pm_status pm_v2f_bwd(const pm_mesh* mesh, const pm_vf_adj* adj, int L, pm_sh_norm norm, int cin, int cout,
                      pm_dtype dtype, const void* h_vert, const void* W, const void* dg_facet, void* dh_vert, float* dW,

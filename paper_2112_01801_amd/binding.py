@@ -24,7 +24,7 @@ PM_MAX_L = 5
 
 EXPORTS = [
     "pm_status_string", "pm_last_error", "pm_workspace_bytes", "pm_validate_mesh", "pm_build_vf_adjacency",
-    "pm_sh_basis", "pm_sh_basis_dirs", "pm_sh_basis_bwd", "pm_f2v", "pm_f2v_bwd", "pm_v2f", "pm_v2f_bwd",
+    "pm_sh_basis", "pm_sh_basis_dirs", "pm_sh_basis_bwd", "pm_f2v", "pm_f2v_bwd", "pm_v2f", "pm_v2f_noalloc", "pm_v2f_bwd",
     "pm_f2f", "pm_f2f_bwd", "pm_profile_enable", "pm_profile_filter", "pm_profile_count", "pm_profile_read", "pm_profile_reset",
     "pm_peak_probe", "pm_f2v_sep", "pm_f2v_sep_bwd", "pm_v2f_sep", "pm_v2f_sep_bwd",
     "pm_cluster_ws_bytes", "pm_validate_clusters", "pm_build_cluster_map", "pm_pool", "pm_pool_bwd", "pm_unpool",
@@ -87,6 +87,7 @@ def lib():
             "pm_f2v": [mp, ap, i32, i32, i32, i32, i32, vp, vp, vp, vp, sz, vp],
             "pm_f2v_bwd": [mp, ap, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, sz, vp],
             "pm_v2f": [mp, i32, i32, i32, i32, i32, vp, vp, vp, vp, sz, vp],
+            "pm_v2f_noalloc": [mp, i32, i32, i32, i32, i32, vp, vp, vp, vp],
             "pm_v2f_bwd": [mp, ap, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, sz, vp],
             "pm_f2f": [i64, i64, vp, vp, i32, i32, i32, i32, i32, vp, vp, vp, vp, sz, vp],
             "pm_f2f_bwd": [i64, i64, vp, vp, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, sz, vp],
@@ -299,6 +300,15 @@ def pm_v2f(mesh: Mesh, L: int, h_vert, W, dtype: int, norm: int = PM_SH_PAPER, o
     m = mesh.c()
     _check(lib().pm_v2f(C.byref(m), L, norm, cin, cout, dtype, _ptr(h_vert), _ptr(W), C.c_void_p(out.data_ptr()),
                         _ptr(ws), ws.numel(), _stream(stream)))
+    return out
+
+
+def pm_v2f_noalloc(mesh: Mesh, L: int, h_vert, W, dtype: int, out, norm: int = PM_SH_PAPER, stream=None):
+    """pm_v2f without a workspace: the library's static scratch array holds the coefficient image; `out` is the caller's."""
+    K, cin, cout = W.shape
+    m = mesh.c()
+    _check(lib().pm_v2f_noalloc(C.byref(m), L, norm, cin, cout, dtype, _ptr(h_vert), _ptr(W), C.c_void_p(out.data_ptr()),
+                                _stream(stream)))
     return out
 
 

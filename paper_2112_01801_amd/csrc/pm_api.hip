@@ -426,6 +426,43 @@ extern "C" pm_status pm_v2f(const pm_mesh* mesh, int L, pm_sh_norm norm, int cin
                              dtype == PM_BF16, st);
 }
 
+// ---- vertex2facet forward without any allocation by caller or library ---------------------------------
+// The folded coefficient image that pm_v2f keeps in the caller's workspace lives here in a file-scope device array.
+// In host code the array's name is only a handle for hipGetSymbolAddress: the device address is looked up once per
+// device (every GPU holds its own copy of the array at its own address) and that pointer is what kernels get.
+static __device__ __align__(256) unsigned char scratch[PM_V2F_NOALLOC_SCRATCH_BYTES];
+
+static pm_status noalloc_scratch(void** out) {
+  static std::mutex mu;
+  static std::map<int, void*> addr;   // device -> address of its copy of `scratch`
+  int dev = 0;
+  PM_CHECK_HIP(hipGetDevice(&dev));
+  std::lock_guard<std::mutex> lock(mu);
+  auto it = addr.find(dev);
+  if (it == addr.end()) {
+    void* p = nullptr;
+    PM_CHECK_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (!p || !pm_aligned16(p)) return pm_fail(PM_ERR_HIP, "no device address for the static scratch array");
+    it = addr.emplace(dev, p).first;
+  }
+  *out = it->second;
+  return PM_OK;
+}
+
+extern "C" pm_status pm_v2f_noalloc(const pm_mesh* mesh, int L, pm_sh_norm norm, int cin, int cout, pm_dtype dtype,
+                                    const void* h_vert, const void* W, void* g_facet, void* stream) {
+  PM_TRY(check_conv_common(L, norm, cin, cout, dtype));
+  PM_TRY(check_mesh(mesh, false));
+  const size_t need = plan_ws(PM_OP_V2F, mesh->n_vert, mesh->n_facet, 0, L, cin, cout, dtype).total;
+  if (need > (size_t)PM_V2F_NOALLOC_SCRATCH_BYTES)
+    return pm_fail(PM_ERR_WORKSPACE, "pm_v2f_noalloc: cin=%d cout=%d need %zu bytes of scratch, the static array has %zu; "
+                   "use pm_v2f with a workspace", cin, cout, need, (size_t)PM_V2F_NOALLOC_SCRATCH_BYTES);
+  void* ptr = nullptr;
+  PM_TRY(noalloc_scratch(&ptr));
+  // the image is rebuilt from W by every call before it is read (stream order), nothing has to start at zero
+  return pm_v2f(mesh, L, norm, cin, cout, dtype, h_vert, W, g_facet, ptr, PM_V2F_NOALLOC_SCRATCH_BYTES, stream);
+}
+
 extern "C" pm_status pm_v2f_bwd(const pm_mesh* mesh, const pm_vf_adj* adj, int L, pm_sh_norm norm, int cin, int cout,
                                 pm_dtype dtype, const void* h_vert, const void* W, const void* dg_facet, void* dh_vert,
                                 float* dW, void* ws, size_t ws_bytes, void* stream) {

@@ -28,10 +28,20 @@ def r16(x):
     return round_to_bf16(np.asarray(x, np.float32)).astype(np.float64)
 
 
-def v2v_forward_bf16(vert, facet, L, h, alpha1, P1, ep1, alpha2, P2, ep2, norm=0):
+def v2v_paths(cin, cmid, cout):
+    """(facet stage fused, point-wise stage fused) for a bf16 call, as the entry point's documentation states: the fused
+    kernels take 32 or 64 input channels and 32..128 output channels in steps of 32; other shapes run the separable
+    entry points with element-wise epilogues, which store the pre-activations too."""
+    ok = lambda ci, co: ci in (32, 64) and co % 32 == 0 and 32 <= co <= 128
+    facet = ok(cin, cmid)
+    return facet, facet and ok(cmid, cout)
+
+
+def v2v_forward_bf16(vert, facet, L, h, alpha1, P1, ep1, alpha2, P2, ep2, norm=0, paths=(True, True)):
     """(o, g, z) of the separable vertex2vertex block with the bf16 stores of the data path:
     the three folded corner matrices diag(s1_j) P1 (matrix-core operand), the saved activations g, the filtered
-    facet rows g * s2(n_f), the vertex means z, the output."""
+    facet rows g * s2(n_f), the vertex means z, the output; on the unfused paths also the pre-activations, and the
+    depth-wise stage then reads the stored (rounded) g."""
     facet = np.asarray(facet, np.int64).reshape(-1, 3)
     h = np.asarray(h, np.float64)
     alpha1, P1 = np.asarray(alpha1, np.float64), np.asarray(P1, np.float64)
@@ -42,7 +52,11 @@ def v2v_forward_bf16(vert, facet, L, h, alpha1, P1, ep1, alpha2, P2, ep2, norm=0
     for j in range(3):
         u += h[facet[:, j]] @ r16(s1[j][:, None] * P1)
     a1, b1, r1 = ov._ep(ep1, P1.shape[1])
+    if not paths[0]:
+        u = r16(u)
     g = ov._act(a1 * u + b1, r1)
+    if not paths[0]:
+        g = r16(g)
     Bn = sh_basis(facet_normals(vert, facet), L, norm) if F else np.zeros((0, K))
     y = r16(g * (Bn @ alpha2))
     deg = np.bincount(facet.reshape(-1), minlength=V).astype(np.float64)
@@ -51,7 +65,10 @@ def v2v_forward_bf16(vert, facet, L, h, alpha1, P1, ep1, alpha2, P2, ep2, norm=0
         np.add.at(z, facet[:, j], y)
     z = r16(z / np.maximum(deg, 1.0)[:, None])
     a2, b2, r2 = ov._ep(ep2, P2.shape[1])
-    o = r16(ov._act(a2 * (z @ P2) + b2, r2))
+    q = z @ P2
+    if not paths[1]:
+        q = r16(q)
+    o = r16(ov._act(a2 * q + b2, r2))
     return o, r16(g), z
 
 

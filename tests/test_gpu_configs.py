@@ -62,7 +62,8 @@ def check_f2v(pm, b, L, cin, cout, dtype, seed, full, ns=NS):
     assert rel_err(to_host(dh[rf]), rdh) < TOL[dtype]
     gp = pm.pm_f2v(mesh, adj, L, h_d, to_dev(Wp, dtype), dt)
     assert rel_err(to_host(gp[rv]), oracle.f2v(b.vert, b.facet, L, h, Wp, rows=rv)) < TOL[dtype]
-    _adjoint_ok(Wp, dW, gp, dg_d, dtype)
+    _adjoint_ok(lambda w: pm.pm_f2v(mesh, adj, L, h_d, w, dt), lambda: make_coeffs(rng, K, cin, cout, dtype), (Wp, gp), dW,
+                dg_d, dtype)
     wr = _wrows(rng, K, cin)
     assert rel_err(to_host(dW).reshape(K * cin, cout)[wr], oracle.f2v_dW_rows(b.vert, b.facet, L, h, dg, wr)) < TOL[dtype]
 
@@ -89,7 +90,8 @@ def check_v2f(pm, b, L, cin, cout, dtype, seed, full, ns=NS):
     assert rel_err(to_host(dh[rv]), rdh) < TOL[dtype]
     gp = pm.pm_v2f(mesh, L, h_d, to_dev(Wp, dtype), dt)
     assert rel_err(to_host(gp[rf]), oracle.v2f(b.n_vert, b.facet, L, h, Wp, rows=rf)) < TOL[dtype]
-    _adjoint_ok(Wp, dW, gp, dg_d, dtype)
+    _adjoint_ok(lambda w: pm.pm_v2f(mesh, L, h_d, w, dt), lambda: make_coeffs(rng, K, cin, cout, dtype), (Wp, gp), dW, dg_d,
+                dtype)
     wr = _wrows(rng, K, cin)
     assert rel_err(to_host(dW).reshape(K * cin, cout)[wr], oracle.v2f_dW_rows(b.n_vert, b.facet, L, h, dg, wr)) < TOL[dtype]
 
@@ -118,7 +120,8 @@ def check_f2f(pm, b, L, cin, cout, dtype, seed, full, ns=NS):
     assert rel_err(to_host(dh[rp]), rdh) < TOL[dtype]
     gp = pm.pm_f2f(t_off, t_bary, L, h_d, to_dev(Wp, dtype), dt)
     assert rel_err(to_host(gp[rf]), oracle.f2f(tex_off, bary, L, h, Wp, rows=rf)) < TOL[dtype]
-    _adjoint_ok(Wp, dW, gp, dg_d, dtype)
+    _adjoint_ok(lambda w: pm.pm_f2f(t_off, t_bary, L, h_d, w, dt), lambda: make_coeffs(rng, K, cin, cout, dtype), (Wp, gp),
+                dW, dg_d, dtype)
     wr = _wrows(rng, K, cin)
     assert rel_err(to_host(dW).reshape(K * cin, cout)[wr], oracle.f2f_dW_rows(tex_off, bary, L, h, dg, wr)) < TOL[dtype]
 

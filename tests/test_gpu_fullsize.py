@@ -68,7 +68,9 @@ def test_config3_f2v_backward_sampled_and_adjoint(pm, c3):
     # adjoint identity with a fresh random W'
     Wp = mg.round_to_bf16(mg.glorot_coeffs(np.random.default_rng(7), cfg.K, cfg.cin, cfg.cout))
     gp = pm.pm_f2v(c3["mesh"], c3["adj"], cfg.L, h_d, to_dev(Wp, "bf16"), pm.PM_BF16)
-    adjoint_ok(Wp, dW, gp, dg_d, "bf16")
+    r7 = np.random.default_rng(70)
+    adjoint_ok(lambda w: pm.pm_f2v(c3["mesh"], c3["adj"], cfg.L, h_d, w, pm.PM_BF16),
+               lambda: mg.round_to_bf16(mg.glorot_coeffs(r7, cfg.K, cfg.cin, cfg.cout)), (Wp, gp), dW, dg_d, "bf16")
     # rows dW[k, ci, :] summed by the oracle over all 2,093,058 facets, element by element
     wr = sample_wrows(np.random.default_rng(8), cfg.K, cfg.cin)
     ref = oracle.f2v_dW_rows(b.vert, b.facet, cfg.L, c3["h"], c3["dg"], wr)

@@ -110,13 +110,13 @@ def test_vertices_of_a_coarse_mesh_level_sampled(pm):
     # operand of the point-wise matrix) differ in scale by sqrt(30), and half a bf16 unit of the large rows, measured
     # against the global rms, exceeds 2e-2 in ANY bf16 data path: rounding_model (the oracle with y and the output
     # rounded to bf16; tests/test_rounding_bounds.py pins it at 4.5e-2 on this very input) gives the bound.  The
-    # result is held to that bound, to 1e-2 from the model itself, to the stated 2e-2 on the rows the scale argument
+    # result is held to that bound, to two bf16 units from the model itself, to the stated 2e-2 on the rows the scale argument
     # does not touch (own rms within twice the global one), and to 2e-2 of its own rms on every row.
     got = to_host(g)
     model = rm.pcloud_forward_bf16(xs, xs, ptr, idx, rho, L, h, alpha, c0, P)
     e, em, d = rel_err(got, ref), rel_err(model, ref), rel_err(got, model)
     print("pcloud forward: err %.2e  model %.2e  from model %.2e" % (e, em, d))
-    assert e < rm.derived_bound(TOL[dtype], em) and d < 1e-2
+    assert e < rm.derived_bound(TOL[dtype], em) and d < 2.0 ** -6     # two bf16 units from the model
     row_rms, rms = np.sqrt(np.mean(ref ** 2, axis=1)), np.sqrt(np.mean(ref ** 2))
     plain = row_rms <= 2.0 * rms
     assert plain.mean() > 0.9

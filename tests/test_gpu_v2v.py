@@ -9,7 +9,7 @@ different (equally valid) subgradient, not an error.  The forward test checks th
 Tolerance: fp32 is held to the stated 1e-4 throughout.  In bf16 the block chains several bf16 stores (two
 convolutions in sequence), so each tensor is held (a) to max(2e-2, 1.25 x the error of rounding_model) against the
 oracle -- rounding_model is the oracle with exactly the stored tensors rounded to bf16, tests/test_rounding_bounds.py
-pins it and the bound it gives -- and (b) to 1e-2 from that model itself.  The facet features g, the output of the
+pins it and the bound it gives -- and (b) to two bf16 units from that model itself.  The facet features g, the output of the
 first convolution alone, keep the stated 2e-2, and so does the second convolution alone: the block's output against
 the oracle's second stage applied to the g the library saved.
 """
@@ -25,7 +25,8 @@ from test_gpu_parity import small_batch
 
 pytestmark = pytest.mark.gpu
 
-NEAR_MODEL = 1e-2      # distance of a bf16 result from the oracle-side model of its stores
+NEAR_MODEL = 2.0 ** -6   # distance of a bf16 result from the oracle-side model of its stores: two bf16 units (a tie that
+                         # fp32 accumulation order rounds the other way, on the element and on one it was computed from)
 
 
 def _held(got, ref, model, dtype, name=""):
@@ -110,7 +111,8 @@ def test_v2v_forward(pm, L, cin, cmid, cout, dtype, mode):
     import torch
     b, rng, (a1, P1, ep1, a2, P2, ep2), h, mesh, adj, d = _setup(pm, L, cin, cmid, cout, dtype, mode, 31)
     ro, rg, rz = v2v.v2v_sep(b.vert, b.facet, L, h, a1, P1, ep1, a2, P2, ep2, parts=True)
-    mo, mgg, mz = rm.v2v_forward_bf16(b.vert, b.facet, L, h, a1, P1, ep1, a2, P2, ep2) if dtype == "bf16" else (None,) * 3
+    mo, mgg, mz = (rm.v2v_forward_bf16(b.vert, b.facet, L, h, a1, P1, ep1, a2, P2, ep2, paths=rm.v2v_paths(cin, cmid, cout))
+                   if dtype == "bf16" else (None,) * 3)
     o = pm.pm_v2v_sep(mesh, adj, L, d["h"], d["a1"], d["P1"], d["ep1"], d["a2"], d["P2"], d["ep2"], pm_dtype(dtype))
     _held(to_host(o), ro, mo, dtype, "o")
     o2, g, z = pm.pm_v2v_sep(mesh, adj, L, d["h"], d["a1"], d["P1"], d["ep1"], d["a2"], d["P2"], d["ep2"], pm_dtype(dtype),

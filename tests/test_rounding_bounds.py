@@ -62,7 +62,7 @@ def test_v2v_block_bound_from_its_bf16_stores(L, cin, cmid, cout, dtype, mode):
     3.7e-2 on these shapes, i.e. a correct data path can exceed the single-convolution bar of 2e-2."""
     b, rng, prm, h = _v2v_inputs(31, L, cin, cmid, cout, mode)
     ro, rg, rz = v2v.v2v_sep(b.vert, b.facet, L, h, *prm, parts=True)
-    mo, mgg, mz = rm.v2v_forward_bf16(b.vert, b.facet, L, h, *prm)
+    mo, mgg, mz = rm.v2v_forward_bf16(b.vert, b.facet, L, h, *prm, paths=rm.v2v_paths(cin, cmid, cout))
     e = [rel_err(mo, ro), rel_err(mgg, rg), rel_err(mz, rz)]
     assert 2e-3 < e[0] < 2.5e-2 and 2e-3 < e[2] < 2.5e-2, e
     assert e[1] < 1.5e-2, e                                # the first convolution alone stays under the stated bar
