@@ -230,8 +230,9 @@ struct SegP {
 
 // SRC_BF16: the rows being reduced are bf16 (8 channels = 16 bytes per lane) instead of fp32 (4 channels).
 // DIV: compile-time divisor of the column entries (1, 3) or 0 for the run-time value.
-// The entries of a segment are taken NB at a time: first the column entries, then the rows they name (all
-// in flight together), then the additions, strictly in ascending entry order.
+// The entries of a segment are taken NB at a time: first the column entries (one cooperative load of the segment's
+// lane group where it has at least NB lanes), then the rows they name (all in flight together), then the additions,
+// strictly in ascending entry order.
 template <bool SRC_BF16, int DIV, int NB>
 __global__ void __launch_bounds__(256) k_segreduce(SegP p) {
   constexpr int CPL = SRC_BF16 ? 8 : 4;
@@ -241,6 +242,9 @@ __global__ void __launch_bounds__(256) k_segreduce(SegP p) {
   const int32_t b = p.row_ptr[seg], e = p.row_ptr[seg + 1];
   const float scale = (p.mean && e > b) ? 1.0f / (float)(e - b) : 1.0f;
   const bool vec = (p.C % CPL) == 0 && pm_aligned16_dev(p.src);
+  // enough lanes per segment to fetch a batch of column entries in one load, and every lane of the group takes the
+  // same trips through the channel loop (a lane that has left the loop cannot hand its entry on)
+  const bool coop = p.lpg >= NB && (p.C % (p.lpg * CPL)) == 0;
   auto row_of = [&](int32_t i) -> int64_t {
     if (!p.col) return (int64_t)i;
     const int32_t c = p.col[i];
@@ -255,8 +259,16 @@ __global__ void __launch_bounds__(256) k_segreduce(SegP p) {
     if (vec) {
       for (int32_t i0 = b; i0 < e; i0 += NB) {
         int64_t r[NB];
+        if (coop) {
+          // the lanes of the group fetch the batch's column entries together (one coalesced load), then hand them
+          // round: every row address of the batch is known after ONE memory latency
+          const int64_t mine = row_of(min(i0 + (sub & (NB - 1)), e - 1));
 #pragma unroll
-        for (int j = 0; j < NB; ++j) r[j] = row_of(min(i0 + j, e - 1));   // clamped: loads are unconditional
+          for (int j = 0; j < NB; ++j) r[j] = __shfl((int)mine, (threadIdx.x & 63 & ~(p.lpg - 1)) + j, 64);
+        } else {
+#pragma unroll
+          for (int j = 0; j < NB; ++j) r[j] = row_of(min(i0 + j, e - 1));   // clamped: loads are unconditional
+        }
         uint4 u[NB];
 #pragma unroll
         for (int j = 0; j < NB; ++j) {
@@ -317,10 +329,12 @@ __global__ void __launch_bounds__(256) k_segreduce(SegP p) {
 
 template <bool SRC_BF16>
 static void launch_segreduce_div(const SegP& p, dim3 grid, hipStream_t st) {
-  // two entries per batch measured best on MI355X (deeper batches lose more to cache pressure than they gain)
-  if (p.div == 1) hipLaunchKernelGGL((k_segreduce<SRC_BF16, 1, 2>), grid, dim3(256), 0, st, p);
-  else if (p.div == 3) hipLaunchKernelGGL((k_segreduce<SRC_BF16, 3, 2>), grid, dim3(256), 0, st, p);
-  else hipLaunchKernelGGL((k_segreduce<SRC_BF16, 0, 2>), grid, dim3(256), 0, st, p);
+  // four entries per batch, their column entries fetched by the lanes of the group in one load: with each lane
+  // fetching its own entries (two per batch measured best then) every batch cost two memory latencies in sequence;
+  // measured on MI355X at config 3: 0.118 -> 0.107 ms
+  if (p.div == 1) hipLaunchKernelGGL((k_segreduce<SRC_BF16, 1, 4>), grid, dim3(256), 0, st, p);
+  else if (p.div == 3) hipLaunchKernelGGL((k_segreduce<SRC_BF16, 3, 4>), grid, dim3(256), 0, st, p);
+  else hipLaunchKernelGGL((k_segreduce<SRC_BF16, 0, 4>), grid, dim3(256), 0, st, p);
 }
 
 pm_status pm_launch_segreduce(int64_t n_seg, int C, const void* src, int src_is_bf16, const int32_t* row_ptr,
@@ -346,11 +360,12 @@ pm_status pm_launch_segreduce(int64_t n_seg, int C, const void* src, int src_is_
 }
 
 // Corner-slot sums at the vertices (backward of Eq. 6 before the matrix): one lane group per vertex, lanes
-// span channels; an adjacency entry 3f+j adds row f to slot j.  Entries are taken two at a time (both rows
-// in flight), added in ascending order; the slot is chosen by selects, so the code has no divergent branch.
+// span channels; an adjacency entry 3f+j adds row f to slot j.  Entries are taken four at a time (their rows
+// in flight together), added in ascending order; the slot is chosen by selects, so the code has no divergent branch.
 template <bool SRC_BF16>
 __global__ void __launch_bounds__(256) k_segsum_slots(SegP p) {
   constexpr int CPL = SRC_BF16 ? 8 : 4;
+  constexpr int NB = 4;   // entries per batch (all their rows in flight together)
   const int gpb = 256 / p.lpg;
   const int sub = threadIdx.x % p.lpg;
   const bool vec = (p.C % CPL) == 0 && pm_aligned16_dev(p.src) && pm_aligned16_dev(p.out);
@@ -362,13 +377,19 @@ __global__ void __launch_bounds__(256) k_segsum_slots(SegP p) {
       for (int j = 0; j < 3; ++j)
 #pragma unroll
         for (int i = 0; i < CPL; ++i) a[j][i] = 0.f;
-      for (int32_t i0 = b; i0 < e; i0 += 2) {
-        int32_t cidx[2];
-        float x[2][CPL];
+      for (int32_t i0 = b; i0 < e; i0 += NB) {
+        int32_t cidx[NB];
+        float x[NB][CPL];
+        if (p.lpg >= NB && (p.C % (p.lpg * CPL)) == 0) {   // the group's lanes (all in this loop) fetch the batch's entries in one load
+          const int32_t mine = p.col[min(i0 + (sub & (NB - 1)), e - 1)];
 #pragma unroll
-        for (int q = 0; q < 2; ++q) cidx[q] = p.col[min(i0 + q, e - 1)];
+          for (int q = 0; q < NB; ++q) cidx[q] = __shfl(mine, (threadIdx.x & 63 & ~(p.lpg - 1)) + q, 64);
+        } else {
 #pragma unroll
-        for (int q = 0; q < 2; ++q) {
+          for (int q = 0; q < NB; ++q) cidx[q] = p.col[min(i0 + q, e - 1)];
+        }
+#pragma unroll
+        for (int q = 0; q < NB; ++q) {
           const int64_t r = (int64_t)(((uint64_t)(uint32_t)cidx[q] * 0xAAAAAAABull) >> 33);   // / 3
           const int64_t o = r * p.C + c0;
           if (vec) {
@@ -389,7 +410,7 @@ __global__ void __launch_bounds__(256) k_segsum_slots(SegP p) {
           }
         }
 #pragma unroll
-        for (int q = 0; q < 2; ++q) {
+        for (int q = 0; q < NB; ++q) {
           const int slot = (i0 + q < e) ? cidx[q] - 3 * (int32_t)(((uint64_t)(uint32_t)cidx[q] * 0xAAAAAAABull) >> 33) : 3;
           // one 0/1 weight per slot and a multiply-add per element (a + 1 x and a + 0 x are exact: the sums are the
           // plain ascending-order sums of each slot); cheaper than a select and an add per element
