@@ -436,11 +436,16 @@ __global__ void __launch_bounds__(NW * 64) k_conv_rows(ConvP p) {
     } else {
       // Weights streamed through a two-slot LDS ring, one barrier per stage: loop order
       // n-block pair -> c-chunk -> k -> n-block, so that every stage is fetched once per tile.
+      // blockIdx.y splits the groups of output blocks (few row tiles, many output channels: more workgroups than
+      // tiles, each streaming its share of the weights)
+      const int nbg_lo = (int)((int64_t)blockIdx.y * NBG / gridDim.y), nbg_hi = (int)((int64_t)(blockIdx.y + 1) * NBG / gridDim.y);
+      const int64_t S_hi = (int64_t)nbg_hi * NCH * K;
+      int64_t q = (int64_t)nbg_lo * NCH * K;  // stage sequence number
+      __syncthreads();                        // the ring is free (previous tile)
 #pragma unroll
-      for (int i = 0; i < PER_T; ++i) lds[i * NT + tid] = p.apack[i * NT + tid];
+      for (int i = 0; i < PER_T; ++i) lds[(q & 1) * STAGE_U4 + i * NT + tid] = p.apack[q * STAGE_U4 + i * NT + tid];
       __syncthreads();
-      int64_t q = 0;  // stage sequence number inside this tile
-      for (int nbg = 0; nbg < NBG; ++nbg) {
+      for (int nbg = nbg_lo; nbg < nbg_hi; ++nbg) {
         floatx16 y[PM_NBS][2];
 #pragma unroll
         for (int a = 0; a < PM_NBS; ++a)
@@ -458,7 +463,7 @@ __global__ void __launch_bounds__(NW * 64) k_conv_rows(ConvP p) {
             asm volatile("" ::: "memory");
             const uint4* stage = lds + (q & 1) * STAGE_U4;
             uint4 pre[PER_T];
-            if (q + 1 < S) {
+            if (q + 1 < S_hi) {
 #pragma unroll
               for (int i = 0; i < PER_T; ++i) pre[i] = p.apack[(q + 1) * STAGE_U4 + i * NT + tid];
             }
@@ -480,7 +485,7 @@ __global__ void __launch_bounds__(NW * 64) k_conv_rows(ConvP p) {
                 pb0 = B[0][k]; pb1 = B[1][k];
               }
             }
-            if (q + 1 < S) {
+            if (q + 1 < S_hi) {
 #pragma unroll
               for (int i = 0; i < PER_T; ++i) lds[((q + 1) & 1) * STAGE_U4 + i * NT + tid] = pre[i];
             }
@@ -513,8 +518,15 @@ static pm_status launch_conv_fast(const ConvP& p, int64_t S, hipStream_t st) {
   const int NT = NW * 64;
   int64_t n_tiles = (p.R + NT - 1) / NT;
   int64_t grid = n_tiles < 256 ? (n_tiles + 7) / 8 * 8 : 256;
+  // streamed weights on a mesh with fewer row tiles than compute units: split the output-block groups over
+  // workgroups as well (each streams its share of the weights; the rows are fetched once per share)
+  int split = 1;
+  if (!RES) {
+    while (split * 2 <= p.NBG && grid * split * 2 <= 256) split *= 2;
+    if (split > p.NBG) split = p.NBG;
+  }
   { ProfScope ps__(st, "k_conv_rows");
-    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(NT), lds, st, p); }
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid, (unsigned)split), dim3(NT), lds, st, p); }
   PM_CHECK_LAUNCH("k_conv_rows");
   return PM_OK;
 }
