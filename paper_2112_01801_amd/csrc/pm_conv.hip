@@ -360,12 +360,12 @@ pm_status pm_launch_segreduce(int64_t n_seg, int C, const void* src, int src_is_
 }
 
 // Corner-slot sums at the vertices (backward of Eq. 6 before the matrix): one lane group per vertex, lanes
-// span channels; an adjacency entry 3f+j adds row f to slot j.  Entries are taken four at a time (their rows
-// in flight together), added in ascending order; the slot is chosen by selects, so the code has no divergent branch.
+// span channels; an adjacency entry 3f+j adds row f to slot j.  Entries are taken two at a time (both rows
+// in flight), added in ascending order; the slot is chosen by selects, so the code has no divergent branch.
 template <bool SRC_BF16>
 __global__ void __launch_bounds__(256) k_segsum_slots(SegP p) {
   constexpr int CPL = SRC_BF16 ? 8 : 4;
-  constexpr int NB = 4;   // entries per batch (all their rows in flight together)
+  constexpr int NB = 2;   // entries per batch (their rows in flight together; four measured slower here)
   const int gpb = 256 / p.lpg;
   const int sub = threadIdx.x % p.lpg;
   const bool vec = (p.C % CPL) == 0 && pm_aligned16_dev(p.src) && pm_aligned16_dev(p.out);
