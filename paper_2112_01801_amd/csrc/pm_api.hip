@@ -208,10 +208,23 @@ static WsPlan plan_ws(pm_op op, int64_t V, int64_t F, int64_t P, int L, int cin,
       w.wgrad = pm_wgrad_ws_bytes(F, 3, cin, cout);
       break;
     case PM_OP_F2F:
+      if (pm_f2f_small_applies(L, cin)) {   // few input channels: one staged 64-channel row per facet
+        w.apack = pm_pack_bytes(pm_pack_geom(1, dt == PM_BF16 ? 128 : K * cin, cout, dt));
+        w.inter = pm_round_up((size_t)F * 256, 256);   // 64 fp32 channels, or a bf16 head and remainder of 64 each
+        break;
+      }
       w.apack = pm_pack_bytes(pm_pack_geom(K, cin, cout, dt));
       w.inter = pm_round_up((size_t)P * cout * esize(dt), 256);   // per-point summands, feature dtype
       break;
     case PM_OP_F2F_BWD:
+      if (pm_f2f_small_applies(L, cin)) {
+        w.apack = pm_pack_bytes(pm_pack_geom(1, cout, K * cin, dt));
+        w.owner = pm_round_up((size_t)(P + 1) * 4, 256);
+        w.inter = pm_round_up((size_t)F * 256, 256);                  // staged rows S_f
+        w.small = pm_round_up((size_t)F * K * cin * 4, 256);           // T_f = W dg_f, fp32
+        w.wgrad = pm_wgrad_ws_bytes(F, 1, K * cin, cout);
+        break;
+      }
       w.apack = pm_pack_bytes(pm_pack_geom(K, cout, cin, dt));
       w.owner = pm_round_up((size_t)(P + 1) * 4, 256);
       w.inter = pm_round_up((size_t)P * K * 4, 256);   // basis rows for the weight gradient
@@ -1178,10 +1191,19 @@ extern "C" pm_status pm_f2f(int64_t n_facet, int64_t n_tex, const int32_t* tex_o
   char* apack = (char*)ws;
   void* yp = apack + w.apack;   // per-point summands of Eq. 7, in the feature dtype (summed in fp32)
   const int yb = dtype == PM_BF16;
-  PM_TRY(pm_launch_pack(PACK_PLAIN, dtype, K, cin, cout, W, nullptr, apack, st));
   BasisSrc bs = basis_none();
   bs.dirs = bary;
   pm_make_sh_table(L, norm, &bs.sh);
+  if (pm_f2f_small_applies(L, cin)) {
+    // few input channels (the paper's shape: 3 colours): mean of the Khatri-Rao rows B_p (x) h_p over the points of a
+    // facet first (K cin <= 64 values), then one contraction per facet with W viewed as [K cin][cout]
+    PM_TRY(pm_launch_f2f_gather(n_facet, tex_off, bary, bs.sh, cin, yb, h_tex, yp, st));
+    PM_TRY(pm_launch_pack(yb ? PACK_PLAIN_TWICE : PACK_PLAIN, dtype, 1, K * cin, cout, W, nullptr, apack, st));
+    const int sc = yb ? 128 : 64;      // bf16 rows: head and remainder
+    RowSrc ss = row_src(yp, dtype, sc);
+    return pm_launch_conv_rows(dtype, B_ONE, X_DIRECT, n_facet, 1, sc, cout, basis_none(), ss, apack, g_facet, yb, st);
+  }
+  PM_TRY(pm_launch_pack(PACK_PLAIN, dtype, K, cin, cout, W, nullptr, apack, st));
   RowSrc xs = row_src(h_tex, dtype, cin);
   PM_TRY(pm_launch_conv_rows(dtype, B_DIRS, X_DIRECT, n_tex, K, cin, cout, bs, xs, apack, yp, yb, st));
   return pm_launch_segreduce(n_facet, cout, yp, yb, tex_off, nullptr, 1, 1, g_facet, dtype == PM_BF16, st);
@@ -1210,6 +1232,26 @@ extern "C" pm_status pm_f2f_bwd(int64_t n_facet, int64_t n_tex, const int32_t* t
   BasisSrc bs = basis_none();
   bs.dirs = bary;
   pm_make_sh_table(L, norm, &bs.sh);
+  if (pm_f2f_small_applies(L, cin)) {
+    // few input channels: everything per facet except the basis weighting of the points (see pm_f2f)
+    const int fb = dtype == PM_BF16, kc = K * cin;
+    void* S = bvals;
+    float* T = (float*)((char*)S + w.inter);
+    void* wgs = (char*)T + w.small;
+    RowSrc dgr = row_src(dg_facet, dtype, cout);
+    if (dh_tex) {
+      PM_TRY(pm_launch_pack(PACK_TRANS, dtype, 1, kc, cout, W, nullptr, apack, st));
+      PM_TRY(pm_launch_conv_rows(dtype, B_ONE, X_DIRECT, n_facet, 1, cout, kc, basis_none(), dgr, apack, T, 0, st));
+      PM_TRY(pm_launch_f2f_scatter(n_tex, owner, tex_off, bary, bs.sh, cin, fb, T, dh_tex, st));
+    }
+    if (dW) {
+      PM_TRY(pm_launch_f2f_gather(n_facet, tex_off, bary, bs.sh, cin, fb, h_tex, S, st));
+      RowSrc sr = row_src(S, dtype, fb ? 128 : 64);     // bf16: the head alone (first 64 channels of the 128)
+      PM_TRY(pm_launch_wgrad(dtype, B_ONE, X_DIRECT, X_DIRECT, n_facet, 1, kc, cout, basis_none(), sr, dgr, dW, wgs, w.wgrad,
+                             nullptr, st));
+    }
+    return PM_OK;
+  }
   RowSrc dys = row_src(dg_facet, dtype, cout);   // gradient reaching point p: dg[owner(p)] / R_owner
   dys.owner = owner; dys.seg_off = tex_off;
   if (dh_tex) {

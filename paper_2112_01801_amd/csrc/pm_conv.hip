@@ -49,6 +49,7 @@ __device__ __forceinline__ void pack_values(const PackP& p, int k, int c0, int n
     ok[e] = c < p.Cc && n < p.Cn;
     j[e] = 0;
     if (MODE == PACK_PLAIN) { ci[e] = c; co[e] = n; }
+    else if (MODE == PACK_PLAIN_TWICE) { ci[e] = c & 63; co[e] = n; ok[e] = ok[e] && ci[e] < p.cin; }
     else if (MODE == PACK_TRANS) { ci[e] = n; co[e] = c; }
     else if (MODE == PACK_FOLD) { j[e] = c / p.cin; ci[e] = c - j[e] * p.cin; co[e] = n; }
     else if (MODE == PACK_FOLD_TRANS) { j[e] = n / p.cin; ci[e] = n - j[e] * p.cin; co[e] = c; }
@@ -57,7 +58,7 @@ __device__ __forceinline__ void pack_values(const PackP& p, int k, int c0, int n
     if (!ok[e]) { j[e] = 0; ci[e] = 0; co[e] = 0; }   // in-bounds dummy, the value is dropped
     v[e] = 0.f;
   }
-  if (MODE == PACK_PLAIN || MODE == PACK_TRANS) {
+  if (MODE == PACK_PLAIN || MODE == PACK_TRANS || MODE == PACK_PLAIN_TWICE) {
 #pragma unroll
     for (int e = 0; e < N; ++e) v[e] = ok[e] ? pack_src(p, k, ci[e], co[e]) : 0.f;
     return;
@@ -126,6 +127,7 @@ pm_status pm_launch_pack(PackMode mode, pm_dtype dt, int K, int cin, int cout, c
   p.K = K; p.cin = cin; p.cout = cout;
   switch (mode) {
     case PACK_PLAIN: p.Kp = K; p.Cc = cin; p.Cn = cout; break;
+    case PACK_PLAIN_TWICE: p.Kp = 1; p.Cc = 128; p.Cn = cout; break;
     case PACK_TRANS: p.Kp = K; p.Cc = cout; p.Cn = cin; break;
     case PACK_FOLD: case PACK_SEP_FOLD: p.Kp = 1; p.Cc = 3 * cin; p.Cn = cout; break;
     case PACK_FOLD_TRANS: p.Kp = 1; p.Cc = cout; p.Cn = 3 * cin; break;
@@ -141,6 +143,7 @@ pm_status pm_launch_pack(PackMode mode, pm_dtype dt, int K, int cin, int cout, c
     const dim3 ge((unsigned)((n_elem + 255) / 256));
     switch (mode) {
       case PACK_PLAIN: hipLaunchKernelGGL(k_pack_elem<PACK_PLAIN>, ge, dim3(256), 0, st, p, n_elem); break;
+      case PACK_PLAIN_TWICE: hipLaunchKernelGGL(k_pack_elem<PACK_PLAIN_TWICE>, ge, dim3(256), 0, st, p, n_elem); break;
       case PACK_TRANS: hipLaunchKernelGGL(k_pack_elem<PACK_TRANS>, ge, dim3(256), 0, st, p, n_elem); break;
       case PACK_FOLD: hipLaunchKernelGGL(k_pack_elem<PACK_FOLD>, ge, dim3(256), 0, st, p, n_elem); break;
       case PACK_FOLD_TRANS: hipLaunchKernelGGL(k_pack_elem<PACK_FOLD_TRANS>, ge, dim3(256), 0, st, p, n_elem); break;

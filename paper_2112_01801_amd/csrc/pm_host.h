@@ -75,12 +75,14 @@ static inline size_t pm_pack_bytes(const PackGeom& g) { return (size_t)g.stages 
 
 // ---- kernel launchers (each enqueues on `st`, returns PM_OK or PM_ERR_HIP) ----------------------
 enum PackMode { PACK_PLAIN = 0, PACK_TRANS = 1, PACK_FOLD = 2, PACK_FOLD_TRANS = 3, PACK_FOLD_BWD = 4,
-                PACK_SEP_FOLD = 5 };
+                PACK_SEP_FOLD = 5, PACK_PLAIN_TWICE = 6 };
 struct FoldCoef { float c[3][PM_MAX_K]; };
 // Builds the MFMA operand image of Wp[k][c][n] from W[K][cin][cout] (src dtype = dt):
 //   PLAIN: Wp[k][ci][co] = W[k][ci][co]          TRANS: Wp[k][co][ci] = W[k][ci][co]
 //   FOLD:  Wp[0][j*cin+ci][co] = sum_k fc[j][k] W[k][ci][co]    FOLD_TRANS: Wp[0][co][j*cin+ci] = same
 //   FOLD_BWD: Wp[0][j*cout+co][ci] = same   (backward-data of the folded form, contraction over (corner, co))
+//   PLAIN_TWICE: K = 1, Wp[0][c][co] = W[0][c mod 64][co] for c < 128 (zero where c mod 64 >= cin): the operand rows carry
+//   a bf16 head in channels 0..63 and the bf16 remainder in channels 64..127
 //   SEP_FOLD (separable vertex2facet): like FOLD with the folded matrices
 //   W_j[ci][co] = s_j[ci] P[ci][co],  s_j[ci] = sum_k fc[j][k] alpha[k][ci];  W is P [cin][cout], alpha [K][cin] fp32
 pm_status pm_launch_pack(PackMode mode, pm_dtype dt, int K, int cin, int cout, const void* W, const FoldCoef* fc,
@@ -164,6 +166,13 @@ pm_status pm_launch_slot_scale_sum(int64_t V, int K, int C, int is_bf16, const v
 // separable vertex2facet: dP, dalpha from the three corner matrices M [3][cin][cout]
 pm_status pm_launch_sep_unfold(int K, int cin, int cout, int p_bf16, const float* M, const float* alpha, const void* P,
                                const FoldCoef* fc, float* dalpha, float* dP, hipStream_t st);
+// facet2facet with few input channels (K cin <= 64): S[f][0..K cin) = mean over the points of f of B_k(d_p) h_p[ci], zero
+// up to 64 channels (feature dtype), and dh[p][ci] = 1/R_f sum_k B_k(d_p) T[owner p][k cin + ci] with T fp32 [F][K cin]
+bool pm_f2f_small_applies(int L, int cin);
+pm_status pm_launch_f2f_gather(int64_t n_facet, const int32_t* tex_off, const float* bary, const ShTable& sh, int cin,
+                               int is_bf16, const void* h, void* S, hipStream_t st);
+pm_status pm_launch_f2f_scatter(int64_t n_tex, const int32_t* owner, const int32_t* tex_off, const float* bary,
+                                const ShTable& sh, int cin, int is_bf16, const float* T, void* dh, hipStream_t st);
 // owner[p] = f for p in [tex_off[f], tex_off[f+1])
 pm_status pm_launch_owner(int64_t n_facet, const int32_t* tex_off, int32_t* owner, hipStream_t st);
 

@@ -224,21 +224,31 @@ def test_v2f_backward_single_gradients(pm, dtype, cin, cout):
     assert rel_err(to_host(dh2), rdh) < TOL[dtype] and rel_err(to_host(dW2), rdW) < TOL[dtype]
 
 
-def test_f2f_empty_facets_and_paper_shape(pm):
-    """Cin = 3 colour channels (the paper's own shape), some facets without texture points."""
+@pytest.mark.parametrize("dtype,L,cin,cout", [("f32", 3, 3, 32), ("bf16", 3, 3, 32), ("bf16", 3, 4, 64), ("f32", 1, 1, 8),
+                                              ("bf16", 2, 3, 96), ("f32", 3, 5, 32)])
+def test_f2f_empty_facets_and_paper_shape(pm, dtype, L, cin, cout):
+    """Few input channels (Cin = 3 colours is the paper's own shape; up to four take the per-facet staging, five the
+    per-point path), some facets without texture points, forward and backward."""
     import torch
     rng = np.random.default_rng(40)
-    res = rng.choice([0, 1, 3, 6, 10, 15], size=700)
+    res = rng.choice([0, 1, 3, 6, 10, 15], size=1700)
     tex_off = np.concatenate([[0], np.cumsum(res)]).astype(np.int32)
     bary = np.concatenate([mg.bary_lattice({0: 0, 1: 0, 3: 1, 6: 2, 10: 3, 15: 4}[r]) for r in res if r > 0], 0)
-    L, cin, cout = 3, 3, 32
-    W = make_coeffs(rng, 16, cin, cout, "f32")
-    h = make_features(rng, bary.shape[0], cin, "f32")
-    g = pm.pm_f2f(torch.from_numpy(tex_off).cuda(), torch.from_numpy(bary).cuda(), L, to_dev(h, "f32"),
-                  to_dev(W, "f32"), 0)
+    K = (L + 1) ** 2
+    W = make_coeffs(rng, K, cin, cout, dtype)
+    h = make_features(rng, bary.shape[0], cin, dtype)
+    dg = make_features(rng, res.shape[0], cout, dtype)
+    t_off, t_bary = torch.from_numpy(tex_off).cuda(), torch.from_numpy(bary).cuda()
+    g = pm.pm_f2f(t_off, t_bary, L, to_dev(h, dtype), to_dev(W, dtype), pm_dtype(dtype))
     ref = oracle.f2f(tex_off, bary, L, h, W)
-    assert rel_err(to_host(g), ref) < 1e-4
+    assert rel_err(to_host(g), ref) < TOL[dtype]
     assert np.all(to_host(g)[res == 0] == 0)
+    dh, dW = pm.pm_f2f_bwd(t_off, t_bary, L, to_dev(h, dtype), to_dev(W, dtype), to_dev(dg, dtype), pm_dtype(dtype))
+    rdh, rdW = oracle.f2f_bwd(tex_off, bary, L, h, W, dg)
+    assert rel_err(to_host(dh), rdh) < TOL[dtype] and rel_err(to_host(dW), rdW) < TOL[dtype]
+    dh1, none = pm.pm_f2f_bwd(t_off, t_bary, L, to_dev(h, dtype), to_dev(W, dtype), to_dev(dg, dtype), pm_dtype(dtype),
+                              want_dW=False)
+    assert none is None and torch.equal(dh1, dh)
 
 
 def test_fan_vertex_and_orthonormal_variant(pm):
