@@ -102,8 +102,11 @@ __device__ __forceinline__ uint4 fetch_granule_fast(const RowSrc& s, int64_t row
   return granule_finish<XM, DT>(raw, m);
 }
 
-template <int DT, int BM, int XM, int LT, int NW, bool RES, bool FAST>
+// FM: 0 = general operand fetch, 1 = branch-free fetch (whole chunks of channels), 2 = the same with a last chunk that is
+// only partly inside the row (granules at or beyond Cc are zero instead of loaded)
+template <int DT, int BM, int XM, int LT, int NW, bool RES, int FM>
 __global__ void __launch_bounds__(NW * 64) k_conv_rows(ConvP p) {
+  constexpr bool FAST = FM != 0;
   extern __shared__ uint4 lds[];
   constexpr int K = (BM == B_ONE) ? 1 : (LT + 1) * (LT + 1);
   constexpr int NT = NW * 64;
@@ -142,6 +145,16 @@ __global__ void __launch_bounds__(NW * 64) k_conv_rows(ConvP p) {
     const int64_t t_ = (int64_t)xcd * tpx + ti_;
     return min(t_ * NT + wave * 64 + fb * 32 + l32, p.R - 1);   // clamped: loads are unconditional
   };
+  auto gload = [&](int64_t rc, const RowMeta& m, int c0, uint4 (&raw)[NRaw<XM>::n]) {
+    if constexpr (FM == 2) {
+      if (c0 >= p.Cc) {
+#pragma unroll
+        for (int j = 0; j < NRaw<XM>::n; ++j) raw[j] = make_uint4(0, 0, 0, 0);
+        return;
+      }
+    }
+    granule_load<XM, DT>(p.xs, rc, m, c0, raw);
+  };
   auto issue_ids = [&](int64_t ti_, TileRaw& t) {
 #pragma unroll
     for (int fb = 0; fb < 2; ++fb) {
@@ -158,7 +171,7 @@ __global__ void __launch_bounds__(NW * 64) k_conv_rows(ConvP p) {
       load_meta_w<XM>(p.xs, true, t.meta[fb]);
       if constexpr (XPRE) {
 #pragma unroll
-        for (int g = 0; g < PM_GC; ++g) granule_load<XM, DT>(p.xs, rc, t.meta[fb], (g * 2 + hh) * EPG, t.xr[fb][g]);
+        for (int g = 0; g < PM_GC; ++g) gload(rc, t.meta[fb], (g * 2 + hh) * EPG, t.xr[fb][g]);
       }
     }
   };
@@ -191,7 +204,7 @@ __global__ void __launch_bounds__(NW * 64) k_conv_rows(ConvP p) {
         for (int fb = 0; fb < 2; ++fb)
 #pragma unroll
           for (int g = 0; g < PM_GC; ++g)
-            granule_load<XM, DT>(p.xs, rowc[fb], cur.meta[fb], (g * 2 + hh) * EPG, xnow[fb][g]);
+            gload(rowc[fb], cur.meta[fb], (g * 2 + hh) * EPG, xnow[fb][g]);
       }
       // arithmetic on this tile's data (loaded during the previous tile)
 #pragma unroll
@@ -240,7 +253,11 @@ __global__ void __launch_bounds__(NW * 64) k_conv_rows(ConvP p) {
           const int c0 = ((ch * PM_GC + g) * 2 + hh) * EPG;
           if constexpr (FAST) {
             if (ch == 0) X[fb][g] = X0[fb][g];
-            else X[fb][g] = fetch_granule_fast<XM, DT>(p.xs, rowc[fb], meta[fb], c0);
+            else {
+              uint4 raw[NRaw<XM>::n];
+              gload(rowc[fb], meta[fb], c0, raw);
+              X[fb][g] = granule_finish<XM, DT>(raw, meta[fb]);
+            }
           } else {
             float v[EPG];
             fetch_vals<XM, EPG>(p.xs, row[fb], ok[fb], meta[fb], c0, v);
@@ -510,9 +527,9 @@ __global__ void __launch_bounds__(NW * 64) k_conv_rows(ConvP p) {
   }
 }
 
-template <int DT, int BM, int XM, int LT, int NW, bool RES, bool FAST>
+template <int DT, int BM, int XM, int LT, int NW, bool RES, int FM>
 static pm_status launch_conv_fast(const ConvP& p, int64_t S, hipStream_t st) {
-  auto kern = k_conv_rows<DT, BM, XM, LT, NW, RES, FAST>;
+  auto kern = k_conv_rows<DT, BM, XM, LT, NW, RES, FM>;
   size_t lds = RES ? (size_t)S * PM_STAGE_BYTES : 2 * (size_t)PM_STAGE_BYTES;
   PM_TRY(pm_set_dyn_lds((const void*)kern, lds));
   const int NT = NW * 64;
@@ -536,10 +553,13 @@ template <int DT, int BM, int XM, int LT, int NW, bool RES>
 static pm_status launch_conv_res(const ConvP& p, int64_t S, hipStream_t st) {
   const int esz = (DT == 1) ? 2 : 4;
   const int chunk = PM_GC * ((DT == 1) ? 16 : 8);
-  bool fast = (p.xs.is_bf16 == (DT == 1)) && pm_aligned16(p.xs.p) && ((p.xs.C * esz) % 16 == 0) &&
-              (p.Cc % chunk == 0);
-  if (fast) return launch_conv_fast<DT, BM, XM, LT, NW, RES, true>(p, S, st);
-  return launch_conv_fast<DT, BM, XM, LT, NW, RES, false>(p, S, st);
+  const int pair = chunk / PM_GC;   // channels of one granule pair (the two half-waves): 16 bf16, 8 fp32
+  const bool fast = (p.xs.is_bf16 == (DT == 1)) && pm_aligned16(p.xs.p) && ((p.xs.C * esz) % 16 == 0);
+  if (fast && p.Cc % chunk == 0) return launch_conv_fast<DT, BM, XM, LT, NW, RES, 1>(p, S, st);
+  // a partly filled last chunk (32 channels of bf16, say): whole granule pairs inside the operand row
+  if (fast && p.Cc % pair == 0 && (XM == X_DIRECT || XM == X_GATHER_SUM || XM == X_GATHER1))
+    return launch_conv_fast<DT, BM, XM, LT, NW, RES, 2>(p, S, st);
+  return launch_conv_fast<DT, BM, XM, LT, NW, RES, 0>(p, S, st);
 }
 
 template <int DT, int BM, int XM, int LT, int NW>

@@ -59,7 +59,7 @@ struct PcSet {
 // Y0 and (HASB) the basis values of each 64-row block.  Block b of the workgroup's row range lives in
 // register set b&1 and in LDS buffer (b/2)&1, slot b&1; its loads are issued one tile before it is
 // written to LDS, its ids one tile before that.
-template <int BM, int YM, int LT, bool HASB, int NY, int Y0, int NX, int X0>
+template <int BM, int YM, int LT, int CBN, int NBN, bool HASB, int NY, int Y0, int NX, int X0>
 __device__ __forceinline__ void pc_producer(const WgradP& p, char* lds, const int lane, const int64_t rbeg,
                                             const int64_t rend, const int n_tiles, const int cbase, const int nbase,
                                             const int kbase) {
@@ -84,18 +84,26 @@ __device__ __forceinline__ void pc_producer(const WgradP& p, char* lds, const in
     if constexpr (HASB) dir_ids<BM>(p.bs, r, d.g);
   };
 
+  // a slab narrower than 64 channels (Cc or Cn = 32, CBN or NBN = 1): the octets beyond it are neither loaded nor
+  // written back; their LDS rows are zero
+  auto x_in = [&](int i) { return (X0 + i) * 8 < 32 * CBN; };     // compile-time after unrolling
+  auto y_in = [&](int i) { return (Y0 + i) * 8 < 32 * NBN; };
   auto issue = [&](int b, const PcIds& d, Set& s) {
     const int64_t r = rowc(b);
 #pragma unroll
-    for (int i = 0; i < NX; ++i)
-      s.x[i] = *(const uint4*)((const uint16_t*)p.xs.p + r * (int64_t)p.xs.C + cbase + (X0 + i) * 8);
+    for (int i = 0; i < NX; ++i) {
+      s.x[i] = make_uint4(0, 0, 0, 0);
+      if (x_in(i)) s.x[i] = *(const uint4*)((const uint16_t*)p.xs.p + r * (int64_t)p.xs.C + cbase + (X0 + i) * 8);
+    }
     if constexpr (NY > 0) {
 #pragma unroll
       for (int j = 0; j < NYS; ++j) {
         const int64_t src = (YM == X_DIRECT) ? r : (int64_t)d.y[j];
 #pragma unroll
-        for (int i = 0; i < NY; ++i)
-          s.y[i][j] = *(const uint4*)((const uint16_t*)p.ys.p + src * (int64_t)p.ys.C + nbase + (Y0 + i) * 8);
+        for (int i = 0; i < NY; ++i) {
+          s.y[i][j] = make_uint4(0, 0, 0, 0);
+          if (y_in(i)) s.y[i][j] = *(const uint4*)((const uint16_t*)p.ys.p + src * (int64_t)p.ys.C + nbase + (Y0 + i) * 8);
+        }
       }
       if constexpr (YM == X_GATHER_SUM) {
 #pragma unroll
@@ -148,7 +156,7 @@ __device__ __forceinline__ void pc_producer(const WgradP& p, char* lds, const in
         }
 #pragma unroll
         for (int e = 0; e < 8; ++e) YT[((Y0 + i) * 8 + e) * XP_F32 + lane] = v[e];
-        if (emit_y && ok) {
+        if (emit_y && ok && y_in(i)) {
           uint4 w;
           w.x = pack_bf16x2(v[0], v[1]); w.y = pack_bf16x2(v[2], v[3]);
           w.z = pack_bf16x2(v[4], v[5]); w.w = pack_bf16x2(v[6], v[7]);
@@ -200,7 +208,8 @@ __device__ __forceinline__ void pc_producer(const WgradP& p, char* lds, const in
   }
 }
 
-template <int BM, int YM, int LT>
+// CBN, NBN: 32-wide blocks of X and of Y channels in a slab (2 = the full 64, 1 = a 32-channel operand)
+template <int BM, int YM, int LT, int CBN, int NBN>
 __global__ void __launch_bounds__(PC_THREADS) k_wgrad_pc(WgradP p) {
   extern __shared__ uint4 lds_raw[];
   char* lds = (char*)lds_raw;
@@ -219,10 +228,10 @@ __global__ void __launch_bounds__(PC_THREADS) k_wgrad_pc(WgradP p) {
   if (wave >= PC_CONS) {
     // octets of Y cost ~50 vector instructions per row, the basis ~100, octets of X almost nothing
     switch (wave - PC_CONS) {
-      case 0: pc_producer<BM, YM, LT, true, 1, 0, 4, 0>(p, lds, lane, rbeg, rend, n_tiles, cbase, nbase, kbase); break;
-      case 1: pc_producer<BM, YM, LT, false, 3, 1, 0, 0>(p, lds, lane, rbeg, rend, n_tiles, cbase, nbase, kbase); break;
-      case 2: pc_producer<BM, YM, LT, false, 2, 4, 2, 4>(p, lds, lane, rbeg, rend, n_tiles, cbase, nbase, kbase); break;
-      default: pc_producer<BM, YM, LT, false, 2, 6, 2, 6>(p, lds, lane, rbeg, rend, n_tiles, cbase, nbase, kbase); break;
+      case 0: pc_producer<BM, YM, LT, CBN, NBN, true, 1, 0, 4, 0>(p, lds, lane, rbeg, rend, n_tiles, cbase, nbase, kbase); break;
+      case 1: pc_producer<BM, YM, LT, CBN, NBN, false, 3, 1, 0, 0>(p, lds, lane, rbeg, rend, n_tiles, cbase, nbase, kbase); break;
+      case 2: pc_producer<BM, YM, LT, CBN, NBN, false, 2, 4, 2, 4>(p, lds, lane, rbeg, rend, n_tiles, cbase, nbase, kbase); break;
+      default: pc_producer<BM, YM, LT, CBN, NBN, false, 2, 6, 2, 6>(p, lds, lane, rbeg, rend, n_tiles, cbase, nbase, kbase); break;
     }
     return;
   }
@@ -231,13 +240,13 @@ __global__ void __launch_bounds__(PC_THREADS) k_wgrad_pc(WgradP p) {
   const bool active = (rs < p.RS) && (2 * kp < kcount);
   const bool kv[2] = {active, active && (2 * kp + 1 < kcount)};
 
-  floatx16 acc[2][2][2];  // [kk][cb][nb]
+  floatx16 acc[2][CBN][NBN];  // [kk][cb][nb]
 #pragma unroll
   for (int a = 0; a < 2; ++a)
 #pragma unroll
-    for (int b = 0; b < 2; ++b)
+    for (int b = 0; b < CBN; ++b)
 #pragma unroll
-      for (int c = 0; c < 2; ++c)
+      for (int c = 0; c < NBN; ++c)
 #pragma unroll
         for (int i = 0; i < 16; ++i) acc[a][b][c][i] = 0.f;
 
@@ -249,14 +258,14 @@ __global__ void __launch_bounds__(PC_THREADS) k_wgrad_pc(WgradP p) {
       const float* YT = (const float*)(XT + PC_XT_BYTES);
       const float* Bs = YT + 64 * XP_F32;
       const int roff = (ss & 3) * 16 + hh * 8;
-      uint4 xf[2];
+      uint4 xf[CBN];
 #pragma unroll
-      for (int cb = 0; cb < 2; ++cb) xf[cb] = *(const uint4*)(XT + (cb * 32 + l32) * PC_XPB + roff * 2);
+      for (int cb = 0; cb < CBN; ++cb) xf[cb] = *(const uint4*)(XT + (cb * 32 + l32) * PC_XPB + roff * 2);
       float2 bq[2];
 #pragma unroll
       for (int kk = 0; kk < 2; ++kk) bq[kk] = *(const float2*)(Bs + (2 * kp + kk) * 64 + roff + 2 * (lane & 3));
 #pragma unroll
-      for (int nb = 0; nb < 2; ++nb) {
+      for (int nb = 0; nb < NBN; ++nb) {
         const float4* s = (const float4*)(YT + (nb * 32 + l32) * XP_F32 + roff);
         const float4 ya = s[0], yb = s[1];
 #pragma unroll
@@ -268,7 +277,7 @@ __global__ void __launch_bounds__(PC_THREADS) k_wgrad_pc(WgradP p) {
           yf.z = pack_bf16x2(quad_bcast<0>(bq[kk].y) * yb.x, quad_bcast<1>(bq[kk].y) * yb.y);
           yf.w = pack_bf16x2(quad_bcast<2>(bq[kk].y) * yb.z, quad_bcast<3>(bq[kk].y) * yb.w);
 #pragma unroll
-          for (int cb = 0; cb < 2; ++cb)
+          for (int cb = 0; cb < CBN; ++cb)
             acc[kk][cb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
                 __builtin_bit_cast(bf16x8, xf[cb]), __builtin_bit_cast(bf16x8, yf), acc[kk][cb][nb], 0, 0, 0);
         }
@@ -285,9 +294,9 @@ __global__ void __launch_bounds__(PC_THREADS) k_wgrad_pc(WgradP p) {
       const int k = kbase + 2 * kp + kk;
       float* dst = p.partial + (slice * p.K + k) * (int64_t)p.Cc * p.Cn;
 #pragma unroll
-      for (int cb = 0; cb < 2; ++cb)
+      for (int cb = 0; cb < CBN; ++cb)
 #pragma unroll
-        for (int nb = 0; nb < 2; ++nb) {
+        for (int nb = 0; nb < NBN; ++nb) {
           const int n = nbase + nb * 32 + l32;
 #pragma unroll
           for (int i = 0; i < 16; ++i) {
@@ -304,20 +313,29 @@ bool pm_wgrad_fuses_basis(pm_dtype mt, BMode bm, XMode xm, XMode ym, int K, int 
   if (mt != PM_BF16 || xm != X_DIRECT || K < 1) return false;
   if (!((bm == B_NORMAL && ym == X_GATHER_SUM) || (bm == B_DIRS && ym == X_GATHER1))) return false;
   if (!xs.is_bf16 || !ys.is_bf16) return false;
-  if (Cc % 64 != 0 || Cn % 64 != 0 || Cc > xs.C || Cn > ys.C) return false;
+  if ((Cc % 64 != 0 && Cc != 32) || (Cn % 64 != 0 && Cn != 32) || Cc > xs.C || Cn > ys.C) return false;
   if (xs.C % 8 != 0 || ys.C % 8 != 0) return false;  // every row starts on a 16-byte boundary
   return pm_aligned16(xs.p) && pm_aligned16(ys.p);
 }
 
-template <int BM, int YM, int LT>
-static pm_status launch_pc(const WgradP& p, int n_part, int slabs, hipStream_t st) {
-  auto kern = k_wgrad_pc<BM, YM, LT>;
+template <int BM, int YM, int LT, int CBN, int NBN>
+static pm_status launch_pc_blocks(const WgradP& p, int n_part, int slabs, hipStream_t st) {
+  auto kern = k_wgrad_pc<BM, YM, LT, CBN, NBN>;
   const size_t lds = 2 * (size_t)PC_BUF_BYTES;
   PM_TRY(pm_set_dyn_lds((const void*)kern, lds));
   { ProfScope ps__(st, "k_wgrad");
     hipLaunchKernelGGL(kern, dim3((unsigned)n_part, (unsigned)slabs), dim3(PC_THREADS), lds, st, p); }
   PM_CHECK_LAUNCH("k_wgrad_pc");
   return PM_OK;
+}
+
+template <int BM, int YM, int LT>
+static pm_status launch_pc(const WgradP& p, int n_part, int slabs, hipStream_t st) {
+  const bool c32 = p.Cc == 32, n32 = p.Cn == 32;
+  if (c32 && n32) return launch_pc_blocks<BM, YM, LT, 1, 1>(p, n_part, slabs, st);
+  if (c32) return launch_pc_blocks<BM, YM, LT, 1, 2>(p, n_part, slabs, st);
+  if (n32) return launch_pc_blocks<BM, YM, LT, 2, 1>(p, n_part, slabs, st);
+  return launch_pc_blocks<BM, YM, LT, 2, 2>(p, n_part, slabs, st);
 }
 
 pm_status pm_launch_wgrad_pc(BMode bm, XMode ym, const WgradP& p, int n_part, int slabs, hipStream_t st) {

@@ -129,6 +129,8 @@ CASES = [  # (L, cin, cout, dtype)
     (3, 64, 32, "bf16"),
     (4, 128, 128, "f32"),    # weight-gradient tiling with several k groups and (c, n) slabs; streamed weights
     (3, 256, 256, "bf16"),
+    (3, 32, 64, "bf16"),     # 32-channel operand on one side of the fused weight-gradient kernel
+    (3, 128, 32, "bf16"),
 ]
 
 
