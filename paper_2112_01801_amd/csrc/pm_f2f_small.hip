@@ -28,17 +28,30 @@ __global__ void __launch_bounds__(256) k_f2f_gather(int64_t F, const int32_t* __
   float acc[FS_ROW];
 #pragma unroll
   for (int i = 0; i < FS_ROW; ++i) acc[i] = 0.f;
-  for (int32_t p = p0; p < p1; ++p) {
-    float x = bary[3 * (int64_t)p], y = bary[3 * (int64_t)p + 1], z = bary[3 * (int64_t)p + 2];
-    normalize_dir(x, y, z);
-    float hv[CIN];
+  // the next point's coordinates and channels are on their way while this point's basis is evaluated
+  auto fetch = [&](int32_t p, float (&d)[3], float (&hv)[CIN]) {
+    d[0] = bary[3 * (int64_t)p]; d[1] = bary[3 * (int64_t)p + 1]; d[2] = bary[3 * (int64_t)p + 2];
 #pragma unroll
     for (int ci = 0; ci < CIN; ++ci)
       hv[ci] = BF16 ? bf16_to_f32(((const uint16_t*)h)[(int64_t)p * CIN + ci]) : ((const float*)h)[(int64_t)p * CIN + ci];
+  };
+  float d[3] = {0.f, 0.f, 1.f}, hv[CIN];
+#pragma unroll
+  for (int ci = 0; ci < CIN; ++ci) hv[ci] = 0.f;
+  if (p1 > p0) fetch(p0, d, hv);
+  for (int32_t p = p0; p < p1; ++p) {
+    float dn[3], hn[CIN];
+    fetch(min(p + 1, p1 - 1), dn, hn);
+    float x = d[0], y = d[1], z = d[2];
+    normalize_dir(x, y, z);
     sh_eval<LT>(x, y, z, sh, [&](int k, float v) {
 #pragma unroll
       for (int ci = 0; ci < CIN; ++ci) acc[k * CIN + ci] = fmaf(v, hv[ci], acc[k * CIN + ci]);
     });
+#pragma unroll
+    for (int q = 0; q < 3; ++q) d[q] = dn[q];
+#pragma unroll
+    for (int ci = 0; ci < CIN; ++ci) hv[ci] = hn[ci];
   }
   const float w = p1 > p0 ? 1.0f / (float)(p1 - p0) : 0.f;
   if constexpr (BF16) {
