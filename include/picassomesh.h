@@ -139,7 +139,9 @@ pm_status pm_v2f_bwd(const pm_mesh* mesh, const pm_vf_adj* adj, int L, pm_sh_nor
 
 /* facet2facet, Eq. 7:  g_f = 1/R_f sum_{p in f} sum_k sum_ci B_k(xi_p/|xi_p|) h_p[ci] W[k][ci][co].
  * tex_off [n_facet+1] is the facet -> texture-point CSR (points of a facet contiguous, R_f may be 0 ->
- * zero row); bary [n_tex,3] barycentric coordinates; h_tex [n_tex,cin]; g_facet [n_facet,cout]. */
+ * zero row); bary [n_tex,3] barycentric coordinates; h_tex [n_tex,cin]; g_facet [n_facet,cout].
+ * With cin <= 4 and L <= 3 (the paper's shape: three colour channels) the sums are taken in the order
+ * (mean over the points of a facet of B (x) h) . W, one contraction per facet; same result up to rounding. */
 pm_status pm_f2f(int64_t n_facet, int64_t n_tex, const int32_t* tex_off, const float* bary, int L, pm_sh_norm norm,
                  int cin, int cout, pm_dtype dtype, const void* h_tex, const void* W, void* g_facet, void* ws,
                  size_t ws_bytes, void* stream);
