@@ -265,7 +265,7 @@ __global__ void __launch_bounds__(256) k_segreduce(SegP p) {
         if (coop) {
           // the lanes of the group fetch the batch's column entries together (one coalesced load), then hand them
           // round: every row address of the batch is known after ONE memory latency
-          const int64_t mine = row_of(min(i0 + (sub & (NB - 1)), e - 1));
+          const int64_t mine = row_of(min(i0 + min(sub, NB - 1), e - 1));
 #pragma unroll
           for (int j = 0; j < NB; ++j) r[j] = __shfl((int)mine, (threadIdx.x & 63 & ~(p.lpg - 1)) + j, 64);
         } else {
@@ -332,12 +332,13 @@ __global__ void __launch_bounds__(256) k_segreduce(SegP p) {
 
 template <bool SRC_BF16>
 static void launch_segreduce_div(const SegP& p, dim3 grid, hipStream_t st) {
-  // four entries per batch, their column entries fetched by the lanes of the group in one load: with each lane
-  // fetching its own entries (two per batch measured best then) every batch cost two memory latencies in sequence;
-  // measured on MI355X at config 3: 0.118 -> 0.107 ms
-  if (p.div == 1) hipLaunchKernelGGL((k_segreduce<SRC_BF16, 1, 4>), grid, dim3(256), 0, st, p);
-  else if (p.div == 3) hipLaunchKernelGGL((k_segreduce<SRC_BF16, 3, 4>), grid, dim3(256), 0, st, p);
-  else hipLaunchKernelGGL((k_segreduce<SRC_BF16, 0, 4>), grid, dim3(256), 0, st, p);
+  // six entries per batch -- the mean valence of a triangle mesh, so most segments take one batch: one latency for the
+  // column entries (fetched by the lanes of the group in one load), one for the rows, all in flight together.
+  // Measured on MI355X at config 3: two entries per batch, each lane fetching its own, 0.118 ms; four per batch with
+  // the cooperative fetch 0.107; six 0.089; eight (two wasted row requests per segment) 0.109
+  if (p.div == 1) hipLaunchKernelGGL((k_segreduce<SRC_BF16, 1, 6>), grid, dim3(256), 0, st, p);
+  else if (p.div == 3) hipLaunchKernelGGL((k_segreduce<SRC_BF16, 3, 6>), grid, dim3(256), 0, st, p);
+  else hipLaunchKernelGGL((k_segreduce<SRC_BF16, 0, 6>), grid, dim3(256), 0, st, p);
 }
 
 pm_status pm_launch_segreduce(int64_t n_seg, int C, const void* src, int src_is_bf16, const int32_t* row_ptr,
