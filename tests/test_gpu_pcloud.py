@@ -49,7 +49,9 @@ def _nbr(pm, xq, xs, ptr, idx, rho):
 
 
 CASES = [(3, 64, 64, "bf16"), (3, 64, 64, "f32"), (2, 20, 24, "f32"), (4, 32, 128, "bf16"), (5, 8, 40, "f32"),
-         (0, 16, 16, "bf16"), (1, 3, 5, "f32"), (3, 136, 16, "bf16")]
+         (0, 16, 16, "bf16"), (1, 3, 5, "f32"), (3, 136, 16, "bf16"),
+         # bf16 with more than 32 basis rows (fp32 tiles), and channel runs that are not whole (element-wise access)
+         (5, 16, 24, "bf16"), (3, 20, 12, "bf16"), (4, 10, 8, "bf16")]
 
 
 @pytest.mark.parametrize("L,cin,cout,dtype", CASES)
