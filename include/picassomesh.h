@@ -269,7 +269,11 @@ pm_status pm_unpool_bwd(const pm_cluster_map* cm, int C, pm_dtype dtype, const v
  * its workspace on every call unless the caller built them once with pm_build_reverse_neighbors and set
  * rev_ptr [n_source+1], rev_col [nnz] (pair ids) and owner [nnz] (query of every pair): all three or none.
  * y_query (forward, may be NULL) receives the depth-wise output y [n_query,cin] of the feature dtype; handed
- * back as y_saved (may be NULL) the backward pass takes dP from it instead of recomputing it. */
+ * back as y_saved (may be NULL) the backward pass takes dP from it instead of recomputing it.
+ * Arithmetic: basis and filter values in fp32, sums over a list in fp32 in list order.  With bf16 features and
+ * L <= 4 the filter sum_k runs on the bf16 matrix cores with both operands split into a bf16 head and remainder
+ * (three products, fp32 accumulation: relative error below 2^-15 per product, i.e. fp32 to within the stated
+ * bar); the coefficient gradients dalpha, dc0 then sum bf16-rounded products h (.) dy in fp32. */
 typedef struct pm_nbr {
   int64_t n_query, n_source, nnz;
   const float* xq;
