@@ -1,11 +1,13 @@
 // vertex2facet forward (Eq. 6) with LDS-staged facet tiles, for the memory-bound shapes bf16, Cin = 32 or 64:
 //     g_f = sum_j W_j^T h_{v_j(f)},   W_j = sum_k B_k(e_j) W[k]   (the three folded matrices of the packed image)
 // The work per facet is three gathered vertex rows (64 or 128 bytes), a 3 Cin x Cout contraction and one output
-// row, so the kernel lives on its memory system.  A workgroup of 4 waves walks tiles of 128 facets: the 384 vertex
-// rows of a tile are fetched with whole-row accesses (16 bytes a lane) into a padded LDS tile (the three rows of a
-// facet side by side, as the concatenated operand row of the folded form), one tile ahead of the arithmetic (ids
-// two tiles ahead), the matrix core takes its operand granules from LDS, and the output tile goes back through
-// LDS so that it leaves in whole rows.  The folded weights (up to 48 KB) stay in LDS.
+// row, so the kernel lives on its memory system.  A workgroup of 4 waves walks tiles of 128 facets, 32 per wave: the
+// 96 vertex rows of a wave's facets are fetched with whole-row accesses (16 bytes a lane) into the wave's own padded
+// LDS region (the three rows of a facet side by side, as the concatenated operand row of the folded form), one tile
+// ahead of the arithmetic (ids two tiles ahead), the matrix core takes its operand granules from LDS, and the
+// wave's output rows go back through the same region so that they leave in whole rows.  The folded weights (up to
+// 48 KB) stay in LDS, shared and read-only; apart from their load there is no workgroup barrier: each wave runs its
+// fetch / contract / store phases on its own, and the phases of the eight waves of a CU overlap.
 //
 // The same kernel serves, by template arguments,
 //   * a point-wise matrix on directly addressed rows (NJ = 1: the tile is 128 consecutive rows), and
@@ -73,8 +75,16 @@ __global__ void __launch_bounds__(256, (NJ == 1 || (CIN == 64 && NB >= 3)) ? 1 :
   uint4* Wl = vt_lds;                                              // [NBG * NCH][VT_STAGE_U4]
   uint4* Aw = vt_lds + NBG * NCH * VT_STAGE_U4;                    // FUSE: [NKC][NB][hi, lo][64] coefficient operands
   float* Ep = (float*)(Aw + NKC * NB * 2 * 64);                    // FUSE: [2][CO] affine
-  char* tile_lds = (char*)(Ep + (FUSE ? 2 * CO : 0));             // [VT_ROWS][PITCH], reused for the output tile
-  float* Bw = (float*)(tile_lds + VT_ROWS * OP) + wave * 32 * KP;  // FUSE: this wave's basis rows [32][KP]
+  char* tile_lds = (char*)(Ep + (FUSE ? 2 * CO : 0));             // four wave regions of tile_bytes / 4
+  // Every wave owns 32 rows of a tile and an LDS region of its own: the staged rows [32][PITCH], reused for the
+  // wave's output rows [32][OP] and (FUSE) its basis rows behind them.  No wave touches another's region, so the
+  // tile loop has no workgroup barrier: the waves of a CU drift apart and each other's memory latencies overlap.
+  char* wl = tile_lds + wave * (p.tile_bytes / 4);
+  float* Bw = (float*)(wl + 32 * OP);                              // FUSE: this wave's basis rows [32][KP]
+  auto wave_sync = [] {    // LDS writes of the wave's lanes are visible to its other lanes
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+  };
   const int64_t n_tiles = (p.F + VT_ROWS - 1) / VT_ROWS;
 
   for (int i = tid; i < NBG * NCH * VT_STAGE_U4; i += 256) Wl[i] = p.apack[i];
@@ -99,12 +109,12 @@ __global__ void __launch_bounds__(256, (NJ == 1 || (CIN == 64 && NB >= 3)) ? 1 :
   for (int i = tid; i < p.tile_bytes / 16; i += 256) ((uint4*)tile_lds)[i] = make_uint4(0, 0, 0, 0);   // the pad stays zero
   __syncthreads();
 
-  // piece i of this thread: item = tid + 256 i -> (row of the tile, corner, 16-byte piece of the source row)
+  // piece i of this lane: item = lane + 64 i -> (row of the wave's 32, corner, 16-byte piece of the source row)
   auto load_ids = [&](int64_t tile, int32_t (&vid)[PT]) {
 #pragma unroll
     for (int i = 0; i < PT; ++i) {
-      const int item = tid + 256 * i;
-      const int64_t f = tile * VT_ROWS + item / IPR;
+      const int item = lane + 64 * i;
+      const int64_t f = tile * VT_ROWS + wave * 32 + item / IPR;
       const int j = (item % IPR) / PPR;
       vid[i] = -1;
       if (tile < n_tiles && f < p.F) vid[i] = (NJ == 3) ? p.facet[3 * f + j] : (int32_t)f;
@@ -113,7 +123,7 @@ __global__ void __launch_bounds__(256, (NJ == 1 || (CIN == 64 && NB >= 3)) ? 1 :
   auto load_rows = [&](const int32_t (&vid)[PT], uint4 (&x)[PT]) {
 #pragma unroll
     for (int i = 0; i < PT; ++i) {
-      const int piece = (tid + 256 * i) % PPR;
+      const int piece = (lane + 64 * i) % PPR;
       x[i] = make_uint4(0, 0, 0, 0);
       if (vid[i] >= 0) x[i] = *(const uint4*)(p.h + (int64_t)vid[i] * CIN + piece * 8);
     }
@@ -121,8 +131,8 @@ __global__ void __launch_bounds__(256, (NJ == 1 || (CIN == 64 && NB >= 3)) ? 1 :
   auto stage_rows = [&](const uint4 (&x)[PT]) {
 #pragma unroll
     for (int i = 0; i < PT; ++i) {
-      const int item = tid + 256 * i;
-      *(uint4*)(tile_lds + (item / IPR) * PITCH + (item % IPR) * 16) = x[i];
+      const int item = lane + 64 * i;
+      *(uint4*)(wl + (item / IPR) * PITCH + (item % IPR) * 16) = x[i];
     }
   };
   // FUSE with the depth-wise stage: corner ids of the lane's own facet (one tile ahead), then its corner positions
@@ -142,7 +152,7 @@ __global__ void __launch_bounds__(256, (NJ == 1 || (CIN == 64 && NB >= 3)) ? 1 :
   load_rows(vid, x);
   load_ids(tile + gridDim.x, vid);
   stage_rows(x);
-  __syncthreads();
+  wave_sync();
   for (; tile < n_tiles; tile += gridDim.x) {
     DirRaw dr;
     if (dw) {
@@ -163,7 +173,7 @@ __global__ void __launch_bounds__(256, (NJ == 1 || (CIN == 64 && NB >= 3)) ? 1 :
     for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
       for (int i = 0; i < 16; ++i) y[nb][i] = 0.f;
-    const char* trow = tile_lds + (wave * 32 + r) * PITCH;
+    const char* trow = wl + r * PITCH;
 #pragma unroll
     for (int ch = 0; ch < NCH; ++ch) {
 #pragma unroll
@@ -177,18 +187,18 @@ __global__ void __launch_bounds__(256, (NJ == 1 || (CIN == 64 && NB >= 3)) ? 1 :
         }
       }
     }
-    __syncthreads();                            // every wave is done with the staged rows of this tile
+    wave_sync();                                // the wave is done with its staged rows of this tile
 
     // the tile of accumulators leaves through the LDS buffer: lane (r, hh) holds, per 32-wide block, channels
     // q4 * 8 + hh * 4 + i of its row; whole rows then go out in 16-byte pieces
-    const int64_t f0 = tile * VT_ROWS;
+    const int64_t f0 = tile * VT_ROWS + wave * 32;   // the wave's first row
     auto store_tile = [&](uint16_t* dst) {
       constexpr int ESZ = OF32 ? 4 : 2;
 #pragma unroll
       for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
         for (int q4 = 0; q4 < 4; ++q4) {
-          char* q = tile_lds + (wave * 32 + r) * OP + (nb * 32 + q4 * 8 + hh * 4) * ESZ;
+          char* q = wl + r * OP + (nb * 32 + q4 * 8 + hh * 4) * ESZ;
           if constexpr (OF32) {
             *(float4*)q = make_float4(y[nb][q4 * 4], y[nb][q4 * 4 + 1], y[nb][q4 * 4 + 2], y[nb][q4 * 4 + 3]);
           } else {
@@ -198,16 +208,16 @@ __global__ void __launch_bounds__(256, (NJ == 1 || (CIN == 64 && NB >= 3)) ? 1 :
             *(uint2*)q = w;
           }
         }
-      __syncthreads();
+      wave_sync();
       constexpr int OPR = 4 * NB * (ESZ / 2);   // 16-byte pieces per output row
 #pragma unroll
-      for (int i = 0; i < (VT_ROWS * OPR) / 256; ++i) {
-        const int item = tid + 256 * i;
+      for (int i = 0; i < (32 * OPR) / 64; ++i) {
+        const int item = lane + 64 * i;
         const int row = item / OPR, piece = item % OPR;
         if (f0 + row < p.F)
-          *(uint4*)((char*)dst + ((f0 + row) * CO * ESZ + piece * 16)) = *(const uint4*)(tile_lds + row * OP + piece * 16);
+          *(uint4*)((char*)dst + ((f0 + row) * CO * ESZ + piece * 16)) = *(const uint4*)(wl + row * OP + piece * 16);
       }
-      __syncthreads();
+      wave_sync();
     };
 
     if constexpr (FUSE) {
@@ -274,7 +284,7 @@ __global__ void __launch_bounds__(256, (NJ == 1 || (CIN == 64 && NB >= 3)) ? 1 :
     }
     if constexpr (NJ == 1 && !FUSE) {
       if (p.row_ptr) {                          // the mean's weight of the row, applied once here for its consumers
-        const int64_t row = min(f0 + wave * 32 + r, p.F - 1);
+        const int64_t row = min(f0 + r, p.F - 1);
         const int32_t deg = p.row_ptr[row + 1] - p.row_ptr[row];
         const float w = deg > 0 ? 1.0f / (float)deg : 0.f;
 #pragma unroll
@@ -288,11 +298,11 @@ __global__ void __launch_bounds__(256, (NJ == 1 || (CIN == 64 && NB >= 3)) ? 1 :
     // rows do not reach
     if constexpr (NJ * CIN * 2 < ROWB) {
       constexpr int PADP = (ROWB - NJ * CIN * 2) / 16;   // 16-byte pieces of pad per row
-      for (int i = tid; i < VT_ROWS * PADP; i += 256)
-        *(uint4*)(tile_lds + (i / PADP) * PITCH + NJ * CIN * 2 + (i % PADP) * 16) = make_uint4(0, 0, 0, 0);
+      for (int i = lane; i < 32 * PADP; i += 64)
+        *(uint4*)(wl + (i / PADP) * PITCH + NJ * CIN * 2 + (i % PADP) * 16) = make_uint4(0, 0, 0, 0);
     }
-    stage_rows(x);                              // the next tile goes into the vacated buffer ...
-    __syncthreads();                            // ... and is visible to every wave
+    stage_rows(x);                              // the wave's rows of the next tile go into the vacated region ...
+    wave_sync();                                // ... and are visible to all its lanes
   }
 }
 
@@ -306,7 +316,8 @@ static pm_status v2f_stage_launch(VtP& p, hipStream_t st, const char* label) {
   constexpr int NBG = (NB + 1) / 2, NCH = vt_nch(CIN, NJ);
   const int nkc = FUSE ? (p.K2 + 15) / 16 : 0;
   const int bw = (FUSE && p.alpha2) ? 4 * 32 * (p.K2 | 1) * 4 : 0;
-  p.tile_bytes = (int)pm_round_up((size_t)std::max(VT_ROWS * vt_pitch(CIN, NJ), VT_ROWS * vt_out_pitch(NB, OF32) + bw), 16);
+  // four wave regions: 32 staged rows, or 32 output rows and the wave's basis rows behind them
+  p.tile_bytes = 4 * (int)pm_round_up((size_t)std::max(32 * vt_pitch(CIN, NJ), 32 * vt_out_pitch(NB, OF32) + bw / 4), 16);
   const size_t lds = (size_t)NBG * NCH * PM_STAGE_BYTES + (FUSE ? (size_t)nkc * NB * 2 * 1024 + 2 * 32 * NB * 4 : 0) + p.tile_bytes;
   if (lds > 160 * 1024) return pm_fail(PM_ERR_UNSUPPORTED, "staged tiles: %zu bytes of LDS", lds);
   int64_t grid = (p.F + VT_ROWS - 1) / VT_ROWS;
