@@ -441,8 +441,8 @@ __global__ void __launch_bounds__(NW * 64) k_conv_rows(ConvP p) {
             }
 #pragma unroll
             for (int i = 0; i < 16; ++i) {   // drain the pipeline
-              y0[i] += pb0 * pu0[i];
-              y1[i] += pb1 * pu1[i];
+              y0[i] = fmaf(pb0, pu0[i], y0[i]);
+              y1[i] = fmaf(pb1, pu1[i], y1[i]);
             }
             asm volatile("" : "+v"(y0), "+v"(y1));
           }
@@ -511,8 +511,8 @@ __global__ void __launch_bounds__(NW * 64) k_conv_rows(ConvP p) {
           if constexpr (BM != B_ONE) {  // drain the pipeline
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
-              y[PM_NBS - 1][0][i] += pb0 * pu0[i];
-              y[PM_NBS - 1][1][i] += pb1 * pu1[i];
+              y[PM_NBS - 1][0][i] = fmaf(pb0, pu0[i], y[PM_NBS - 1][0][i]);
+              y[PM_NBS - 1][1][i] = fmaf(pb1, pu1[i], y[PM_NBS - 1][1][i]);
             }
             asm volatile("" : "+v"(y[PM_NBS - 1][0]), "+v"(y[PM_NBS - 1][1]));
           }

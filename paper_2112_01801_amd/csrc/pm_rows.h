@@ -130,10 +130,10 @@ __device__ __forceinline__ void fetch_vals(const RowSrc& s, int64_t r, bool vali
     for (int i = 0; i < N; ++i) v[i] = t[i] * m.w[0];
     load_vals<N>(s.p, s.is_bf16, m.id[1], s.C, c0, t);
 #pragma unroll
-    for (int i = 0; i < N; ++i) v[i] += t[i] * m.w[1];
+    for (int i = 0; i < N; ++i) v[i] = fmaf(t[i], m.w[1], v[i]);   // explicit: every copy of this code rounds alike
     load_vals<N>(s.p, s.is_bf16, m.id[2], s.C, c0, t);
 #pragma unroll
-    for (int i = 0; i < N; ++i) v[i] += t[i] * m.w[2];
+    for (int i = 0; i < N; ++i) v[i] = fmaf(t[i], m.w[2], v[i]);
   } else if constexpr (XM == X_GATHER_CAT) {
     const int C = s.C;
     int j = c0 / C, cc = c0 - j * C;

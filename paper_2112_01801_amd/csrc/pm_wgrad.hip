@@ -123,10 +123,10 @@ __device__ __forceinline__ void raw_combine(const Raw8 (&raw)[NSrc<M>::n], const
     for (int i = 0; i < 8; ++i) v[i] *= m.w[0];
     raw_to_f32(raw[1], t);
 #pragma unroll
-    for (int i = 0; i < 8; ++i) v[i] += t[i] * m.w[1];
+    for (int i = 0; i < 8; ++i) v[i] = fmaf(t[i], m.w[1], v[i]);
     raw_to_f32(raw[2], t);
 #pragma unroll
-    for (int i = 0; i < 8; ++i) v[i] += t[i] * m.w[2];
+    for (int i = 0; i < 8; ++i) v[i] = fmaf(t[i], m.w[2], v[i]);
   }
 }
 

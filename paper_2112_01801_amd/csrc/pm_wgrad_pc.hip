@@ -150,8 +150,10 @@ __device__ __forceinline__ void pc_producer(const WgradP& p, char* lds, const in
 #pragma unroll
           for (int e = 0; e < 8; ++e) {
             const float f = (e & 1) ? bf16hi_to_f32(w[e >> 1]) : bf16lo_to_f32(w[e >> 1]);
+            // explicit fused multiply-adds: left to the compiler's contraction, the copies of this code before and inside
+            // the tile loop rounded differently (a row's dy then depended on where a workgroup's range starts)
             if (j == 0) v[e] = (YM == X_DIRECT) ? f : f * wt[0];
-            else v[e] += f * wt[j];
+            else v[e] = fmaf(f, wt[j], v[e]);
           }
         }
 #pragma unroll
