@@ -126,3 +126,29 @@ def test_pcloud_rows_on_query_ranges(pm):
         idx_p = idx[ptr[lo]:ptr[hi]].astype(np.int32)
         nb = pm.Neighbors(xs_d[lo:hi], xs_d, t(ptr_p), t(idx_p), rho)
         assert torch.equal(pm.pm_pcloud_conv(nb, L, h, alpha, c0, Pw, dt), g_all[lo:hi]), (lo, hi)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_separable_rows_on_facet_ranges(pm, dtype):
+    """Separable forms: vertex2facet forward rows and the facet gradients of facet2vertex on facet ranges."""
+    import torch
+    L, cin, cout = 3, 64, 64
+    rng = np.random.default_rng(45)
+    b = mg.pack_batch([mg.heightfield(160, 160, rng, random_diag=True)])
+    mesh = pm.mesh_to_device(b)
+    adj = pm.pm_build_vf_adjacency(mesh)
+    F, V = b.n_facet, b.n_vert
+    K = (L + 1) ** 2
+    alpha = torch.from_numpy((rng.standard_normal((K, cin)) * 0.3).astype(np.float32)).cuda()
+    Pw = to_dev(make_coeffs(rng, 1, cin, cout, dtype)[0], dtype)
+    hV = to_dev(make_features(rng, V, cin, dtype), dtype)
+    hF = to_dev(make_features(rng, F, cin, dtype), dtype)
+    dgV = to_dev(make_features(rng, V, cout, dtype), dtype)
+    dt = pm_dtype(dtype)
+    g_all = pm.pm_v2f_sep(mesh, L, hV, alpha, Pw, dt)
+    dh_all = pm.pm_f2v_sep_bwd(mesh, adj, L, hF, alpha, Pw, dgV, dt, want_dw=False)[0]
+    for lo, hi in _ranges(F, 3):
+        part = pm.Mesh(vert=mesh.vert, facet=mesh.facet[lo:hi], vert_off=None, facet_off=None, n_vert=V, n_mesh=1)
+        assert torch.equal(pm.pm_v2f_sep(part, L, hV, alpha, Pw, dt), g_all[lo:hi]), (dtype, lo, hi)
+        dh = pm.pm_f2v_sep_bwd(part, adj, L, hF[lo:hi], alpha, Pw, dgV, dt, want_dw=False)[0]
+        assert torch.equal(dh, dh_all[lo:hi]), (dtype, lo, hi)
