@@ -236,50 +236,88 @@ __global__ void __launch_bounds__(256, (NJ == 1 || (CIN == 64 && NB >= 3)) ? 1 :
         }
       if (p.save) store_tile(p.save);
       if (dw) {
-        // basis of the wave's 32 facets into its own LDS rows (both half-waves hold the same rows), then the
-        // filter values of every accumulator element from the fp32 matrix core
         float nx, ny, nz;
         dir_finish<B_NORMAL>(dr, nx, ny, nz);
-        sh_eval<-1>(nx, ny, nz, p.sh, [&](int k, float v) {
-          if (hh == 0) Bw[r * KP + k] = v;
-        });
-        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        // per 32-wide block and chunk of 16 basis functions: the lane's basis operand (functions 16 kc + 8 hh + i
-        // of its row) split into head and remainder, then the three leading products
+        constexpr bool L3REG = !(CIN == 32 && NB == 4);   // that instance has no registers to spare
+        if (L3REG && p.sh.L == 3 && p.K2 == 16) {
+          // L = 3: the 16 basis values of the lane's facet stay in registers (unrolled recurrence); the lane's operand
+          // -- functions 8 hh .. 8 hh + 7 of its row -- is selected from them and split into head and remainder: no
+          // LDS round trip, one chunk of 16 functions
+          float b0[8], b1[8];        // two arrays: a select between elements of one would become a run-time index
+          sh_eval<3>(nx, ny, nz, p.sh, [&](int k, float v) {
+            if (k < 8) b0[k] = v;
+            else b1[k - 8] = v;
+          });
+          float v[8];
 #pragma unroll
-        for (int nb = 0; nb < NB; ++nb) {
-          floatx16 S;
+          for (int i = 0; i < 8; ++i) v[i] = hh ? b1[i] : b0[i];
+          const uint4 bh = make_uint4(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]), pack_bf16x2(v[4], v[5]),
+                                      pack_bf16x2(v[6], v[7]));
+          const uint32_t hw[4] = {bh.x, bh.y, bh.z, bh.w};
 #pragma unroll
-          for (int i = 0; i < 16; ++i) S[i] = 0.f;
-#pragma unroll 1
-          for (int kc = 0; kc < NKC; ++kc) {
-            float v[8];
+          for (int i = 0; i < 4; ++i) {
+            v[2 * i] -= bf16lo_to_f32(hw[i]);
+            v[2 * i + 1] -= bf16hi_to_f32(hw[i]);
+          }
+          const uint4 bl = make_uint4(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]), pack_bf16x2(v[4], v[5]),
+                                      pack_bf16x2(v[6], v[7]));
 #pragma unroll
-            for (int i = 0; i < 8; ++i) {
-              const int k = kc * 16 + 8 * hh + i;
-              v[i] = (k < p.K2) ? Bw[r * KP + k] : 0.f;
-            }
-            const uint4 bh = make_uint4(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]), pack_bf16x2(v[4], v[5]),
-                                        pack_bf16x2(v[6], v[7]));
-            const uint32_t hw[4] = {bh.x, bh.y, bh.z, bh.w};
+          for (int nb = 0; nb < NB; ++nb) {
+            floatx16 S;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-              v[2 * i] -= bf16lo_to_f32(hw[i]);
-              v[2 * i + 1] -= bf16hi_to_f32(hw[i]);
-            }
-            const uint4 bl = make_uint4(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]), pack_bf16x2(v[4], v[5]),
-                                        pack_bf16x2(v[6], v[7]));
-            const bf16x8 ah = __builtin_bit_cast(bf16x8, Aw[((kc * NB + nb) * 2 + 0) * 64 + lane]);
-            const bf16x8 al = __builtin_bit_cast(bf16x8, Aw[((kc * NB + nb) * 2 + 1) * 64 + lane]);
+            for (int i = 0; i < 16; ++i) S[i] = 0.f;
+            const bf16x8 ah = __builtin_bit_cast(bf16x8, Aw[(nb * 2 + 0) * 64 + lane]);
+            const bf16x8 al = __builtin_bit_cast(bf16x8, Aw[(nb * 2 + 1) * 64 + lane]);
             S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al, __builtin_bit_cast(bf16x8, bh), S, 0, 0, 0);
             S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, __builtin_bit_cast(bf16x8, bl), S, 0, 0, 0);
             S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, __builtin_bit_cast(bf16x8, bh), S, 0, 0, 0);
-          }
 #pragma unroll
-          for (int i = 0; i < 16; ++i) y[nb][i] *= S[i];
+            for (int i = 0; i < 16; ++i) y[nb][i] *= S[i];
+          }
+        } else {
+          // basis of the wave's 32 facets into its own LDS rows (both half-waves hold the same rows), then the
+          // filter values of every accumulator element from the fp32 matrix core
+          sh_eval<-1>(nx, ny, nz, p.sh, [&](int k, float v) {
+            if (hh == 0) Bw[r * KP + k] = v;
+          });
+          __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+          __builtin_amdgcn_wave_barrier();
+          // per 32-wide block and chunk of 16 basis functions: the lane's basis operand (functions 16 kc + 8 hh + i
+          // of its row) split into head and remainder, then the three leading products
+#pragma unroll
+          for (int nb = 0; nb < NB; ++nb) {
+            floatx16 S;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) S[i] = 0.f;
+#pragma unroll 1
+            for (int kc = 0; kc < NKC; ++kc) {
+              float v[8];
+#pragma unroll
+              for (int i = 0; i < 8; ++i) {
+                const int k = kc * 16 + 8 * hh + i;
+                v[i] = (k < p.K2) ? Bw[r * KP + k] : 0.f;
+              }
+              const uint4 bh = make_uint4(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]), pack_bf16x2(v[4], v[5]),
+                                          pack_bf16x2(v[6], v[7]));
+              const uint32_t hw[4] = {bh.x, bh.y, bh.z, bh.w};
+#pragma unroll
+              for (int i = 0; i < 4; ++i) {
+                v[2 * i] -= bf16lo_to_f32(hw[i]);
+                v[2 * i + 1] -= bf16hi_to_f32(hw[i]);
+              }
+              const uint4 bl = make_uint4(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]), pack_bf16x2(v[4], v[5]),
+                                          pack_bf16x2(v[6], v[7]));
+              const bf16x8 ah = __builtin_bit_cast(bf16x8, Aw[((kc * NB + nb) * 2 + 0) * 64 + lane]);
+              const bf16x8 al = __builtin_bit_cast(bf16x8, Aw[((kc * NB + nb) * 2 + 1) * 64 + lane]);
+              S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al, __builtin_bit_cast(bf16x8, bh), S, 0, 0, 0);
+              S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, __builtin_bit_cast(bf16x8, bl), S, 0, 0, 0);
+              S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, __builtin_bit_cast(bf16x8, bh), S, 0, 0, 0);
+            }
+#pragma unroll
+            for (int i = 0; i < 16; ++i) y[nb][i] *= S[i];
+          }
+          __builtin_amdgcn_wave_barrier();        // the basis rows have been read
         }
-        __builtin_amdgcn_wave_barrier();        // the basis rows have been read
       }
     }
     if constexpr (NJ == 1 && !FUSE) {
