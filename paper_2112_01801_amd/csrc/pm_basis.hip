@@ -79,7 +79,7 @@ __global__ void __launch_bounds__(256) k_basis_dirs(int64_t n, const float* __re
   float x = dirs[3 * i], y = dirs[3 * i + 1], z = dirs[3 * i + 2];
   normalize_dir(x, y, z);
   float* out = basis + i * K;
-  sh_eval<-1>(x, y, z, T, [&](int k, float v) { out[k] = v; });
+  sh_eval_any(x, y, z, T, [&](int k, float v) { out[k] = v; });
 }
 
 // Gradient of sum_k db[k] B_k(d/|d|) with respect to d.  With u = d/|d|, the Cartesian form

@@ -38,6 +38,27 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
 
 // Unit facet normal by the right-hand rule on the stored corner order, (x2-x1) x (x3-x1).
 // A (near-)degenerate facet, squared cross-product length < 1e-30, takes (0,0,1).
+// Cross product and squared length with their multiply-adds written out.  Directions and basis values are evaluated
+// in several kernels (and in several copies of a kernel's code); left to the compiler's contraction, which products
+// are fused differs from copy to copy, and the same facet gets basis values that differ in the last bit.  With the
+// fused operations explicit (and contraction off in these functions) every copy computes the same bits.
+__device__ __forceinline__ void cross_fixed(float ux, float uy, float uz, float wx, float wy, float wz, float& cx,
+                                            float& cy, float& cz) {
+#pragma clang fp contract(off)
+  cx = fmaf(uy, wz, -(uz * wy));
+  cy = fmaf(uz, wx, -(ux * wz));
+  cz = fmaf(ux, wy, -(uy * wx));
+}
+// a - b rounded once, never contracted with a product that made a (which some copies of a code would do and others not)
+__device__ __forceinline__ float sub_fixed(float a, float b) {
+#pragma clang fp contract(off)
+  return a - b;
+}
+__device__ __forceinline__ float norm2_fixed(float x, float y, float z) {
+#pragma clang fp contract(off)
+  return fmaf(x, x, fmaf(y, y, z * z));
+}
+
 __device__ __forceinline__ void facet_normal(const float* __restrict__ vert, int v0, int v1, int v2, float& nx,
                                              float& ny, float& nz) {
   const float* a = vert + 3 * (int64_t)v0;
@@ -46,10 +67,9 @@ __device__ __forceinline__ void facet_normal(const float* __restrict__ vert, int
   float ax = a[0], ay = a[1], az = a[2];
   float ux = b[0] - ax, uy = b[1] - ay, uz = b[2] - az;
   float wx = c[0] - ax, wy = c[1] - ay, wz = c[2] - az;
-  float cx = uy * wz - uz * wy;
-  float cy = uz * wx - ux * wz;
-  float cz = ux * wy - uy * wx;
-  float l2 = cx * cx + cy * cy + cz * cz;
+  float cx, cy, cz;
+  cross_fixed(ux, uy, uz, wx, wy, wz, cx, cy, cz);
+  float l2 = norm2_fixed(cx, cy, cz);
   if (l2 < 1e-30f) {
     nx = 0.f; ny = 0.f; nz = 1.f;
   } else {
@@ -59,7 +79,7 @@ __device__ __forceinline__ void facet_normal(const float* __restrict__ vert, int
 }
 
 __device__ __forceinline__ void normalize_dir(float& x, float& y, float& z) {
-  float l2 = x * x + y * y + z * z;
+  float l2 = norm2_fixed(x, y, z);
   float r = 1.0f / sqrtf(l2);
   x *= r; y *= r; z *= r;
 }
@@ -73,14 +93,16 @@ __device__ __forceinline__ void normalize_dir(float& x, float& y, float& z) {
 // LT < 0 takes the degree from the table at run time.
 template <int LT, class Sink>
 __device__ __forceinline__ void sh_eval(float x, float y, float z, const ShTable& T, Sink sink) {
+#pragma clang fp contract(off)
+  // (the multiply-adds below are explicit: every copy of this code, in whichever kernel, gives the same bits)
   const int L = (LT >= 0) ? LT : T.L;
   float cm = 1.f, sm = 0.f;  // Re, Im of (x+iy)^m
   float qmm = 1.f;           // Q_m^m = (2m-1)!!
 #pragma unroll
   for (int m = 0; m <= L; ++m) {
     if (m > 0) {
-      float c2 = cm * x - sm * y;
-      sm = cm * y + sm * x;
+      float c2 = fmaf(cm, x, -(sm * y));
+      sm = fmaf(cm, y, sm * x);
       cm = c2;
       qmm *= (float)(2 * m - 1);
     }
@@ -94,7 +116,7 @@ __device__ __forceinline__ void sh_eval(float x, float y, float z, const ShTable
         q1 = (float)(2 * m + 1) * z * q0;
         q = q1;
       } else {
-        q = ((float)(2 * l - 1) * z * q1 - (float)(l + m - 1) * q0) / (float)(l - m);
+        q = fmaf(-(float)(l + m - 1), q0, (float)(2 * l - 1) * z * q1) / (float)(l - m);
         q0 = q1;
         q1 = q;
       }
@@ -102,5 +124,20 @@ __device__ __forceinline__ void sh_eval(float x, float y, float z, const ShTable
       sink(l * (l + 1) + m, v * cm);
       if (m > 0) sink(l * (l + 1) - m, v * sm);
     }
+  }
+}
+
+// The degree taken from the table, evaluated by the unrolled code of that degree (a wave-uniform branch): the
+// run-time-degree loops of sh_eval<-1> cost several times the instructions of the unrolled recurrence.
+template <class Sink>
+__device__ __forceinline__ void sh_eval_any(float x, float y, float z, const ShTable& T, Sink sink) {
+  switch (T.L) {
+    case 0: sh_eval<0>(x, y, z, T, sink); break;
+    case 1: sh_eval<1>(x, y, z, T, sink); break;
+    case 2: sh_eval<2>(x, y, z, T, sink); break;
+    case 3: sh_eval<3>(x, y, z, T, sink); break;
+    case 4: sh_eval<4>(x, y, z, T, sink); break;
+    case 5: sh_eval<5>(x, y, z, T, sink); break;
+    default: sh_eval<-1>(x, y, z, T, sink); break;
   }
 }

@@ -70,7 +70,9 @@ __device__ __forceinline__ void pc_split8(const float (&v)[8], uint4& hi, uint4&
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     h[i] = pack_bf16x2(v[2 * i], v[2 * i + 1]);
-    l[i] = pack_bf16x2(v[2 * i] - bf16lo_to_f32(h[i]), v[2 * i + 1] - bf16hi_to_f32(h[i]));
+    // a plain rounded subtraction: were it contracted with a product that made v, the remainder would come from the
+    // unrounded product in some copies of this code and from the rounded one in others
+    l[i] = pack_bf16x2(sub_fixed(v[2 * i], bf16lo_to_f32(h[i])), sub_fixed(v[2 * i + 1], bf16hi_to_f32(h[i])));
   }
   hi = make_uint4(h[0], h[1], h[2], h[3]);
   lo = make_uint4(l[0], l[1], l[2], l[3]);
@@ -115,7 +117,7 @@ __global__ void __launch_bounds__(256) k_pc_dw(PcP p) {
     if constexpr (SPLIT) {
       const uint16_t h = (uint16_t)f32_to_bf16_bits(x);
       Ph[lane * PC_PP + k] = h;
-      Pl[lane * PC_PP + k] = (uint16_t)f32_to_bf16_bits(x - bf16_to_f32(h));
+      Pl[lane * PC_PP + k] = (uint16_t)f32_to_bf16_bits(sub_fixed(x, bf16_to_f32(h)));   // (never contracted: see pc_split8)
       if constexpr (MODE == 2) {
         const int kl = k - p.kc0;
         if (kl >= 0 && kl < PC_KC && k < p.K) Th[kl * PC_TP + lane] = h;
@@ -245,7 +247,7 @@ __global__ void __launch_bounds__(256) k_pc_dw(PcP p) {
         e2 = st_ent(j4 + 12);
         if (has) {
           const float dx = p.sign * (pt.x - xr[0]), dyy = p.sign * (pt.y - xr[1]), dz = p.sign * (pt.z - xr[2]);
-          const float r = sqrtf(dx * dx + dyy * dyy + dz * dz);
+          const float r = sqrtf(norm2_fixed(dx, dyy, dz));
           const float Z = fminf(r * p.inv_rho, 1.0f);
           float ux = 0.f, uy = 0.f, uz = 1.f;
           if (r > 0.f) { const float ir = 1.0f / r; ux = dx * ir; uy = dyy * ir; uz = dz * ir; }
@@ -276,7 +278,7 @@ __global__ void __launch_bounds__(256) k_pc_dw(PcP p) {
               }
             }
           } else {
-            sh_eval<-1>(ux, uy, uz, p.sh, [&](int k, float v) { put(k, Z * v); });
+            sh_eval_any(ux, uy, uz, p.sh, [&](int k, float v) { put(k, Z * v); });
             put(p.K, 1.0f - Z);
           }
           if constexpr (SPLIT && MODE == 2) Wz[lane] = 1.0f - Z;
@@ -386,7 +388,7 @@ __global__ void __launch_bounds__(256) k_pc_dw(PcP p) {
 #pragma unroll
             for (int q = 0; q < 4; ++q)
 #pragma unroll
-              for (int t = 0; t < 4; ++t) acc[q][t] += hv[q][t] * S[t][q];
+              for (int t = 0; t < 4; ++t) acc[q][t] = fmaf(hv[q][t], S[t][q], acc[q][t]);   // explicit: the three modes round alike
           }
           if constexpr (MODE == 2) {
             float pe[4][CPL];
@@ -404,7 +406,7 @@ __global__ void __launch_bounds__(256) k_pc_dw(PcP p) {
               if (p.kc0 == 0) {
                 const float z1 = SPLIT ? Wz[rr] : Bw[rr * KP + p.K];
 #pragma unroll
-                for (int t = 0; t < 4; ++t) E[t] += z1 * pe[q][t];
+                for (int t = 0; t < 4; ++t) E[t] = fmaf(z1, pe[q][t], E[t]);
               }
             }
             if constexpr (SPLIT) {

@@ -207,8 +207,9 @@ __device__ __forceinline__ void dir_finish(const DirRaw& d, float& x, float& y, 
   if constexpr (BM == B_NORMAL) {
     const float ux = d.v[3] - d.v[0], uy = d.v[4] - d.v[1], uz = d.v[5] - d.v[2];
     const float wx = d.v[6] - d.v[0], wy = d.v[7] - d.v[1], wz = d.v[8] - d.v[2];
-    const float cx = uy * wz - uz * wy, cy = uz * wx - ux * wz, cz = ux * wy - uy * wx;
-    const float l2 = cx * cx + cy * cy + cz * cz;
+    float cx, cy, cz;
+    cross_fixed(ux, uy, uz, wx, wy, wz, cx, cy, cz);
+    const float l2 = norm2_fixed(cx, cy, cz);
     const bool deg = l2 < 1e-30f;
     const float r = 1.0f / sqrtf(deg ? 1.0f : l2);
     x = deg ? 0.f : cx * r;

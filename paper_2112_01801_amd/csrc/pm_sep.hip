@@ -90,7 +90,7 @@ __global__ void __launch_bounds__(256) k_dw_f2v(SepP p) {
         if (r < p.F) {
           float x, y, z;
           row_direction<B_NORMAL>(p.bs, r, x, y, z);
-          sh_eval<-1>(x, y, z, p.bs.sh, [&](int k, float v) {
+          sh_eval_any(x, y, z, p.bs.sh, [&](int k, float v) {
             const int kl = k - k0;
             if (kl >= 0 && kl < kn) Bw[lane * KP + kl] = v;
           });

@@ -277,7 +277,7 @@ __global__ void __launch_bounds__(256, (NJ == 1 || (CIN == 64 && NB >= 3)) ? 1 :
         } else {
           // basis of the wave's 32 facets into its own LDS rows (both half-waves hold the same rows), then the
           // filter values of every accumulator element from the fp32 matrix core
-          sh_eval<-1>(nx, ny, nz, p.sh, [&](int k, float v) {
+          sh_eval_any(nx, ny, nz, p.sh, [&](int k, float v) {
             if (hh == 0) Bw[r * KP + k] = v;
           });
           __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
