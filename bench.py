@@ -26,8 +26,12 @@ PEAK_MFMA_TFLOPS = {"bf16": 2500.0, "f32": 157.3}
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--settle-ms", type=float, default=60.0,
+                    help="untimed load before the warm-up steps: after idling (set-up, uploads) the board's power "
+                         "management needs about 40 ms of this load before clocks and step times are steady "
+                         "(steps 0-9 after an idle second: 1.1-1.5 ms, 10-19: 1.02, 20-29: 0.98, from 40 on: 0.955)")
     ap.add_argument("--grid", type=int, default=1024, help="height-field side (1024 = the benchmark config)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--oracle-rows", type=int, default=0,
@@ -40,6 +44,19 @@ def parse():
                          "same mesh and print one JSON line with per-kernel times")
     ap.add_argument("--ops-dtype", default="bf16", choices=["bf16", "f32"])
     return ap.parse_args()
+
+
+def settle(fn, torch, ms):
+    """Run `fn` back to back for `ms` milliseconds (untimed): brings the device from idle to its steady clocks."""
+    if ms <= 0:
+        return 0
+    n, t0 = 0, time.perf_counter()
+    while (time.perf_counter() - t0) * 1e3 < ms:
+        for _ in range(4):
+            fn()
+        n += 4
+        torch.cuda.synchronize()
+    return n
 
 
 def kernel_models(F, V, K, cin, cout, e):
@@ -140,6 +157,7 @@ def main():
     # Warm-up.  Every kernel of the warm-up steps is bracketed by HIP events (the `kernels` table); that finds
     # the dominant kernel.  A pair of events costs the stream a few microseconds (14 pairs a step: ~5 % of this
     # step), so the timed region brackets the dominant kernel alone, whose durations give `roofline`.
+    settled = settle(step, torch, args.settle_ms)
     pm.pm_profile_filter("")
     pm.pm_profile_reset()
     pm.pm_profile_enable(True)
@@ -223,6 +241,7 @@ def main():
     out = {
         "metric": "mesh-conv facets/sec (fwd+bwd) at 1 MI355X",
         "value": value, "unit": "facets/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "settle_steps": settled,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "config 3: %dx%d height-field, F=%d V=%d, L=3 (K=16), 64->64, bf16 in / fp32 "
@@ -310,6 +329,7 @@ def config_ops(args, pm, mg, torch):
                 x = rnd(P, cin); fn = lambda: pm.pm_f2f(t_off, t_bary, L, x, W, DT)
             else:
                 x, d = rnd(P, cin), rnd(F, cout); fn = lambda: pm.pm_f2f_bwd(t_off, t_bary, L, x, W, d, DT)
+            settle(fn, torch, args.settle_ms)
             for _ in range(max(1, args.warmup)):
                 fn()
             torch.cuda.synchronize()
@@ -433,6 +453,7 @@ def all_ops(args, cfg, pm, mg, torch):
                        (args.grid, args.grid, F, V, P, L, cin, cout, args.ops_dtype),
            "steps": args.steps, "ops": {}}
     for name, (fn, rows) in ops.items():
+        settle(fn, torch, args.settle_ms)
         for _ in range(max(1, args.warmup)):
             fn()
         torch.cuda.synchronize()
