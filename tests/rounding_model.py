@@ -132,6 +132,22 @@ def pcloud_dh_bf16(xq, xs, nbr_ptr, nbr_idx, rho, L, h, alpha, c0, P, dg, norm=0
     return r16(dh)
 
 
+def f2v_dh_bf16(vert, facet, L, W, dg, norm=0):
+    """dh of the dense facet2vertex backward (transposed Eq. 5) with the two bf16 roundings of the data path: the
+    gathered gradient row dy_f = sum_j dg[v_j] / deg(v_j) is the bf16 operand of the matrix cores (it is not a stored
+    feature, so it is not representable exactly), and the output row is stored in bf16."""
+    facet = np.asarray(facet, np.int64).reshape(-1, 3)
+    W, dg = np.asarray(W, np.float64), np.asarray(dg, np.float64)
+    V, F = dg.shape[0], facet.shape[0]
+    deg = np.bincount(facet.reshape(-1), minlength=V).astype(np.float64)
+    dy = np.zeros((F, dg.shape[1]))
+    for j in range(3):
+        dy += dg[facet[:, j]] / np.maximum(deg[facet[:, j]], 1.0)[:, None]
+    dy = r16(dy)
+    B = sh_basis(facet_normals(vert, facet), L, norm) if F else np.zeros((0, (L + 1) ** 2))
+    return r16(np.einsum("fk,fo,kio->fi", B, dy, W, optimize=True))
+
+
 def derived_bound(stated: float, model_err: float) -> float:
     """The bar for the HIP result against the oracle: the stated tolerance, or what the storage format alone implies
     (plus a quarter for fp32 accumulation order and ties that round the other way)."""

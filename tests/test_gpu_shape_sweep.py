@@ -1,0 +1,86 @@
+"""Seeded sweep over operator shapes: degrees, channel counts and dtypes drawn at random (fixed seeds) so that the
+dispatch boundaries between the kernels' fast and general paths (whole and partial channel chunks, 32-wide slabs,
+resident and streamed weights, vector and element-wise access, few-channel staging) are crossed by shapes nobody
+picked by hand.  Every case: facet2vertex, vertex2facet and facet2facet, forward and backward, against the oracle."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2112_01801_amd import meshgen as mg
+import rounding_model as rm
+from parity_util import TOL, make_coeffs, make_features, pm_dtype, rel_err, to_dev, to_host
+
+pytestmark = pytest.mark.gpu
+
+POOL = [1, 2, 3, 4, 5, 7, 8, 12, 16, 20, 24, 32, 33, 40, 48, 56, 64, 72, 80, 96, 104, 128, 136, 160, 192, 256]
+
+
+def _cases(n=28):
+    rng = np.random.default_rng(20211201)
+    out = []
+    while len(out) < n:
+        L = int(rng.integers(0, 6))
+        cin, cout = int(rng.choice(POOL)), int(rng.choice(POOL))
+        if (L + 1) ** 2 * cin * cout > 400_000:          # keeps the oracle at about a second per operator
+            continue
+        out.append((L, cin, cout, "bf16" if rng.random() < 0.6 else "f32", int(rng.integers(1, 1 << 30))))
+    return out
+
+
+@pytest.fixture(scope="module")
+def pm():
+    import torch
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    from paper_2112_01801_amd import binding
+    binding.lib()
+    return binding
+
+
+def _mesh(seed):
+    """Two perturbed icospheres and a height-field with deleted facets: ~2.3k facets, ragged tiles, uneven valences."""
+    rng = np.random.default_rng(seed)
+    meshes = []
+    for lvl in (2, 3):
+        v, f = mg.icosphere_f64(lvl)
+        v = v * (1 + rng.normal(0, 0.03, (v.shape[0], 1))) * rng.uniform(0.5, 1.5, (1, 3))
+        meshes.append((v.astype(np.float32), f))
+    v, f = mg.heightfield(int(rng.integers(12, 28)), int(rng.integers(12, 28)), rng, random_diag=True)
+    meshes.append((v, mg.delete_facets(f, 0.1, rng)))
+    return mg.pack_batch(meshes), rng
+
+
+@pytest.mark.parametrize("L,cin,cout,dtype,seed", _cases())
+def test_three_operators_forward_backward(pm, L, cin, cout, dtype, seed):
+    import torch
+    b, rng = _mesh(seed)
+    K, dt, tol = (L + 1) ** 2, pm_dtype(dtype), TOL[dtype]
+    W = make_coeffs(rng, K, cin, cout, dtype)
+    W_d = to_dev(W, dtype)
+    mesh = pm.mesh_to_device(b)
+    adj = pm.pm_build_vf_adjacency(mesh)
+    F, V = b.n_facet, b.n_vert
+    # facet2vertex (Eq. 5)
+    h, dg = make_features(rng, F, cin, dtype), make_features(rng, V, cout, dtype)
+    assert rel_err(to_host(pm.pm_f2v(mesh, adj, L, to_dev(h, dtype), W_d, dt)), oracle.f2v(b.vert, b.facet, L, h, W)) < tol
+    dh, dW = pm.pm_f2v_bwd(mesh, adj, L, to_dev(h, dtype), W_d, to_dev(dg, dtype), dt)
+    rdh, rdW = oracle.f2v_bwd(b.vert, b.facet, L, h, W, dg)
+    # dh passes two bf16 roundings by construction (the gathered gradient row as matrix-core operand, the output):
+    # with few output channels the stated bar is at the edge of what that implies, so the bar is the larger of the
+    # stated one and 1.25 x the error of the oracle-side model of those two roundings
+    tol_dh = tol if dtype == "f32" else rm.derived_bound(tol, rel_err(rm.f2v_dh_bf16(b.vert, b.facet, L, W, dg), rdh))
+    assert rel_err(to_host(dh), rdh) < tol_dh and rel_err(to_host(dW), rdW) < tol
+    # vertex2facet (Eq. 6)
+    h, dg = make_features(rng, V, cin, dtype), make_features(rng, F, cout, dtype)
+    assert rel_err(to_host(pm.pm_v2f(mesh, L, to_dev(h, dtype), W_d, dt)), oracle.v2f(V, b.facet, L, h, W)) < tol
+    dh, dW = pm.pm_v2f_bwd(mesh, adj, L, to_dev(h, dtype), W_d, to_dev(dg, dtype), dt)
+    rdh, rdW = oracle.v2f_bwd(V, b.facet, L, h, W, dg)
+    assert rel_err(to_host(dh), rdh) < tol and rel_err(to_host(dW), rdW) < tol
+    # facet2facet (Eq. 7) on the textures of Eq. 8
+    tex_off, bary = mg.texture_layout(b, 3, 1)
+    P = int(tex_off[-1])
+    h, dg = make_features(rng, P, cin, dtype), make_features(rng, F, cout, dtype)
+    t_off, t_bary = torch.from_numpy(tex_off.astype(np.int32)).cuda(), torch.from_numpy(bary).cuda()
+    assert rel_err(to_host(pm.pm_f2f(t_off, t_bary, L, to_dev(h, dtype), W_d, dt)), oracle.f2f(tex_off, bary, L, h, W)) < tol
+    dh, dW = pm.pm_f2f_bwd(t_off, t_bary, L, to_dev(h, dtype), W_d, to_dev(dg, dtype), dt)
+    rdh, rdW = oracle.f2f_bwd(tex_off, bary, L, h, W, dg)
+    assert rel_err(to_host(dh), rdh) < tol and rel_err(to_host(dW), rdW) < tol

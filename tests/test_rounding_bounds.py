@@ -50,6 +50,18 @@ def test_model_without_rounding_is_the_oracle(monkeypatch):
                                opc.pcloud_conv(xs, xs, ptr, idx, 0.2, 2, hh, alpha, c0, P), rtol=1e-12, atol=1e-13)
 
 
+def test_dense_f2v_dh_model_without_rounding_is_the_oracle(monkeypatch):
+    import oracle
+    monkeypatch.setattr(rm, "r16", lambda x: np.asarray(x, np.float64))
+    b = small_batch(33)
+    rng = np.random.default_rng(533)
+    L, cin, cout = 2, 6, 5
+    W = rng.standard_normal(((L + 1) ** 2, cin, cout))
+    h, dg = rng.standard_normal((b.n_facet, cin)), rng.standard_normal((b.n_vert, cout))
+    rdh, _ = oracle.f2v_bwd(b.vert, b.facet, L, h, W, dg)
+    np.testing.assert_allclose(rm.f2v_dh_bf16(b.vert, b.facet, L, W, dg), rdh, rtol=1e-11, atol=1e-12)
+
+
 def test_one_store_is_half_a_bf16_ulp():
     x = np.random.default_rng(0).standard_normal(100000)
     rel = np.abs(rm.r16(x) - x) / np.abs(x)
