@@ -84,3 +84,39 @@ def test_three_operators_forward_backward(pm, L, cin, cout, dtype, seed):
     dh, dW = pm.pm_f2f_bwd(t_off, t_bary, L, to_dev(h, dtype), W_d, to_dev(dg, dtype), dt)
     rdh, rdW = oracle.f2f_bwd(tex_off, bary, L, h, W, dg)
     assert rel_err(to_host(dh), rdh) < tol and rel_err(to_host(dW), rdW) < tol
+
+
+def _sep_cases(n=16):
+    rng = np.random.default_rng(20211202)
+    out = []
+    for _ in range(n):
+        out.append((int(rng.integers(0, 6)), int(rng.choice(POOL)), int(rng.choice(POOL)),
+                    "bf16" if rng.random() < 0.6 else "f32", int(rng.integers(1, 1 << 30))))
+    return out
+
+
+@pytest.mark.parametrize("L,cin,cout,dtype,seed", _sep_cases())
+def test_separable_operators_forward_backward(pm, L, cin, cout, dtype, seed):
+    """The depth-wise separable forms (one SH coefficient set per channel, then a point-wise matrix) on random shapes."""
+    import torch
+    b, rng = _mesh(seed)
+    K, dt, tol = (L + 1) ** 2, pm_dtype(dtype), TOL[dtype]
+    alpha = (rng.uniform(-1, 1, (K, cin)) / np.sqrt(K)).astype(np.float32)
+    P = (rng.uniform(-1, 1, (cin, cout)) * np.sqrt(3.0 / cin)).astype(np.float32)
+    P = mg.round_to_bf16(P) if dtype == "bf16" else P
+    a_d, P_d = torch.from_numpy(alpha).cuda(), to_dev(P, dtype)
+    mesh = pm.mesh_to_device(b)
+    adj = pm.pm_build_vf_adjacency(mesh)
+    F, V = b.n_facet, b.n_vert
+    h, dg = make_features(rng, F, cin, dtype), make_features(rng, V, cout, dtype)
+    g = pm.pm_f2v_sep(mesh, adj, L, to_dev(h, dtype), a_d, P_d, dt)
+    assert rel_err(to_host(g), oracle.f2v_sep(b.vert, b.facet, L, h, alpha, P)) < tol
+    dh, da, dP = pm.pm_f2v_sep_bwd(mesh, adj, L, to_dev(h, dtype), a_d, P_d, to_dev(dg, dtype), dt)
+    rdh, rda, rdP = oracle.f2v_sep_bwd(b.vert, b.facet, L, h, alpha, P, dg)
+    assert rel_err(to_host(dh), rdh) < tol and rel_err(to_host(da), rda) < tol and rel_err(to_host(dP), rdP) < tol
+    h, dg = make_features(rng, V, cin, dtype), make_features(rng, F, cout, dtype)
+    g = pm.pm_v2f_sep(mesh, L, to_dev(h, dtype), a_d, P_d, dt)
+    assert rel_err(to_host(g), oracle.v2f_sep(V, b.facet, L, h, alpha, P)) < tol
+    dh, da, dP = pm.pm_v2f_sep_bwd(mesh, adj, L, to_dev(h, dtype), a_d, P_d, to_dev(dg, dtype), dt)
+    rdh, rda, rdP = oracle.v2f_sep_bwd(V, b.facet, L, h, alpha, P, dg)
+    assert rel_err(to_host(dh), rdh) < tol and rel_err(to_host(da), rda) < tol and rel_err(to_host(dP), rdP) < tol
